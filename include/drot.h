@@ -1,0 +1,145 @@
+/*
+ * drot.h -- C ABI of the MI355X (gfx950) Douglas-Rachford solver for regularized discrete
+ * optimal transport
+ *
+ *        minimise  <C,X> + h(X)   subject to  X 1_n = p,  X^T 1_m = q,  X >= 0      (problem (1))
+ *
+ * with h in {0, (lambda/2)||X||_F^2, mu*sum_g ||X_g||_2 + (lambda/2)||X||_F^2} (Section 3:
+ * quadratic and group-lasso regularization; groups g = (class of source row, target column)).
+ *
+ * Every iteration is one sweep over the m x n plan (eq. (8): X <- prox_{rho h}([X + phi 1^T +
+ * 1 varphi^T - rho C]_+), fused with the row and column sums) followed by the O(m+n) vector
+ * recursion of eq. (6).  All of it runs in hand-written HIP kernels on the caller's stream.
+ *
+ * Conventions
+ *   - All matrix pointers are DEVICE pointers to row-major fp32 arrays with pitch n (no padding).
+ *     Any m, n >= 1 and any 4-byte-aligned base address are accepted; 16-byte alignment and
+ *     n % 4 == 0 are not required.
+ *   - The caller owns C, p, q, X_out, row_class and the point clouds; the library never frees or
+ *     reallocates them and never writes C, p, q, row_class.  The handle owns only workspace.
+ *   - Preconditions that are NOT checked (they would need a pass over the data): p, q >= 0 with
+ *     sum(p) = sum(q) = 1, C >= 0 and finite, labels in range.  The stepsize default assumes
+ *     max(C) = 1 ("Stepsize selection").
+ *   - Return value: 0 = DROT_OK, 1 = DROT_MAX_ITERS (ran out of iterations before reaching tol;
+ *     a status, the outputs are valid), negative = error, nothing was computed.  No exceptions
+ *     cross the boundary.  One solve at a time per handle; different handles are independent.
+ *   - drot_solve* return after the stream work they enqueued has completed (they synchronise
+ *     with `stream` only), so X_out and drot_get_info are valid on return.
+ */
+#ifndef DROT_H_
+#define DROT_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct drot_handle_s* drot_handle;
+
+typedef enum {
+  DROT_REG_NONE = 0,        /* h = 0                                   (eq. (5))            */
+  DROT_REG_QUADRATIC = 1,   /* h = (lambda/2)||X||_F^2                 (Quadratic Regularization) */
+  DROT_REG_GROUP_LASSO = 2  /* h = mu sum_g ||X_g||_2 + (lambda/2)||X||_F^2 (Group Lasso Regularization) */
+} drot_reg_kind;
+
+enum {
+  DROT_OK = 0,
+  DROT_MAX_ITERS = 1,
+  DROT_ERR_INVALID_ARG = -1,
+  DROT_ERR_ALLOC = -2,
+  DROT_ERR_HIP = -3,
+  DROT_ERR_NOT_INITIALIZED = -4
+};
+
+/* Regularizer parameters; HOST struct, read during the call. */
+typedef struct {
+  float lambda;          /* weight of (lambda/2)||X||_F^2, >= 0; used by QUADRATIC and GROUP_LASSO */
+  float mu;              /* group-lasso weight, >= 0; GROUP_LASSO only                              */
+  int num_classes;       /* GROUP_LASSO only: number of row classes, >= 1                           */
+  const int* row_class;  /* GROUP_LASSO only: DEVICE pointer, m labels in [0, num_classes)          */
+} drot_reg_params;
+
+/* Result of the last solve on a handle (host struct). */
+typedef struct {
+  int iters;         /* iterations performed (index of the returned iterate X_iters)             */
+  int converged;     /* 1 if the residual test passed, else 0                                    */
+  float r_row;       /* ||X 1_n - p||_2 of the returned iterate (Appendix C, r_primal)           */
+  float r_col;       /* ||X^T 1_m - q||_2                                                        */
+  double objective;  /* <C,X> + h(X)                        (filled when the gap was requested)  */
+  double gap;        /* duality gap of (X, phi, varphi), Appendix C                              */
+  double dual_res;   /* dual constraint violation where h* is an indicator, else 0               */
+} drot_info;
+
+/*
+ * Create a solver for problems up to max_m x max_n on the current HIP device.  Allocates the
+ * O(m+n) vectors, the partial-sum buffers of the fused reductions and a pinned status block.
+ * Errors: INVALID_ARG (null out, sizes < 1), ALLOC, HIP.
+ */
+int drot_create(drot_handle* out, int max_m, int max_n);
+
+/* Free the workspace.  A null handle is DROT_ERR_INVALID_ARG. */
+int drot_destroy(drot_handle h);
+
+/*
+ * Options (all optional; defaults in brackets).
+ *   check_every [100]: the residual test of Appendix C is evaluated on the device every this many
+ *       iterations; the solve stops at the first test that passes.  >= 1.
+ *   compute_gap [1]: evaluate objective, duality gap and dual residual of the returned iterate
+ *       (one extra read-only pass over X and C at the end of the solve).
+ */
+int drot_set_check_every(drot_handle h, int check_every);
+int drot_set_compute_gap(drot_handle h, int enable);
+
+/*
+ * Continuation [off].  When enabled, drot_solve does not restart from X_0 = 0: it resumes the
+ * iteration from the state the previous solve on this handle left (phi, varphi and the running
+ * sums of eq. (6) in the workspace, the plan in X_out, which must still hold that solve's output;
+ * same m, n, C, p, q and regularizer are the caller's responsibility).  Running K1 then K2
+ * iterations this way gives bit-for-bit the iterate of one K1+K2 solve.  INVALID_ARG at the next
+ * solve if no solve has run or the sizes differ.  drot_info.iters counts the iterations of the call.
+ */
+int drot_set_continue(drot_handle h, int enable);
+
+/*
+ * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
+ * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
+ * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.
+ */
+int drot_set_profile(drot_handle h, int enable);
+int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
+
+/*
+ * Solve problem (1) by the iteration of eq. (8) + eq. (6), starting from X_0 = 0 and the
+ * phi_0, varphi_0 of the Initialization paragraph.
+ *
+ *   C [in]      DEVICE, m*n fp32 row-major, the cost
+ *   p, q [in]   DEVICE, m resp. n fp32, the marginals
+ *   stepsize    rho; <= 0 selects 2/(m+n) ("Stepsize selection")
+ *   reg_kind, reg_params   the regularizer; reg_params may be NULL for DROT_REG_NONE
+ *   max_iters   >= 0; with tol <= 0 exactly max_iters iterations are run
+ *   tol         stop when max(||X1-p||_2, ||X^T1-q||_2) <= tol at a check (eq. "stopping criteria")
+ *   X_out [out] DEVICE, m*n fp32 row-major; used as the iterate buffer, contents on entry ignored
+ *   stream      hipStream_t (as void*); NULL = the default stream
+ *
+ * Errors: INVALID_ARG (null pointers, m/n outside [1, max], negative max_iters or weights,
+ * unknown reg_kind, GROUP_LASSO without labels), HIP.
+ */
+int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n,
+               float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,
+               int max_iters, float tol, float* X_out, void* stream);
+
+/* Results of the last solve (host struct).  NOT_INITIALIZED if no solve has run. */
+int drot_get_info(drot_handle h, drot_info* out);
+
+/*
+ * Copy phi (m floats) and varphi (n floats) of the last solve into DEVICE buffers; u = phi/rho,
+ * v = varphi/rho estimate the dual potentials (Appendix C).  Either pointer may be NULL.
+ */
+int drot_get_duals(drot_handle h, float* phi_out, float* varphi_out);
+
+/* Human-readable text for a return code. */
+const char* drot_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DROT_H_ */

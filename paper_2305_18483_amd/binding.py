@@ -1,0 +1,196 @@
+"""Thin ctypes binding of libdrot.so (C ABI declared in include/drot.h).
+
+Argument marshalling only: every step of the solver runs inside the HIP library.  PyTorch is
+used for device buffers and the stream handle.  There is no CPU fallback: if the library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdrot.so")
+
+DROT_REG_NONE, DROT_REG_QUADRATIC, DROT_REG_GROUP_LASSO = 0, 1, 2
+DROT_OK, DROT_MAX_ITERS = 0, 1
+DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -1, -2, -3, -4
+
+# every symbol include/drot.h declares
+EXPORTED_SYMBOLS = (
+    "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
+    "drot_set_profile", "drot_get_profile", "drot_solve", "drot_get_info", "drot_get_duals", "drot_strerror",
+)
+
+
+class drot_reg_params(ctypes.Structure):
+    _fields_ = [("lambda_", ctypes.c_float), ("mu", ctypes.c_float), ("num_classes", ctypes.c_int),
+                ("row_class", ctypes.c_void_p)]
+
+
+class drot_info(ctypes.Structure):
+    _fields_ = [("iters", ctypes.c_int), ("converged", ctypes.c_int), ("r_row", ctypes.c_float),
+                ("r_col", ctypes.c_float), ("objective", ctypes.c_double), ("gap", ctypes.c_double),
+                ("dual_res", ctypes.c_double)]
+
+
+class DrotError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdrot.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2305_18483_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.drot_create.argtypes = [ctypes.POINTER(vp), ci, ci]
+    lib.drot_destroy.argtypes = [vp]
+    lib.drot_set_check_every.argtypes = [vp, ci]
+    lib.drot_set_compute_gap.argtypes = [vp, ci]
+    lib.drot_set_continue.argtypes = [vp, ci]
+    lib.drot_set_profile.argtypes = [vp, ci]
+    lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    lib.drot_solve.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp]
+    lib.drot_get_info.argtypes = [vp, ctypes.POINTER(drot_info)]
+    lib.drot_get_duals.argtypes = [vp, vp, vp]
+    lib.drot_strerror.argtypes = [ci]
+    lib.drot_strerror.restype = ctypes.c_char_p
+    for name in EXPORTED_SYMBOLS:
+        if name != "drot_strerror":
+            getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().drot_strerror(int(code)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor], dtype, what: str):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous {dtype} tensor on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+@dataclass
+class SolveResult:
+    X: torch.Tensor
+    code: int  # DROT_OK or DROT_MAX_ITERS
+    iters: int
+    converged: bool
+    r_row: float
+    r_col: float
+    objective: float
+    gap: float
+    dual_res: float
+
+
+class Solver:
+    """Owns one drot_handle (workspace for problems up to max_m x max_n on the current device)."""
+
+    def __init__(self, max_m: int, max_n: int, check_every: Optional[int] = None, compute_gap: Optional[bool] = None):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        rc = self._lib.drot_create(ctypes.byref(self._h), int(max_m), int(max_n))
+        if rc != DROT_OK:
+            self._h = ctypes.c_void_p()
+            raise DrotError(rc, "drot_create")
+        if check_every is not None:
+            self.set_check_every(check_every)
+        if compute_gap is not None:
+            self.set_compute_gap(compute_gap)
+
+    def set_check_every(self, k: int) -> None:
+        rc = self._lib.drot_set_check_every(self._h, int(k))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_check_every")
+
+    def set_compute_gap(self, enable: bool) -> None:
+        rc = self._lib.drot_set_compute_gap(self._h, int(bool(enable)))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_compute_gap")
+
+    def set_continue(self, enable: bool) -> None:
+        rc = self._lib.drot_set_continue(self._h, int(bool(enable)))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_continue")
+
+    def set_profile(self, enable: bool) -> None:
+        rc = self._lib.drot_set_profile(self._h, int(bool(enable)))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_profile")
+
+    def profile(self) -> tuple:
+        """(mean sweep duration in ms, number of sweeps timed) of the last solve in profile mode."""
+        ms, cnt = ctypes.c_double(), ctypes.c_int()
+        rc = self._lib.drot_get_profile(self._h, ctypes.byref(ms), ctypes.byref(cnt))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_profile")
+        return ms.value, cnt.value
+
+    def solve(self, C: torch.Tensor, p: torch.Tensor, q: torch.Tensor, *, stepsize: float = 0.0,
+              reg_kind: int = DROT_REG_NONE, lam: float = 0.0, mu: float = 0.0,
+              row_class: Optional[torch.Tensor] = None, num_classes: int = 0, max_iters: int = 1000,
+              tol: float = 0.0, X_out: Optional[torch.Tensor] = None,
+              stream: Optional[torch.cuda.Stream] = None) -> SolveResult:
+        """drot_solve; raises DrotError on a negative return code."""
+        m, n = C.shape
+        if X_out is None:
+            X_out = torch.empty_like(C)
+        params = drot_reg_params(float(lam), float(mu), int(num_classes),
+                                 None if row_class is None else row_class.data_ptr())
+        if row_class is not None:
+            _ptr(row_class, torch.int32, "row_class")
+        stream = stream if stream is not None else torch.cuda.current_stream(C.device)
+        rc = self._lib.drot_solve(self._h, _ptr(C, torch.float32, "C"), _ptr(p, torch.float32, "p"),
+                                  _ptr(q, torch.float32, "q"), int(m), int(n), float(stepsize), int(reg_kind),
+                                  ctypes.byref(params), int(max_iters), float(tol),
+                                  _ptr(X_out, torch.float32, "X_out"), ctypes.c_void_p(stream.cuda_stream))
+        if rc < 0:
+            raise DrotError(rc, "drot_solve")
+        info = self.info()
+        return SolveResult(X=X_out, code=rc, iters=info.iters, converged=bool(info.converged), r_row=info.r_row,
+                           r_col=info.r_col, objective=info.objective, gap=info.gap, dual_res=info.dual_res)
+
+    def info(self) -> drot_info:
+        out = drot_info()
+        rc = self._lib.drot_get_info(self._h, ctypes.byref(out))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_info")
+        return out
+
+    def duals(self, m: int, n: int, device) -> tuple:
+        phi = torch.empty(m, dtype=torch.float32, device=device)
+        varphi = torch.empty(n, dtype=torch.float32, device=device)
+        rc = self._lib.drot_get_duals(self._h, ctypes.c_void_p(phi.data_ptr()), ctypes.c_void_p(varphi.data_ptr()))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_duals")
+        return phi, varphi
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.drot_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,950 @@
+// Douglas-Rachford splitting for regularized discrete optimal transport on MI355X (gfx950).
+//
+// One iteration = one sweep over the m x n plan (eq. (8): X <- prox_{rho h}([X + phi 1^T +
+// 1 varphi^T - rho C]_+), fused with the row sums, column sums and grand total the marginal
+// projection needs) followed by the O(m+n) recursion of eq. (6).  Y is never formed (Section
+// 2.1: "Y_k can be eliminated").  The sweep is HBM bound (12 bytes per element: read X, read C,
+// write X; about 8 flops), so there is no MFMA here: the design is coalesced 128-bit row-major
+// accesses, many loads in flight per lane, DPP wave reductions for the row sums, register column
+// partials folded through LDS, and a deterministic two-stage reduction instead of atomics.
+//
+// Data layout in HBM
+//   X, C        m x n fp32 row-major, pitch n, caller-owned
+//   phi/varphi  fp32, what the sweep reads;  a, b, theta: fp64 running sums of eq. (6)
+//   rowpart     [nseg][m]  fp32: row sums of every 256-column segment
+//   colpart     [ntr][n]   fp32: column sums of every row tile
+//   tilesum     [ntr*nseg] fp32: grand total per tile (gives eta without a second pass)
+//
+// This file is the whole product path: kernels, host loop and the C ABI of include/drot.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "drot.h"
+
+namespace {
+
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef f4v f4u __attribute__((aligned(4)));  // 128-bit access that only needs 4-byte alignment
+
+constexpr int kBlock = 256;          // threads per workgroup in the sweep kernels (4 waves)
+constexpr int kWavesPerBlock = 4;
+constexpr int kSegCols = 256;        // columns per tile: 64 lanes x 4
+constexpr int kMaxWaveRows = 64;     // rows per wave per tile (<= 64: one lane keeps one row sum)
+constexpr float kMaskedOut = -1.0e30f;  // added to columns past n so that [.]_+ yields exactly 0
+
+// ------------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+
+// Sum over the 64 lanes of a wave; the result is wave-uniform (read back from lane 63).
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_mov<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
+  v += dpp_mov<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
+  v += dpp_mov<0x141, 0xF>(v);  // row_half_mirror
+  v += dpp_mov<0x140, 0xF>(v);  // row_mirror: every lane of a 16-lane row holds the row total
+  v += dpp_mov<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+  v += dpp_mov<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
+__device__ __forceinline__ f4v load4(const float* __restrict__ ptr, int nvalid) {
+  if (nvalid == 4) return *reinterpret_cast<const f4u*>(ptr);
+  f4v v = {0.f, 0.f, 0.f, 0.f};
+  if (nvalid > 0) v.x = ptr[0];
+  if (nvalid > 1) v.y = ptr[1];
+  if (nvalid > 2) v.z = ptr[2];
+  return v;
+}
+
+__device__ __forceinline__ void store4(float* __restrict__ ptr, f4v v, int nvalid) {
+  if (nvalid == 4) {
+    *reinterpret_cast<f4u*>(ptr) = v;
+    return;
+  }
+  if (nvalid > 0) ptr[0] = v.x;
+  if (nvalid > 1) ptr[1] = v.y;
+  if (nvalid > 2) ptr[2] = v.z;
+}
+
+// varphi of this lane's four columns; columns past n get a huge negative value so that the
+// nonnegativity clamp zeroes them and they drop out of every sum.
+__device__ __forceinline__ f4v load_varphi(const float* __restrict__ varphi, int j0, int nvalid) {
+  f4v v = {kMaskedOut, kMaskedOut, kMaskedOut, kMaskedOut};
+  if (nvalid == 4) return *reinterpret_cast<const f4u*>(varphi + j0);
+  if (nvalid > 0) v.x = varphi[j0];
+  if (nvalid > 1) v.y = varphi[j0 + 1];
+  if (nvalid > 2) v.z = varphi[j0 + 2];
+  return v;
+}
+
+// [x + phi_i + varphi_j - rho c]_+   (first half of eq. (8))
+__device__ __forceinline__ f4v xbar4(f4v x, f4v c, f4v pv, float rho) {
+  f4v v;
+  v.x = fmaxf(fmaf(-rho, c.x, x.x + pv.x), 0.f);
+  v.y = fmaxf(fmaf(-rho, c.y, x.y + pv.y), 0.f);
+  v.z = fmaxf(fmaf(-rho, c.z, x.z + pv.z), 0.f);
+  v.w = fmaxf(fmaf(-rho, c.w, x.w + pv.w), 0.f);
+  return v;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double* red /* blockDim.x doubles */) {
+  const int t = threadIdx.x;
+  red[t] = v;
+  __syncthreads();
+  for (int s = blockDim.x >> 1; s > 0; s >>= 1) {
+    if (t < s) red[t] += red[t + s];
+    __syncthreads();
+  }
+  const double out = red[0];
+  __syncthreads();
+  return out;
+}
+
+// ------------------------------------------------------------------------------------------
+// device-side state shared by the kernels of one solve
+// ------------------------------------------------------------------------------------------
+struct DeviceStatus {
+  double r2, s2;                 // ||X1-p||^2, ||X^T1-q||^2 of the last checked iterate
+  double cost, h, dual_lin, h_conj, gap, dual_res;
+  int iters;                     // iteration the residuals belong to
+  int converged;
+};
+
+struct SweepArgs {
+  float* X;
+  const float* C;
+  const float* phi;
+  const float* varphi;
+  float* rowpart;
+  float* colpart;
+  float* tilesum;
+  const int* done;
+  int m, n, tmw, nseg;
+  float rho, scale;
+};
+
+// ------------------------------------------------------------------------------------------
+// S1-S4: the sweep for h = 0 and h = (lambda/2)||X||^2 (a constant scale, Section 3).
+// grid = (nseg, ntr); a workgroup owns 4*tmw rows x 256 columns; each wave owns tmw whole
+// row segments of 1 KiB, U rows in flight at a time.  EDGE marks the last column segment when
+// n is not a multiple of 256: only there do lanes check how many of their 4 columns exist.
+// ------------------------------------------------------------------------------------------
+template <bool EDGE>
+__device__ __forceinline__ f4v ld4(const float* __restrict__ ptr, int nvalid) {
+  if (!EDGE) return *reinterpret_cast<const f4u*>(ptr);
+  return load4(ptr, nvalid);
+}
+template <bool EDGE>
+__device__ __forceinline__ void st4(float* __restrict__ ptr, f4v v, int nvalid) {
+  if (!EDGE) *reinterpret_cast<f4u*>(ptr) = v;
+  else store4(ptr, v, nvalid);
+}
+
+// Folds the four waves' column partials through LDS, writes the tile's column sums and total.
+__device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wave, int seg, int tr, int n, int nseg,
+                                                   float* __restrict__ colpart, float* __restrict__ tilesum) {
+  __shared__ float cs[kWavesPerBlock][kSegCols];
+  __shared__ float ws[kWavesPerBlock];
+  *reinterpret_cast<f4v*>(&cs[wave][lane * 4]) = colacc;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const float csum = (cs[0][t] + cs[1][t]) + (cs[2][t] + cs[3][t]);
+  const int j = seg * kSegCols + t;
+  if (j < n) colpart[(size_t)tr * n + j] = csum;
+  const float tot = wave_sum(csum);
+  if (lane == 0) ws[wave] = tot;
+  __syncthreads();
+  if (t == 0) tilesum[tr * nseg + seg] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+}
+
+template <bool FIRST, bool EDGE, int U>
+__device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr) {
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
+  const int rend = min(rbeg + A.tmw, A.m);
+  const float rho = A.rho, scale = A.scale;
+  // lane r holds phi of row rbeg + r; rows read it back with a scalar lane read
+  const float phi_lane = (rbeg + lane < rend) ? A.phi[rbeg + lane] : 0.f;
+  const float* __restrict__ Cp = A.C + (size_t)rbeg * A.n + j0;
+  float* __restrict__ Xp = A.X + (size_t)rbeg * A.n + j0;
+  const size_t pitch = (size_t)A.n;
+
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float rowkeep = 0.f;  // lane r keeps the sum of row rbeg + r
+  const int nrows = rend - rbeg;
+  int r = 0;
+  for (; r + U <= nrows; r += U) {
+    f4v x[U], c[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      c[u] = ld4<EDGE>(Cp + (size_t)(r + u) * pitch, nvalid);
+      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE>(Xp + (size_t)(r + u) * pitch, nvalid);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), r + u));
+      const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
+      st4<EDGE>(Xp + (size_t)(r + u) * pitch, v, nvalid);
+      colacc += v;
+      const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+      rowkeep = (lane == r + u) ? tot : rowkeep;
+    }
+  }
+  for (; r < nrows; ++r) {
+    const f4v c = ld4<EDGE>(Cp + (size_t)r * pitch, nvalid);
+    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE>(Xp + (size_t)r * pitch, nvalid);
+    const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), r));
+    const f4v v = xbar4(x, c, vp + ph, rho) * scale;
+    st4<EDGE>(Xp + (size_t)r * pitch, v, nvalid);
+    colacc += v;
+    const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+    rowkeep = (lane == r) ? tot : rowkeep;
+  }
+  if (lane < nrows) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
+  write_col_partials(colacc, lane, wave, seg, tr, A.n, A.nseg, A.colpart, A.tilesum);
+}
+
+template <bool FIRST, int U>
+__global__ __launch_bounds__(kBlock) void sweep_kernel(SweepArgs A) {
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, U>(A, lane, wave, seg, tr);
+  else sweep_body<FIRST, true, U>(A, lane, wave, seg, tr);
+}
+
+// ------------------------------------------------------------------------------------------
+// Group lasso, general labels, two passes (Section "Group-lasso Regularized DROT": when a
+// group does not fit one workgroup the reduction goes through global memory and a second
+// kernel applies the scale).  Pass 1 accumulates sum_{i in class} Xbar_ij^2 per (class, column).
+// ------------------------------------------------------------------------------------------
+struct GroupArgs {
+  SweepArgs S;
+  const int* row_class;
+  float* gsq;   // [num_classes][n]
+  float thr;    // rho * mu
+};
+
+__device__ __forceinline__ void flush_group(float* __restrict__ g, f4v acc, int nvalid) {
+  if (nvalid > 0) atomicAdd(g + 0, acc.x);
+  if (nvalid > 1) atomicAdd(g + 1, acc.y);
+  if (nvalid > 2) atomicAdd(g + 2, acc.z);
+  if (nvalid > 3) atomicAdd(g + 3, acc.w);
+}
+
+template <bool FIRST>
+__global__ __launch_bounds__(kBlock) void gl_norm_kernel(GroupArgs G) {
+  const SweepArgs& A = G.S;
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int j0 = blockIdx.x * kSegCols + lane * 4;
+  const int nvalid = min(max(A.n - j0, 0), 4);
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const int rbeg = blockIdx.y * (kWavesPerBlock * A.tmw) + wave * A.tmw;
+  const int rend = min(rbeg + A.tmw, A.m);
+  int cur = -1;
+  f4v acc = {0.f, 0.f, 0.f, 0.f};
+  for (int i = rbeg; i < rend; ++i) {
+    const int cls = G.row_class[i];
+    if (cls != cur) {
+      if (cur >= 0) flush_group(G.gsq + (size_t)cur * A.n + j0, acc, nvalid);
+      cur = cls;
+      acc = f4v{0.f, 0.f, 0.f, 0.f};
+    }
+    const size_t off = (size_t)i * A.n + j0;
+    const f4v c = load4(A.C + off, nvalid);
+    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + off, nvalid);
+    const f4v v = xbar4(x, c, vp + A.phi[i], A.rho);
+    acc += v * v;
+  }
+  if (cur >= 0) flush_group(G.gsq + (size_t)cur * A.n + j0, acc, nvalid);
+}
+
+// scale of one group from its squared norm t: [1 - rho mu / sqrt(t)]_+ / (1 + rho lambda), 0 at t = 0
+__device__ __forceinline__ float group_scale(float t, float thr, float qscale) {
+  if (!(t > 0.f)) return 0.f;
+  return fmaxf(1.f - thr / sqrtf(t), 0.f) * qscale;
+}
+
+template <bool FIRST>
+__global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
+  const SweepArgs& A = G.S;
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = min(max(A.n - j0, 0), 4);
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
+  const int rend = min(rbeg + A.tmw, A.m);
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float rowkeep = 0.f;
+  int cur = -1;
+  f4v sc = {0.f, 0.f, 0.f, 0.f};
+  for (int i = rbeg; i < rend; ++i) {
+    const int cls = G.row_class[i];
+    if (cls != cur) {
+      cur = cls;
+      const f4v t = load4(G.gsq + (size_t)cls * A.n + j0, nvalid);
+      sc.x = group_scale(t.x, G.thr, A.scale);
+      sc.y = group_scale(t.y, G.thr, A.scale);
+      sc.z = group_scale(t.z, G.thr, A.scale);
+      sc.w = group_scale(t.w, G.thr, A.scale);
+    }
+    const size_t off = (size_t)i * A.n + j0;
+    const f4v c = load4(A.C + off, nvalid);
+    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + off, nvalid);
+    const f4v v = xbar4(x, c, vp + A.phi[i], A.rho) * sc;
+    store4(A.X + off, v, nvalid);
+    colacc += v;
+    const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+    rowkeep = (lane == i - rbeg) ? tot : rowkeep;
+  }
+  if (lane < rend - rbeg) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
+  write_col_partials(colacc, lane, wave, seg, tr, A.n, A.nseg, A.colpart, A.tilesum);
+}
+
+__global__ void fill_kernel(float* __restrict__ dst, size_t count, float value, const int* done) {
+  if (done && *done) return;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x)
+    dst[e] = value;
+}
+
+// ------------------------------------------------------------------------------------------
+// S0: starting point of the Initialization paragraph: X_0 = 0 (never materialised: the first
+// sweep does not read X), phi_0, varphi_0 constants, and a_0 = Y_0 1 - p, b_0 = Y_0^T 1 - q,
+// theta_0 = 1^T a_0/(m+n) with Y_0 = phi_0 1^T + 1 varphi_0^T, the values that make eq. (6)
+// reproduce eq. (4).  One workgroup.
+// ------------------------------------------------------------------------------------------
+struct VecState {
+  float* phi;
+  float* varphi;
+  double* a;
+  double* b;
+  double* theta;   // [2], indexed by iteration parity
+  double* sum_p;   // [1]
+  double* resid_part;
+  int* done;
+  DeviceStatus* status;
+};
+
+__global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __restrict__ p,
+                                                    const float* __restrict__ q, int m, int n) {
+  __shared__ double red[1024];
+  const int t = threadIdx.x;
+  const double mn = (double)m + (double)n;
+  const double phi0 = (1.0 + (double)m / mn) / (3.0 * mn);
+  const double varphi0 = (1.0 + (double)n / mn) / (3.0 * mn);
+  double sp = 0.0;
+  for (int i = t; i < m; i += blockDim.x) {
+    const double pi = (double)p[i];
+    sp += pi;
+    V.phi[i] = (float)phi0;
+    V.a[i] = (double)n * (phi0 + varphi0) - pi;
+  }
+  for (int j = t; j < n; j += blockDim.x) {
+    V.varphi[j] = (float)varphi0;
+    V.b[j] = (double)m * (phi0 + varphi0) - (double)q[j];
+  }
+  const double sum_p = block_sum_f64(sp, red);
+  if (t == 0) {
+    *V.sum_p = sum_p;
+    V.theta[0] = ((double)m * (double)n * (phi0 + varphi0) - sum_p) / mn;
+    V.theta[1] = 0.0;
+    *V.done = 0;
+    *V.status = DeviceStatus{};
+  }
+}
+
+// Re-arms the stop flag and the status block when a solve continues from the handle's state.
+__global__ void reset_kernel(VecState V) {
+  *V.done = 0;
+  *V.status = DeviceStatus{};
+}
+
+// ------------------------------------------------------------------------------------------
+// S5: eq. (6).  r = X1 - p, s = X^T1 - q from the partial sums, eta = 1^T r/(m+n) from the tile
+// totals, then phi+ = (a - 2r + (2 eta - theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m,
+// a -= r, b -= s, theta -= eta.  fp64 throughout; phi, varphi are rounded to fp32 for the sweep.
+// A workgroup owns 64 rows or 64 columns; its 4 waves split the partials.  Also leaves the
+// squared residuals per workgroup (S6).
+// ------------------------------------------------------------------------------------------
+struct VecArgs {
+  VecState V;
+  const float* rowpart;
+  const float* colpart;
+  const float* tilesum;
+  const float* p;
+  const float* q;
+  int m, n, nseg, ntr, ntiles, nbm, par;
+};
+
+__global__ __launch_bounds__(kBlock) void vec_kernel(VecArgs A) {
+  if (*A.V.done) return;
+  __shared__ double red[kBlock];
+  const int t = threadIdx.x;
+  double acc = 0.0;
+  for (int e = t; e < A.ntiles; e += kBlock) acc += (double)A.tilesum[e];
+  const double sum_x = block_sum_f64(acc, red);
+  const double mn = (double)A.m + (double)A.n;
+  const double eta = (sum_x - *A.V.sum_p) / mn;
+  const double theta = A.V.theta[A.par];
+  const double cst = 2.0 * eta - theta;
+  const int sub = t >> 6, l = t & 63;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
+  const int len = rows ? A.m : A.n;
+  const int nparts = rows ? A.nseg : A.ntr;
+  const float* part = rows ? A.rowpart : A.colpart;
+  double s = 0.0;
+  if (idx < len)
+    for (int k = sub; k < nparts; k += 4) s += (double)part[(size_t)k * len + idx];
+  red[t] = s;
+  __syncthreads();
+  double rr = 0.0;
+  if (sub == 0 && idx < len) {
+    const double total = (red[l] + red[64 + l]) + (red[128 + l] + red[192 + l]);
+    if (rows) {
+      const double r = total - (double)A.p[idx];
+      const double ai = A.V.a[idx];
+      A.V.phi[idx] = (float)((ai - 2.0 * r + cst) / (double)A.n);
+      A.V.a[idx] = ai - r;
+      rr = r * r;
+    } else {
+      const double r = total - (double)A.q[idx];
+      const double bi = A.V.b[idx];
+      A.V.varphi[idx] = (float)((bi - 2.0 * r + cst) / (double)A.m);
+      A.V.b[idx] = bi - r;
+      rr = r * r;
+    }
+  }
+  __syncthreads();
+  const double r2 = block_sum_f64(rr, red);
+  if (t == 0) {
+    A.V.resid_part[blockIdx.x] = r2;
+    if (blockIdx.x == 0) A.V.theta[A.par ^ 1] = theta - eta;
+  }
+}
+
+// S6: r_primal of Appendix C from the per-workgroup squared residuals; raises the stop flag at
+// the first check that passes so that every later kernel of the solve returns at once.
+__global__ __launch_bounds__(kBlock) void status_kernel(VecState V, int nbm, int nbn, int iters, double tol) {
+  if (*V.done) return;
+  __shared__ double red[kBlock];
+  const int t = threadIdx.x;
+  double r = 0.0, s = 0.0;
+  for (int e = t; e < nbm; e += kBlock) r += V.resid_part[e];
+  for (int e = t; e < nbn; e += kBlock) s += V.resid_part[nbm + e];
+  const double r2 = block_sum_f64(r, red);
+  const double s2 = block_sum_f64(s, red);
+  if (t == 0) {
+    V.status->r2 = r2;
+    V.status->s2 = s2;
+    V.status->iters = iters;
+    if (tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol) {
+      V.status->converged = 1;
+      __threadfence();
+      *V.done = 1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// S7: objective, duality gap and dual residual of (X, phi, varphi) (Appendix C).  One read-only
+// pass: <C,X>, ||X||_F^2 and ||[phi 1^T + 1 varphi^T - rho C]_+||_F^2 per tile, plus, for the
+// group lasso, the same two squared norms per (class, column) group.
+// ------------------------------------------------------------------------------------------
+struct GapArgs {
+  const float* X;
+  const float* C;
+  const float* phi;
+  const float* varphi;
+  const int* row_class;  // null unless group lasso
+  float* gap_part;       // [ntiles][3]
+  float* gx;             // [num_classes][n] sum x^2   (group lasso)
+  float* gw;             // [num_classes][n] sum w^2
+  int m, n, tmw, nseg;
+  float rho;
+};
+
+__global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = min(max(A.n - j0, 0), 4);
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
+  const int rend = min(rbeg + A.tmw, A.m);
+  float cx = 0.f, xx = 0.f, ww = 0.f;
+  int cur = -1;
+  f4v ax = {0.f, 0.f, 0.f, 0.f}, aw = {0.f, 0.f, 0.f, 0.f};
+  for (int i = rbeg; i < rend; ++i) {
+    const size_t off = (size_t)i * A.n + j0;
+    const f4v c = load4(A.C + off, nvalid);
+    const f4v x = load4(A.X + off, nvalid);
+    const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c, vp + A.phi[i], A.rho);
+    const f4v x2 = x * x, w2 = w * w, cxv = c * x;
+    cx += (cxv.x + cxv.y) + (cxv.z + cxv.w);
+    xx += (x2.x + x2.y) + (x2.z + x2.w);
+    ww += (w2.x + w2.y) + (w2.z + w2.w);
+    if (A.row_class) {
+      const int cls = A.row_class[i];
+      if (cls != cur) {
+        if (cur >= 0) {
+          flush_group(A.gx + (size_t)cur * A.n + j0, ax, nvalid);
+          flush_group(A.gw + (size_t)cur * A.n + j0, aw, nvalid);
+        }
+        cur = cls;
+        ax = f4v{0.f, 0.f, 0.f, 0.f};
+        aw = f4v{0.f, 0.f, 0.f, 0.f};
+      }
+      ax += x2;
+      aw += w2;
+    }
+  }
+  if (cur >= 0) {
+    flush_group(A.gx + (size_t)cur * A.n + j0, ax, nvalid);
+    flush_group(A.gw + (size_t)cur * A.n + j0, aw, nvalid);
+  }
+  __shared__ float ws[3][kWavesPerBlock];
+  const float a0 = wave_sum(cx), a1 = wave_sum(xx), a2 = wave_sum(ww);
+  if (lane == 0) { ws[0][wave] = a0; ws[1][wave] = a1; ws[2][wave] = a2; }
+  __syncthreads();
+  if (threadIdx.x < 3) {
+    const int k = threadIdx.x;
+    A.gap_part[(size_t)(tr * A.nseg + seg) * 3 + k] = (ws[k][0] + ws[k][1]) + (ws[k][2] + ws[k][3]);
+  }
+}
+
+// Combines the partials into the terms of the gap formula, in fp64.  With u = phi/rho,
+// v = varphi/rho, W = [u 1^T + 1 v^T - C]_+ :  gap = <C,X> + h(X) - (p^T u + q^T v) + h*(W);
+// where h* is an indicator the violation is reported as dual_res instead.
+__global__ __launch_bounds__(1024) void gap_final_kernel(VecState V, const float* __restrict__ gap_part, int ntiles,
+                                                         const float* __restrict__ gx, const float* __restrict__ gw,
+                                                         size_t ngroups, const float* __restrict__ p,
+                                                         const float* __restrict__ q, int m, int n, double rho,
+                                                         int reg_kind, double lambda, double mu) {
+  __shared__ double red[1024];
+  const int t = threadIdx.x;
+  double cx = 0.0, xx = 0.0, ww = 0.0, dl = 0.0, gl = 0.0, ex2 = 0.0;
+  for (int e = t; e < ntiles; e += blockDim.x) {
+    cx += (double)gap_part[(size_t)e * 3 + 0];
+    xx += (double)gap_part[(size_t)e * 3 + 1];
+    ww += (double)gap_part[(size_t)e * 3 + 2];
+  }
+  for (int i = t; i < m; i += blockDim.x) dl += (double)p[i] * (double)V.phi[i];
+  for (int j = t; j < n; j += blockDim.x) dl += (double)q[j] * (double)V.varphi[j];
+  if (reg_kind == DROT_REG_GROUP_LASSO) {
+    for (size_t g = t; g < ngroups; g += blockDim.x) {
+      gl += sqrt((double)gx[g]);
+      double ex = sqrt((double)gw[g]) / rho - mu;
+      if (ex < 0.0) ex = 0.0;
+      ex2 += ex * ex;
+    }
+  }
+  cx = block_sum_f64(cx, red);
+  xx = block_sum_f64(xx, red);
+  ww = block_sum_f64(ww, red) / (rho * rho);  // ||W||_F^2
+  dl = block_sum_f64(dl, red) / rho;
+  gl = block_sum_f64(gl, red);
+  ex2 = block_sum_f64(ex2, red);
+  if (t == 0) {
+    double h = 0.0, hconj = 0.0, dres = 0.0;
+    if (reg_kind == DROT_REG_NONE || (reg_kind == DROT_REG_QUADRATIC && lambda <= 0.0)) {
+      dres = sqrt(ww);
+    } else if (reg_kind == DROT_REG_QUADRATIC) {
+      h = 0.5 * lambda * xx;
+      hconj = ww / (2.0 * lambda);
+    } else {
+      h = mu * gl + 0.5 * lambda * xx;
+      if (lambda > 0.0) hconj = ex2 / (2.0 * lambda);
+      else dres = sqrt(ex2);
+    }
+    V.status->cost = cx;
+    V.status->h = h;
+    V.status->dual_lin = dl;
+    V.status->h_conj = hconj;
+    V.status->gap = cx + h - dl + hconj;
+    V.status->dual_res = dres;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// rows per wave per tile: as tall as possible while the launch still has enough workgroups to
+// fill 256 compute units several times over (small problems get flatter tiles, as the paper's
+// "adapt the number of columns per block to the problem size").
+int choose_tmw(int m, int n) {
+  const int nseg = ceil_div(n, kSegCols);
+  for (int tmw = kMaxWaveRows; tmw > 8; tmw >>= 1) {
+    if ((long long)nseg * ceil_div(m, kWavesPerBlock * tmw) >= 2048) return tmw;
+  }
+  return 8;
+}
+constexpr int kMinTileRows = kWavesPerBlock * 8;
+constexpr int kMaxProfiled = 256;  // sweeps timed per solve in profile mode
+
+}  // namespace
+
+struct drot_handle_s {
+  int device = -1;
+  int max_m = 0, max_n = 0;
+  int check_every = 100;
+  int compute_gap = 1;
+  int continue_next = 0;  // the next solve resumes from the state the last one left
+  int profile = 0;        // record HIP events around every sweep launch
+  bool solved = false;
+  int last_m = 0, last_n = 0;
+  long long iters_done = 0;  // iterations applied to the state held by this handle
+  // sweep timing (profile mode): event pairs recorded on the solve's stream
+  hipEvent_t prof_ev[2 * kMaxProfiled] = {};
+  int prof_count = 0;
+  double prof_sweep_ms = 0.0;
+  // device workspace
+  float *phi = nullptr, *varphi = nullptr;
+  double *a = nullptr, *b = nullptr, *theta = nullptr, *sum_p = nullptr, *resid_part = nullptr;
+  float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
+  float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
+  size_t gbuf_len = 0;
+  int* done = nullptr;
+  DeviceStatus* status = nullptr;
+  // pinned host mirror of the status block, two slots for the pipelined residual checks
+  DeviceStatus* host_status = nullptr;
+  hipEvent_t ev[2] = {nullptr, nullptr};
+  drot_info info{};
+};
+
+namespace {
+
+#define DROT_HIP(expr)                                                                   \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess) {                                                              \
+      fprintf(stderr, "drot: %s failed: %s\n", #expr, hipGetErrorString(e_));            \
+      return DROT_ERR_HIP;                                                               \
+    }                                                                                    \
+  } while (0)
+
+template <typename T>
+int dev_alloc(T** ptr, size_t count) {
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(ptr), count * sizeof(T));
+  if (e != hipSuccess) {
+    *ptr = nullptr;
+    return DROT_ERR_ALLOC;
+  }
+  return DROT_OK;
+}
+
+void free_all(drot_handle h) {
+  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf};
+  double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->resid_part};
+  for (float* b : fbufs) (void)hipFree(b);
+  for (double* b : dbufs) (void)hipFree(b);
+  (void)hipFree(h->done);
+  (void)hipFree(h->status);
+  if (h->host_status) (void)hipHostFree(h->host_status);
+  for (auto& e : h->ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto& e : h->prof_ev)
+    if (e) (void)hipEventDestroy(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* drot_strerror(int code) {
+  switch (code) {
+    case DROT_OK: return "ok";
+    case DROT_MAX_ITERS: return "maximum number of iterations reached before the tolerance";
+    case DROT_ERR_INVALID_ARG: return "invalid argument";
+    case DROT_ERR_ALLOC: return "device or pinned-host allocation failed";
+    case DROT_ERR_HIP: return "HIP runtime error";
+    case DROT_ERR_NOT_INITIALIZED: return "no solve has been run on this handle";
+    default: return "unknown code";
+  }
+}
+
+int drot_create(drot_handle* out, int max_m, int max_n) {
+  if (!out || max_m < 1 || max_n < 1) return DROT_ERR_INVALID_ARG;
+  *out = nullptr;
+  drot_handle h = new (std::nothrow) drot_handle_s();
+  if (!h) return DROT_ERR_ALLOC;
+  if (hipGetDevice(&h->device) != hipSuccess) {
+    delete h;
+    return DROT_ERR_HIP;
+  }
+  h->max_m = max_m;
+  h->max_n = max_n;
+  const size_t nseg = (size_t)ceil_div(max_n, kSegCols);
+  const size_t ntr = (size_t)ceil_div(max_m, kMinTileRows);
+  const size_t nb = (size_t)ceil_div(max_m, 64) + (size_t)ceil_div(max_n, 64);
+  int rc = DROT_OK;
+  auto take = [&](int r) { if (rc == DROT_OK) rc = r; };
+  take(dev_alloc(&h->phi, (size_t)max_m));
+  take(dev_alloc(&h->varphi, (size_t)max_n + 4));
+  take(dev_alloc(&h->a, (size_t)max_m));
+  take(dev_alloc(&h->b, (size_t)max_n));
+  take(dev_alloc(&h->theta, 2));
+  take(dev_alloc(&h->sum_p, 1));
+  take(dev_alloc(&h->resid_part, nb));
+  take(dev_alloc(&h->rowpart, nseg * (size_t)max_m));
+  take(dev_alloc(&h->colpart, ntr * (size_t)max_n));
+  take(dev_alloc(&h->tilesum, nseg * ntr));
+  take(dev_alloc(&h->gap_part, nseg * ntr * 3));
+  take(dev_alloc(&h->done, 1));
+  take(dev_alloc(&h->status, 1));
+  if (rc == DROT_OK && hipHostMalloc(reinterpret_cast<void**>(&h->host_status), 2 * sizeof(DeviceStatus)) != hipSuccess) {
+    h->host_status = nullptr;
+    rc = DROT_ERR_ALLOC;
+  }
+  for (auto& e : h->ev)
+    if (rc == DROT_OK && hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+      e = nullptr;
+      rc = DROT_ERR_HIP;
+    }
+  if (rc != DROT_OK) {
+    free_all(h);
+    delete h;
+    (void)hipGetLastError();
+    return rc;
+  }
+  *out = h;
+  return DROT_OK;
+}
+
+int drot_destroy(drot_handle h) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  free_all(h);
+  delete h;
+  return DROT_OK;
+}
+
+int drot_set_check_every(drot_handle h, int check_every) {
+  if (!h || check_every < 1) return DROT_ERR_INVALID_ARG;
+  h->check_every = check_every;
+  return DROT_OK;
+}
+
+int drot_set_compute_gap(drot_handle h, int enable) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  h->compute_gap = enable ? 1 : 0;
+  return DROT_OK;
+}
+
+int drot_set_continue(drot_handle h, int enable) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  h->continue_next = enable ? 1 : 0;
+  return DROT_OK;
+}
+
+int drot_set_profile(drot_handle h, int enable) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  if (enable)
+    for (auto& e : h->prof_ev)
+      if (!e && hipEventCreate(&e) != hipSuccess) {
+        e = nullptr;
+        return DROT_ERR_HIP;
+      }
+  h->profile = enable ? 1 : 0;
+  return DROT_OK;
+}
+
+int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed) {
+  if (!h || !sweep_ms_avg || !sweeps_timed) return DROT_ERR_INVALID_ARG;
+  if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
+  *sweeps_timed = h->prof_count;
+  *sweep_ms_avg = h->prof_count > 0 ? h->prof_sweep_ms / h->prof_count : 0.0;
+  return DROT_OK;
+}
+
+int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
+               drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
+               float* X_out, void* stream_v) {
+  if (!h || !C || !p || !q || !X_out) return DROT_ERR_INVALID_ARG;
+  if (m < 1 || n < 1 || m > h->max_m || n > h->max_n || max_iters < 0) return DROT_ERR_INVALID_ARG;
+  if (reg_kind != DROT_REG_NONE && reg_kind != DROT_REG_QUADRATIC && reg_kind != DROT_REG_GROUP_LASSO)
+    return DROT_ERR_INVALID_ARG;
+  if (!(tol == tol) || !(stepsize == stepsize)) return DROT_ERR_INVALID_ARG;  // NaN
+  float lambda = 0.f, mu = 0.f;
+  int num_classes = 0;
+  const int* row_class = nullptr;
+  if (reg_kind != DROT_REG_NONE) {
+    if (!reg_params) return DROT_ERR_INVALID_ARG;
+    lambda = reg_params->lambda;
+    if (!(lambda >= 0.f)) return DROT_ERR_INVALID_ARG;
+    if (reg_kind == DROT_REG_GROUP_LASSO) {
+      mu = reg_params->mu;
+      num_classes = reg_params->num_classes;
+      row_class = reg_params->row_class;
+      if (!(mu >= 0.f) || num_classes < 1 || !row_class) return DROT_ERR_INVALID_ARG;
+    }
+  }
+  int cur_dev = -1;
+  DROT_HIP(hipGetDevice(&cur_dev));
+  if (cur_dev != h->device) return DROT_ERR_INVALID_ARG;  // the workspace lives on the creating device
+  const bool resume = h->continue_next != 0;
+  if (resume && (!h->solved || m != h->last_m || n != h->last_n)) return DROT_ERR_INVALID_ARG;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+  const float rho = stepsize > 0.f ? stepsize : 2.0f / (float)(m + n);
+  // 1/(1 + rho*lambda) evaluated in fp64 from the fp32 inputs, rounded once
+  const float qscale = (float)(1.0 / (1.0 + (double)rho * (double)lambda));
+
+  const int tmw = choose_tmw(m, n);
+  const int nseg = ceil_div(n, kSegCols);
+  const int ntr = ceil_div(m, kWavesPerBlock * tmw);
+  const int ntiles = nseg * ntr;
+  const int nbm = ceil_div(m, 64), nbn = ceil_div(n, 64);
+
+  size_t ngroups = 0;
+  if (reg_kind == DROT_REG_GROUP_LASSO) {
+    ngroups = (size_t)num_classes * (size_t)n;
+    if (h->gbuf_len < 2 * ngroups) {
+      DROT_HIP(hipStreamSynchronize(stream));
+      (void)hipFree(h->gbuf);
+      h->gbuf = nullptr;
+      h->gbuf_len = 0;
+      if (dev_alloc(&h->gbuf, 2 * ngroups) != DROT_OK) return DROT_ERR_ALLOC;
+      h->gbuf_len = 2 * ngroups;
+    }
+  }
+
+  VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->sum_p, h->resid_part, h->done, h->status};
+  const long long k_base = resume ? h->iters_done : 0;
+  if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
+  else hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
+
+  SweepArgs S{X_out, C, h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->done,
+              m, n, tmw, nseg, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
+  GroupArgs G{S, row_class, h->gbuf, rho * mu};
+  VecArgs VA{V, h->rowpart, h->colpart, h->tilesum, p, q, m, n, nseg, ntr, ntiles, nbm, 0};
+  const dim3 grid(nseg, ntr), block(kBlock);
+
+  if (max_iters == 0 && !resume)
+    hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, X_out, (size_t)m * n, 0.f, (const int*)nullptr);
+
+  const bool checking = tol > 0.f;
+  int k = 0, slot = 0, checks = 0;
+  bool converged = false;
+  while (k < max_iters && !converged) {
+    const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
+    for (int c = 0; c < chunk; ++c, ++k) {
+      const bool first = (k_base + k == 0);
+      const bool timed = h->profile && k < kMaxProfiled;
+      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
+      if (reg_kind == DROT_REG_GROUP_LASSO) {
+        hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((ngroups + 255) / 256), 4)), dim3(256), 0, stream,
+                           h->gbuf, ngroups, 0.f, (const int*)h->done);
+        if (first) {
+          hipLaunchKernelGGL(gl_norm_kernel<true>, grid, block, 0, stream, G);
+          hipLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, G);
+        } else {
+          hipLaunchKernelGGL(gl_norm_kernel<false>, grid, block, 0, stream, G);
+          hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
+        }
+      } else if (first) {
+        hipLaunchKernelGGL((sweep_kernel<true, 4>), grid, block, 0, stream, S);
+      } else {
+        hipLaunchKernelGGL((sweep_kernel<false, 4>), grid, block, 0, stream, S);
+      }
+      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k + 1], stream));
+      VA.par = (int)((k_base + k) & 1);
+      hipLaunchKernelGGL(vec_kernel, dim3(nbm + nbn), block, 0, stream, VA);
+    }
+    if (checking) {
+      // the test runs on the device; the host reads it one chunk late so the queue never drains
+      hipLaunchKernelGGL(status_kernel, dim3(1), block, 0, stream, V, nbm, nbn, k, (double)tol);
+      DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
+      DROT_HIP(hipEventRecord(h->ev[slot], stream));
+      if (checks > 0) {
+        DROT_HIP(hipEventSynchronize(h->ev[slot ^ 1]));
+        if (h->host_status[slot ^ 1].converged) converged = true;
+      }
+      slot ^= 1;
+      ++checks;
+    }
+  }
+  // final state: residuals of the returned iterate (no-op if the stop flag is already up)
+  if (k > 0)
+    hipLaunchKernelGGL(status_kernel, dim3(1), block, 0, stream, V, nbm, nbn, k, checking ? (double)tol : 0.0);
+  if (h->compute_gap) {
+    float* gx = h->gbuf;
+    float* gw = h->gbuf ? h->gbuf + ngroups : nullptr;
+    if (reg_kind == DROT_REG_GROUP_LASSO)
+      hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((2 * ngroups + 255) / 256), 4)), dim3(256), 0, stream,
+                         h->gbuf, 2 * ngroups, 0.f, (const int*)nullptr);
+    GapArgs GA{X_out, C, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, tmw, nseg, rho};
+    hipLaunchKernelGGL(gap_kernel, grid, block, 0, stream, GA);
+    hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(1024), 0, stream, V, (const float*)h->gap_part, ntiles,
+                       (const float*)gx, (const float*)gw, ngroups, p, q, m, n, (double)rho, (int)reg_kind,
+                       (double)lambda, (double)mu);
+  }
+  DROT_HIP(hipMemcpyAsync(&h->host_status[0], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
+  DROT_HIP(hipStreamSynchronize(stream));
+  DROT_HIP(hipGetLastError());
+
+  const DeviceStatus& st = h->host_status[0];
+  h->prof_count = 0;
+  h->prof_sweep_ms = 0.0;
+  if (h->profile) {
+    const int timed = k < kMaxProfiled ? k : kMaxProfiled;
+    for (int e = 0; e < timed; ++e) {
+      float ms = 0.f;
+      DROT_HIP(hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]));
+      h->prof_sweep_ms += (double)ms;
+    }
+    h->prof_count = timed;
+  }
+  h->iters_done = k_base + (max_iters == 0 ? 0 : st.iters);
+  h->info.iters = max_iters == 0 ? 0 : st.iters;
+  h->info.converged = st.converged;
+  // with zero iterations X = 0 and no sums were formed: report the residuals as not evaluated
+  h->info.r_row = max_iters == 0 ? INFINITY : (float)std::sqrt(st.r2);
+  h->info.r_col = max_iters == 0 ? INFINITY : (float)std::sqrt(st.s2);
+  h->info.objective = h->compute_gap ? st.cost + st.h : 0.0;
+  h->info.gap = h->compute_gap ? st.gap : 0.0;
+  h->info.dual_res = h->compute_gap ? st.dual_res : 0.0;
+  h->solved = true;
+  h->last_m = m;
+  h->last_n = n;
+  if (checking && !st.converged) return DROT_MAX_ITERS;
+  return DROT_OK;
+}
+
+int drot_get_info(drot_handle h, drot_info* out) {
+  if (!h || !out) return DROT_ERR_INVALID_ARG;
+  if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
+  *out = h->info;
+  return DROT_OK;
+}
+
+int drot_get_duals(drot_handle h, float* phi_out, float* varphi_out) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
+  if (phi_out)
+    DROT_HIP(hipMemcpy(phi_out, h->phi, sizeof(float) * (size_t)h->last_m, hipMemcpyDeviceToDevice));
+  if (varphi_out)
+    DROT_HIP(hipMemcpy(varphi_out, h->varphi, sizeof(float) * (size_t)h->last_n, hipMemcpyDeviceToDevice));
+  return DROT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,214 @@
+"""GPU parity tests: the HIP solver (through the C ABI) against the fp64 CPU oracle.
+
+Run on the MI355X machine with `python -u -m pytest tests -m gpu -x -v --timeout 600 --timeout-method thread`.
+Each case prints what it is about to run (and flushes) before touching the GPU.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import drot_inputs
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def drot():
+    import paper_2305_18483_amd as drot_mod
+
+    drot_mod.load_library()  # raises if the HIP library is missing: no fallback
+    assert torch.cuda.is_available()
+    return drot_mod
+
+
+def _run_case(drot, oracle, P, K, label, solver=None, **kw):
+    _say(f"{label}: {P.name} m={P.m} n={P.n} reg={P.reg_kind} K={K}")
+    solver = solver or drot.Solver(P.m, P.n)
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, K, **kw)
+    assert gres.code == drot.DROT_OK and gres.iters == K
+    ores = pu.oracle_solve(oracle, P, K, stepsize=kw.get("stepsize") or None)
+    ratio = pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, stepsize=kw.get("stepsize") or None, label=label)
+    _say(f"{label}: plan error / scale = {ratio:.2e}")
+    return gres, Xg, ores
+
+
+# ---------------------------------------------------------------------------------------------
+# the five benchmark configurations
+# ---------------------------------------------------------------------------------------------
+def test_cfg1_unregularized_100_fixed_2000(drot, oracle):
+    _run_case(drot, oracle, drot_inputs.config(1), 2000, "cfg1")
+
+
+def test_cfg2_quadratic_1000_fixed_3000(drot, oracle):
+    _run_case(drot, oracle, drot_inputs.config(2), 3000, "cfg2")
+
+
+def test_cfg2_quadratic_1000_to_tolerance(drot, oracle):
+    # the configuration iterates to a marginal residual of 1e-5; the oracle is run to 1e-4 (a few
+    # thousand iterations) and must stop at the same check; the GPU run to 1e-5 is then verified by
+    # fp64 properties of its result (feasibility, KKT form, gap)
+    P = drot_inputs.config(2)
+    solver = drot.Solver(P.m, P.n, check_every=100)
+    _say("cfg2 to 1e-4 against the oracle")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 200000, tol=1e-4)
+    ores = pu.oracle_solve(oracle, P, 200000, tol=1e-4, check_every=100)
+    assert gres.code == drot.DROT_OK and gres.converged
+    # a borderline check may flip with fp32 rounding: allow one check interval
+    assert abs(gres.iters - ores.iters) <= 100, (gres.iters, ores.iters)
+    if gres.iters == ores.iters:
+        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="cfg2 tol 1e-4")
+    _say(f"cfg2 to 1e-5 (GPU iters to 1e-4: {gres.iters})")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 400000, tol=1e-5)
+    assert gres.code == drot.DROT_OK and gres.converged and gres.iters % 100 == 0
+    r, s = pu.residuals(P, Xg)
+    assert max(r, s) <= 1e-5 + 1e-7
+    t = pu.fp64_terms(oracle, P, Xg, phig, varphig)
+    rho = float(P.rho)
+    kkt = np.maximum((phig[:, None].astype(np.float64) + varphig[None, :]) / rho - P.C, 0.0) / np.float32(P.lam)
+    # at a fixed point X = [u (+) v - C]_+ / lambda; away from it the two differ by O(residual)
+    assert np.abs(kkt - Xg).max() <= 2e-2 * np.abs(Xg).max()
+    assert abs(t.gap) <= 1e-2 * abs(t.objective)
+    _say(f"cfg2 to 1e-5: iters={gres.iters} gap={t.gap:.3e} obj={t.objective:.6f}")
+
+
+def test_cfg3_unregularized_10000_reduced_K(drot, oracle):
+    # full size, the launch configuration the benchmark times; K bounded by the oracle's speed
+    _run_case(drot, oracle, drot_inputs.config(3), 30, "cfg3")
+
+
+def test_cfg4_quadratic_20000_reduced_K(drot, oracle):
+    _run_case(drot, oracle, drot_inputs.config(4), 12, "cfg4")
+
+
+def test_cfg5_group_lasso_5000_reduced_K(drot, oracle):
+    _run_case(drot, oracle, drot_inputs.config(5), 150, "cfg5")
+
+
+def test_cfg5_recipe_1000_fixed_1000(drot, oracle):
+    _run_case(drot, oracle, drot_inputs.config(5, size=1000), 1000, "cfg5 small")
+
+
+# ---------------------------------------------------------------------------------------------
+# ragged shapes, several tiles, tails; all three regularizers
+# ---------------------------------------------------------------------------------------------
+SHAPES = [(1, 1), (1, 700), (700, 1), (5, 3), (64, 256), (65, 257), (333, 517), (257, 1023), (1300, 900),
+          (2050, 1030)]
+
+
+@pytest.mark.parametrize("m,n", SHAPES)
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_ragged_shapes(drot, oracle, m, n, kind):
+    P = drot_inputs.random_problem(m, n, seed=1000 + 3 * m + n, reg_kind=kind, lam=0.5 if kind else 0.0,
+                                   mu=0.05 if kind == 2 else 0.0, num_classes=min(7, m))
+    _run_case(drot, oracle, P, 150, f"ragged {m}x{n} kind={kind}")
+
+
+def test_group_lasso_unsorted_labels(drot, oracle):
+    P = drot_inputs.random_problem(300, 413, seed=77, reg_kind=2, lam=0.1, mu=0.08, num_classes=5,
+                                   sorted_classes=False)
+    assert (np.diff(P.row_class) < 0).any()
+    _run_case(drot, oracle, P, 300, "group lasso, unsorted labels")
+
+
+def test_group_lasso_without_quadratic_term(drot, oracle):
+    P = drot_inputs.random_problem(200, 320, seed=78, reg_kind=2, lam=0.0, mu=0.05, num_classes=4)
+    _run_case(drot, oracle, P, 300, "group lasso, lambda=0")
+
+
+def test_explicit_stepsize(drot, oracle):
+    P = drot_inputs.random_problem(120, 90, seed=5, reg_kind=1, lam=0.3)
+    _run_case(drot, oracle, P, 400, "explicit stepsize", stepsize=0.02)
+
+
+# ---------------------------------------------------------------------------------------------
+# stopping rule, edge cases, reuse, streams, determinism, error paths
+# ---------------------------------------------------------------------------------------------
+def test_stops_at_first_passing_check(drot, oracle):
+    P = drot_inputs.random_problem(90, 110, seed=9)
+    solver = drot.Solver(P.m, P.n, check_every=10)
+    _say("stopping rule")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 50000, tol=1e-4)
+    ores = pu.oracle_solve(oracle, P, 50000, tol=1e-4, check_every=10)
+    assert gres.converged and gres.code == drot.DROT_OK
+    assert abs(gres.iters - ores.iters) <= 10
+    if gres.iters == ores.iters:
+        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="stopping")
+    r, s = pu.residuals(P, Xg)
+    assert max(r, s) <= 1e-4 + 1e-7
+    # out of iterations before the tolerance: a status, not an error
+    gres2, _, _, _ = pu.gpu_solve(solver, P, 20, tol=1e-9)
+    assert gres2.code == drot.DROT_MAX_ITERS and not gres2.converged and gres2.iters == 20
+
+
+def test_zero_iterations_returns_x0(drot):
+    P = drot_inputs.random_problem(33, 47, seed=3)
+    solver = drot.Solver(P.m, P.n)
+    X = torch.full((P.m, P.n), 7.0, device="cuda:0")
+    gres, Xg, _, _ = pu.gpu_solve(solver, P, 0, X_out=X)
+    assert gres.iters == 0 and not Xg.any()
+
+
+def test_handle_reuse_across_sizes_and_bitwise_determinism(drot, oracle):
+    solver = drot.Solver(600, 800)
+    big = drot_inputs.random_problem(600, 800, seed=11, reg_kind=1, lam=0.2)
+    small = drot_inputs.random_problem(130, 77, seed=12)
+    _say("handle reuse")
+    _, Xa, _, _ = pu.gpu_solve(solver, big, 100)
+    _run_case(drot, oracle, small, 100, "reuse small after big", solver=solver)
+    _, Xb, _, _ = pu.gpu_solve(solver, big, 100)
+    assert np.array_equal(Xa, Xb)  # fixed reduction order: bit-identical reruns
+    with pytest.raises(drot.DrotError):
+        pu.gpu_solve(solver, drot_inputs.random_problem(601, 10, seed=1), 1)  # larger than the handle
+
+
+def test_runs_on_a_side_stream(drot, oracle):
+    P = drot_inputs.random_problem(210, 190, seed=21, reg_kind=1, lam=0.4)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        _run_case(drot, oracle, P, 120, "side stream", stream=s)
+
+
+def test_invalid_arguments_are_rejected(drot):
+    P = drot_inputs.random_problem(10, 12, seed=2)
+    solver = drot.Solver(P.m, P.n)
+    C, p, q, _ = pu.to_dev(P)
+    with pytest.raises(drot.DrotError):
+        solver.solve(C, p, q, max_iters=-1)
+    with pytest.raises(drot.DrotError):
+        solver.solve(C, p, q, reg_kind=7)
+    with pytest.raises(drot.DrotError):
+        solver.solve(C, p, q, reg_kind=drot.DROT_REG_QUADRATIC, lam=-1.0)
+    with pytest.raises(drot.DrotError):
+        solver.solve(C, p, q, reg_kind=drot.DROT_REG_GROUP_LASSO, mu=0.1, num_classes=2)  # no labels
+    with pytest.raises(drot.DrotError):
+        solver.set_check_every(0)
+    with pytest.raises(drot.DrotError):
+        drot.Solver(0, 5)
+
+
+def test_continuation_is_bit_identical_to_one_long_solve(drot):
+    P = drot_inputs.random_problem(310, 530, seed=31, reg_kind=1, lam=0.2)
+    solver = drot.Solver(P.m, P.n)
+    _say("continuation")
+    _, X_long, phi_long, _ = pu.gpu_solve(solver, P, 90)
+    X = torch.empty((P.m, P.n), device="cuda:0")
+    pu.gpu_solve(solver, P, 37, X_out=X)
+    solver.set_continue(True)
+    res, X_two, phi_two, _ = pu.gpu_solve(solver, P, 53, X_out=X)
+    solver.set_continue(False)
+    assert res.iters == 53
+    assert np.array_equal(X_long, X_two) and np.array_equal(phi_long, phi_two)
+    # profile mode reports a positive mean sweep time and does not change the result
+    solver.set_profile(True)
+    _, X_prof, _, _ = pu.gpu_solve(solver, P, 90)
+    ms, cnt = solver.profile()
+    solver.set_profile(False)
+    assert cnt == 90 and ms > 0.0 and np.array_equal(X_prof, X_long)

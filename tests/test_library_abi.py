@@ -1,0 +1,75 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what include/drot.h declares, and its
+argument validation answers without a GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2305_18483_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2305_18483_amd import build
+
+        build.build()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "drot.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(drot_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2305_18483_amd import binding
+
+    declared = _declared_functions()
+    assert declared, "no declarations found in include/drot.h"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in drot.h but not exported by libdrot.so"
+    assert sorted(binding.EXPORTED_SYMBOLS) == declared
+
+
+def test_argument_validation_without_a_gpu(lib):
+    from paper_2305_18483_amd import binding
+
+    h = ctypes.c_void_p()
+    assert lib.drot_create(None, 4, 4) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_create(ctypes.byref(h), 0, 4) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_create(ctypes.byref(h), 4, -1) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_destroy(None) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_set_check_every(None, 10) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_get_info(None, None) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_solve(None, None, None, None, 1, 1, 0.0, 0, None, 1, 0.0, None, None) == binding.DROT_ERR_INVALID_ARG
+    for code in (0, 1, -1, -2, -3, -4, 99):
+        assert isinstance(binding.strerror(code), str) and binding.strerror(code)
+
+
+def test_struct_layouts_match_the_header():
+    from paper_2305_18483_amd import binding
+
+    # drot_info: int, int, float, float, double x3 ; drot_reg_params: float, float, int, pointer
+    assert ctypes.sizeof(binding.drot_info) == 40
+    assert binding.drot_info.objective.offset == 16
+    assert ctypes.sizeof(binding.drot_reg_params) == 24
+    assert binding.drot_reg_params.row_class.offset == 16
+
+
+def test_input_generators_are_seeded_and_normalised():
+    import numpy as np
+
+    import drot_inputs
+
+    a, b = drot_inputs.config(1), drot_inputs.config(1)
+    assert np.array_equal(a.C, b.C) and a.C.dtype == np.float32 and a.C.max() == 1.0 and a.C.min() >= 0.0
+    assert abs(float(a.p.sum()) - 1.0) < 1e-5 and abs(float(a.q.sum()) - 1.0) < 1e-5
+    g = drot_inputs.config(5, size=200)
+    assert g.row_class.shape == (200,) and g.num_classes == 10 and (np.diff(g.row_class) >= 0).all()
+    r = drot_inputs.random_problem(17, 9, seed=4, reg_kind=2, num_classes=3, sorted_classes=False)
+    assert r.C.shape == (17, 9) and r.row_class.max() < 3
