@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the Douglas-Rachford OT solver on one MI355X.
+
+A step is one iteration of the method: the sweep over the m x n plan (prox of nonnegativity, cost
+and regularizer fused with the row/column sums), the O(m+n) vector update, and the periodic
+residual test where one is scheduled.  Default workload: the quadratically regularized
+20000 x 20000 configuration (C and X 1.6 GB each, resident in HBM before timing starts).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--size N]
+
+prints one JSON line: iterations/s, the HBM roofline of the sweep kernel (12 bytes per element per
+iteration, kernel time from HIP events recorded on the launch stream), the time to a marginal
+residual of 1e-4, and the CPU oracle timed on a bounded sample on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 12.0}  # read X, read C, write X (algorithmic, every regularizer)
+
+# HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
+# copy kernel of known size (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: 20000 x 20000)")
+    ap.add_argument("--size", type=int, default=0, help="override m = n (same recipe)")
+    ap.add_argument("--tol", type=float, default=1e-4, help="residual of the time-to-tolerance leg")
+    ap.add_argument("--tol-max-iters", type=int, default=40000)
+    ap.add_argument("--check-every", type=int, default=100)
+    ap.add_argument("--skip-tol", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0: sized for ~20 s)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import drot_inputs
+    import paper_2305_18483_amd as drot
+
+    drot.load_library()  # raises if the HIP library has not been built: there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    P = drot_inputs.config(args.config, size=args.size or None)
+    m, n = P.m, P.n
+    log(f"workload {P.name}: m={m} n={n} reg_kind={P.reg_kind} lambda={P.lam} mu={P.mu} (generated in {time.time() - t0:.1f} s)")
+    C = torch.from_numpy(P.C).to(dev)
+    p = torch.from_numpy(P.p).to(dev)
+    q = torch.from_numpy(P.q).to(dev)
+    rc = None if P.row_class is None else torch.from_numpy(P.row_class).to(dev)
+    X = torch.empty_like(C)
+    kw = dict(reg_kind=P.reg_kind, lam=P.lam, mu=P.mu, row_class=rc, num_classes=P.num_classes, X_out=X)
+    solver = drot.Solver(m, n, check_every=args.check_every, compute_gap=False)
+    torch.cuda.synchronize()
+
+    # ---- warm-up (cold start), then exactly K steady-state iterations continuing from it --------------
+    K, W = args.steps, args.warmup
+    solver.solve(C, p, q, max_iters=W, **kw)
+    solver.set_continue(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = solver.solve(C, p, q, max_iters=K, **kw)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert res.iters == K
+    ms_per_step = elapsed / K * 1e3
+    log(f"{K} iterations in {elapsed:.3f} s -> {K / elapsed:.1f} it/s, {ms_per_step:.4f} ms/iteration")
+
+    # ---- sweep kernel duration from HIP events on the launch stream (profile mode, separate solve) ----
+    solver.set_profile(True)
+    solver.solve(C, p, q, max_iters=min(K, 256), **kw)
+    sweep_ms, sweeps = solver.profile()
+    solver.set_profile(False)
+    solver.set_continue(False)
+    algo_bytes = BYTES_PER_ELEMENT[P.reg_kind] * m * n
+    achieved = algo_bytes / (sweep_ms * 1e-3) / 1e9 if sweep_ms > 0 else 0.0
+    log(f"sweep: {sweep_ms:.4f} ms mean over {sweeps} launches -> {achieved:.0f} GB/s algorithmic "
+        f"({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(P.name),
+                "kernel": "gl_norm+gl_apply" if P.reg_kind == 2 else "sweep_kernel", "kernel_ms": round(sweep_ms, 5),
+                "algorithmic_bytes": algo_bytes}
+
+    # ---- time to tolerance (cold start, residual test every check_every iterations) -------------------
+    tol_leg = None
+    if not args.skip_tol:
+        solver.set_compute_gap(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r = solver.solve(C, p, q, max_iters=args.tol_max_iters, tol=args.tol, **kw)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        tol_leg = {"tol": args.tol, "seconds": round(dt, 4), "iters": r.iters, "converged": bool(r.converged),
+                   "r_row": r.r_row, "r_col": r.r_col, "objective": r.objective, "gap": r.gap,
+                   "dual_res": r.dual_res, "check_every": args.check_every}
+        log(f"time to {args.tol:g}: {dt:.3f} s, {r.iters} iterations, converged={r.converged}, "
+            f"residuals {r.r_row:.2e}/{r.r_col:.2e}, objective {r.objective:.6f}, gap {r.gap:.3e}")
+        solver.set_compute_gap(False)
+
+    # ---- CPU oracle on the host cores of this machine, bounded sample of the same workload ---------------
+    cpu = None
+    if not args.skip_cpu:
+        from oracle import drot_oracle
+
+        drot_oracle.build()
+        del X
+        torch.cuda.empty_cache()
+        iters = args.cpu_iters or max(2, min(200, int(20.0 / (2.5e-9 * m * n + 1e-6))))
+        t0 = time.perf_counter()
+        drot_oracle.solve(P.C, P.p, P.q, rho=float(P.rho), reg_kind=P.reg_kind, lam=float(np.float32(P.lam)),
+                          mu=float(np.float32(P.mu)), row_class=P.row_class, num_classes=P.num_classes,
+                          max_iters=iters)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(iters / dt, 4), "unit": "iterations/s", "cores": drot_oracle.num_threads(),
+               "kind": "oracle", "sample": f"{iters} iterations of the same {m}x{n} problem (fp64, explicit X, Y, Z)",
+               "seconds": round(dt, 2)}
+        log(f"oracle: {iters} iterations in {dt:.1f} s on {cpu['cores']} threads -> {cpu['value']} it/s")
+
+    out = {
+        "metric": "DR iterations/sec at m=n=20000 fp32" if (args.config == 4 and not args.size)
+        else f"DR iterations/sec at {m}x{n} fp32",
+        "value": round(K / elapsed, 2), "unit": "iterations/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": P.name, "m": m, "n": n, "reg_kind": int(P.reg_kind), "lambda": P.lam, "mu": P.mu,
+                   "stepsize": float(P.rho), "check_every": args.check_every},
+        "hbm_gbs_whole_iteration": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline, "time_to_tol": tol_leg, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

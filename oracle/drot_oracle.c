@@ -24,10 +24,22 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORACLE_REG_NONE 0
 #define ORACLE_REG_QUADRATIC 1
 #define ORACLE_REG_GROUP_LASSO 2
+
+/* Number of threads the parallel loops below use (for reporting the CPU baseline). */
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
 
 /* Row sums rs[i] = sum_j A_ij and column sums cs[j] = sum_i A_ij, each a left-to-right sum. */
 void oracle_row_col_sums(const double* A, int m, int n, double* rs, double* cs) {

@@ -61,6 +61,8 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_double, ctypes.c_double,
             _c_int_p, ctypes.c_int, _c_double_p]
         lib.oracle_objective_gap.restype = None
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -75,6 +77,11 @@ def _ip(a: Optional[np.ndarray]):
 
 def _f64(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def num_threads() -> int:
+    """Threads the oracle's parallel loops use (OpenMP's maximum for this process)."""
+    return int(_load().oracle_num_threads())
 
 
 def default_stepsize(m: int, n: int) -> float:

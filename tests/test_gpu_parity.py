@@ -54,7 +54,7 @@ def test_cfg2_quadratic_1000_fixed_3000(drot, oracle):
 def test_cfg2_quadratic_1000_to_tolerance(drot, oracle):
     # the configuration iterates to a marginal residual of 1e-5; the oracle is run to 1e-4 (a few
     # thousand iterations) and must stop at the same check; the GPU run to 1e-5 is then verified by
-    # fp64 properties of its result (feasibility, KKT form, gap)
+    # fp64 properties of its result (feasibility, gap)
     P = drot_inputs.config(2)
     solver = drot.Solver(P.m, P.n, check_every=100)
     _say("cfg2 to 1e-4 against the oracle")
@@ -71,11 +71,11 @@ def test_cfg2_quadratic_1000_to_tolerance(drot, oracle):
     r, s = pu.residuals(P, Xg)
     assert max(r, s) <= 1e-5 + 1e-7
     t = pu.fp64_terms(oracle, P, Xg, phig, varphig)
-    rho = float(P.rho)
-    kkt = np.maximum((phig[:, None].astype(np.float64) + varphig[None, :]) / rho - P.C, 0.0) / np.float32(P.lam)
-    # at a fixed point X = [u (+) v - C]_+ / lambda; away from it the two differ by O(residual)
-    assert np.abs(kkt - Xg).max() <= 2e-2 * np.abs(Xg).max()
+    # (the KKT form X = [u (+) v - C]_+ / lambda divides by rho*lambda = 1e-5 and only holds at the
+    # exact fixed point, so it is pinned on the oracle at convergence, not here)
+    _say(f"cfg2 to 1e-5: gap={t.gap:.3e} obj={t.objective:.6f} reported gap={gres.gap:.3e}")
     assert abs(t.gap) <= 1e-2 * abs(t.objective)
+    assert abs(gres.gap - t.gap) <= 2e-5 * max(abs(t.cost), abs(t.dual_linear), abs(t.h_conj))
     _say(f"cfg2 to 1e-5: iters={gres.iters} gap={t.gap:.3e} obj={t.objective:.6f}")
 
 
