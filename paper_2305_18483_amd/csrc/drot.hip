@@ -5,15 +5,18 @@
 // projection needs) followed by the O(m+n) recursion of eq. (6).  Y is never formed (Section
 // 2.1: "Y_k can be eliminated").  The sweep is HBM bound (12 bytes per element: read X, read C,
 // write X; about 8 flops), so there is no MFMA here: the design is coalesced 128-bit row-major
-// accesses, many loads in flight per lane, DPP wave reductions for the row sums, register column
-// partials folded through LDS, and a deterministic two-stage reduction instead of atomics.
+// accesses, DPP wave reductions for the row sums, register column partials folded through LDS,
+// and a deterministic two-stage reduction instead of atomics.  Measured on MI355X, this kind of
+// read-modify-write stream runs fastest when every wave issues one batch of loads, stores and
+// retires (no loop: a wave that loops waits on its own store acknowledgements, loads and stores
+// sharing one in-order counter) and when the loads and stores are marked non-temporal; so the
+// sweep is loop-free: a wave owns 2 rows x 256 columns, a workgroup 16 such waves (32 rows).
 //
 // Data layout in HBM
 //   X, C        m x n fp32 row-major, pitch n, caller-owned
-//   phi/varphi  fp32, what the sweep reads;  a, b, theta: fp64 running sums of eq. (6)
+//   phi/varphi  fp32, what the sweep reads;  a, b, theta, r, s: fp64 vectors of eq. (6)
 //   rowpart     [nseg][m]  fp32: row sums of every 256-column segment
-//   colpart     [ntr][n]   fp32: column sums of every row tile
-//   tilesum     [ntr*nseg] fp32: grand total per tile (gives eta without a second pass)
+//   colpart     [ntr][n]   fp32: column sums of every 32-row tile
 //
 // This file is the whole product path: kernels, host loop and the C ABI of include/drot.h.
 #include <hip/hip_runtime.h>
@@ -31,10 +34,13 @@ namespace {
 typedef float f4v __attribute__((ext_vector_type(4)));
 typedef f4v f4u __attribute__((aligned(4)));  // 128-bit access that only needs 4-byte alignment
 
-constexpr int kBlock = 256;          // threads per workgroup in the sweep kernels (4 waves)
+constexpr int kBlock = 256;          // threads per workgroup in the group-lasso and gap kernels (4 waves)
 constexpr int kWavesPerBlock = 4;
 constexpr int kSegCols = 256;        // columns per tile: 64 lanes x 4
-constexpr int kMaxWaveRows = 64;     // rows per wave per tile (<= 64: one lane keeps one row sum)
+constexpr int kTileRows = 32;        // rows per tile, the same in every matrix kernel
+constexpr int kSweepWaves = 16;      // sweep: waves per workgroup, stacked along the rows
+constexpr int kSweepRows = kTileRows / kSweepWaves;   // sweep: rows per wave (one batch, no loop)
+constexpr int kLoopRows = kTileRows / kWavesPerBlock; // looping kernels: rows per wave
 constexpr float kMaskedOut = -1.0e30f;  // added to columns past n so that [.]_+ yields exactly 0
 
 // ------------------------------------------------------------------------------------------
@@ -127,103 +133,108 @@ struct SweepArgs {
   const float* varphi;
   float* rowpart;
   float* colpart;
-  float* tilesum;
   const int* done;
-  int m, n, tmw, nseg;
+  int m, n;
   float rho, scale;
 };
 
 // ------------------------------------------------------------------------------------------
 // S1-S4: the sweep for h = 0 and h = (lambda/2)||X||^2 (a constant scale, Section 3).
-// grid = (nseg, ntr); a workgroup owns 4*tmw rows x 256 columns; each wave owns tmw whole
-// row segments of 1 KiB, U rows in flight at a time.  EDGE marks the last column segment when
-// n is not a multiple of 256: only there do lanes check how many of their 4 columns exist.
+// grid = (nseg, ntr); a workgroup owns 32 rows x 256 columns; each of its 16 waves loads its
+// 2 row segments of 1 KiB of X and C, updates, stores and is done.  EDGE marks the last column
+// segment when n is not a multiple of 256: only there do lanes check how many of their 4
+// columns exist.  NT marks the accesses non-temporal (used when X and C cannot stay in cache).
 // ------------------------------------------------------------------------------------------
-template <bool EDGE>
+template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v ld4(const float* __restrict__ ptr, int nvalid) {
-  if (!EDGE) return *reinterpret_cast<const f4u*>(ptr);
-  return load4(ptr, nvalid);
+  if (EDGE) return load4(ptr, nvalid);
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const f4u*>(ptr));
+  return *reinterpret_cast<const f4u*>(ptr);
 }
-template <bool EDGE>
+template <bool EDGE, bool NT>
 __device__ __forceinline__ void st4(float* __restrict__ ptr, f4v v, int nvalid) {
-  if (!EDGE) *reinterpret_cast<f4u*>(ptr) = v;
-  else store4(ptr, v, nvalid);
+  if (EDGE) store4(ptr, v, nvalid);
+  else if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(ptr));
+  else *reinterpret_cast<f4u*>(ptr) = v;
 }
 
-// Folds the four waves' column partials through LDS, writes the tile's column sums and total.
-__device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wave, int seg, int tr, int n, int nseg,
-                                                   float* __restrict__ colpart, float* __restrict__ tilesum) {
-  __shared__ float cs[kWavesPerBlock][kSegCols];
-  __shared__ float ws[kWavesPerBlock];
+// Folds the column partials of the NW waves of a workgroup through LDS and writes the tile's
+// column sums (fixed order: deterministic).
+template <int NW>
+__device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wave, int seg, int tr, int n,
+                                                   float* __restrict__ colpart) {
+  __shared__ float cs[NW][kSegCols];
   *reinterpret_cast<f4v*>(&cs[wave][lane * 4]) = colacc;
   __syncthreads();
   const int t = threadIdx.x;
-  const float csum = (cs[0][t] + cs[1][t]) + (cs[2][t] + cs[3][t]);
-  const int j = seg * kSegCols + t;
-  if (j < n) colpart[(size_t)tr * n + j] = csum;
-  const float tot = wave_sum(csum);
-  if (lane == 0) ws[wave] = tot;
-  __syncthreads();
-  if (t == 0) tilesum[tr * nseg + seg] = (ws[0] + ws[1]) + (ws[2] + ws[3]);
+  if (t < kSegCols) {
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) sum += cs[k][t];
+    const int j = seg * kSegCols + t;
+    if (j < n) colpart[(size_t)tr * n + j] = sum;
+  }
 }
 
-template <bool FIRST, bool EDGE, int U>
+template <bool FIRST, bool EDGE, bool NT>
 __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr) {
+  constexpr int U = kSweepRows;
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
-  const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
-  const int rend = min(rbeg + A.tmw, A.m);
-  const float rho = A.rho, scale = A.scale;
-  // lane r holds phi of row rbeg + r; rows read it back with a scalar lane read
-  const float phi_lane = (rbeg + lane < rend) ? A.phi[rbeg + lane] : 0.f;
-  const float* __restrict__ Cp = A.C + (size_t)rbeg * A.n + j0;
-  float* __restrict__ Xp = A.X + (size_t)rbeg * A.n + j0;
-  const size_t pitch = (size_t)A.n;
-
+  const int r0 = tr * kTileRows + wave * U;
+  const int nrows = min(max(A.m - r0, 0), U);
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
-  float rowkeep = 0.f;  // lane r keeps the sum of row rbeg + r
-  const int nrows = rend - rbeg;
-  int r = 0;
-  for (; r + U <= nrows; r += U) {
+  if (nrows > 0) {
+    const f4v vp = load_varphi(A.varphi, j0, nvalid);
+    // lane u holds phi of row r0 + u; rows read it back with a scalar lane read
+    const float phi_lane = (lane < nrows) ? A.phi[r0 + lane] : 0.f;
+    const float* __restrict__ Cp = A.C + (size_t)r0 * A.n + j0;
+    float* __restrict__ Xp = A.X + (size_t)r0 * A.n + j0;
+    const size_t pitch = (size_t)A.n;
+    const float rho = A.rho, scale = A.scale;
     f4v x[U], c[U];
+    if (nrows == U) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        c[u] = ld4<EDGE, NT>(Cp + u * pitch, nvalid);
+        x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * pitch, nvalid);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        c[u] = f4v{0.f, 0.f, 0.f, 0.f};
+        x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+        if (u < nrows) {
+          c[u] = ld4<EDGE, NT>(Cp + u * pitch, nvalid);
+          if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * pitch, nvalid);
+        }
+      }
+    }
+    float rowkeep = 0.f;  // lane u keeps the sum of row r0 + u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      c[u] = ld4<EDGE>(Cp + (size_t)(r + u) * pitch, nvalid);
-      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE>(Xp + (size_t)(r + u) * pitch, nvalid);
+      if (u < nrows) {
+        const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
+        const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
+        st4<EDGE, NT>(Xp + u * pitch, v, nvalid);
+        colacc += v;
+        const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+        rowkeep = (lane == u) ? tot : rowkeep;
+      }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), r + u));
-      const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
-      st4<EDGE>(Xp + (size_t)(r + u) * pitch, v, nvalid);
-      colacc += v;
-      const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
-      rowkeep = (lane == r + u) ? tot : rowkeep;
-    }
+    if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
   }
-  for (; r < nrows; ++r) {
-    const f4v c = ld4<EDGE>(Cp + (size_t)r * pitch, nvalid);
-    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE>(Xp + (size_t)r * pitch, nvalid);
-    const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), r));
-    const f4v v = xbar4(x, c, vp + ph, rho) * scale;
-    st4<EDGE>(Xp + (size_t)r * pitch, v, nvalid);
-    colacc += v;
-    const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
-    rowkeep = (lane == r) ? tot : rowkeep;
-  }
-  if (lane < nrows) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
-  write_col_partials(colacc, lane, wave, seg, tr, A.n, A.nseg, A.colpart, A.tilesum);
+  write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.colpart);
 }
 
-template <bool FIRST, int U>
-__global__ __launch_bounds__(kBlock) void sweep_kernel(SweepArgs A) {
+template <bool FIRST, bool NT>
+__global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A) {
   if (*A.done) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, U>(A, lane, wave, seg, tr);
-  else sweep_body<FIRST, true, U>(A, lane, wave, seg, tr);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT>(A, lane, wave, seg, tr);
+  else sweep_body<FIRST, true, false>(A, lane, wave, seg, tr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -254,8 +265,8 @@ __global__ __launch_bounds__(kBlock) void gl_norm_kernel(GroupArgs G) {
   const int j0 = blockIdx.x * kSegCols + lane * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const int rbeg = blockIdx.y * (kWavesPerBlock * A.tmw) + wave * A.tmw;
-  const int rend = min(rbeg + A.tmw, A.m);
+  const int rbeg = blockIdx.y * kTileRows + wave * kLoopRows;
+  const int rend = min(rbeg + kLoopRows, A.m);
   int cur = -1;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   for (int i = rbeg; i < rend; ++i) {
@@ -290,8 +301,8 @@ __global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
-  const int rend = min(rbeg + A.tmw, A.m);
+  const int rbeg = tr * kTileRows + wave * kLoopRows;
+  const int rend = min(rbeg + kLoopRows, A.m);
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
   float rowkeep = 0.f;
   int cur = -1;
@@ -316,7 +327,7 @@ __global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
     rowkeep = (lane == i - rbeg) ? tot : rowkeep;
   }
   if (lane < rend - rbeg) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
-  write_col_partials(colacc, lane, wave, seg, tr, A.n, A.nseg, A.colpart, A.tilesum);
+  write_col_partials<kWavesPerBlock>(colacc, lane, wave, seg, tr, A.n, A.colpart);
 }
 
 __global__ void fill_kernel(float* __restrict__ dst, size_t count, float value, const int* done) {
@@ -337,8 +348,10 @@ struct VecState {
   double* a;
   double* b;
   double* theta;   // [2], indexed by iteration parity
-  double* sum_p;   // [1]
-  double* resid_part;
+  double* r;       // [m] row residuals X 1 - p of the last sweep
+  double* s;       // [n] column residuals
+  double* part;    // [2][nbm + nbn]: per-workgroup sum of residuals, sum of squared residuals
+  double* resid;   // [2]: ||r||^2, ||s||^2
   int* done;
   DeviceStatus* status;
 };
@@ -363,7 +376,6 @@ __global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __r
   }
   const double sum_p = block_sum_f64(sp, red);
   if (t == 0) {
-    *V.sum_p = sum_p;
     V.theta[0] = ((double)m * (double)n * (phi0 + varphi0) - sum_p) / mn;
     V.theta[1] = 0.0;
     *V.done = 0;
@@ -378,89 +390,121 @@ __global__ void reset_kernel(VecState V) {
 }
 
 // ------------------------------------------------------------------------------------------
-// S5: eq. (6).  r = X1 - p, s = X^T1 - q from the partial sums, eta = 1^T r/(m+n) from the tile
-// totals, then phi+ = (a - 2r + (2 eta - theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m,
-// a -= r, b -= s, theta -= eta.  fp64 throughout; phi, varphi are rounded to fp32 for the sweep.
-// A workgroup owns 64 rows or 64 columns; its 4 waves split the partials.  Also leaves the
-// squared residuals per workgroup (S6).
+// S5, first half: r = X1 - p and s = X^T1 - q from the partial sums, in fp64.  A workgroup owns
+// 64 rows or 64 columns; its 16 waves split the partials.  Leaves per workgroup the sum and the
+// sum of squares of its residuals (for eta and for the stopping test, S6).
 // ------------------------------------------------------------------------------------------
-struct VecArgs {
+struct ReduceArgs {
   VecState V;
   const float* rowpart;
   const float* colpart;
-  const float* tilesum;
   const float* p;
   const float* q;
-  int m, n, nseg, ntr, ntiles, nbm, par;
+  int m, n, nseg, ntr, nbm, nbn;
 };
 
-__global__ __launch_bounds__(kBlock) void vec_kernel(VecArgs A) {
+constexpr int kReduceThreads = 1024;
+
+__global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   if (*A.V.done) return;
-  __shared__ double red[kBlock];
+  __shared__ double red[kReduceThreads];
   const int t = threadIdx.x;
-  double acc = 0.0;
-  for (int e = t; e < A.ntiles; e += kBlock) acc += (double)A.tilesum[e];
-  const double sum_x = block_sum_f64(acc, red);
-  const double mn = (double)A.m + (double)A.n;
-  const double eta = (sum_x - *A.V.sum_p) / mn;
-  const double theta = A.V.theta[A.par];
-  const double cst = 2.0 * eta - theta;
   const int sub = t >> 6, l = t & 63;
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
   const int len = rows ? A.m : A.n;
   const int nparts = rows ? A.nseg : A.ntr;
-  const float* part = rows ? A.rowpart : A.colpart;
-  double s = 0.0;
-  if (idx < len)
-    for (int k = sub; k < nparts; k += 4) s += (double)part[(size_t)k * len + idx];
-  red[t] = s;
+  const float* __restrict__ part = rows ? A.rowpart : A.colpart;
+  double acc = 0.0;
+  if (idx < len) {
+#pragma unroll 4
+    for (int k = sub; k < nparts; k += kReduceThreads / 64) acc += (double)part[(size_t)k * len + idx];
+  }
+  red[t] = acc;
   __syncthreads();
-  double rr = 0.0;
-  if (sub == 0 && idx < len) {
-    const double total = (red[l] + red[64 + l]) + (red[128 + l] + red[192 + l]);
-    if (rows) {
-      const double r = total - (double)A.p[idx];
-      const double ai = A.V.a[idx];
-      A.V.phi[idx] = (float)((ai - 2.0 * r + cst) / (double)A.n);
-      A.V.a[idx] = ai - r;
-      rr = r * r;
-    } else {
-      const double r = total - (double)A.q[idx];
-      const double bi = A.V.b[idx];
-      A.V.varphi[idx] = (float)((bi - 2.0 * r + cst) / (double)A.m);
-      A.V.b[idx] = bi - r;
-      rr = r * r;
-    }
+  for (int h = kReduceThreads / 2; h >= 64; h >>= 1) {  // fold the 16 waves' partials, lane by lane
+    if (t < h) red[t] += red[t + h];
+    __syncthreads();
+  }
+  double res = 0.0;
+  if (t < 64 && idx < len) {
+    res = red[t] - (double)(rows ? A.p[idx] : A.q[idx]);
+    (rows ? A.V.r : A.V.s)[idx] = res;
   }
   __syncthreads();
-  const double r2 = block_sum_f64(rr, red);
+  // sum and sum of squares over the 64 residuals of this workgroup
+  if (t < 64) { red[t] = res; red[64 + t] = res * res; }
+  __syncthreads();
+  for (int h = 32; h > 0; h >>= 1) {
+    if (t < h) { red[t] += red[t + h]; red[64 + t] += red[64 + t + h]; }
+    __syncthreads();
+  }
   if (t == 0) {
-    A.V.resid_part[blockIdx.x] = r2;
-    if (blockIdx.x == 0) A.V.theta[A.par ^ 1] = theta - eta;
+    A.V.part[blockIdx.x] = red[0];
+    A.V.part[A.nbm + A.nbn + blockIdx.x] = red[64];
   }
 }
 
-// S6: r_primal of Appendix C from the per-workgroup squared residuals; raises the stop flag at
-// the first check that passes so that every later kernel of the solve returns at once.
-__global__ __launch_bounds__(kBlock) void status_kernel(VecState V, int nbm, int nbn, int iters, double tol) {
-  if (*V.done) return;
-  __shared__ double red[kBlock];
+// ------------------------------------------------------------------------------------------
+// S5, second half: eq. (6) with f = 1_m, e = 1_n.  eta = 1^T r/(m+n); phi+ = (a - 2r + (2 eta -
+// theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m, a -= r, b -= s, theta -= eta.  fp64; phi and
+// varphi are rounded to fp32 for the sweep.  Every workgroup re-derives eta from the per-workgroup
+// sums (a few hundred doubles); workgroup 0 also stores theta+ and the squared residual norms.
+// ------------------------------------------------------------------------------------------
+struct UpdateArgs {
+  VecState V;
+  int m, n, nbm, nbn, par;
+};
+
+__global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
+  if (*A.V.done) return;
+  __shared__ double red[kReduceThreads];
   const int t = threadIdx.x;
-  double r = 0.0, s = 0.0;
-  for (int e = t; e < nbm; e += kBlock) r += V.resid_part[e];
-  for (int e = t; e < nbn; e += kBlock) s += V.resid_part[nbm + e];
-  const double r2 = block_sum_f64(r, red);
-  const double s2 = block_sum_f64(s, red);
-  if (t == 0) {
-    V.status->r2 = r2;
-    V.status->s2 = s2;
-    V.status->iters = iters;
-    if (tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol) {
-      V.status->converged = 1;
-      __threadfence();
-      *V.done = 1;
+  double acc = 0.0;
+  for (int e = t; e < A.nbm; e += kReduceThreads) acc += A.V.part[e];
+  const double sum_r = block_sum_f64(acc, red);
+  const double mn = (double)A.m + (double)A.n;
+  const double eta = sum_r / mn;
+  const double theta = A.V.theta[A.par];
+  const double cst = 2.0 * eta - theta;
+  const long long g = (long long)blockIdx.x * kReduceThreads + t;
+  if (g < A.m) {
+    const double r = A.V.r[g], ai = A.V.a[g];
+    A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
+    A.V.a[g] = ai - r;
+  } else if (g < (long long)A.m + A.n) {
+    const long long j = g - A.m;
+    const double sj = A.V.s[j], bj = A.V.b[j];
+    A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
+    A.V.b[j] = bj - sj;
+  }
+  if (blockIdx.x == 0) {
+    double r2 = 0.0, s2 = 0.0;
+    const double* sq = A.V.part + A.nbm + A.nbn;
+    for (int e = t; e < A.nbm; e += kReduceThreads) r2 += sq[e];
+    for (int e = t; e < A.nbn; e += kReduceThreads) s2 += sq[A.nbm + e];
+    r2 = block_sum_f64(r2, red);
+    s2 = block_sum_f64(s2, red);
+    if (t == 0) {
+      A.V.theta[A.par ^ 1] = theta - eta;
+      A.V.resid[0] = r2;
+      A.V.resid[1] = s2;
     }
+  }
+}
+
+// S6: r_primal of Appendix C; raises the stop flag at the first check that passes so that every
+// later kernel of the solve returns at once.
+__global__ void status_kernel(VecState V, int iters, double tol) {
+  if (*V.done) return;
+  const double r2 = V.resid[0], s2 = V.resid[1];
+  V.status->r2 = r2;
+  V.status->s2 = s2;
+  V.status->iters = iters;
+  if (tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol) {
+    V.status->converged = 1;
+    __threadfence();
+    *V.done = 1;
   }
 }
 
@@ -478,7 +522,7 @@ struct GapArgs {
   float* gap_part;       // [ntiles][3]
   float* gx;             // [num_classes][n] sum x^2   (group lasso)
   float* gw;             // [num_classes][n] sum w^2
-  int m, n, tmw, nseg;
+  int m, n, nseg;
   float rho;
 };
 
@@ -489,8 +533,8 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const int rbeg = tr * (kWavesPerBlock * A.tmw) + wave * A.tmw;
-  const int rend = min(rbeg + A.tmw, A.m);
+  const int rbeg = tr * kTileRows + wave * kLoopRows;
+  const int rend = min(rbeg + kLoopRows, A.m);
   float cx = 0.f, xx = 0.f, ww = 0.f;
   int cur = -1;
   f4v ax = {0.f, 0.f, 0.f, 0.f}, aw = {0.f, 0.f, 0.f, 0.f};
@@ -590,17 +634,9 @@ __global__ __launch_bounds__(1024) void gap_final_kernel(VecState V, const float
 // ------------------------------------------------------------------------------------------
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// rows per wave per tile: as tall as possible while the launch still has enough workgroups to
-// fill 256 compute units several times over (small problems get flatter tiles, as the paper's
-// "adapt the number of columns per block to the problem size").
-int choose_tmw(int m, int n) {
-  const int nseg = ceil_div(n, kSegCols);
-  for (int tmw = kMaxWaveRows; tmw > 8; tmw >>= 1) {
-    if ((long long)nseg * ceil_div(m, kWavesPerBlock * tmw) >= 2048) return tmw;
-  }
-  return 8;
-}
-constexpr int kMinTileRows = kWavesPerBlock * 8;
+// Non-temporal accesses pay off once X and C together are far beyond what the caches hold
+// (256 MB of memory-side cache); below that, keeping the lines cached is the better choice.
+inline bool use_nontemporal(int m, int n) { return 8.0 * (double)m * (double)n > 512.0 * 1024 * 1024; }
 constexpr int kMaxProfiled = 256;  // sweeps timed per solve in profile mode
 
 }  // namespace
@@ -621,8 +657,8 @@ struct drot_handle_s {
   double prof_sweep_ms = 0.0;
   // device workspace
   float *phi = nullptr, *varphi = nullptr;
-  double *a = nullptr, *b = nullptr, *theta = nullptr, *sum_p = nullptr, *resid_part = nullptr;
-  float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
+  double *a = nullptr, *b = nullptr, *theta = nullptr, *r = nullptr, *s = nullptr, *part = nullptr, *resid = nullptr;
+  float *rowpart = nullptr, *colpart = nullptr, *gap_part = nullptr;
   float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
   size_t gbuf_len = 0;
   int* done = nullptr;
@@ -655,8 +691,8 @@ int dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(drot_handle h) {
-  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf};
-  double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->resid_part};
+  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->gap_part, h->gbuf};
+  double* dbufs[] = {h->a, h->b, h->theta, h->r, h->s, h->part, h->resid};
   for (float* b : fbufs) (void)hipFree(b);
   for (double* b : dbufs) (void)hipFree(b);
   (void)hipFree(h->done);
@@ -696,7 +732,7 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   h->max_m = max_m;
   h->max_n = max_n;
   const size_t nseg = (size_t)ceil_div(max_n, kSegCols);
-  const size_t ntr = (size_t)ceil_div(max_m, kMinTileRows);
+  const size_t ntr = (size_t)ceil_div(max_m, kTileRows);
   const size_t nb = (size_t)ceil_div(max_m, 64) + (size_t)ceil_div(max_n, 64);
   int rc = DROT_OK;
   auto take = [&](int r) { if (rc == DROT_OK) rc = r; };
@@ -705,11 +741,12 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->a, (size_t)max_m));
   take(dev_alloc(&h->b, (size_t)max_n));
   take(dev_alloc(&h->theta, 2));
-  take(dev_alloc(&h->sum_p, 1));
-  take(dev_alloc(&h->resid_part, nb));
+  take(dev_alloc(&h->r, (size_t)max_m));
+  take(dev_alloc(&h->s, (size_t)max_n));
+  take(dev_alloc(&h->part, 2 * nb));
+  take(dev_alloc(&h->resid, 2));
   take(dev_alloc(&h->rowpart, nseg * (size_t)max_m));
   take(dev_alloc(&h->colpart, ntr * (size_t)max_n));
-  take(dev_alloc(&h->tilesum, nseg * ntr));
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));
   take(dev_alloc(&h->done, 1));
   take(dev_alloc(&h->status, 1));
@@ -809,10 +846,10 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   // 1/(1 + rho*lambda) evaluated in fp64 from the fp32 inputs, rounded once
   const float qscale = (float)(1.0 / (1.0 + (double)rho * (double)lambda));
 
-  const int tmw = choose_tmw(m, n);
   const int nseg = ceil_div(n, kSegCols);
-  const int ntr = ceil_div(m, kWavesPerBlock * tmw);
+  const int ntr = ceil_div(m, kTileRows);
   const int ntiles = nseg * ntr;
+  const bool nt = use_nontemporal(m, n);
   const int nbm = ceil_div(m, 64), nbn = ceil_div(n, 64);
 
   size_t ngroups = 0;
@@ -828,16 +865,18 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     }
   }
 
-  VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->sum_p, h->resid_part, h->done, h->status};
+  VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->r, h->s, h->part, h->resid, h->done, h->status};
   const long long k_base = resume ? h->iters_done : 0;
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
   else hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
 
-  SweepArgs S{X_out, C, h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->done,
-              m, n, tmw, nseg, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
+  SweepArgs S{X_out, C, h->phi, h->varphi, h->rowpart, h->colpart, h->done,
+              m, n, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
   GroupArgs G{S, row_class, h->gbuf, rho * mu};
-  VecArgs VA{V, h->rowpart, h->colpart, h->tilesum, p, q, m, n, nseg, ntr, ntiles, nbm, 0};
-  const dim3 grid(nseg, ntr), block(kBlock);
+  ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, nseg, ntr, nbm, nbn};
+  UpdateArgs UA{V, m, n, nbm, nbn, 0};
+  const dim3 grid(nseg, ntr), block(kBlock), sweep_block(64 * kSweepWaves);
+  const dim3 update_grid(ceil_div(m + n, kReduceThreads));
 
   if (max_iters == 0 && !resume)
     hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, X_out, (size_t)m * n, 0.f, (const int*)nullptr);
@@ -862,17 +901,20 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
           hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
         }
       } else if (first) {
-        hipLaunchKernelGGL((sweep_kernel<true, 4>), grid, block, 0, stream, S);
+        hipLaunchKernelGGL((sweep_kernel<true, false>), grid, sweep_block, 0, stream, S);
+      } else if (nt) {
+        hipLaunchKernelGGL((sweep_kernel<false, true>), grid, sweep_block, 0, stream, S);
       } else {
-        hipLaunchKernelGGL((sweep_kernel<false, 4>), grid, block, 0, stream, S);
+        hipLaunchKernelGGL((sweep_kernel<false, false>), grid, sweep_block, 0, stream, S);
       }
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k + 1], stream));
-      VA.par = (int)((k_base + k) & 1);
-      hipLaunchKernelGGL(vec_kernel, dim3(nbm + nbn), block, 0, stream, VA);
+      UA.par = (int)((k_base + k) & 1);
+      hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
+      hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
     }
     if (checking) {
       // the test runs on the device; the host reads it one chunk late so the queue never drains
-      hipLaunchKernelGGL(status_kernel, dim3(1), block, 0, stream, V, nbm, nbn, k, (double)tol);
+      hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, (double)tol);
       DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
       DROT_HIP(hipEventRecord(h->ev[slot], stream));
       if (checks > 0) {
@@ -885,14 +927,14 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   }
   // final state: residuals of the returned iterate (no-op if the stop flag is already up)
   if (k > 0)
-    hipLaunchKernelGGL(status_kernel, dim3(1), block, 0, stream, V, nbm, nbn, k, checking ? (double)tol : 0.0);
+    hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, checking ? (double)tol : 0.0);
   if (h->compute_gap) {
     float* gx = h->gbuf;
     float* gw = h->gbuf ? h->gbuf + ngroups : nullptr;
     if (reg_kind == DROT_REG_GROUP_LASSO)
       hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((2 * ngroups + 255) / 256), 4)), dim3(256), 0, stream,
                          h->gbuf, 2 * ngroups, 0.f, (const int*)nullptr);
-    GapArgs GA{X_out, C, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, tmw, nseg, rho};
+    GapArgs GA{X_out, C, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, nseg, rho};
     hipLaunchKernelGGL(gap_kernel, grid, block, 0, stream, GA);
     hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(1024), 0, stream, V, (const float*)h->gap_part, ntiles,
                        (const float*)gx, (const float*)gw, ngroups, p, q, m, n, (double)rho, (int)reg_kind,
