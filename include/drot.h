@@ -100,6 +100,14 @@ int drot_set_compute_gap(drot_handle h, int enable);
 int drot_set_continue(drot_handle h, int enable);
 
 /*
+ * Group-lasso path [automatic].  By default a group-lasso solve uses the group-resident kernel
+ * (a whole class x 64 columns in one workgroup's registers, 12 bytes per element) when every class
+ * is one run of at most 1024 consecutive rows, and otherwise the general two-pass path (any labels,
+ * 20 bytes per element, fp32 atomics for the group norms).  enable = 1 forces the two-pass path.
+ */
+int drot_set_group_two_pass(drot_handle h, int enable);
+
+/*
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
  * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.
@@ -121,7 +129,8 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
  *   stream      hipStream_t (as void*); NULL = the default stream
  *
  * Errors: INVALID_ARG (null pointers, m/n outside [1, max], negative max_iters or weights,
- * unknown reg_kind, GROUP_LASSO without labels), HIP.
+ * unknown reg_kind, GROUP_LASSO without labels or with a label outside [0, num_classes): the
+ * labels are copied to the host and checked at the start of a group-lasso solve), ALLOC, HIP.
  */
 int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n,
                float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,

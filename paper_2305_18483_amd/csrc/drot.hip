@@ -26,6 +26,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "drot.h"
 
@@ -328,6 +329,105 @@ __global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
   }
   if (lane < rend - rbeg) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
   write_col_partials<kWavesPerBlock>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+}
+
+// ------------------------------------------------------------------------------------------
+// Group lasso, group-resident variant (Section "Group-lasso Regularized DROT", small-group case:
+// reduce and broadcast inside one thread block).  Needs rows sorted by class.  A workgroup of
+// 1024 threads owns one class (a run of up to 64*K consecutive rows) x 64 columns and keeps the
+// whole slab of Xbar in registers: 16 lanes x 128-bit along the columns, 64 row lanes, K rows per
+// thread, all loads in flight at once.  Squared norms per column are folded through LDS, the
+// scale is broadcast, X is stored once: 12 bytes per element like the plain sweep.
+// Row sums: rowpart[strip][i] with 64-column strips; column sums: colpart[class run][j].
+// ------------------------------------------------------------------------------------------
+constexpr int kSlabCols = 64;
+constexpr int kSlabRowLanes = 64;
+
+struct SlabArgs {
+  SweepArgs S;
+  const int* run_start;  // [nruns] first row of every run of equal labels
+  const int* run_len;    // [nruns]
+  float thr;             // rho * mu
+};
+
+// sum over the 16 lanes of a DPP row (lanes sharing one matrix row); every lane gets the total
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_mov<0xB1, 0xF>(v);
+  v += dpp_mov<0x4E, 0xF>(v);
+  v += dpp_mov<0x141, 0xF>(v);
+  v += dpp_mov<0x140, 0xF>(v);
+  return v;
+}
+
+template <bool FIRST, int K>
+__global__ __launch_bounds__(1024) void gl_slab_kernel(SlabArgs G) {
+  const SweepArgs& A = G.S;
+  if (*A.done) return;
+  __shared__ float red[kSlabRowLanes][kSlabCols];
+  __shared__ float bcast[kSlabCols];
+  const int t = threadIdx.x;
+  const int cx = t & 15, ry = t >> 4;
+  const int strip = blockIdx.x, run = blockIdx.y;
+  const int start = G.run_start[run], len = G.run_len[run];
+  const int j0 = strip * kSlabCols + cx * 4;
+  const int nvalid = min(max(A.n - j0, 0), 4);
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const size_t pitch = (size_t)A.n;
+  const float* __restrict__ Cp = A.C + (size_t)(start + ry) * pitch + j0;
+  float* __restrict__ Xp = A.X + (size_t)(start + ry) * pitch + j0;
+
+  f4v x[K], c[K];
+  float ph[K];
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int r = ry + kSlabRowLanes * k;
+    c[k] = f4v{0.f, 0.f, 0.f, 0.f};
+    x[k] = f4v{0.f, 0.f, 0.f, 0.f};
+    ph[k] = kMaskedOut;  // rows past the run: the clamp zeroes them
+    if (r < len) {
+      c[k] = load4(Cp + (size_t)(kSlabRowLanes * k) * pitch, nvalid);
+      if (!FIRST) x[k] = load4(Xp + (size_t)(kSlabRowLanes * k) * pitch, nvalid);
+      ph[k] = A.phi[start + r];
+    }
+  }
+  f4v sq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    x[k] = xbar4(x[k], c[k], vp + ph[k], A.rho);
+    sq += x[k] * x[k];
+  }
+  // squared norm of every column's group: fold the 64 row lanes through LDS
+  *reinterpret_cast<f4v*>(&red[ry][cx * 4]) = sq;
+  __syncthreads();
+  if (t < kSlabCols) {
+    float tsum = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < kSlabRowLanes; ++k) tsum += red[k][t];
+    bcast[t] = group_scale(tsum, G.thr, A.scale);
+  }
+  __syncthreads();
+  const f4v sc = *reinterpret_cast<const f4v*>(&bcast[cx * 4]);
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int r = ry + kSlabRowLanes * k;
+    const f4v v = x[k] * sc;
+    const float rs = row16_sum((v.x + v.y) + (v.z + v.w));
+    colacc += v;
+    if (r < len) {
+      store4(Xp + (size_t)(kSlabRowLanes * k) * pitch, v, nvalid);
+      if (cx == 0) A.rowpart[(size_t)strip * A.m + start + r] = rs;
+    }
+  }
+  *reinterpret_cast<f4v*>(&red[ry][cx * 4]) = colacc;  // safe: every read of red happened before the last barrier
+  __syncthreads();
+  if (t < kSlabCols) {
+    float csum = 0.f;
+#pragma unroll 8
+    for (int k = 0; k < kSlabRowLanes; ++k) csum += red[k][t];
+    const int j = strip * kSlabCols + t;
+    if (j < A.n) A.colpart[(size_t)run * A.n + j] = csum;
+  }
 }
 
 __global__ void fill_kernel(float* __restrict__ dst, size_t count, float value, const int* done) {
@@ -637,6 +737,22 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Non-temporal accesses pay off once X and C together are far beyond what the caches hold
 // (256 MB of memory-side cache); below that, keeping the lines cached is the better choice.
 inline bool use_nontemporal(int m, int n) { return 8.0 * (double)m * (double)n > 512.0 * 1024 * 1024; }
+template <bool FIRST>
+void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a) {
+  const dim3 block(1024);
+  switch (k) {
+    case 1: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 1>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 2>), grid, block, 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 4>), grid, block, 0, stream, a); break;
+    case 8: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 8>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 16>), grid, block, 0, stream, a); break;
+  }
+}
+void launch_slab(bool first, int k, dim3 grid, hipStream_t stream, const SlabArgs& a) {
+  if (first) launch_slab_k<true>(k, grid, stream, a);
+  else launch_slab_k<false>(k, grid, stream, a);
+}
+
 constexpr int kMaxProfiled = 256;  // sweeps timed per solve in profile mode
 
 }  // namespace
@@ -648,6 +764,7 @@ struct drot_handle_s {
   int compute_gap = 1;
   int continue_next = 0;  // the next solve resumes from the state the last one left
   int profile = 0;        // record HIP events around every sweep launch
+  int force_two_pass = 0; // group lasso: always take the general two-pass path
   bool solved = false;
   int last_m = 0, last_n = 0;
   long long iters_done = 0;  // iterations applied to the state held by this handle
@@ -661,6 +778,9 @@ struct drot_handle_s {
   float *rowpart = nullptr, *colpart = nullptr, *gap_part = nullptr;
   float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
   size_t gbuf_len = 0;
+  int* runbuf = nullptr;  // group-resident path: run_start[], run_len[] of the label runs
+  size_t runbuf_len = 0;
+  int max_runs = 0;       // rows of colpart available
   int* done = nullptr;
   DeviceStatus* status = nullptr;
   // pinned host mirror of the status block, two slots for the pipelined residual checks
@@ -697,6 +817,7 @@ void free_all(drot_handle h) {
   for (double* b : dbufs) (void)hipFree(b);
   (void)hipFree(h->done);
   (void)hipFree(h->status);
+  (void)hipFree(h->runbuf);
   if (h->host_status) (void)hipHostFree(h->host_status);
   for (auto& e : h->ev)
     if (e) (void)hipEventDestroy(e);
@@ -745,8 +866,9 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->s, (size_t)max_n));
   take(dev_alloc(&h->part, 2 * nb));
   take(dev_alloc(&h->resid, 2));
-  take(dev_alloc(&h->rowpart, nseg * (size_t)max_m));
+  take(dev_alloc(&h->rowpart, (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m));  // 64-column strips (group-resident path) are the finest
   take(dev_alloc(&h->colpart, ntr * (size_t)max_n));
+  h->max_runs = (int)ntr;
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));
   take(dev_alloc(&h->done, 1));
   take(dev_alloc(&h->status, 1));
@@ -791,6 +913,12 @@ int drot_set_compute_gap(drot_handle h, int enable) {
 int drot_set_continue(drot_handle h, int enable) {
   if (!h) return DROT_ERR_INVALID_ARG;
   h->continue_next = enable ? 1 : 0;
+  return DROT_OK;
+}
+
+int drot_set_group_two_pass(drot_handle h, int enable) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  h->force_two_pass = enable ? 1 : 0;
   return DROT_OK;
 }
 
@@ -865,6 +993,50 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     }
   }
 
+  // Group lasso: if every class is one run of consecutive rows short enough to sit in a workgroup's
+  // registers, take the group-resident kernel; otherwise the general two-pass path.
+  int slab_k = 0, nruns = 0;
+  if (reg_kind == DROT_REG_GROUP_LASSO) {
+    std::vector<int> labels((size_t)m);
+    DROT_HIP(hipMemcpyAsync(labels.data(), row_class, sizeof(int) * (size_t)m, hipMemcpyDeviceToHost, stream));
+    DROT_HIP(hipStreamSynchronize(stream));
+    std::vector<int> runs;  // start, len pairs
+    std::vector<char> seen((size_t)num_classes, 0);
+    bool one_run_per_class = true;
+    int maxlen = 0;
+    for (int i = 0; i < m;) {
+      const int c = labels[(size_t)i];
+      if (c < 0 || c >= num_classes) return DROT_ERR_INVALID_ARG;
+      int e = i + 1;
+      while (e < m && labels[(size_t)e] == c) ++e;
+      if (seen[(size_t)c]) one_run_per_class = false;
+      seen[(size_t)c] = 1;
+      runs.push_back(i);
+      runs.push_back(e - i);
+      if (e - i > maxlen) maxlen = e - i;
+      i = e;
+    }
+    nruns = (int)(runs.size() / 2);
+    if (!h->force_two_pass && one_run_per_class && maxlen <= kSlabRowLanes * 16 && nruns <= h->max_runs) {
+      slab_k = 1;
+      while (kSlabRowLanes * slab_k < maxlen) slab_k *= 2;
+      if (h->runbuf_len < runs.size()) {
+        (void)hipFree(h->runbuf);
+        h->runbuf = nullptr;
+        h->runbuf_len = 0;
+        if (dev_alloc(&h->runbuf, runs.size()) != DROT_OK) return DROT_ERR_ALLOC;
+        h->runbuf_len = runs.size();
+      }
+      // de-interleave: run_start[0..nruns), run_len[0..nruns)
+      std::vector<int> table(runs.size());
+      for (int r = 0; r < nruns; ++r) {
+        table[(size_t)r] = runs[2 * (size_t)r];
+        table[(size_t)nruns + r] = runs[2 * (size_t)r + 1];
+      }
+      DROT_HIP(hipMemcpy(h->runbuf, table.data(), sizeof(int) * table.size(), hipMemcpyHostToDevice));
+    }
+  }
+
   VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->r, h->s, h->part, h->resid, h->done, h->status};
   const long long k_base = resume ? h->iters_done : 0;
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
@@ -873,7 +1045,12 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   SweepArgs S{X_out, C, h->phi, h->varphi, h->rowpart, h->colpart, h->done,
               m, n, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
   GroupArgs G{S, row_class, h->gbuf, rho * mu};
-  ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, nseg, ntr, nbm, nbn};
+  SlabArgs SL{S, h->runbuf, h->runbuf ? h->runbuf + nruns : nullptr, rho * mu};
+  const dim3 slab_grid(ceil_div(n, kSlabCols), nruns > 0 ? nruns : 1);
+  // the partial sums the reduction reads: per 256-column segment and 32-row tile, or, on the
+  // group-resident path, per 64-column strip and label run
+  ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, slab_k ? ceil_div(n, kSlabCols) : nseg,
+                slab_k ? nruns : ntr, nbm, nbn};
   UpdateArgs UA{V, m, n, nbm, nbn, 0};
   const dim3 grid(nseg, ntr), block(kBlock), sweep_block(64 * kSweepWaves);
   const dim3 update_grid(ceil_div(m + n, kReduceThreads));
@@ -890,7 +1067,9 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
       const bool first = (k_base + k == 0);
       const bool timed = h->profile && k < kMaxProfiled;
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
-      if (reg_kind == DROT_REG_GROUP_LASSO) {
+      if (slab_k) {
+        launch_slab(first, slab_k, slab_grid, stream, SL);
+      } else if (reg_kind == DROT_REG_GROUP_LASSO) {
         hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((ngroups + 255) / 256), 4)), dim3(256), 0, stream,
                            h->gbuf, ngroups, 0.f, (const int*)h->done);
         if (first) {

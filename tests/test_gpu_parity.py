@@ -212,3 +212,34 @@ def test_continuation_is_bit_identical_to_one_long_solve(drot):
     ms, cnt = solver.profile()
     solver.set_profile(False)
     assert cnt == 90 and ms > 0.0 and np.array_equal(X_prof, X_long)
+
+
+def _two_class_problem(m, n, first_len, seed, lam=0.05, mu=0.05):
+    P = drot_inputs.random_problem(m, n, seed=seed, reg_kind=2, lam=lam, mu=mu, num_classes=2)
+    P.row_class = np.concatenate([np.zeros(first_len, np.int32), np.ones(m - first_len, np.int32)])
+    return P
+
+
+@pytest.mark.parametrize("m,first_len,label", [(1200, 900, "one class of 900 rows (16 rows per lane)"),
+                                               (1500, 1100, "one class of 1100 rows (two-pass fallback)"),
+                                               (700, 130, "classes of 130 and 570 rows")])
+def test_group_lasso_class_sizes(drot, oracle, m, first_len, label):
+    _run_case(drot, oracle, _two_class_problem(m, 333, first_len, seed=90 + m), 120, f"group lasso, {label}")
+
+
+def test_group_lasso_both_paths_agree_with_the_oracle(drot, oracle):
+    # sorted labels: the group-resident kernel by default, the two-pass path when forced
+    P = drot_inputs.config(5, size=600)
+    solver = drot.Solver(P.m, P.n)
+    _run_case(drot, oracle, P, 200, "group lasso, group-resident path", solver=solver)
+    solver.set_group_two_pass(True)
+    _run_case(drot, oracle, P, 200, "group lasso, forced two-pass path", solver=solver)
+
+
+def test_group_lasso_label_out_of_range_is_rejected(drot):
+    P = drot_inputs.random_problem(40, 50, seed=8, reg_kind=2, lam=0.1, mu=0.1, num_classes=3)
+    P.row_class = P.row_class.copy()
+    P.row_class[7] = 3
+    solver = drot.Solver(P.m, P.n)
+    with pytest.raises(drot.DrotError):
+        pu.gpu_solve(solver, P, 5)
