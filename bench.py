@@ -46,6 +46,7 @@ def main() -> int:
     ap.add_argument("--tol", type=float, default=1e-4, help="residual of the time-to-tolerance leg")
     ap.add_argument("--tol-max-iters", type=int, default=40000)
     ap.add_argument("--check-every", type=int, default=100)
+    ap.add_argument("--nontemporal", type=int, default=-1, help="-1: library default, 0/1: force off/on")
     ap.add_argument("--skip-tol", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0: sized for ~20 s)")
@@ -77,6 +78,7 @@ def main() -> int:
     X = torch.empty_like(C)
     kw = dict(reg_kind=P.reg_kind, lam=P.lam, mu=P.mu, row_class=rc, num_classes=P.num_classes, X_out=X)
     solver = drot.Solver(m, n, check_every=args.check_every, compute_gap=False)
+    solver.set_nontemporal(args.nontemporal)
     torch.cuda.synchronize()
 
     # ---- warm-up (cold start), then exactly K steady-state iterations continuing from it --------------

@@ -16,7 +16,8 @@
  *     Any m, n >= 1 and any 4-byte-aligned base address are accepted; 16-byte alignment and
  *     n % 4 == 0 are not required.
  *   - The caller owns C, p, q, X_out, row_class and the point clouds; the library never frees or
- *     reallocates them and never writes C, p, q, row_class.  The handle owns only workspace.
+ *     reallocates them and never writes C, p, q, row_class.  The handle owns only workspace
+ *     (including, for unaligned problems, padded working copies of C and X: 8*m*ceil32(n) bytes).
  *   - Preconditions that are NOT checked (they would need a pass over the data): p, q >= 0 with
  *     sum(p) = sum(q) = 1, C >= 0 and finite, labels in range.  The stepsize default assumes
  *     max(C) = 1 ("Stepsize selection").
@@ -108,6 +109,14 @@ int drot_set_continue(drot_handle h, int enable);
 int drot_set_group_two_pass(drot_handle h, int enable);
 
 /*
+ * Non-temporal accesses in the sweep [-1 = chosen by problem size].  mode 1 marks the loads and
+ * stores of X and C non-temporal (best when X and C are far larger than the caches), mode 0 keeps
+ * them cacheable (best when they fit), -1 decides from 8*m*n bytes.  A tuning knob: results are
+ * identical in every mode.
+ */
+int drot_set_nontemporal(drot_handle h, int mode);
+
+/*
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
  * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.
@@ -125,7 +134,10 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
  *   reg_kind, reg_params   the regularizer; reg_params may be NULL for DROT_REG_NONE
  *   max_iters   >= 0; with tol <= 0 exactly max_iters iterations are run
  *   tol         stop when max(||X1-p||_2, ||X^T1-q||_2) <= tol at a check (eq. "stopping criteria")
- *   X_out [out] DEVICE, m*n fp32 row-major; used as the iterate buffer, contents on entry ignored
+ *   X_out [out] DEVICE, m*n fp32 row-major; contents on entry ignored.  It is the iterate buffer
+ *               itself when n % 32 == 0 and the address is a multiple of 128; otherwise the
+ *               library iterates on an internal copy with padded rows (and likewise reads C
+ *               from a padded copy), and writes X_out once at the end
  *   stream      hipStream_t (as void*); NULL = the default stream
  *
  * Errors: INVALID_ARG (null pointers, m/n outside [1, max], negative max_iters or weights,

@@ -39,6 +39,7 @@ constexpr int kBlock = 256;          // threads per workgroup in the group-lasso
 constexpr int kWavesPerBlock = 4;
 constexpr int kSegCols = 256;        // columns per tile: 64 lanes x 4
 constexpr int kTileRows = 32;        // rows per tile, the same in every matrix kernel
+constexpr int kAlignElems = 32;      // rows of X and C are kept on 128-byte lines (padded working copies otherwise)
 constexpr int kSweepWaves = 16;      // sweep: waves per workgroup, stacked along the rows
 constexpr int kSweepRows = kTileRows / kSweepWaves;   // sweep: rows per wave (one batch, no loop)
 constexpr int kLoopRows = kTileRows / kWavesPerBlock; // looping kernels: rows per wave
@@ -136,6 +137,7 @@ struct SweepArgs {
   float* colpart;
   const int* done;
   int m, n;
+  int ldx, ldc;          // row pitch of X and of C in elements (n, or the padded working copies' pitch)
   float rho, scale;
 };
 
@@ -145,6 +147,11 @@ struct SweepArgs {
 // 2 row segments of 1 KiB of X and C, updates, stores and is done.  EDGE marks the last column
 // segment when n is not a multiple of 256: only there do lanes check how many of their 4
 // columns exist.  NT marks the accesses non-temporal (used when X and C cannot stay in cache).
+//
+// Alignment (what the paper's "shifted work areas" of Section "General Optimization" are for):
+// row segments that straddle 128-byte lines cost 10-28 % here, so the host hands this kernel
+// rows that start on a line: the caller's arrays when n % 32 == 0 and the base is aligned, else
+// working copies with the pitch rounded up to 32 elements (ldx, ldc).
 // ------------------------------------------------------------------------------------------
 template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v ld4(const float* __restrict__ ptr, int nvalid) {
@@ -189,16 +196,16 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
     const f4v vp = load_varphi(A.varphi, j0, nvalid);
     // lane u holds phi of row r0 + u; rows read it back with a scalar lane read
     const float phi_lane = (lane < nrows) ? A.phi[r0 + lane] : 0.f;
-    const float* __restrict__ Cp = A.C + (size_t)r0 * A.n + j0;
-    float* __restrict__ Xp = A.X + (size_t)r0 * A.n + j0;
-    const size_t pitch = (size_t)A.n;
+    const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+    const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+    float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
     const float rho = A.rho, scale = A.scale;
     f4v x[U], c[U];
     if (nrows == U) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        c[u] = ld4<EDGE, NT>(Cp + u * pitch, nvalid);
-        x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * pitch, nvalid);
+        c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+        x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
       }
     } else {
 #pragma unroll
@@ -206,8 +213,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
         c[u] = f4v{0.f, 0.f, 0.f, 0.f};
         x[u] = f4v{0.f, 0.f, 0.f, 0.f};
         if (u < nrows) {
-          c[u] = ld4<EDGE, NT>(Cp + u * pitch, nvalid);
-          if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * pitch, nvalid);
+          c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+          if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
         }
       }
     }
@@ -217,7 +224,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
       if (u < nrows) {
         const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
         const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
-        st4<EDGE, NT>(Xp + u * pitch, v, nvalid);
+        st4<EDGE, NT>(Xp + u * ldx, v, nvalid);
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
@@ -277,9 +284,8 @@ __global__ __launch_bounds__(kBlock) void gl_norm_kernel(GroupArgs G) {
       cur = cls;
       acc = f4v{0.f, 0.f, 0.f, 0.f};
     }
-    const size_t off = (size_t)i * A.n + j0;
-    const f4v c = load4(A.C + off, nvalid);
-    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + off, nvalid);
+    const f4v c = load4(A.C + (size_t)i * A.ldc + j0, nvalid);
+    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v v = xbar4(x, c, vp + A.phi[i], A.rho);
     acc += v * v;
   }
@@ -318,11 +324,10 @@ __global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
       sc.z = group_scale(t.z, G.thr, A.scale);
       sc.w = group_scale(t.w, G.thr, A.scale);
     }
-    const size_t off = (size_t)i * A.n + j0;
-    const f4v c = load4(A.C + off, nvalid);
-    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + off, nvalid);
+    const f4v c = load4(A.C + (size_t)i * A.ldc + j0, nvalid);
+    const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v v = xbar4(x, c, vp + A.phi[i], A.rho) * sc;
-    store4(A.X + off, v, nvalid);
+    store4(A.X + (size_t)i * A.ldx + j0, v, nvalid);
     colacc += v;
     const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
     rowkeep = (lane == i - rbeg) ? tot : rowkeep;
@@ -372,9 +377,9 @@ __global__ __launch_bounds__(1024) void gl_slab_kernel(SlabArgs G) {
   const int j0 = strip * kSlabCols + cx * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const size_t pitch = (size_t)A.n;
-  const float* __restrict__ Cp = A.C + (size_t)(start + ry) * pitch + j0;
-  float* __restrict__ Xp = A.X + (size_t)(start + ry) * pitch + j0;
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)(start + ry) * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)(start + ry) * ldx + j0;
 
   f4v x[K], c[K];
   float ph[K];
@@ -385,8 +390,8 @@ __global__ __launch_bounds__(1024) void gl_slab_kernel(SlabArgs G) {
     x[k] = f4v{0.f, 0.f, 0.f, 0.f};
     ph[k] = kMaskedOut;  // rows past the run: the clamp zeroes them
     if (r < len) {
-      c[k] = load4(Cp + (size_t)(kSlabRowLanes * k) * pitch, nvalid);
-      if (!FIRST) x[k] = load4(Xp + (size_t)(kSlabRowLanes * k) * pitch, nvalid);
+      c[k] = load4(Cp + (size_t)(kSlabRowLanes * k) * ldc, nvalid);
+      if (!FIRST) x[k] = load4(Xp + (size_t)(kSlabRowLanes * k) * ldx, nvalid);
       ph[k] = A.phi[start + r];
     }
   }
@@ -415,7 +420,7 @@ __global__ __launch_bounds__(1024) void gl_slab_kernel(SlabArgs G) {
     const float rs = row16_sum((v.x + v.y) + (v.z + v.w));
     colacc += v;
     if (r < len) {
-      store4(Xp + (size_t)(kSlabRowLanes * k) * pitch, v, nvalid);
+      store4(Xp + (size_t)(kSlabRowLanes * k) * ldx, v, nvalid);
       if (cx == 0) A.rowpart[(size_t)strip * A.m + start + r] = rs;
     }
   }
@@ -623,6 +628,7 @@ struct GapArgs {
   float* gx;             // [num_classes][n] sum x^2   (group lasso)
   float* gw;             // [num_classes][n] sum w^2
   int m, n, nseg;
+  int ldx, ldc;
   float rho;
 };
 
@@ -639,9 +645,8 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
   int cur = -1;
   f4v ax = {0.f, 0.f, 0.f, 0.f}, aw = {0.f, 0.f, 0.f, 0.f};
   for (int i = rbeg; i < rend; ++i) {
-    const size_t off = (size_t)i * A.n + j0;
-    const f4v c = load4(A.C + off, nvalid);
-    const f4v x = load4(A.X + off, nvalid);
+    const f4v c = load4(A.C + (size_t)i * A.ldc + j0, nvalid);
+    const f4v x = load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c, vp + A.phi[i], A.rho);
     const f4v x2 = x * x, w2 = w * w, cxv = c * x;
     cx += (cxv.x + cxv.y) + (cxv.z + cxv.w);
@@ -734,9 +739,10 @@ __global__ __launch_bounds__(1024) void gap_final_kernel(VecState V, const float
 // ------------------------------------------------------------------------------------------
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Non-temporal accesses pay off once X and C together are far beyond what the caches hold
-// (256 MB of memory-side cache); below that, keeping the lines cached is the better choice.
-inline bool use_nontemporal(int m, int n) { return 8.0 * (double)m * (double)n > 512.0 * 1024 * 1024; }
+// Non-temporal accesses pay off once X and C together no longer fit the 256 MB memory-side cache;
+// below that, keeping the lines cached is the better choice.  Measured crossover on MI355X:
+// cacheable wins at 8mn = 290 MB (7.2 vs 6.1 TB/s), non-temporal wins at 393 MB (6.1 vs 5.7 TB/s).
+inline bool use_nontemporal(int m, int n) { return 8.0 * (double)m * (double)n > 320.0 * 1024 * 1024; }
 template <bool FIRST>
 void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a) {
   const dim3 block(1024);
@@ -765,6 +771,7 @@ struct drot_handle_s {
   int continue_next = 0;  // the next solve resumes from the state the last one left
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
+  int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
   bool solved = false;
   int last_m = 0, last_n = 0;
   long long iters_done = 0;  // iterations applied to the state held by this handle
@@ -778,6 +785,10 @@ struct drot_handle_s {
   float *rowpart = nullptr, *colpart = nullptr, *gap_part = nullptr;
   float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
   size_t gbuf_len = 0;
+  // padded working copies of C and X (pitch rounded up to 32 elements), made when the caller's
+  // arrays do not start every row on a 128-byte line; grown on demand
+  float *cpad = nullptr, *xpad = nullptr;
+  size_t cpad_len = 0, xpad_len = 0;
   int* runbuf = nullptr;  // group-resident path: run_start[], run_len[] of the label runs
   size_t runbuf_len = 0;
   int max_runs = 0;       // rows of colpart available
@@ -818,6 +829,8 @@ void free_all(drot_handle h) {
   (void)hipFree(h->done);
   (void)hipFree(h->status);
   (void)hipFree(h->runbuf);
+  (void)hipFree(h->cpad);
+  (void)hipFree(h->xpad);
   if (h->host_status) (void)hipHostFree(h->host_status);
   for (auto& e : h->ev)
     if (e) (void)hipEventDestroy(e);
@@ -922,6 +935,12 @@ int drot_set_group_two_pass(drot_handle h, int enable) {
   return DROT_OK;
 }
 
+int drot_set_nontemporal(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 1) return DROT_ERR_INVALID_ARG;
+  h->nontemporal = mode;
+  return DROT_OK;
+}
+
 int drot_set_profile(drot_handle h, int enable) {
   if (!h) return DROT_ERR_INVALID_ARG;
   if (enable)
@@ -974,10 +993,26 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   // 1/(1 + rho*lambda) evaluated in fp64 from the fp32 inputs, rounded once
   const float qscale = (float)(1.0 / (1.0 + (double)rho * (double)lambda));
 
+  if (reinterpret_cast<uintptr_t>(X_out) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return DROT_ERR_INVALID_ARG;
   const int nseg = ceil_div(n, kSegCols);
   const int ntr = ceil_div(m, kTileRows);
   const int ntiles = nseg * ntr;
-  const bool nt = use_nontemporal(m, n);
+  const bool nt = h->nontemporal < 0 ? use_nontemporal(m, n) : h->nontemporal != 0;
+  // Rows that do not start on 128-byte lines are slow to stream: work on padded copies then.
+  const int ld_pad = ceil_div(n, kAlignElems) * kAlignElems;
+  const bool pad_c = (n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0);
+  const bool pad_x = (n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(X_out) % 128 != 0);
+  auto grow = [&](float** buf, size_t* len) -> int {
+    const size_t need = (size_t)m * (size_t)ld_pad;
+    if (*len >= need) return DROT_OK;
+    if (hipStreamSynchronize(stream) != hipSuccess) return DROT_ERR_HIP;
+    (void)hipFree(*buf);
+    *buf = nullptr;
+    *len = 0;
+    if (dev_alloc(buf, need) != DROT_OK) return DROT_ERR_ALLOC;
+    *len = need;
+    return DROT_OK;
+  };
   const int nbm = ceil_div(m, 64), nbn = ceil_div(n, 64);
 
   size_t ngroups = 0;
@@ -1042,8 +1077,28 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
   else hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
 
-  SweepArgs S{X_out, C, h->phi, h->varphi, h->rowpart, h->colpart, h->done,
-              m, n, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
+  const float* Cw = C;      // the arrays the kernels work on
+  float* Xw = X_out;
+  int ldc = n, ldx = n;
+  if (pad_c) {
+    const int rc = grow(&h->cpad, &h->cpad_len);
+    if (rc != DROT_OK) return rc;
+    Cw = h->cpad;
+    ldc = ld_pad;
+    DROT_HIP(hipMemcpy2DAsync(h->cpad, sizeof(float) * (size_t)ld_pad, C, sizeof(float) * (size_t)n,
+                              sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
+  }
+  if (pad_x) {
+    const int rc = grow(&h->xpad, &h->xpad_len);
+    if (rc != DROT_OK) return rc;
+    Xw = h->xpad;
+    ldx = ld_pad;
+    if (resume)  // the plan of the previous solve is in X_out (the contract of drot_set_continue)
+      DROT_HIP(hipMemcpy2DAsync(h->xpad, sizeof(float) * (size_t)ld_pad, X_out, sizeof(float) * (size_t)n,
+                                sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
+  }
+  SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, h->done,
+              m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
   GroupArgs G{S, row_class, h->gbuf, rho * mu};
   SlabArgs SL{S, h->runbuf, h->runbuf ? h->runbuf + nruns : nullptr, rho * mu};
   const dim3 slab_grid(ceil_div(n, kSlabCols), nruns > 0 ? nruns : 1);
@@ -1113,12 +1168,15 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     if (reg_kind == DROT_REG_GROUP_LASSO)
       hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((2 * ngroups + 255) / 256), 4)), dim3(256), 0, stream,
                          h->gbuf, 2 * ngroups, 0.f, (const int*)nullptr);
-    GapArgs GA{X_out, C, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, nseg, rho};
+    GapArgs GA{Xw, Cw, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, nseg, ldx, ldc, rho};
     hipLaunchKernelGGL(gap_kernel, grid, block, 0, stream, GA);
     hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(1024), 0, stream, V, (const float*)h->gap_part, ntiles,
                        (const float*)gx, (const float*)gw, ngroups, p, q, m, n, (double)rho, (int)reg_kind,
                        (double)lambda, (double)mu);
   }
+  if (pad_x && !(max_iters == 0 && !resume))
+    DROT_HIP(hipMemcpy2DAsync(X_out, sizeof(float) * (size_t)n, h->xpad, sizeof(float) * (size_t)ld_pad,
+                              sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   DROT_HIP(hipMemcpyAsync(&h->host_status[0], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
   DROT_HIP(hipStreamSynchronize(stream));
   DROT_HIP(hipGetLastError());

@@ -243,3 +243,27 @@ def test_group_lasso_label_out_of_range_is_rejected(drot):
     solver = drot.Solver(P.m, P.n)
     with pytest.raises(drot.DrotError):
         pu.gpu_solve(solver, P, 5)
+
+
+@pytest.mark.parametrize("xoff,coff", [(1, 1), (2, 0), (3, 1), (0, 3)])
+@pytest.mark.parametrize("m,n", [(70, 517), (131, 1022)])
+def test_unaligned_base_pointers(drot, oracle, m, n, xoff, coff):
+    # X_out and C handed over as views that start 4, 8 or 12 bytes past a 16-byte boundary
+    P = drot_inputs.random_problem(m, n, seed=500 + 7 * xoff + coff, reg_kind=1, lam=0.3)
+    _say(f"unaligned bases: X +{4 * xoff} B, C +{4 * coff} B, {m}x{n}")
+    dev = torch.device("cuda:0")
+    Cbuf = torch.zeros(m * n + 8, device=dev)
+    Xbuf = torch.full((m * n + 8,), 3.0, device=dev)
+    C = Cbuf[coff:coff + m * n].view(m, n)
+    C.copy_(torch.from_numpy(P.C))
+    X = Xbuf[xoff:xoff + m * n].view(m, n)
+    assert X.data_ptr() % 16 == 4 * xoff and C.data_ptr() % 16 == 4 * coff
+    solver = drot.Solver(m, n)
+    p, q = torch.from_numpy(P.p).to(dev), torch.from_numpy(P.q).to(dev)
+    res = solver.solve(C, p, q, reg_kind=P.reg_kind, lam=P.lam, max_iters=150, X_out=X)
+    phi, varphi = solver.duals(m, n, dev)
+    torch.cuda.synchronize()
+    ores = pu.oracle_solve(oracle, P, 150)
+    pu.assert_parity(oracle, P, res, X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores, label="unaligned")
+    # nothing outside the m*n window was touched
+    assert (Xbuf[:xoff] == 3.0).all() and (Xbuf[xoff + m * n:] == 3.0).all()
