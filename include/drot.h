@@ -117,6 +117,13 @@ int drot_set_group_two_pass(drot_handle h, int enable);
 int drot_set_nontemporal(drot_handle h, int mode);
 
 /*
+ * Fused vector update [-1 = automatic].  For small problems (at most 2048 rows and 4096 tiles of
+ * 32 x 256) the O(m+n) update of eq. (6) is computed at the head of the next sweep, so that an
+ * iteration is one kernel launch instead of three; mode 0 always runs the separate kernels.
+ */
+int drot_set_fused_update(drot_handle h, int mode);
+
+/*
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
  * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.

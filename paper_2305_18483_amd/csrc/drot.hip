@@ -135,10 +135,31 @@ struct SweepArgs {
   const float* varphi;
   float* rowpart;
   float* colpart;
+  float* tilesum;        // [ntr*nseg] total of every tile (only read by the fused vector update)
   const int* done;
   int m, n;
   int ldx, ldc;          // row pitch of X and of C in elements (n, or the padded working copies' pitch)
   float rho, scale;
+};
+
+// Inputs of the vector update when it is fused into the head of the next sweep (small problems):
+// the partial sums the previous sweep left and the eq. (6) state before / after the update.
+struct FusedUpdateArgs {
+  const float* rowpart_prev;
+  const float* colpart_prev;
+  const float* tilesum_prev;
+  const float* p;
+  const float* q;
+  const double* a_in;
+  const double* b_in;
+  double* a_out;
+  double* b_out;
+  const double* theta_in;
+  double* theta_out;
+  const double* sum_p;
+  float* phi_out;
+  float* varphi_out;
+  int nseg, ntr;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -184,18 +205,21 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
   }
 }
 
-template <bool FIRST, bool EDGE, bool NT>
-__device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr) {
+template <bool FIRST, bool EDGE, bool NT, bool PRO>
+__device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr,
+                                           const float* __restrict__ lds_phi, const float* __restrict__ lds_varphi) {
   constexpr int U = kSweepRows;
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int r0 = tr * kTileRows + wave * U;
   const int nrows = min(max(A.m - r0, 0), U);
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float wave_total = 0.f;
   if (nrows > 0) {
-    const f4v vp = load_varphi(A.varphi, j0, nvalid);
+    // with the fused update (PRO) phi and varphi of this tile were just computed into LDS
+    const f4v vp = PRO ? *reinterpret_cast<const f4v*>(lds_varphi + lane * 4) : load_varphi(A.varphi, j0, nvalid);
     // lane u holds phi of row r0 + u; rows read it back with a scalar lane read
-    const float phi_lane = (lane < nrows) ? A.phi[r0 + lane] : 0.f;
+    const float phi_lane = (lane < nrows) ? (PRO ? lds_phi[wave * U + lane] : A.phi[r0 + lane]) : 0.f;
     const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
     const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
     float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
@@ -228,21 +252,107 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
+        wave_total += tot;
       }
     }
     if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
   }
   write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  if (A.tilesum) {  // total of the tile, for the fused update of the next sweep
+    __shared__ float wt[kSweepWaves];
+    if (lane == 0) wt[wave] = wave_total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float tot = 0.f;
+#pragma unroll
+      for (int k = 0; k < kSweepWaves; ++k) tot += wt[k];
+      A.tilesum[tr * gridDim.x + seg] = tot;
+    }
+  }
 }
 
-template <bool FIRST, bool NT>
-__global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A) {
+// Vector update of eq. (6) for the 32 rows and 256 columns of one tile, computed redundantly by
+// every workgroup that needs them from the previous sweep's partial sums (worth it while the
+// partials are few: small m).  Same arithmetic as reduce_kernel + update_kernel; the workgroups
+// of the first tile column / tile row also store the new a, phi / b, varphi, workgroup (0,0)
+// the new theta.  Results land in LDS for the sweep that follows.
+__device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpdateArgs& F, int seg, int tr,
+                                             float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
+  __shared__ double red[64 * kSweepWaves];
+  const int t = threadIdx.x;
+  double acc = 0.0;
+  const int ntiles = F.nseg * F.ntr;
+  for (int e = t; e < ntiles; e += 64 * kSweepWaves) acc += (double)F.tilesum_prev[e];
+  const double sum_x = block_sum_f64(acc, red);
+  const double mn = (double)A.m + (double)A.n;
+  const double eta = (sum_x - *F.sum_p) / mn;
+  const double theta = *F.theta_in;
+  const double cst = 2.0 * eta - theta;
+  // columns: 4 groups of 256 threads split the row tiles.  The partials are summed in the order
+  // reduce_kernel uses (16 interleaved subsequences, then a fixed tree), so that both ways of
+  // doing the update give the same bits.
+  const int sub = t >> 8, cidx = t & 255;
+  const int j = seg * kSegCols + cidx;
+  double sj = 0.0;
+  if (j < A.n) {
+    double q4[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int k = sub, w = 0; k < F.ntr; k += 4, w = (w + 1) & 3) q4[w] += (double)F.colpart_prev[(size_t)k * A.n + j];
+    sj = (q4[0] + q4[2]) + (q4[1] + q4[3]);  // residues sub, sub+8 | sub+4, sub+12
+  }
+  red[t] = sj;
+  __syncthreads();
+  if (t < kSegCols) {
+    float out = kMaskedOut;
+    if (j < A.n) {
+      const double res = (red[t] + red[512 + t]) + (red[256 + t] + red[768 + t]) - (double)F.q[j];
+      const double bj = F.b_in[j];
+      out = (float)((bj - 2.0 * res + cst) / (double)A.m);
+      if (tr == 0) {
+        F.b_out[j] = bj - res;
+        F.varphi_out[j] = out;
+      }
+    }
+    lds_varphi[t] = out;
+  } else if (t < kSegCols + kTileRows) {
+    const int l = t - kSegCols;
+    const int i = tr * kTileRows + l;
+    float out = 0.f;
+    if (i < A.m) {
+      double q16[16];
+#pragma unroll
+      for (int w = 0; w < 16; ++w) q16[w] = 0.0;
+      for (int k0 = 0; k0 < F.nseg; k0 += 16) {
+#pragma unroll
+        for (int w = 0; w < 16; ++w)
+          if (k0 + w < F.nseg) q16[w] += (double)F.rowpart_prev[(size_t)(k0 + w) * A.m + i];
+      }
+      double ri = (((q16[0] + q16[8]) + (q16[4] + q16[12])) + ((q16[2] + q16[10]) + (q16[6] + q16[14]))) +
+                  (((q16[1] + q16[9]) + (q16[5] + q16[13])) + ((q16[3] + q16[11]) + (q16[7] + q16[15])));
+      ri -= (double)F.p[i];
+      const double ai = F.a_in[i];
+      out = (float)((ai - 2.0 * ri + cst) / (double)A.n);
+      if (seg == 0) {
+        F.a_out[i] = ai - ri;
+        F.phi_out[i] = out;
+      }
+    }
+    lds_phi[l] = out;
+  }
+  if (seg == 0 && tr == 0 && t == 0) *F.theta_out = theta - eta;
+  __syncthreads();
+}
+
+template <bool FIRST, bool NT, bool PRO>
+__global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, FusedUpdateArgs F) {
   if (*A.done) return;
+  __shared__ float lds_phi[kTileRows];
+  __shared__ float lds_varphi[kSegCols];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT>(A, lane, wave, seg, tr);
-  else sweep_body<FIRST, true, false>(A, lane, wave, seg, tr);
+  if (PRO) fused_update(A, F, seg, tr, lds_phi, lds_varphi);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, false, PRO>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -453,6 +563,7 @@ struct VecState {
   double* a;
   double* b;
   double* theta;   // [2], indexed by iteration parity
+  double* sum_p;   // [1] sum of p
   double* r;       // [m] row residuals X 1 - p of the last sweep
   double* s;       // [n] column residuals
   double* part;    // [2][nbm + nbn]: per-workgroup sum of residuals, sum of squared residuals
@@ -481,6 +592,7 @@ __global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __r
   }
   const double sum_p = block_sum_f64(sp, red);
   if (t == 0) {
+    *V.sum_p = sum_p;
     V.theta[0] = ((double)m * (double)n * (phi0 + varphi0) - sum_p) / mn;
     V.theta[1] = 0.0;
     *V.done = 0;
@@ -558,6 +670,12 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
 // ------------------------------------------------------------------------------------------
 struct UpdateArgs {
   VecState V;
+  const float* tilesum;  // non-null: eta from the tile totals, exactly as the fused update computes it
+  int ntiles;
+  const double* a_in;  // a, b before the update and after it (the two halves of a double buffer)
+  const double* b_in;
+  double* a_out;
+  double* b_out;
   int m, n, nbm, nbn, par;
 };
 
@@ -566,22 +684,27 @@ __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
   __shared__ double red[kReduceThreads];
   const int t = threadIdx.x;
   double acc = 0.0;
-  for (int e = t; e < A.nbm; e += kReduceThreads) acc += A.V.part[e];
-  const double sum_r = block_sum_f64(acc, red);
+  if (A.tilesum) {
+    for (int e = t; e < A.ntiles; e += kReduceThreads) acc += (double)A.tilesum[e];
+  } else {
+    for (int e = t; e < A.nbm; e += kReduceThreads) acc += A.V.part[e];
+  }
+  double sum_r = block_sum_f64(acc, red);
+  if (A.tilesum) sum_r -= *A.V.sum_p;
   const double mn = (double)A.m + (double)A.n;
   const double eta = sum_r / mn;
   const double theta = A.V.theta[A.par];
   const double cst = 2.0 * eta - theta;
   const long long g = (long long)blockIdx.x * kReduceThreads + t;
   if (g < A.m) {
-    const double r = A.V.r[g], ai = A.V.a[g];
+    const double r = A.V.r[g], ai = A.a_in[g];
     A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
-    A.V.a[g] = ai - r;
+    A.a_out[g] = ai - r;
   } else if (g < (long long)A.m + A.n) {
     const long long j = g - A.m;
-    const double sj = A.V.s[j], bj = A.V.b[j];
+    const double sj = A.V.s[j], bj = A.b_in[j];
     A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
-    A.V.b[j] = bj - sj;
+    A.b_out[j] = bj - sj;
   }
   if (blockIdx.x == 0) {
     double r2 = 0.0, s2 = 0.0;
@@ -772,6 +895,7 @@ struct drot_handle_s {
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
+  int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
   bool solved = false;
   int last_m = 0, last_n = 0;
   long long iters_done = 0;  // iterations applied to the state held by this handle
@@ -781,8 +905,11 @@ struct drot_handle_s {
   double prof_sweep_ms = 0.0;
   // device workspace
   float *phi = nullptr, *varphi = nullptr;
-  double *a = nullptr, *b = nullptr, *theta = nullptr, *r = nullptr, *s = nullptr, *part = nullptr, *resid = nullptr;
-  float *rowpart = nullptr, *colpart = nullptr, *gap_part = nullptr;
+  // a, b, rowpart, colpart, tilesum are double buffers (two halves), indexed by iteration parity
+  double *a = nullptr, *b = nullptr, *theta = nullptr, *sum_p = nullptr, *r = nullptr, *s = nullptr, *part = nullptr,
+         *resid = nullptr;
+  float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
+  size_t rowpart_half = 0, colpart_half = 0, tilesum_half = 0;
   float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
   size_t gbuf_len = 0;
   // padded working copies of C and X (pitch rounded up to 32 elements), made when the caller's
@@ -822,8 +949,8 @@ int dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(drot_handle h) {
-  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->gap_part, h->gbuf};
-  double* dbufs[] = {h->a, h->b, h->theta, h->r, h->s, h->part, h->resid};
+  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf};
+  double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid};
   for (float* b : fbufs) (void)hipFree(b);
   for (double* b : dbufs) (void)hipFree(b);
   (void)hipFree(h->done);
@@ -872,15 +999,20 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   auto take = [&](int r) { if (rc == DROT_OK) rc = r; };
   take(dev_alloc(&h->phi, (size_t)max_m));
   take(dev_alloc(&h->varphi, (size_t)max_n + 4));
-  take(dev_alloc(&h->a, (size_t)max_m));
-  take(dev_alloc(&h->b, (size_t)max_n));
+  take(dev_alloc(&h->a, 2 * (size_t)max_m));
+  take(dev_alloc(&h->b, 2 * (size_t)max_n));
   take(dev_alloc(&h->theta, 2));
+  take(dev_alloc(&h->sum_p, 1));
   take(dev_alloc(&h->r, (size_t)max_m));
   take(dev_alloc(&h->s, (size_t)max_n));
   take(dev_alloc(&h->part, 2 * nb));
   take(dev_alloc(&h->resid, 2));
-  take(dev_alloc(&h->rowpart, (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m));  // 64-column strips (group-resident path) are the finest
-  take(dev_alloc(&h->colpart, ntr * (size_t)max_n));
+  h->rowpart_half = (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m;  // 64-column strips (group-resident path) are the finest
+  h->colpart_half = ntr * (size_t)max_n;
+  h->tilesum_half = nseg * ntr;
+  take(dev_alloc(&h->rowpart, 2 * h->rowpart_half));
+  take(dev_alloc(&h->colpart, 2 * h->colpart_half));
+  take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
   h->max_runs = (int)ntr;
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));
   take(dev_alloc(&h->done, 1));
@@ -938,6 +1070,12 @@ int drot_set_group_two_pass(drot_handle h, int enable) {
 int drot_set_nontemporal(drot_handle h, int mode) {
   if (!h || mode < -1 || mode > 1) return DROT_ERR_INVALID_ARG;
   h->nontemporal = mode;
+  return DROT_OK;
+}
+
+int drot_set_fused_update(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 0) return DROT_ERR_INVALID_ARG;
+  h->fused_update = mode;
   return DROT_OK;
 }
 
@@ -1072,7 +1210,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     }
   }
 
-  VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->r, h->s, h->part, h->resid, h->done, h->status};
+  VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid, h->done, h->status};
   const long long k_base = resume ? h->iters_done : 0;
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
   else hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
@@ -1097,7 +1235,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
       DROT_HIP(hipMemcpy2DAsync(h->xpad, sizeof(float) * (size_t)ld_pad, X_out, sizeof(float) * (size_t)n,
                                 sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   }
-  SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, h->done,
+  SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, nullptr, h->done,
               m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
   GroupArgs G{S, row_class, h->gbuf, rho * mu};
   SlabArgs SL{S, h->runbuf, h->runbuf ? h->runbuf + nruns : nullptr, rho * mu};
@@ -1106,7 +1244,20 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   // group-resident path, per 64-column strip and label run
   ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, slab_k ? ceil_div(n, kSlabCols) : nseg,
                 slab_k ? nruns : ntr, nbm, nbn};
-  UpdateArgs UA{V, m, n, nbm, nbn, 0};
+  UpdateArgs UA{V, nullptr, 0, nullptr, nullptr, nullptr, nullptr, m, n, nbm, nbn, 0};
+  // Small problems: the vector update of iteration s-1 is computed at the head of sweep s by every
+  // workgroup for its own rows and columns (one launch per iteration instead of three); the
+  // separate reduce + update kernels then run only where the state must be complete in memory:
+  // before a residual check and at the end.
+  // (eta comes from the tile totals whenever the problem is small enough for that path, whether or
+  // not the fusion is switched on, so that both settings produce the same bits)
+  const bool small = reg_kind != DROT_REG_GROUP_LASSO && ntr <= 64 && ntiles <= 4096;
+  const bool fused = small && h->fused_update != 0;
+  auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
+  auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
+  auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
+  auto colp = [&](long long g) { return h->colpart + (size_t)(g & 1) * h->colpart_half; };
+  auto tsum = [&](long long g) { return h->tilesum + (size_t)(g & 1) * h->tilesum_half; };
   const dim3 grid(nseg, ntr), block(kBlock), sweep_block(64 * kSweepWaves);
   const dim3 update_grid(ceil_div(m + n, kReduceThreads));
 
@@ -1116,12 +1267,17 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   const bool checking = tol > 0.f;
   int k = 0, slot = 0, checks = 0;
   bool converged = false;
+  bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
   while (k < max_iters && !converged) {
     const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
     for (int c = 0; c < chunk; ++c, ++k) {
-      const bool first = (k_base + k == 0);
+      const long long sw = k_base + k + 1;  // this sweep produces X_sw; its sums live in the sw-parity buffers
+      const bool first = (sw == 1);
       const bool timed = h->profile && k < kMaxProfiled;
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
+      S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
+      S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
+      S.tilesum = small ? tsum(sw) : nullptr;
       if (slab_k) {
         launch_slab(first, slab_k, slab_grid, stream, SL);
       } else if (reg_kind == DROT_REG_GROUP_LASSO) {
@@ -1134,17 +1290,38 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
           hipLaunchKernelGGL(gl_norm_kernel<false>, grid, block, 0, stream, G);
           hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
         }
+      } else if (!materialized) {
+        // update sw-1 (from the sums of X_{sw-1} and the state of generation sw-2) rides along
+        const FusedUpdateArgs F{rowp(sw - 1), colp(sw - 1), tsum(sw - 1), p, q, a_buf(sw - 2), b_buf(sw - 2),
+                                a_buf(sw - 1), b_buf(sw - 1), h->theta + ((sw - 2) & 1), h->theta + ((sw - 1) & 1),
+                                h->sum_p, h->phi, h->varphi, nseg, ntr};
+        if (nt) hipLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, S, F);
+        else hipLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, S, F);
       } else if (first) {
-        hipLaunchKernelGGL((sweep_kernel<true, false>), grid, sweep_block, 0, stream, S);
+        hipLaunchKernelGGL((sweep_kernel<true, false, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
       } else if (nt) {
-        hipLaunchKernelGGL((sweep_kernel<false, true>), grid, sweep_block, 0, stream, S);
+        hipLaunchKernelGGL((sweep_kernel<false, true, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
       } else {
-        hipLaunchKernelGGL((sweep_kernel<false, false>), grid, sweep_block, 0, stream, S);
+        hipLaunchKernelGGL((sweep_kernel<false, false, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
       }
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k + 1], stream));
-      UA.par = (int)((k_base + k) & 1);
-      hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
-      hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
+      if (!fused || c == chunk - 1) {
+        // complete the state in memory: update sw from the sums of X_sw
+        RA.rowpart = rowp(sw);
+        RA.colpart = colp(sw);
+        UA.a_in = a_buf(sw - 1);
+        UA.b_in = b_buf(sw - 1);
+        UA.a_out = a_buf(sw);
+        UA.b_out = b_buf(sw);
+        UA.par = (int)((sw - 1) & 1);
+        UA.tilesum = small ? tsum(sw) : nullptr;
+        UA.ntiles = ntiles;
+        hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
+        hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
+        materialized = true;
+      } else {
+        materialized = false;
+      }
     }
     if (checking) {
       // the test runs on the device; the host reads it one chunk late so the queue never drains

@@ -267,3 +267,22 @@ def test_unaligned_base_pointers(drot, oracle, m, n, xoff, coff):
     pu.assert_parity(oracle, P, res, X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores, label="unaligned")
     # nothing outside the m*n window was touched
     assert (Xbuf[:xoff] == 3.0).all() and (Xbuf[xoff + m * n:] == 3.0).all()
+
+
+@pytest.mark.parametrize("m,n,kind", [(333, 517, 1), (1000, 1000, 0), (2048, 300, 1)])
+def test_fused_and_separate_vector_updates_give_the_same_bits(drot, oracle, m, n, kind):
+    # small problems fold the eq. (6) update into the next sweep; both ways must agree exactly,
+    # whatever the spacing of the residual checks
+    P = drot_inputs.random_problem(m, n, seed=600 + m, reg_kind=kind, lam=0.2 if kind else 0.0)
+    _say(f"fused vs separate update {m}x{n}")
+    solver = drot.Solver(m, n)
+    _, X_fused, phi_fused, varphi_fused = pu.gpu_solve(solver, P, 120)
+    solver.set_fused_update(0)
+    _, X_sep, phi_sep, varphi_sep = pu.gpu_solve(solver, P, 120)
+    solver.set_fused_update(-1)
+    assert np.array_equal(X_fused, X_sep) and np.array_equal(phi_fused, phi_sep) and np.array_equal(varphi_fused, varphi_sep)
+    solver.set_check_every(7)
+    res, X_chk, phi_chk, _ = pu.gpu_solve(solver, P, 120, tol=1e-12)  # checks every 7 iterations, never passes
+    assert res.iters == 120 and np.array_equal(X_chk, X_fused) and np.array_equal(phi_chk, phi_fused)
+    ores = pu.oracle_solve(oracle, P, 120)
+    pu.assert_parity(oracle, P, res, X_chk, phi_chk, varphi_fused, ores, check_gap=False, label="fused")
