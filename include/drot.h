@@ -124,6 +124,17 @@ int drot_set_nontemporal(drot_handle h, int mode);
 int drot_set_fused_update(drot_handle h, int mode);
 
 /*
+ * Even/odd cost skipping [off] (Section "Quadratically Regularized DROT" of the paper's GPU
+ * appendix).  When enabled, sweeps pair up: the first of a pair stores X - rho*C, the second reads
+ * that and needs no C, so C is read every second sweep (20 instead of 24 bytes per element and
+ * pair).  Row and column sums are always those of X itself, and X_out is the plain plan on return
+ * and at every residual check.  The rounding differs slightly from the plain scheme (same
+ * tolerance against the fp64 iteration).  Applies to the none/quadratic sweeps of problems too
+ * large for the fused small-problem path; ignored otherwise.
+ */
+int drot_set_skip_cost(drot_handle h, int enable);
+
+/*
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
  * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.

@@ -205,7 +205,10 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
   }
 }
 
-template <bool FIRST, bool EDGE, bool NT, bool PRO>
+// MODE selects the paper's even/odd scheme (Section "Quadratically Regularized DROT"): 0 = plain
+// (read X and C, store X); 1 = read X and C, store X - rho*C; 2 = read the shifted X only (no C)
+// and store the plain X.  A 1-sweep followed by a 2-sweep moves 20 bytes per element instead of 24.
+template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE>
 __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr,
                                            const float* __restrict__ lds_phi, const float* __restrict__ lds_varphi) {
   constexpr int U = kSweepRows;
@@ -228,7 +231,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
     if (nrows == U) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+        c[u] = MODE == 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
         x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
       }
     } else {
@@ -237,7 +240,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
         c[u] = f4v{0.f, 0.f, 0.f, 0.f};
         x[u] = f4v{0.f, 0.f, 0.f, 0.f};
         if (u < nrows) {
-          c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+          if (MODE != 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
           if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
         }
       }
@@ -247,8 +250,18 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
     for (int u = 0; u < U; ++u) {
       if (u < nrows) {
         const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
+        // (in MODE 2 the stored value already carries - rho*C and c is zero)
         const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
-        st4<EDGE, NT>(Xp + u * ldx, v, nvalid);
+        if (MODE == 1) {
+          f4v sh;
+          sh.x = fmaf(-rho, c[u].x, v.x);
+          sh.y = fmaf(-rho, c[u].y, v.y);
+          sh.z = fmaf(-rho, c[u].z, v.z);
+          sh.w = fmaf(-rho, c[u].w, v.w);
+          st4<EDGE, NT>(Xp + u * ldx, sh, nvalid);
+        } else {
+          st4<EDGE, NT>(Xp + u * ldx, v, nvalid);
+        }
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
@@ -342,7 +355,7 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   __syncthreads();
 }
 
-template <bool FIRST, bool NT, bool PRO>
+template <bool FIRST, bool NT, bool PRO, int MODE = 0>
 __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, FusedUpdateArgs F) {
   if (*A.done) return;
   __shared__ float lds_phi[kTileRows];
@@ -351,8 +364,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
   if (PRO) fused_update(A, F, seg, tr, lds_phi, lds_varphi);
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
-  else sweep_body<FIRST, true, false, PRO>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, false, PRO, MODE>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -896,6 +909,7 @@ struct drot_handle_s {
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
+  int skip_cost = 0;      // even/odd scheme: C is read only every second sweep
   bool solved = false;
   int last_m = 0, last_n = 0;
   long long iters_done = 0;  // iterations applied to the state held by this handle
@@ -1079,6 +1093,12 @@ int drot_set_fused_update(drot_handle h, int mode) {
   return DROT_OK;
 }
 
+int drot_set_skip_cost(drot_handle h, int enable) {
+  if (!h) return DROT_ERR_INVALID_ARG;
+  h->skip_cost = enable ? 1 : 0;
+  return DROT_OK;
+}
+
 int drot_set_profile(drot_handle h, int enable) {
   if (!h) return DROT_ERR_INVALID_ARG;
   if (enable)
@@ -1253,6 +1273,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   // not the fusion is switched on, so that both settings produce the same bits)
   const bool small = reg_kind != DROT_REG_GROUP_LASSO && ntr <= 64 && ntiles <= 4096;
   const bool fused = small && h->fused_update != 0;
+  const bool skip_cost = h->skip_cost && reg_kind != DROT_REG_GROUP_LASSO && !fused;
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
   auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
@@ -1297,12 +1318,27 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
                                 h->sum_p, h->phi, h->varphi, nseg, ntr};
         if (nt) hipLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, S, F);
         else hipLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, S, F);
-      } else if (first) {
-        hipLaunchKernelGGL((sweep_kernel<true, false, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
-      } else if (nt) {
-        hipLaunchKernelGGL((sweep_kernel<false, true, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
       } else {
-        hipLaunchKernelGGL((sweep_kernel<false, false, false>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
+        // even/odd scheme: inside a chunk the sweeps pair up as (store X - rho*C, then read it
+        // without C); an odd chunk starts with one plain sweep, so X is plain at every chunk end
+        int mode = 0;
+        if (skip_cost) {
+          const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
+          if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
+        }
+        const FusedUpdateArgs none{};
+        if (first) {
+          if (mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, S, none);
+          else hipLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, S, none);
+        } else if (nt) {
+          if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, S, none);
+          else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, S, none);
+          else hipLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, S, none);
+        } else {
+          if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, S, none);
+          else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, S, none);
+          else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, S, none);
+        }
       }
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k + 1], stream));
       if (!fused || c == chunk - 1) {

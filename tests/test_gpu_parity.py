@@ -286,3 +286,31 @@ def test_fused_and_separate_vector_updates_give_the_same_bits(drot, oracle, m, n
     assert res.iters == 120 and np.array_equal(X_chk, X_fused) and np.array_equal(phi_chk, phi_fused)
     ores = pu.oracle_solve(oracle, P, 120)
     pu.assert_parity(oracle, P, res, X_chk, phi_chk, varphi_fused, ores, check_gap=False, label="fused")
+
+
+@pytest.mark.parametrize("K,check_every", [(150, 100), (151, 100), (37, 7)])
+@pytest.mark.parametrize("kind", [0, 1])
+def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
+    # C is read every second sweep (the first sweep of a pair stores X - rho*C); the result must
+    # still match the fp64 iteration within the same tolerance, for odd and even iteration counts
+    P = drot_inputs.random_problem(700, 1300, seed=700 + K, reg_kind=kind, lam=0.3 if kind else 0.0)
+    solver = drot.Solver(P.m, P.n, check_every=check_every)
+    solver.set_fused_update(0)  # the scheme applies to the unfused sweep
+    solver.set_skip_cost(True)
+    _say(f"even/odd K={K} check_every={check_every} kind={kind}")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, K, tol=1e-12)  # residual checks active, never pass
+    assert gres.iters == K
+    ores = pu.oracle_solve(oracle, P, K)
+    ratio = pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="even/odd")
+    _say(f"even/odd: plan error / scale = {ratio:.2e}")
+
+
+def test_even_odd_full_size_sampled(drot, oracle):
+    # 10000 x 10000 (the unfused, non-temporal launch configuration the benchmark times)
+    P = drot_inputs.config(3)
+    solver = drot.Solver(P.m, P.n)
+    solver.set_skip_cost(True)
+    _say("even/odd at 10000 x 10000, K=25")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 25)
+    ores = pu.oracle_solve(oracle, P, 25)
+    pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="even/odd cfg3")
