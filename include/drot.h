@@ -166,6 +166,21 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
                float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,
                int max_iters, float tol, float* X_out, void* stream);
 
+/*
+ * Warm start: like drot_solve, but the iteration starts from a caller-supplied point instead of
+ * X_0 = 0 and the constants of the Initialization paragraph (which the paper offers as one choice;
+ * the iteration converges from any start).  On entry X_inout holds X_0 (m*n, entries >= 0) and
+ * phi0[m], varphi0[n] (DEVICE, read only) hold phi_0, varphi_0; the iteration starts at
+ * Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T (eq. (5)).  On return X_inout holds the new plan.  Feeding
+ * back the X_out, phi, varphi of an earlier solve continues that solve (to rounding); potentials
+ * of a related problem give a head start (the paper's remark on better dual initialisations).
+ * Costs one extra read of X.  Errors as drot_solve, plus INVALID_ARG for null phi0 / varphi0.
+ */
+int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* q, int m, int n,
+                    float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,
+                    int max_iters, float tol, float* X_inout, const float* phi0, const float* varphi0,
+                    void* stream);
+
 /* Results of the last solve (host struct).  NOT_INITIALIZED if no solve has run. */
 int drot_get_info(drot_handle h, drot_info* out);
 

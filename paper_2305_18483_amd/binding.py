@@ -23,7 +23,7 @@ DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
-    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_solve", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_solve", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
 )
 
 
@@ -70,6 +70,7 @@ def load_library() -> ctypes.CDLL:
     lib.drot_set_profile.argtypes = [vp, ci]
     lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.drot_solve.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp]
+    lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_get_info.argtypes = [vp, ctypes.POINTER(drot_info)]
     lib.drot_get_duals.argtypes = [vp, vp, vp]
     lib.drot_strerror.argtypes = [ci]
@@ -173,22 +174,31 @@ class Solver:
               reg_kind: int = DROT_REG_NONE, lam: float = 0.0, mu: float = 0.0,
               row_class: Optional[torch.Tensor] = None, num_classes: int = 0, max_iters: int = 1000,
               tol: float = 0.0, X_out: Optional[torch.Tensor] = None,
-              stream: Optional[torch.cuda.Stream] = None) -> SolveResult:
-        """drot_solve; raises DrotError on a negative return code."""
+              stream: Optional[torch.cuda.Stream] = None, phi0: Optional[torch.Tensor] = None,
+              varphi0: Optional[torch.Tensor] = None) -> SolveResult:
+        """drot_solve (or drot_solve_warm when phi0 and varphi0 are given: X_out then holds X_0 on entry);
+        raises DrotError on a negative return code."""
         m, n = C.shape
+        warm = phi0 is not None or varphi0 is not None
         if X_out is None:
+            if warm:
+                raise ValueError("a warm start needs X_out holding the starting plan")
             X_out = torch.empty_like(C)
         params = drot_reg_params(float(lam), float(mu), int(num_classes),
                                  None if row_class is None else row_class.data_ptr())
         if row_class is not None:
             _ptr(row_class, torch.int32, "row_class")
         stream = stream if stream is not None else torch.cuda.current_stream(C.device)
-        rc = self._lib.drot_solve(self._h, _ptr(C, torch.float32, "C"), _ptr(p, torch.float32, "p"),
-                                  _ptr(q, torch.float32, "q"), int(m), int(n), float(stepsize), int(reg_kind),
-                                  ctypes.byref(params), int(max_iters), float(tol),
-                                  _ptr(X_out, torch.float32, "X_out"), ctypes.c_void_p(stream.cuda_stream))
+        common = (self._h, _ptr(C, torch.float32, "C"), _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"),
+                  int(m), int(n), float(stepsize), int(reg_kind), ctypes.byref(params), int(max_iters), float(tol),
+                  _ptr(X_out, torch.float32, "X_out"))
+        if warm:
+            rc = self._lib.drot_solve_warm(*common, _ptr(phi0, torch.float32, "phi0"),
+                                           _ptr(varphi0, torch.float32, "varphi0"), ctypes.c_void_p(stream.cuda_stream))
+        else:
+            rc = self._lib.drot_solve(*common, ctypes.c_void_p(stream.cuda_stream))
         if rc < 0:
-            raise DrotError(rc, "drot_solve")
+            raise DrotError(rc, "drot_solve_warm" if warm else "drot_solve")
         info = self.info()
         return SolveResult(X=X_out, code=rc, iters=info.iters, converged=bool(info.converged), r_row=info.r_row,
                            r_col=info.r_col, objective=info.objective, gap=info.gap, dual_res=info.dual_res)

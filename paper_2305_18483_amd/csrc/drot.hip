@@ -208,6 +208,7 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
 // MODE selects the paper's even/odd scheme (Section "Quadratically Regularized DROT"): 0 = plain
 // (read X and C, store X); 1 = read X and C, store X - rho*C; 2 = read the shifted X only (no C)
 // and store the plain X.  A 1-sweep followed by a 2-sweep moves 20 bytes per element instead of 24.
+// MODE 3 only forms the row and column sums of X as it stands (no update, no store): the warm start.
 template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE>
 __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr,
                                            const float* __restrict__ lds_phi, const float* __restrict__ lds_varphi) {
@@ -231,7 +232,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
     if (nrows == U) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        c[u] = MODE == 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+        c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
         x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
       }
     } else {
@@ -240,7 +241,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
         c[u] = f4v{0.f, 0.f, 0.f, 0.f};
         x[u] = f4v{0.f, 0.f, 0.f, 0.f};
         if (u < nrows) {
-          if (MODE != 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+          if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
           if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
         }
       }
@@ -251,8 +252,10 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
       if (u < nrows) {
         const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
         // (in MODE 2 the stored value already carries - rho*C and c is zero)
-        const f4v v = xbar4(x[u], c[u], vp + ph, rho) * scale;
-        if (MODE == 1) {
+        const f4v v = MODE == 3 ? x[u] : xbar4(x[u], c[u], vp + ph, rho) * scale;
+        if (MODE == 3) {
+          // sums only
+        } else if (MODE == 1) {
           f4v sh;
           sh.x = fmaf(-rho, c[u].x, v.x);
           sh.y = fmaf(-rho, c[u].y, v.y);
@@ -617,6 +620,42 @@ __global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __r
 __global__ void reset_kernel(VecState V) {
   *V.done = 0;
   *V.status = DeviceStatus{};
+}
+
+// Warm start: state of eq. (6) for a caller-supplied starting point (X_0, phi_0, varphi_0), i.e.
+// Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T (eq. (5)): a_0 = Y_0 1 - p = (X_0 1 - p) + n phi_0 + (1^T varphi_0) 1,
+// b_0 = (X_0^T 1 - q) + m varphi_0 + (1^T phi_0) 1, theta_0 = 1^T a_0 / (m+n).  The residuals
+// X_0 1 - p and X_0^T 1 - q come from reduce_kernel (V.r, V.s).  One workgroup.
+__global__ __launch_bounds__(1024) void warm_init_kernel(VecState V, const float* __restrict__ p,
+                                                         const float* __restrict__ phi0,
+                                                         const float* __restrict__ varphi0, int m, int n) {
+  __shared__ double red[1024];
+  const int t = threadIdx.x;
+  double sp = 0.0, sphi = 0.0, svarphi = 0.0;
+  for (int i = t; i < m; i += blockDim.x) { sp += (double)p[i]; sphi += (double)phi0[i]; }
+  for (int j = t; j < n; j += blockDim.x) svarphi += (double)varphi0[j];
+  sp = block_sum_f64(sp, red);
+  sphi = block_sum_f64(sphi, red);
+  svarphi = block_sum_f64(svarphi, red);
+  double sa = 0.0;
+  for (int i = t; i < m; i += blockDim.x) {
+    const double f = (double)phi0[i];
+    const double ai = V.r[i] + (double)n * f + svarphi;
+    V.a[i] = ai;
+    V.phi[i] = phi0[i];
+    sa += ai;
+  }
+  for (int j = t; j < n; j += blockDim.x) {
+    const double f = (double)varphi0[j];
+    V.b[j] = V.s[j] + (double)m * f + sphi;
+    V.varphi[j] = varphi0[j];
+  }
+  sa = block_sum_f64(sa, red);
+  if (t == 0) {
+    *V.sum_p = sp;
+    V.theta[0] = sa / ((double)m + (double)n);
+    V.theta[1] = 0.0;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1119,10 +1158,11 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed) {
   return DROT_OK;
 }
 
-int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
-               drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
-               float* X_out, void* stream_v) {
+static int solve_impl(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
+                      drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
+                      float* X_out, const float* phi0, const float* varphi0, bool warm, void* stream_v) {
   if (!h || !C || !p || !q || !X_out) return DROT_ERR_INVALID_ARG;
+  if (warm && (!phi0 || !varphi0)) return DROT_ERR_INVALID_ARG;
   if (m < 1 || n < 1 || m > h->max_m || n > h->max_n || max_iters < 0) return DROT_ERR_INVALID_ARG;
   if (reg_kind != DROT_REG_NONE && reg_kind != DROT_REG_QUADRATIC && reg_kind != DROT_REG_GROUP_LASSO)
     return DROT_ERR_INVALID_ARG;
@@ -1144,7 +1184,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   int cur_dev = -1;
   DROT_HIP(hipGetDevice(&cur_dev));
   if (cur_dev != h->device) return DROT_ERR_INVALID_ARG;  // the workspace lives on the creating device
-  const bool resume = h->continue_next != 0;
+  const bool resume = h->continue_next != 0 && !warm;
   if (resume && (!h->solved || m != h->last_m || n != h->last_n)) return DROT_ERR_INVALID_ARG;
   hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
   const float rho = stepsize > 0.f ? stepsize : 2.0f / (float)(m + n);
@@ -1233,7 +1273,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   VecState V{h->phi, h->varphi, h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid, h->done, h->status};
   const long long k_base = resume ? h->iters_done : 0;
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
-  else hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
+  else if (!warm) hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, V, p, q, m, n);
 
   const float* Cw = C;      // the arrays the kernels work on
   float* Xw = X_out;
@@ -1251,7 +1291,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     if (rc != DROT_OK) return rc;
     Xw = h->xpad;
     ldx = ld_pad;
-    if (resume)  // the plan of the previous solve is in X_out (the contract of drot_set_continue)
+    if (resume || warm)  // the plan to start from is in X_out
       DROT_HIP(hipMemcpy2DAsync(h->xpad, sizeof(float) * (size_t)ld_pad, X_out, sizeof(float) * (size_t)n,
                                 sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   }
@@ -1282,7 +1322,22 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   const dim3 grid(nseg, ntr), block(kBlock), sweep_block(64 * kSweepWaves);
   const dim3 update_grid(ceil_div(m + n, kReduceThreads));
 
-  if (max_iters == 0 && !resume)
+  if (warm) {
+    // sums of X_0 (a sweep that only adds up), residuals, then the eq. (6) state of the starting point
+    hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, V);
+    S.rowpart = rowp(0);
+    S.colpart = colp(0);
+    hipLaunchKernelGGL((sweep_kernel<false, false, false, 3>), grid, sweep_block, 0, stream, S, FusedUpdateArgs{});
+    RA.rowpart = rowp(0);
+    RA.colpart = colp(0);
+    RA.nseg = nseg;
+    RA.ntr = ntr;
+    hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
+    hipLaunchKernelGGL(warm_init_kernel, dim3(1), dim3(1024), 0, stream, V, p, phi0, varphi0, m, n);
+    RA.nseg = slab_k ? ceil_div(n, kSlabCols) : nseg;
+    RA.ntr = slab_k ? nruns : ntr;
+  }
+  if (max_iters == 0 && !resume && !warm)
     hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, X_out, (size_t)m * n, 0.f, (const int*)nullptr);
 
   const bool checking = tol > 0.f;
@@ -1293,7 +1348,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
     const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
     for (int c = 0; c < chunk; ++c, ++k) {
       const long long sw = k_base + k + 1;  // this sweep produces X_sw; its sums live in the sw-parity buffers
-      const bool first = (sw == 1);
+      const bool first = (sw == 1) && !warm;  // X_0 = 0: nothing to read
       const bool timed = h->profile && k < kMaxProfiled;
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
@@ -1387,7 +1442,7 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
                        (const float*)gx, (const float*)gw, ngroups, p, q, m, n, (double)rho, (int)reg_kind,
                        (double)lambda, (double)mu);
   }
-  if (pad_x && !(max_iters == 0 && !resume))
+  if (pad_x && !(max_iters == 0 && !resume && !warm))
     DROT_HIP(hipMemcpy2DAsync(X_out, sizeof(float) * (size_t)n, h->xpad, sizeof(float) * (size_t)ld_pad,
                               sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   DROT_HIP(hipMemcpyAsync(&h->host_status[0], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
@@ -1420,6 +1475,20 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
   h->last_n = n;
   if (checking && !st.converged) return DROT_MAX_ITERS;
   return DROT_OK;
+}
+
+int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
+               drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
+               float* X_out, void* stream) {
+  return solve_impl(h, C, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_out, nullptr, nullptr, false,
+                    stream);
+}
+
+int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
+                    drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
+                    float* X_inout, const float* phi0, const float* varphi0, void* stream) {
+  return solve_impl(h, C, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_inout, phi0, varphi0, true,
+                    stream);
 }
 
 int drot_get_info(drot_handle h, drot_info* out) {

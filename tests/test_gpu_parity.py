@@ -314,3 +314,48 @@ def test_even_odd_full_size_sampled(drot, oracle):
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 25)
     ores = pu.oracle_solve(oracle, P, 25)
     pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="even/odd cfg3")
+
+
+@pytest.mark.parametrize("kind,m,n", [(0, 150, 210), (1, 2300, 700), (2, 600, 333)])
+def test_warm_start_matches_the_oracle_from_the_same_point(drot, oracle, kind, m, n):
+    # start from an arbitrary (X_0, phi_0, varphi_0): Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T, eq. (5)
+    P = drot_inputs.random_problem(m, n, seed=800 + kind, reg_kind=kind, lam=0.2 if kind else 0.0,
+                                   mu=0.04 if kind == 2 else 0.0, num_classes=4)
+    rng = np.random.default_rng(801)
+    X0 = (np.outer(P.p, P.q) * rng.uniform(0.0, 2.0, size=(m, n))).astype(np.float32)
+    phi0 = rng.uniform(0.0, 1.0 / (m + n), size=m).astype(np.float32)
+    varphi0 = rng.uniform(0.0, 1.0 / (m + n), size=n).astype(np.float32)
+    K = 100
+    _say(f"warm start kind={kind} {m}x{n}")
+    dev = torch.device("cuda:0")
+    C, p, q, rc = pu.to_dev(P)
+    X = torch.from_numpy(X0).to(dev)
+    solver = drot.Solver(m, n)
+    res = solver.solve(C, p, q, reg_kind=kind, lam=P.lam, mu=P.mu, row_class=rc, num_classes=P.num_classes,
+                       max_iters=K, X_out=X, phi0=torch.from_numpy(phi0).to(dev), varphi0=torch.from_numpy(varphi0).to(dev))
+    phi, varphi = solver.duals(m, n, dev)
+    torch.cuda.synchronize()
+    ores = oracle.solve(P.C, P.p, P.q, rho=float(P.rho), reg_kind=kind, lam=float(np.float32(P.lam)),
+                        mu=float(np.float32(P.mu)), row_class=P.row_class, num_classes=P.num_classes, max_iters=K,
+                        X0=X0, phi0=phi0, varphi0=varphi0)
+    assert res.iters == K
+    pu.assert_parity(oracle, P, res, X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores, label="warm start")
+
+
+def test_warm_start_from_a_checkpoint_continues_the_solve(drot, oracle):
+    # save (X, phi, varphi) after K1 iterations, restart from them on a fresh handle for K2 more
+    P = drot_inputs.random_problem(400, 560, seed=810, reg_kind=1, lam=0.2)
+    K1, K2 = 80, 70
+    dev = torch.device("cuda:0")
+    a = drot.Solver(P.m, P.n)
+    _, X_full, phi_full, _ = pu.gpu_solve(a, P, K1 + K2)
+    _, X_half, phi_half, varphi_half = pu.gpu_solve(a, P, K1)
+    b = drot.Solver(P.m, P.n)
+    C, p, q, _ = pu.to_dev(P)
+    X = torch.from_numpy(X_half).to(dev)
+    res = b.solve(C, p, q, reg_kind=1, lam=P.lam, max_iters=K2, X_out=X, phi0=torch.from_numpy(phi_half).to(dev),
+                  varphi0=torch.from_numpy(varphi_half).to(dev))
+    torch.cuda.synchronize()
+    err = np.abs(X.cpu().numpy().astype(np.float64) - X_full).max() / np.abs(X_full).max()
+    _say(f"checkpoint restart: difference / scale = {err:.2e}")
+    assert res.iters == K2 and err <= 1e-5
