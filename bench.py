@@ -48,6 +48,7 @@ def main() -> int:
     ap.add_argument("--check-every", type=int, default=100)
     ap.add_argument("--nontemporal", type=int, default=-1, help="-1: library default, 0/1: force off/on")
     ap.add_argument("--skip-cost", action="store_true", help="even/odd scheme: read C every second sweep")
+    ap.add_argument("--points", action="store_true", help="on-the-fly cost from the point clouds (drot_solve_points)")
     ap.add_argument("--skip-tol", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0: sized for ~20 s)")
@@ -130,6 +131,31 @@ def main() -> int:
         log(f"even/odd scheme: {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration "
             f"({skip_leg['hbm_gbs_whole_iteration']:.0f} GB/s at 10 B/element)")
 
+    # ---- the same K iterations with the cost recomputed from the point clouds (8 B/element) ------------
+    points_leg = None
+    if P.reg_kind != 2 and P.xs is not None and (args.points or not args.skip_tol):
+        xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
+        cs = float(np.float32(1.0 / P.cmax))
+        pkw = dict(reg_kind=P.reg_kind, lam=P.lam, X_out=X)
+        solver.solve_points(xs, xt, cs, p, q, max_iters=W, **pkw)
+        solver.set_continue(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        solver.solve_points(xs, xt, cs, p, q, max_iters=K, **pkw)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        solver.set_profile(True)
+        solver.solve_points(xs, xt, cs, p, q, max_iters=min(K, 256), **pkw)
+        pms, _ = solver.profile()
+        solver.set_profile(False)
+        solver.set_continue(False)
+        points_leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
+                      "d": int(P.xs.shape[1]), "algorithmic_bytes_per_iteration": 8.0 * m * n,
+                      "kernel_ms": round(pms, 5), "kernel_hbm_gbs": round(8.0 * m * n / (pms * 1e-3) / 1e9, 1),
+                      "kernel_tflops": round(2.0 * P.xs.shape[1] * m * n / (pms * 1e-3) / 1e12, 2)}
+        log(f"cost from point clouds (d={points_leg['d']}): {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; sweep "
+            f"{pms:.4f} ms = {points_leg['kernel_hbm_gbs']:.0f} GB/s at 8 B/element, {points_leg['kernel_tflops']} TFLOP/s fp32 MFMA")
+
     # ---- time to tolerance (cold start, residual test every check_every iterations) -------------------
     tol_leg = None
     if not args.skip_tol:
@@ -174,7 +200,7 @@ def main() -> int:
         "config": {"workload": P.name, "m": m, "n": n, "reg_kind": int(P.reg_kind), "lambda": P.lam, "mu": P.mu,
                    "stepsize": float(P.rho), "check_every": args.check_every},
         "hbm_gbs_whole_iteration": round(algo_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "time_to_tol": tol_leg, "even_odd_cost_skipping": skip_leg, "cpu_baseline": cpu,
+        "roofline": roofline, "time_to_tol": tol_leg, "even_odd_cost_skipping": skip_leg, "cost_from_points": points_leg, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0

@@ -167,6 +167,22 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
                int max_iters, float tol, float* X_out, void* stream);
 
 /*
+ * On-the-fly cost: like drot_solve, but the cost is C_ij = cost_scale * ||xs_i - xt_j||_2^2 for two
+ * point clouds and is recomputed in every sweep instead of being read from memory (8 instead of 12
+ * bytes per element of HBM traffic, 2d flops per element on the matrix cores; no m x n cost array).
+ *   xs [in]  DEVICE, m*d fp32 row-major (source points), xt [in] DEVICE, n*d fp32 (target points), d >= 1
+ *   cost_scale > 0; 1/max_ij ||xs_i - xt_j||^2 gives the normalisation the stepsize default assumes
+ * The cost is evaluated in fp32 as cost_scale*max(|xs_i|^2 + |xt_j|^2 - 2 xs_i.xt_j, 0) (squared
+ * norms accumulated in fp64), so it agrees with a stored fp32 cost to a few 1e-7 absolute, and the
+ * iterates agree with the stored-cost solve to that perturbation accumulated over the iterations.
+ * DROT_REG_NONE and DROT_REG_QUADRATIC only.  Other arguments, results and errors as drot_solve.
+ */
+int drot_solve_points(drot_handle h, const float* xs, const float* xt, int d, float cost_scale,
+                      const float* p, const float* q, int m, int n, float stepsize,
+                      drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters,
+                      float tol, float* X_out, void* stream);
+
+/*
  * Warm start: like drot_solve, but the iteration starts from a caller-supplied point instead of
  * X_0 = 0 and the constants of the Initialization paragraph (which the paper offers as one choice;
  * the iteration converges from any start).  On entry X_inout holds X_0 (m*n, entries >= 0) and

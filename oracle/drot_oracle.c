@@ -227,6 +227,24 @@ int oracle_drot_solve(const float* C, const double* p, const double* q, int m, i
 }
 
 /*
+ * Cost of the variant that takes two point clouds instead of a matrix: C_ij = scale*||xs_i - xt_j||_2^2
+ * (squared Euclidean cost between the samples, normalised by `scale`, as in the paper's experiments),
+ * from the fp32 points, difference form, fp64 arithmetic, rounded once to fp32.
+ */
+void oracle_sqdist_cost(const float* xs, const float* xt, int m, int n, int d, double scale, float* C_out) {
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < m; ++i)
+    for (int j = 0; j < n; ++j) {
+      double acc = 0.0;
+      for (int k = 0; k < d; ++k) {
+        const double diff = (double)xs[(size_t)i * d + k] - (double)xt[(size_t)j * d + k];
+        acc += diff * diff;
+      }
+      C_out[(size_t)i * n + j] = (float)(scale * acc);
+    }
+}
+
+/*
  * Objective and duality gap of a triple (X, phi, varphi) (Appendix C, stopping criteria).
  * With u = phi/rho, v = varphi/rho and W = [u 1^T + 1 v^T - C]_+ :
  *     gap = <C,X> + h(X) - (p^T u + q^T v) + h*(W)

@@ -61,6 +61,9 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_double, ctypes.c_double,
             _c_int_p, ctypes.c_int, _c_double_p]
         lib.oracle_objective_gap.restype = None
+        lib.oracle_sqdist_cost.argtypes = [_c_float_p, _c_float_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_double, _c_float_p]
+        lib.oracle_sqdist_cost.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -94,6 +97,19 @@ def initial_vectors(m: int, n: int):
     phi0 = (1.0 + m / (m + n)) / (3.0 * (m + n))
     varphi0 = (1.0 + n / (m + n)) / (3.0 * (m + n))
     return np.full(m, phi0), np.full(n, varphi0)
+
+
+def sqdist_cost(xs, xt, scale) -> np.ndarray:
+    """C_ij = scale * ||xs_i - xt_j||^2 from fp32 point clouds (fp64 arithmetic, one rounding to fp32)."""
+    xs = np.ascontiguousarray(xs, dtype=np.float32)
+    xt = np.ascontiguousarray(xt, dtype=np.float32)
+    m, d = xs.shape
+    n = xt.shape[0]
+    assert xt.shape[1] == d
+    C = np.empty((m, n), dtype=np.float32)
+    _load().oracle_sqdist_cost(xs.ctypes.data_as(_c_float_p), xt.ctypes.data_as(_c_float_p), m, n, d, float(scale),
+                               C.ctypes.data_as(_c_float_p))
+    return C
 
 
 def project_marginals(V, p, q):

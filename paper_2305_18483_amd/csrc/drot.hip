@@ -372,6 +372,158 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
 }
 
 // ------------------------------------------------------------------------------------------
+// On-the-fly cost: C_ij = cost_scale * ||xs_i - xt_j||^2 recomputed from the two point clouds in
+// every sweep instead of being read (8 bytes per element of HBM traffic instead of 12, plus
+// 2d flops per element).  The inner products xs_i . xt_j of a 32 x 256 tile are a dense
+// contraction, so they go to the matrix cores: each of the 16 waves forms a 16 x 32 block with
+// v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate), writes it to LDS, and after a barrier every
+// wave reads its two row segments back in the sweep's own layout (4 columns per lane), turns them
+// into costs with the precomputed squared norms and proceeds exactly as the stored-cost sweep.
+// The loads of X are issued before the matrix phase so that their latency is hidden behind it.
+//
+// Packed point layout (made once per solve by pack_points_kernel): P[row][kk][t] = pts[row][4t + kk],
+// kk = 0..3, t = 0..dq-1 with dq = ceil(d/16)*4 (zero padded): in MFMA step t lane (r, kk) needs
+// element k = 4t + kk of row r, so its operands for 4 consecutive steps are one 128-bit load.
+// ------------------------------------------------------------------------------------------
+struct PointArgs {
+  const float* xs_pack;  // [m][4][dq]
+  const float* xt_pack;  // [n][4][dq]
+  const float* xs_sq;    // [m] squared norms
+  const float* xt_sq;    // [n]
+  int dq;
+  float cost_scale;
+};
+
+__global__ void pack_points_kernel(const float* __restrict__ pts, int rows, int d, int dq, float* __restrict__ pack,
+                                   float* __restrict__ sq) {
+  const int row = blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= rows) return;
+  double acc = 0.0;
+  for (int k = 0; k < 4 * dq; ++k) {
+    const float v = k < d ? pts[(size_t)row * d + k] : 0.f;
+    acc += (double)v * (double)v;
+    pack[((size_t)row * 4 + (k & 3)) * dq + (k >> 2)] = v;
+  }
+  sq[row] = (float)acc;
+}
+
+constexpr int kDotPitch = kSegCols + 4;  // LDS row pitch of the inner-product tile (keeps rows 16-byte aligned)
+
+template <bool FIRST, bool NT>
+__global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArgs A, PointArgs Pt) {
+  if (*A.done) return;
+  __shared__ float dots[kTileRows][kDotPitch];
+  constexpr int U = kSweepRows;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = min(max(A.n - j0, 0), 4);
+  const int r0 = tr * kTileRows + wave * U;
+  const int nrows = min(max(A.m - r0, 0), U);
+  const size_t ldx = (size_t)A.ldx;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+
+  // sweep layout: start the loads of X and of the per-row / per-column vectors
+  f4v x[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+    if (!FIRST && u < nrows) {
+      if (NT && nvalid == 4) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(Xp + u * ldx));
+      else x[u] = load4(Xp + u * ldx, nvalid);
+    }
+  }
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const f4v ysq = load4(Pt.xt_sq + j0, nvalid);
+  const float phi_lane = (lane < nrows) ? A.phi[r0 + lane] : 0.f;
+  const float xsq_lane = (lane < nrows) ? Pt.xs_sq[r0 + lane] : 0.f;
+
+  // matrix phase: this wave's 16 x 32 block of inner products
+  {
+    const int r = lane & 15, kk = lane >> 4;
+    const int R0 = (wave >> 3) * 16, cb = (wave & 7) * 32;
+    const int row = tr * kTileRows + R0 + r;
+    const int col0 = seg * kSegCols + cb + r, col1 = col0 + 16;
+    const int dq = Pt.dq;
+    const float* __restrict__ ap = Pt.xs_pack + ((size_t)min(row, A.m - 1) * 4 + kk) * dq;
+    const float* __restrict__ bp0 = Pt.xt_pack + ((size_t)min(col0, A.n - 1) * 4 + kk) * dq;
+    const float* __restrict__ bp1 = Pt.xt_pack + ((size_t)min(col1, A.n - 1) * 4 + kk) * dq;
+    f4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < dq; t += 4) {
+      // rows / columns past the edge reuse the last valid one: their products are never read
+      const f4v a = *reinterpret_cast<const f4v*>(ap + t);
+      const f4v b0 = *reinterpret_cast<const f4v*>(bp0 + t);
+      const f4v b1 = *reinterpret_cast<const f4v*>(bp1 + t);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b0.x, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b1.x, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b0.y, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b1.y, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b0.z, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b1.z, acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b0.w, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b1.w, acc1, 0, 0, 0);
+    }
+    // accumulator i of lane (r, kk) is element (row 4*kk + i, column r) of the 16 x 16 block
+    dots[R0 + 4 * kk + 0][cb + r] = acc0.x;
+    dots[R0 + 4 * kk + 1][cb + r] = acc0.y;
+    dots[R0 + 4 * kk + 2][cb + r] = acc0.z;
+    dots[R0 + 4 * kk + 3][cb + r] = acc0.w;
+    dots[R0 + 4 * kk + 0][cb + 16 + r] = acc1.x;
+    dots[R0 + 4 * kk + 1][cb + 16 + r] = acc1.y;
+    dots[R0 + 4 * kk + 2][cb + 16 + r] = acc1.z;
+    dots[R0 + 4 * kk + 3][cb + 16 + r] = acc1.w;
+  }
+  __syncthreads();
+
+  // sweep phase, as in sweep_body with the cost taken from the tile of inner products
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  if (nrows > 0) {
+    const float rho = A.rho, scale = A.scale, cs = Pt.cost_scale;
+    float rowkeep = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (u < nrows) {
+        const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
+        const float xsq = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xsq_lane), u));
+        const f4v dv = *reinterpret_cast<const f4v*>(&dots[wave * U + u][lane * 4]);
+        f4v c;
+        c.x = cs * fmaxf(fmaf(-2.f, dv.x, xsq + ysq.x), 0.f);
+        c.y = cs * fmaxf(fmaf(-2.f, dv.y, xsq + ysq.y), 0.f);
+        c.z = cs * fmaxf(fmaf(-2.f, dv.z, xsq + ysq.z), 0.f);
+        c.w = cs * fmaxf(fmaf(-2.f, dv.w, xsq + ysq.w), 0.f);
+        const f4v v = xbar4(x[u], c, vp + ph, rho) * scale;
+        if (NT && nvalid == 4) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(Xp + u * ldx));
+        else store4(Xp + u * ldx, v, nvalid);
+        colacc += v;
+        const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+        rowkeep = (lane == u) ? tot : rowkeep;
+      }
+    }
+    if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
+  }
+  write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+}
+
+// The same cost for the kernels off the hot path (gap evaluation): plain fp32 FMAs over the packed points.
+__device__ __forceinline__ f4v cost4_from_points(const PointArgs& Pt, int i, int j0, int nvalid) {
+  f4v c = {0.f, 0.f, 0.f, 0.f};
+  const float xsq = Pt.xs_sq[i];
+  const float* __restrict__ a = Pt.xs_pack + (size_t)i * 4 * Pt.dq;
+  float out[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < 4; ++k) {
+    if (k < nvalid) {
+      const float* __restrict__ b = Pt.xt_pack + (size_t)(j0 + k) * 4 * Pt.dq;
+      float dot = 0.f;
+      for (int e = 0; e < 4 * Pt.dq; ++e) dot = fmaf(a[e], b[e], dot);
+      out[k] = Pt.cost_scale * fmaxf(fmaf(-2.f, dot, xsq + Pt.xt_sq[j0 + k]), 0.f);
+    }
+  }
+  c.x = out[0]; c.y = out[1]; c.z = out[2]; c.w = out[3];
+  return c;
+}
+
+// ------------------------------------------------------------------------------------------
 // Group lasso, general labels, two passes (Section "Group-lasso Regularized DROT": when a
 // group does not fit one workgroup the reduction goes through global memory and a second
 // kernel applies the scale).  Pass 1 accumulates sum_{i in class} Xbar_ij^2 per (class, column).
@@ -805,6 +957,7 @@ struct GapArgs {
   int m, n, nseg;
   int ldx, ldc;
   float rho;
+  PointArgs pts;         // used instead of C when C is null
 };
 
 __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
@@ -820,7 +973,7 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
   int cur = -1;
   f4v ax = {0.f, 0.f, 0.f, 0.f}, aw = {0.f, 0.f, 0.f, 0.f};
   for (int i = rbeg; i < rend; ++i) {
-    const f4v c = load4(A.C + (size_t)i * A.ldc + j0, nvalid);
+    const f4v c = A.C ? load4(A.C + (size_t)i * A.ldc + j0, nvalid) : cost4_from_points(A.pts, i, j0, nvalid);
     const f4v x = load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c, vp + A.phi[i], A.rho);
     const f4v x2 = x * x, w2 = w * w, cxv = c * x;
@@ -969,6 +1122,8 @@ struct drot_handle_s {
   // arrays do not start every row on a 128-byte line; grown on demand
   float *cpad = nullptr, *xpad = nullptr;
   size_t cpad_len = 0, xpad_len = 0;
+  float* ptbuf = nullptr;  // on-the-fly cost: packed point clouds and their squared norms
+  size_t ptbuf_len = 0;
   int* runbuf = nullptr;  // group-resident path: run_start[], run_len[] of the label runs
   size_t runbuf_len = 0;
   int max_runs = 0;       // rows of colpart available
@@ -1010,6 +1165,7 @@ void free_all(drot_handle h) {
   (void)hipFree(h->status);
   (void)hipFree(h->runbuf);
   (void)hipFree(h->cpad);
+  (void)hipFree(h->ptbuf);
   (void)hipFree(h->xpad);
   if (h->host_status) (void)hipHostFree(h->host_status);
   for (auto& e : h->ev)
@@ -1158,10 +1314,25 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed) {
   return DROT_OK;
 }
 
-static int solve_impl(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
-                      drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
-                      float* X_out, const float* phi0, const float* varphi0, bool warm, void* stream_v) {
-  if (!h || !C || !p || !q || !X_out) return DROT_ERR_INVALID_ARG;
+// Where the cost comes from: a stored matrix, or two point clouds (C_ij = scale * ||xs_i - xt_j||^2).
+struct CostSource {
+  const float* C = nullptr;
+  const float* xs = nullptr;  // [m][d]
+  const float* xt = nullptr;  // [n][d]
+  int d = 0;
+  float scale = 0.f;
+};
+
+static int solve_impl(drot_handle h, const CostSource& cost, const float* p, const float* q, int m, int n,
+                      float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters,
+                      float tol, float* X_out, const float* phi0, const float* varphi0, bool warm, void* stream_v) {
+  const float* C = cost.C;
+  const bool from_points = cost.C == nullptr;
+  if (!h || !p || !q || !X_out) return DROT_ERR_INVALID_ARG;
+  if (from_points) {
+    if (!cost.xs || !cost.xt || cost.d < 1 || !(cost.scale > 0.f) || warm) return DROT_ERR_INVALID_ARG;
+    if (reg_kind == DROT_REG_GROUP_LASSO) return DROT_ERR_INVALID_ARG;  // stored-cost paths only
+  }
   if (warm && (!phi0 || !varphi0)) return DROT_ERR_INVALID_ARG;
   if (m < 1 || n < 1 || m > h->max_m || n > h->max_n || max_iters < 0) return DROT_ERR_INVALID_ARG;
   if (reg_kind != DROT_REG_NONE && reg_kind != DROT_REG_QUADRATIC && reg_kind != DROT_REG_GROUP_LASSO)
@@ -1192,13 +1363,15 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
   const float qscale = (float)(1.0 / (1.0 + (double)rho * (double)lambda));
 
   if (reinterpret_cast<uintptr_t>(X_out) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return DROT_ERR_INVALID_ARG;
+  if (from_points && (reinterpret_cast<uintptr_t>(cost.xs) % 4 || reinterpret_cast<uintptr_t>(cost.xt) % 4))
+    return DROT_ERR_INVALID_ARG;
   const int nseg = ceil_div(n, kSegCols);
   const int ntr = ceil_div(m, kTileRows);
   const int ntiles = nseg * ntr;
   const bool nt = h->nontemporal < 0 ? use_nontemporal(m, n) : h->nontemporal != 0;
   // Rows that do not start on 128-byte lines are slow to stream: work on padded copies then.
   const int ld_pad = ceil_div(n, kAlignElems) * kAlignElems;
-  const bool pad_c = (n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0);
+  const bool pad_c = !from_points && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0));
   const bool pad_x = (n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(X_out) % 128 != 0);
   auto grow = [&](float** buf, size_t* len) -> int {
     const size_t need = (size_t)m * (size_t)ld_pad;
@@ -1297,6 +1470,27 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
   }
   SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, nullptr, h->done,
               m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
+  // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
+  PointArgs PT{};
+  if (from_points) {
+    const int dq = ceil_div(cost.d, 16) * 4;
+    const size_t need = (size_t)(m + n) * 4 * (size_t)dq + (size_t)m + (size_t)n;
+    if (h->ptbuf_len < need) {
+      DROT_HIP(hipStreamSynchronize(stream));
+      (void)hipFree(h->ptbuf);
+      h->ptbuf = nullptr;
+      h->ptbuf_len = 0;
+      if (dev_alloc(&h->ptbuf, need) != DROT_OK) return DROT_ERR_ALLOC;
+      h->ptbuf_len = need;
+    }
+    float* xs_pack = h->ptbuf;
+    float* xt_pack = xs_pack + (size_t)m * 4 * dq;
+    float* xs_sq = xt_pack + (size_t)n * 4 * dq;
+    float* xt_sq = xs_sq + m;
+    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(m, 256)), dim3(256), 0, stream, cost.xs, m, cost.d, dq, xs_pack, xs_sq);
+    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, stream, cost.xt, n, cost.d, dq, xt_pack, xt_sq);
+    PT = PointArgs{xs_pack, xt_pack, xs_sq, xt_sq, dq, cost.scale};
+  }
   GroupArgs G{S, row_class, h->gbuf, rho * mu};
   SlabArgs SL{S, h->runbuf, h->runbuf ? h->runbuf + nruns : nullptr, rho * mu};
   const dim3 slab_grid(ceil_div(n, kSlabCols), nruns > 0 ? nruns : 1);
@@ -1311,9 +1505,9 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
   // before a residual check and at the end.
   // (eta comes from the tile totals whenever the problem is small enough for that path, whether or
   // not the fusion is switched on, so that both settings produce the same bits)
-  const bool small = reg_kind != DROT_REG_GROUP_LASSO && ntr <= 64 && ntiles <= 4096;
+  const bool small = reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096;
   const bool fused = small && h->fused_update != 0;
-  const bool skip_cost = h->skip_cost && reg_kind != DROT_REG_GROUP_LASSO && !fused;
+  const bool skip_cost = h->skip_cost && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
   auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
@@ -1354,7 +1548,11 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
       S.tilesum = small ? tsum(sw) : nullptr;
-      if (slab_k) {
+      if (from_points) {
+        if (first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, S, PT);
+        else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
+        else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, S, PT);
+      } else if (slab_k) {
         launch_slab(first, slab_k, slab_grid, stream, SL);
       } else if (reg_kind == DROT_REG_GROUP_LASSO) {
         hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((ngroups + 255) / 256), 4)), dim3(256), 0, stream,
@@ -1436,7 +1634,7 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
     if (reg_kind == DROT_REG_GROUP_LASSO)
       hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((2 * ngroups + 255) / 256), 4)), dim3(256), 0, stream,
                          h->gbuf, 2 * ngroups, 0.f, (const int*)nullptr);
-    GapArgs GA{Xw, Cw, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, nseg, ldx, ldc, rho};
+    GapArgs GA{Xw, Cw, h->phi, h->varphi, row_class, h->gap_part, gx, gw, m, n, nseg, ldx, ldc, rho, PT};
     hipLaunchKernelGGL(gap_kernel, grid, block, 0, stream, GA);
     hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(1024), 0, stream, V, (const float*)h->gap_part, ntiles,
                        (const float*)gx, (const float*)gw, ngroups, p, q, m, n, (double)rho, (int)reg_kind,
@@ -1480,14 +1678,33 @@ static int solve_impl(drot_handle h, const float* C, const float* p, const float
 int drot_solve(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
                drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
                float* X_out, void* stream) {
-  return solve_impl(h, C, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_out, nullptr, nullptr, false,
+  if (!C) return DROT_ERR_INVALID_ARG;
+  CostSource cost;
+  cost.C = C;
+  return solve_impl(h, cost, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_out, nullptr, nullptr, false,
+                    stream);
+}
+
+int drot_solve_points(drot_handle h, const float* xs, const float* xt, int d, float cost_scale, const float* p,
+                      const float* q, int m, int n, float stepsize, drot_reg_kind reg_kind,
+                      const drot_reg_params* reg_params, int max_iters, float tol, float* X_out, void* stream) {
+  if (!xs || !xt) return DROT_ERR_INVALID_ARG;
+  CostSource cost;
+  cost.xs = xs;
+  cost.xt = xt;
+  cost.d = d;
+  cost.scale = cost_scale;
+  return solve_impl(h, cost, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_out, nullptr, nullptr, false,
                     stream);
 }
 
 int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* q, int m, int n, float stepsize,
                     drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
                     float* X_inout, const float* phi0, const float* varphi0, void* stream) {
-  return solve_impl(h, C, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_inout, phi0, varphi0, true,
+  if (!C) return DROT_ERR_INVALID_ARG;
+  CostSource cost;
+  cost.C = C;
+  return solve_impl(h, cost, p, q, m, n, stepsize, reg_kind, reg_params, max_iters, tol, X_inout, phi0, varphi0, true,
                     stream);
 }
 

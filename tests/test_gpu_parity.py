@@ -359,3 +359,27 @@ def test_warm_start_from_a_checkpoint_continues_the_solve(drot, oracle):
     err = np.abs(X.cpu().numpy().astype(np.float64) - X_full).max() / np.abs(X_full).max()
     _say(f"checkpoint restart: difference / scale = {err:.2e}")
     assert res.iters == K2 and err <= 1e-5
+
+
+@pytest.mark.parametrize("m,n,d,kind", [(150, 210, 3, 0), (333, 517, 10, 1), (1300, 900, 32, 1), (64, 256, 1, 0),
+                                        (70, 300, 17, 1)])
+def test_cost_from_point_clouds(drot, oracle, m, n, d, kind):
+    # cost recomputed on the matrix cores in every sweep; the oracle gets the same cost formed in fp64
+    P = drot_inputs.random_problem(m, n, seed=900 + d, d=d, reg_kind=kind, lam=0.3 if kind else 0.0)
+    scale = np.float32(1.0 / P.cmax)
+    P.C = oracle.sqdist_cost(P.xs, P.xt, float(scale))
+    assert abs(float(P.C.max()) - 1.0) < 1e-3
+    K = 150
+    _say(f"point-cloud cost {m}x{n} d={d} kind={kind}")
+    dev = torch.device("cuda:0")
+    solver = drot.Solver(m, n)
+    res = solver.solve_points(torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev), float(scale),
+                              torch.from_numpy(P.p).to(dev), torch.from_numpy(P.q).to(dev), reg_kind=kind, lam=P.lam,
+                              max_iters=K)
+    phi, varphi = solver.duals(m, n, dev)
+    torch.cuda.synchronize()
+    ores = pu.oracle_solve(oracle, P, K)
+    assert res.iters == K
+    ratio = pu.assert_parity(oracle, P, res, res.X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores,
+                             label="points")
+    _say(f"point-cloud cost: plan error / scale = {ratio:.2e}")

@@ -420,3 +420,16 @@ def test_stopping_rule_takes_first_passing_check(oracle):
     expected = next(k for k in range(10, 5001, 10) if r[k - 1] <= tol)
     assert res.iters == expected
     assert max(res.res_row[-1], res.res_col[-1]) <= tol
+
+
+def test_point_cloud_cost_matches_numpy_and_scipy(oracle):
+    from scipy.spatial.distance import cdist
+
+    rng = np.random.default_rng(77)
+    xs = rng.normal(size=(13, 5)).astype(np.float32)
+    xt = rng.normal(0.5, 2.0, size=(9, 5)).astype(np.float32)
+    ref = cdist(xs.astype(np.float64), xt.astype(np.float64), metric="sqeuclidean")
+    C = oracle.sqdist_cost(xs, xt, 0.25)
+    assert C.dtype == np.float32 and C.shape == (13, 9)
+    assert np.abs(C - 0.25 * ref).max() <= 1e-6 * (0.25 * ref).max()
+    assert (oracle.sqdist_cost(xs, xs, 1.0).diagonal() == 0).all()
