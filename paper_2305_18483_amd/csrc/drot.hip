@@ -105,16 +105,18 @@ __device__ __forceinline__ f4v xbar4(f4v x, f4v c, f4v pv, float rho) {
   return v;
 }
 
-__device__ __forceinline__ double block_sum_f64(double v, double* red /* blockDim.x doubles */) {
+// Sum of one double per thread over the workgroup, the same value (same bits) in every thread:
+// butterfly inside each wave, then the wave sums added in wave order.  red: >= blockDim.x/64 doubles.
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
   const int t = threadIdx.x;
-  red[t] = v;
+  const int nw = (blockDim.x + 63) >> 6;
+  __syncthreads();  // red may still be read by the previous use
+  if ((t & 63) == 0) red[t >> 6] = v;
   __syncthreads();
-  for (int s = blockDim.x >> 1; s > 0; s >>= 1) {
-    if (t < s) red[t] += red[t + s];
-    __syncthreads();
-  }
-  const double out = red[0];
-  __syncthreads();
+  double out = 0.0;
+  for (int w = 0; w < nw; ++w) out += red[w];
   return out;
 }
 
@@ -209,43 +211,133 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
 // (read X and C, store X); 1 = read X and C, store X - rho*C; 2 = read the shifted X only (no C)
 // and store the plain X.  A 1-sweep followed by a 2-sweep moves 20 bytes per element instead of 24.
 // MODE 3 only forms the row and column sums of X as it stands (no update, no store): the warm start.
+// Vector update of eq. (6) for the 32 rows and 256 columns of one tile, computed redundantly by
+// every workgroup that needs them from the previous sweep's partial sums (worth it while the
+// partials are few: small m).  Same arithmetic as reduce_kernel + update_kernel; the workgroups
+// of the first tile column / tile row also store the new a, phi / b, varphi, workgroup (0,0)
+// the new theta.  Results land in LDS for the sweep that follows.
+__device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpdateArgs& F, int seg, int tr,
+                                             float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
+  __shared__ double red[64 * kSweepWaves];
+  const int t = threadIdx.x;
+  // Everything below is latency: issue every load that does not depend on another one first
+  // (tile totals, column partials, row partials, p, q, a, b, theta), then synchronise.
+  double acc = 0.0;
+  const int ntiles = F.nseg * F.ntr;
+  for (int e = t; e < ntiles; e += 64 * kSweepWaves) acc += (double)F.tilesum_prev[e];
+  // columns: 4 groups of 256 threads split the row tiles.  The partials are summed in the order
+  // reduce_kernel uses (16 interleaved subsequences, then a fixed tree), so that both ways of
+  // doing the update give the same bits.
+  const int sub = t >> 8, cidx = t & 255;
+  const int j = seg * kSegCols + cidx;
+  double sj = 0.0;
+  if (j < A.n) {
+    double q4[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int k = sub, w = 0; k < F.ntr; k += 4, w = (w + 1) & 3) q4[w] += (double)F.colpart_prev[(size_t)k * A.n + j];
+    sj = (q4[0] + q4[2]) + (q4[1] + q4[3]);  // residues sub, sub+8 | sub+4, sub+12
+  }
+  // rows: one thread per row of the tile (threads 256 .. 287)
+  const int l = t - kSegCols;
+  const int i = tr * kTileRows + l;
+  const bool row_thread = l >= 0 && l < kTileRows && i < A.m;
+  double ri = 0.0, ai = 0.0;
+  if (row_thread) {
+    double q16[16];
+#pragma unroll
+    for (int w = 0; w < 16; ++w) q16[w] = 0.0;
+    for (int k0 = 0; k0 < F.nseg; k0 += 16) {
+#pragma unroll
+      for (int w = 0; w < 16; ++w)
+        if (k0 + w < F.nseg) q16[w] += (double)F.rowpart_prev[(size_t)(k0 + w) * A.m + i];
+    }
+    ri = (((q16[0] + q16[8]) + (q16[4] + q16[12])) + ((q16[2] + q16[10]) + (q16[6] + q16[14]))) +
+         (((q16[1] + q16[9]) + (q16[5] + q16[13])) + ((q16[3] + q16[11]) + (q16[7] + q16[15])));
+    ri -= (double)F.p[i];
+    ai = F.a_in[i];
+  }
+  const bool col_thread = t < kSegCols && j < A.n;
+  double qj = 0.0, bj = 0.0;
+  if (col_thread) {
+    qj = (double)F.q[j];
+    bj = F.b_in[j];
+  }
+  const double sum_p = *F.sum_p;
+  const double theta = *F.theta_in;
+
+  const double sum_x = block_sum_f64(acc, red);
+  const double mn = (double)A.m + (double)A.n;
+  const double eta = (sum_x - sum_p) / mn;
+  const double cst = 2.0 * eta - theta;
+  __syncthreads();  // every thread has read the wave sums of block_sum_f64
+  red[t] = sj;
+  __syncthreads();
+  if (t < kSegCols) {
+    float out = kMaskedOut;
+    if (col_thread) {
+      const double res = (red[t] + red[512 + t]) + (red[256 + t] + red[768 + t]) - qj;
+      out = (float)((bj - 2.0 * res + cst) / (double)A.m);
+      if (tr == 0) {
+        F.b_out[j] = bj - res;
+        F.varphi_out[j] = out;
+      }
+    }
+    lds_varphi[t] = out;
+  } else if (l < kTileRows) {
+    float out = 0.f;
+    if (row_thread) {
+      out = (float)((ai - 2.0 * ri + cst) / (double)A.n);
+      if (seg == 0) {
+        F.a_out[i] = ai - ri;
+        F.phi_out[i] = out;
+      }
+    }
+    lds_phi[l] = out;
+  }
+  if (seg == 0 && tr == 0 && t == 0) *F.theta_out = theta - eta;
+  __syncthreads();
+}
+
 template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE>
-__device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wave, int seg, int tr,
-                                           const float* __restrict__ lds_phi, const float* __restrict__ lds_varphi) {
+__device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdateArgs& F, int lane, int wave, int seg,
+                                           int tr, float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
   constexpr int U = kSweepRows;
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int r0 = tr * kTileRows + wave * U;
   const int nrows = min(max(A.m - r0, 0), U);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const float rho = A.rho, scale = A.scale;
+
+  // the one batch of loads of this wave
+  f4v x[U], c[U];
+  if (nrows == U) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      c[u] = f4v{0.f, 0.f, 0.f, 0.f};
+      x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+      if (u < nrows) {
+        if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
+        if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
+      }
+    }
+  }
+  // with the fused update (PRO) phi and varphi of this tile are computed into LDS while the loads fly
+  if (PRO) fused_update(A, F, seg, tr, lds_phi, lds_varphi);
+
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
   float wave_total = 0.f;
   if (nrows > 0) {
-    // with the fused update (PRO) phi and varphi of this tile were just computed into LDS
     const f4v vp = PRO ? *reinterpret_cast<const f4v*>(lds_varphi + lane * 4) : load_varphi(A.varphi, j0, nvalid);
     // lane u holds phi of row r0 + u; rows read it back with a scalar lane read
     const float phi_lane = (lane < nrows) ? (PRO ? lds_phi[wave * U + lane] : A.phi[r0 + lane]) : 0.f;
-    const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
-    const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
-    float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
-    const float rho = A.rho, scale = A.scale;
-    f4v x[U], c[U];
-    if (nrows == U) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
-        x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        c[u] = f4v{0.f, 0.f, 0.f, 0.f};
-        x[u] = f4v{0.f, 0.f, 0.f, 0.f};
-        if (u < nrows) {
-          if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
-          if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
-        }
-      }
-    }
     float rowkeep = 0.f;  // lane u keeps the sum of row r0 + u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -287,77 +379,6 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, int lane, int wav
   }
 }
 
-// Vector update of eq. (6) for the 32 rows and 256 columns of one tile, computed redundantly by
-// every workgroup that needs them from the previous sweep's partial sums (worth it while the
-// partials are few: small m).  Same arithmetic as reduce_kernel + update_kernel; the workgroups
-// of the first tile column / tile row also store the new a, phi / b, varphi, workgroup (0,0)
-// the new theta.  Results land in LDS for the sweep that follows.
-__device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpdateArgs& F, int seg, int tr,
-                                             float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
-  __shared__ double red[64 * kSweepWaves];
-  const int t = threadIdx.x;
-  double acc = 0.0;
-  const int ntiles = F.nseg * F.ntr;
-  for (int e = t; e < ntiles; e += 64 * kSweepWaves) acc += (double)F.tilesum_prev[e];
-  const double sum_x = block_sum_f64(acc, red);
-  const double mn = (double)A.m + (double)A.n;
-  const double eta = (sum_x - *F.sum_p) / mn;
-  const double theta = *F.theta_in;
-  const double cst = 2.0 * eta - theta;
-  // columns: 4 groups of 256 threads split the row tiles.  The partials are summed in the order
-  // reduce_kernel uses (16 interleaved subsequences, then a fixed tree), so that both ways of
-  // doing the update give the same bits.
-  const int sub = t >> 8, cidx = t & 255;
-  const int j = seg * kSegCols + cidx;
-  double sj = 0.0;
-  if (j < A.n) {
-    double q4[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int k = sub, w = 0; k < F.ntr; k += 4, w = (w + 1) & 3) q4[w] += (double)F.colpart_prev[(size_t)k * A.n + j];
-    sj = (q4[0] + q4[2]) + (q4[1] + q4[3]);  // residues sub, sub+8 | sub+4, sub+12
-  }
-  red[t] = sj;
-  __syncthreads();
-  if (t < kSegCols) {
-    float out = kMaskedOut;
-    if (j < A.n) {
-      const double res = (red[t] + red[512 + t]) + (red[256 + t] + red[768 + t]) - (double)F.q[j];
-      const double bj = F.b_in[j];
-      out = (float)((bj - 2.0 * res + cst) / (double)A.m);
-      if (tr == 0) {
-        F.b_out[j] = bj - res;
-        F.varphi_out[j] = out;
-      }
-    }
-    lds_varphi[t] = out;
-  } else if (t < kSegCols + kTileRows) {
-    const int l = t - kSegCols;
-    const int i = tr * kTileRows + l;
-    float out = 0.f;
-    if (i < A.m) {
-      double q16[16];
-#pragma unroll
-      for (int w = 0; w < 16; ++w) q16[w] = 0.0;
-      for (int k0 = 0; k0 < F.nseg; k0 += 16) {
-#pragma unroll
-        for (int w = 0; w < 16; ++w)
-          if (k0 + w < F.nseg) q16[w] += (double)F.rowpart_prev[(size_t)(k0 + w) * A.m + i];
-      }
-      double ri = (((q16[0] + q16[8]) + (q16[4] + q16[12])) + ((q16[2] + q16[10]) + (q16[6] + q16[14]))) +
-                  (((q16[1] + q16[9]) + (q16[5] + q16[13])) + ((q16[3] + q16[11]) + (q16[7] + q16[15])));
-      ri -= (double)F.p[i];
-      const double ai = F.a_in[i];
-      out = (float)((ai - 2.0 * ri + cst) / (double)A.n);
-      if (seg == 0) {
-        F.a_out[i] = ai - ri;
-        F.phi_out[i] = out;
-      }
-    }
-    lds_phi[l] = out;
-  }
-  if (seg == 0 && tr == 0 && t == 0) *F.theta_out = theta - eta;
-  __syncthreads();
-}
-
 template <bool FIRST, bool NT, bool PRO, int MODE = 0>
 __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, FusedUpdateArgs F) {
   if (*A.done) return;
@@ -366,9 +387,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
-  if (PRO) fused_update(A, F, seg, tr, lds_phi, lds_varphi);
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
-  else sweep_body<FIRST, true, false, PRO, MODE>(A, lane, wave, seg, tr, lds_phi, lds_varphi);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, false, PRO, MODE>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
 }
 
 // ------------------------------------------------------------------------------------------
