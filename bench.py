@@ -29,7 +29,7 @@ BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 12.0}  # read X, read C, write X (algo
 
 # HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # copy kernel of known size (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg4_quad_20000": 4.8564e9}  # profiles/sweep_kernel_cfg4_20000.md
+MEASURED_TRAFFIC_BYTES = {"cfg4_quad_20000": 4.8563e9}  # profiles/sweep_kernel_cfg4_20000.md
 
 
 def log(msg: str) -> None:
