@@ -102,7 +102,7 @@ int drot_set_continue(drot_handle h, int enable);
 
 /*
  * Group-lasso path [automatic].  By default a group-lasso solve uses the group-resident kernel
- * (a whole class x 64 columns in one workgroup's registers, 12 bytes per element) when every class
+ * (a whole class x 32 columns in one workgroup's registers, 12 bytes per element) when every class
  * is one run of at most 1024 consecutive rows, and otherwise the general two-pass path (any labels,
  * 20 bytes per element, fp32 atomics for the group norms).  enable = 1 forces the two-pass path.
  */
