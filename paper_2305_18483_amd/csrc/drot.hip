@@ -142,6 +142,9 @@ struct SweepArgs {
   int m, n;
   int ldx, ldc;          // row pitch of X and of C in elements (n, or the padded working copies' pitch)
   float rho, scale;
+  int n_mem;             // columns the sweep may touch in memory: n, or the pitch when X and C are both the
+                         // library's padded copies (their pad columns are kept at zero), so that the last
+                         // lanes of a row can use full 128-bit accesses
 };
 
 // Inputs of the vector update when it is fused into the head of the next sweep (small problems):
@@ -302,7 +305,9 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
                                            int tr, float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
   constexpr int U = kSweepRows;
   const int j0 = seg * kSegCols + lane * 4;
-  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;      // columns of this lane that exist
+  // columns of this lane that may be accessed (the plain sums of MODE 3 have no mask: existing columns only)
+  const int nmem = EDGE ? min(max((MODE == 3 ? A.n : A.n_mem) - j0, 0), 4) : 4;
   const int r0 = tr * kTileRows + wave * U;
   const int nrows = min(max(A.m - r0, 0), U);
   const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
@@ -315,8 +320,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
   if (nrows == U) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nvalid);
-      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nvalid);
+      c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nmem);
+      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nmem);
     }
   } else {
 #pragma unroll
@@ -324,8 +329,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
       c[u] = f4v{0.f, 0.f, 0.f, 0.f};
       x[u] = f4v{0.f, 0.f, 0.f, 0.f};
       if (u < nrows) {
-        if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nvalid);
-        if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nvalid);
+        if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+        if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
       }
     }
   }
@@ -353,9 +358,9 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
           sh.y = fmaf(-rho, c[u].y, v.y);
           sh.z = fmaf(-rho, c[u].z, v.z);
           sh.w = fmaf(-rho, c[u].w, v.w);
-          st4<EDGE, NT>(Xp + u * ldx, sh, nvalid);
+          st4<EDGE, NT>(Xp + u * ldx, sh, nmem);
         } else {
-          st4<EDGE, NT>(Xp + u * ldx, v, nvalid);
+          st4<EDGE, NT>(Xp + u * ldx, v, nmem);
         }
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
@@ -1418,6 +1423,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     *len = 0;
     if (dev_alloc(buf, need) != DROT_OK) return DROT_ERR_ALLOC;
     *len = need;
+    // the pad columns must hold finite values: they are read (and masked out) by the last lanes of a row
+    hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, *buf, need, 0.f, (const int*)nullptr);
     return DROT_OK;
   };
   const int nbm = ceil_div(m, 64), nbn = ceil_div(n, 64);
@@ -1505,7 +1512,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
                                 sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   }
   SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, nullptr, h->done,
-              m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale};
+              m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale,
+              (pad_x && (pad_c || from_points)) ? ld_pad : n};
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
   PointArgs PT{};
   if (from_points) {
