@@ -214,6 +214,24 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
 // (read X and C, store X); 1 = read X and C, store X - rho*C; 2 = read the shifted X only (no C)
 // and store the plain X.  A 1-sweep followed by a 2-sweep moves 20 bytes per element instead of 24.
 // MODE 3 only forms the row and column sums of X as it stands (no update, no store): the warm start.
+// Sum of `count` fp32 partials part[k*stride], k = 0..count-1, in the order every form of the vector
+// update uses: 16 interleaved subsequences added left to right, then a fixed tree over the 16.
+__device__ __forceinline__ double sum_partials_16(const float* __restrict__ part, size_t stride, int count) {
+  double q16[16];
+#pragma unroll
+  for (int w = 0; w < 16; ++w) q16[w] = 0.0;
+  for (int k0 = 0; k0 < count; k0 += 16) {
+    // 16 independent loads in flight (clamped index, the excess ones add +0, which changes no bit)
+    float v[16];
+#pragma unroll
+    for (int w = 0; w < 16; ++w) v[w] = part[(size_t)min(k0 + w, count - 1) * stride];
+#pragma unroll
+    for (int w = 0; w < 16; ++w) q16[w] += (k0 + w < count) ? (double)v[w] : 0.0;
+  }
+  return (((q16[0] + q16[8]) + (q16[4] + q16[12])) + ((q16[2] + q16[10]) + (q16[6] + q16[14]))) +
+         (((q16[1] + q16[9]) + (q16[5] + q16[13])) + ((q16[3] + q16[11]) + (q16[7] + q16[15])));
+}
+
 // Vector update of eq. (6) for the 32 rows and 256 columns of one tile, computed redundantly by
 // every workgroup that needs them from the previous sweep's partial sums (worth it while the
 // partials are few: small m).  Same arithmetic as reduce_kernel + update_kernel; the workgroups
@@ -236,7 +254,11 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   double sj = 0.0;
   if (j < A.n) {
     double q4[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int k = sub, w = 0; k < F.ntr; k += 4, w = (w + 1) & 3) q4[w] += (double)F.colpart_prev[(size_t)k * A.n + j];
+    float v[16];  // at most 64 row tiles on this path: all 16 loads in flight (clamped; the excess ones add +0)
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = F.colpart_prev[(size_t)min(sub + 4 * u, F.ntr - 1) * A.n + j];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) q4[u & 3] += (sub + 4 * u < F.ntr) ? (double)v[u] : 0.0;
     sj = (q4[0] + q4[2]) + (q4[1] + q4[3]);  // residues sub, sub+8 | sub+4, sub+12
   }
   // rows: one thread per row of the tile (threads 256 .. 287)
@@ -245,17 +267,7 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   const bool row_thread = l >= 0 && l < kTileRows && i < A.m;
   double ri = 0.0, ai = 0.0;
   if (row_thread) {
-    double q16[16];
-#pragma unroll
-    for (int w = 0; w < 16; ++w) q16[w] = 0.0;
-    for (int k0 = 0; k0 < F.nseg; k0 += 16) {
-#pragma unroll
-      for (int w = 0; w < 16; ++w)
-        if (k0 + w < F.nseg) q16[w] += (double)F.rowpart_prev[(size_t)(k0 + w) * A.m + i];
-    }
-    ri = (((q16[0] + q16[8]) + (q16[4] + q16[12])) + ((q16[2] + q16[10]) + (q16[6] + q16[14]))) +
-         (((q16[1] + q16[9]) + (q16[5] + q16[13])) + ((q16[3] + q16[11]) + (q16[7] + q16[15])));
-    ri -= (double)F.p[i];
+    ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.m, F.nseg) - (double)F.p[i];
     ai = F.a_in[i];
   }
   const bool col_thread = t < kSegCols && j < A.n;
@@ -674,21 +686,28 @@ __device__ __forceinline__ float rowlanes_sum(float v) {
 }
 
 // CX lanes x 128-bit along the columns (strip of 4*CX columns), 1024/CX row lanes, K rows per thread.
-template <bool FIRST, int K, int CX>
-__global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G) {
+// PRO: the eq. (6) update of the previous sweep is computed here first (small problems), as in
+// fused_update: every workgroup derives phi of the rows of its run (one thread per row) and varphi
+// of its own 32 columns from the previous sweep's partial sums, in the summation order of
+// reduce_kernel, and hands them to the lanes through LDS.
+template <bool FIRST, int K, int CX, bool PRO>
+__global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, FusedUpdateArgs F) {
   constexpr int COLS = 4 * CX, RL = kSlabThreads / CX;
+  static_assert(kSlabMaxRows <= kSlabThreads, "the fused update gives every row of a run a thread");
   const SweepArgs& A = G.S;
   if (*A.done) return;
   __shared__ float red[RL][COLS];  // 16 KiB either way
   __shared__ float part[16][COLS];
   __shared__ float bcast[COLS];
+  __shared__ float lds_varphi[COLS];
+  __shared__ float lds_phi[kSlabThreads];
+  __shared__ double dred[kSlabThreads / 64];
   const int t = threadIdx.x;
   const int cx = t % CX, ry = t / CX;
   const int strip = blockIdx.x, run = blockIdx.y;
   const int start = G.run_start[run], len = G.run_len[run];
   const int j0 = strip * COLS + cx * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
-  const f4v vp = load_varphi(A.varphi, j0, nvalid);
   const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
   const float* __restrict__ Cp = A.C + (size_t)(start + ry) * ldc + j0;
   float* __restrict__ Xp = A.X + (size_t)(start + ry) * ldx + j0;
@@ -704,8 +723,66 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G) {
     if (r < len) {
       c[k] = load4(Cp + (size_t)(RL * k) * ldc, nvalid);
       if (!FIRST) x[k] = load4(Xp + (size_t)(RL * k) * ldx, nvalid);
-      ph[k] = A.phi[start + r];
+      if (!PRO) ph[k] = A.phi[start + r];
     }
+  }
+  f4v vp;
+  if (PRO) {
+    // ---- eq. (6) from the previous sweep's sums (F.nseg = number of strips, F.ntr = number of runs) ----
+    double acc = 0.0;
+    const int ntiles = F.nseg * F.ntr;
+    for (int e = t; e < ntiles; e += kSlabThreads) acc += (double)F.tilesum_prev[e];
+    // rows: thread t owns row t of the run; columns: the last 32 threads own the strip's columns
+    const bool row_thread = t < len;
+    const int i = start + t;
+    double ri = 0.0, ai = 0.0;
+    if (row_thread) {
+      ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.m, F.nseg) - (double)F.p[i];
+      ai = F.a_in[i];
+    }
+    const int cidx = t - (kSlabThreads - COLS);
+    const int jc = strip * COLS + cidx;
+    const bool col_thread = cidx >= 0 && jc < A.n;
+    double sres = 0.0, bold = 0.0;
+    if (col_thread) {
+      sres = sum_partials_16(F.colpart_prev + jc, (size_t)A.n, F.ntr) - (double)F.q[jc];
+      bold = F.b_in[jc];
+    }
+    const double sum_p = *F.sum_p;
+    const double theta = *F.theta_in;
+    const double sum_x = block_sum_f64(acc, dred);
+    const double mn = (double)A.m + (double)A.n;
+    const double eta = (sum_x - sum_p) / mn;
+    const double cst = 2.0 * eta - theta;
+    {
+      float out = kMaskedOut;  // rows past the run: the clamp zeroes them
+      if (row_thread) {
+        out = (float)((ai - 2.0 * ri + cst) / (double)A.n);
+        if (strip == 0) {
+          F.a_out[i] = ai - ri;
+          F.phi_out[i] = out;
+        }
+      }
+      lds_phi[t] = out;
+    }
+    if (cidx >= 0) {
+      float out = kMaskedOut;
+      if (col_thread) {
+        out = (float)((bold - 2.0 * sres + cst) / (double)A.m);
+        if (run == 0) {
+          F.b_out[jc] = bold - sres;
+          F.varphi_out[jc] = out;
+        }
+      }
+      lds_varphi[cidx] = out;
+    }
+    if (strip == 0 && run == 0 && t == 0) *F.theta_out = theta - eta;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < K; ++k) ph[k] = lds_phi[ry + RL * k];
+    vp = *reinterpret_cast<const f4v*>(&lds_varphi[cx * 4]);
+  } else {
+    vp = load_varphi(A.varphi, j0, nvalid);
   }
   f4v sq = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -752,6 +829,10 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G) {
   if (t < COLS) {
     const int j = strip * COLS + t;
     if (j < A.n) A.colpart[(size_t)run * A.n + j] = csum;
+  }
+  if (A.tilesum && t < 64) {  // total of the slab, for the fused update of the next sweep (wave 0)
+    const float tot = wave_sum(t < COLS ? csum : 0.f);
+    if (t == 0) A.tilesum[run * gridDim.x + strip] = tot;
   }
 }
 
@@ -1113,19 +1194,20 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // below that, keeping the lines cached is the better choice.  Measured crossover on MI355X:
 // cacheable wins at 8mn = 290 MB (7.2 vs 6.1 TB/s), non-temporal wins at 393 MB (6.1 vs 5.7 TB/s).
 inline bool use_nontemporal(int m, int n) { return 8.0 * (double)m * (double)n > 320.0 * 1024 * 1024; }
-template <bool FIRST>
-void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a) {
+template <bool FIRST, bool PRO>
+void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a, const FusedUpdateArgs& f) {
   const dim3 block(kSlabThreads);
   switch (k) {
-    case 1: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 1, kSlabLanes>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 2, kSlabLanes>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 4, kSlabLanes>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 8, kSlabLanes>), grid, block, 0, stream, a); break;
+    case 1: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 1, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
+    case 2: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 2, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
+    case 4: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 4, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
+    default: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 8, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
   }
 }
-void launch_slab(bool first, int k, dim3 grid, hipStream_t stream, const SlabArgs& a) {
-  if (first) launch_slab_k<true>(k, grid, stream, a);
-  else launch_slab_k<false>(k, grid, stream, a);
+void launch_slab(bool first, bool pro, int k, dim3 grid, hipStream_t stream, const SlabArgs& a, const FusedUpdateArgs& f) {
+  if (pro) launch_slab_k<false, true>(k, grid, stream, a, f);
+  else if (first) launch_slab_k<true, false>(k, grid, stream, a, f);
+  else launch_slab_k<false, false>(k, grid, stream, a, f);
 }
 
 constexpr int kMaxProfiled = 256;  // sweeps timed per solve in profile mode
@@ -1259,7 +1341,7 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->resid, 2));
   h->rowpart_half = (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m;  // 32-column strips (group-resident path) are the finest
   h->colpart_half = ntr * (size_t)max_n;
-  h->tilesum_half = nseg * ntr;
+  h->tilesum_half = nseg * ntr > 4096 ? nseg * ntr : 4096;  // (the group-resident path has up to 4096 slabs)
   take(dev_alloc(&h->rowpart, 2 * h->rowpart_half));
   take(dev_alloc(&h->colpart, 2 * h->colpart_half));
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
@@ -1549,7 +1631,10 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // before a residual check and at the end.
   // (eta comes from the tile totals whenever the problem is small enough for that path, whether or
   // not the fusion is switched on, so that both settings produce the same bits)
-  const bool small = reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096;
+  const int nstrips = ceil_div(n, kSlabCols);
+  const bool small_slab = slab_k && nstrips <= 64 && nruns <= 64 && nstrips * nruns <= 4096;
+  const bool small = small_slab ||
+                     (reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096);
   const bool fused = small && h->fused_update != 0;
   const bool skip_cost = h->skip_cost && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
@@ -1597,7 +1682,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
         else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, S, PT);
       } else if (slab_k) {
-        launch_slab(first, slab_k, slab_grid, stream, SL);
+        SL.S.tilesum = S.tilesum;
+        const FusedUpdateArgs F{rowp(sw - 1), colp(sw - 1), tsum(sw - 1), p, q, a_buf(sw - 2), b_buf(sw - 2),
+                                a_buf(sw - 1), b_buf(sw - 1), h->theta + ((sw - 2) & 1), h->theta + ((sw - 1) & 1),
+                                h->sum_p, h->phi, h->varphi, nstrips, nruns};
+        launch_slab(first, !materialized, slab_k, slab_grid, stream, SL, F);
       } else if (reg_kind == DROT_REG_GROUP_LASSO) {
         hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((ngroups + 255) / 256), 4)), dim3(256), 0, stream,
                            h->gbuf, ngroups, 0.f, (const int*)h->done);
@@ -1648,7 +1737,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         UA.b_out = b_buf(sw);
         UA.par = (int)((sw - 1) & 1);
         UA.tilesum = small ? tsum(sw) : nullptr;
-        UA.ntiles = ntiles;
+        UA.ntiles = small_slab ? nstrips * nruns : ntiles;
         hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
         hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
         materialized = true;

@@ -288,6 +288,32 @@ def test_fused_and_separate_vector_updates_give_the_same_bits(drot, oracle, m, n
     pu.assert_parity(oracle, P, res, X_chk, phi_chk, varphi_fused, ores, check_gap=False, label="fused")
 
 
+@pytest.mark.parametrize("m,n,classes", [(333, 517, 3), (1500, 1000, 2), (1203, 2047, 5), (700, 90, 1)])
+def test_group_lasso_fused_and_separate_vector_updates_give_the_same_bits(drot, oracle, m, n, classes):
+    # the same for the group-resident group-lasso sweep (1, 2, 4 or 8 rows per thread)
+    P = drot_inputs.random_problem(m, n, seed=650 + m, reg_kind=2, lam=0.1, mu=0.02, num_classes=classes)
+    _say(f"group lasso, fused vs separate update {m}x{n}, {classes} classes")
+    solver = drot.Solver(m, n)
+    _, X_fused, phi_fused, varphi_fused = pu.gpu_solve(solver, P, 90)
+    solver.set_fused_update(0)
+    _, X_sep, phi_sep, varphi_sep = pu.gpu_solve(solver, P, 90)
+    solver.set_fused_update(-1)
+    assert np.array_equal(X_fused, X_sep) and np.array_equal(phi_fused, phi_sep) and np.array_equal(varphi_fused, varphi_sep)
+    solver.set_check_every(7)
+    res, X_chk, phi_chk, _ = pu.gpu_solve(solver, P, 90, tol=1e-12)
+    assert res.iters == 90 and np.array_equal(X_chk, X_fused) and np.array_equal(phi_chk, phi_fused)
+    # continuation in two halves lands on the same bits
+    solver.set_check_every(100)
+    X = torch.empty((P.m, P.n), device="cuda:0")
+    pu.gpu_solve(solver, P, 41, X_out=X)
+    solver.set_continue(True)
+    _, X_two, phi_two, _ = pu.gpu_solve(solver, P, 49, X_out=X)
+    solver.set_continue(False)
+    assert np.array_equal(X_two, X_fused) and np.array_equal(phi_two, phi_fused)
+    ores = pu.oracle_solve(oracle, P, 90)
+    pu.assert_parity(oracle, P, res, X_chk, phi_chk, varphi_fused, ores, check_gap=False, label="fused group lasso")
+
+
 @pytest.mark.parametrize("K,check_every", [(150, 100), (151, 100), (37, 7)])
 @pytest.mark.parametrize("kind", [0, 1])
 def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
