@@ -124,23 +124,31 @@ int drot_set_nontemporal(drot_handle h, int mode);
 int drot_set_fused_update(drot_handle h, int mode);
 
 /*
- * Even/odd cost skipping [off] (Section "Quadratically Regularized DROT" of the paper's GPU
- * appendix).  When enabled, sweeps pair up: the first of a pair stores X - rho*C, the second reads
- * that and needs no C, so C is read every second sweep (20 instead of 24 bytes per element and
- * pair).  Row and column sums are always those of X itself, and X_out is the plain plan on return
- * and at every residual check.  The rounding differs slightly from the plain scheme (same
- * tolerance against the fp64 iteration).  Applies to the none/quadratic sweeps of problems too
- * large for the fused small-problem path; ignored otherwise.
+ * Even/odd cost skipping [-1 = automatic] (Section "Quadratically Regularized DROT" of the paper's
+ * GPU appendix).  Sweeps pair up: the first of a pair stores X - rho*C, the second reads that and
+ * needs no C, so C is read every second sweep (20 instead of 24 bytes per element and pair).  Row
+ * and column sums are always those of X itself, and X_out is the plain plan on return and at every
+ * residual check.  The rounding differs slightly from the plain scheme (same tolerance against the
+ * fp64 iteration).  The scheme applies to the none/quadratic sweeps over a stored cost whose vector
+ * update is not fused into the sweep.  mode -1 uses it for every such problem too large for the
+ * fused small-problem path, mode 1 also for small problems whose fusion has been switched off,
+ * mode 0 never (C read by every sweep).
  */
-int drot_set_skip_cost(drot_handle h, int enable);
+int drot_set_skip_cost(drot_handle h, int mode);
 
 /*
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
- * how many were timed.  Costs two event records per iteration, so leave it off when timing a solve.
+ * how many were timed (with even/odd cost skipping the two kinds of sweep alternate, starting with
+ * the one that reads C when the number of iterations between checks is even).  Costs two event records per iteration, so leave it off when timing a solve.
  */
 int drot_set_profile(drot_handle h, int enable);
 int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
+/* The individual durations, in launch order: sweep_ms [out] HOST, capacity floats; sweep_kind [out]
+ * HOST, capacity ints or NULL: 0 = the sweep read X and C, 1 = it also stored X - rho*C (first of an
+ * even/odd pair), 2 = it read the shifted X and no C (second of a pair); *sweeps_timed receives how
+ * many the last solve timed (at most min(capacity, that many) entries are written). */
+int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed);
 
 /*
  * Solve problem (1) by the iteration of eq. (8) + eq. (6), starting from X_0 = 0 and the

@@ -23,7 +23,7 @@ DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
-    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
 )
 
 
@@ -69,6 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.drot_set_skip_cost.argtypes = [vp, ci]
     lib.drot_set_profile.argtypes = [vp, ci]
     lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
+    lib.drot_get_profile_sweeps.argtypes = [vp, ctypes.POINTER(cf), ctypes.POINTER(ci), ci, ctypes.POINTER(ci)]
     lib.drot_solve.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp]
     lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_solve_points.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf,
@@ -154,8 +155,8 @@ class Solver:
         if rc != DROT_OK:
             raise DrotError(rc, "drot_set_fused_update")
 
-    def set_skip_cost(self, enable: bool) -> None:
-        rc = self._lib.drot_set_skip_cost(self._h, int(bool(enable)))
+    def set_skip_cost(self, mode: int) -> None:
+        rc = self._lib.drot_set_skip_cost(self._h, int(mode))
         if rc != DROT_OK:
             raise DrotError(rc, "drot_set_skip_cost")
 
@@ -171,6 +172,17 @@ class Solver:
         if rc != DROT_OK:
             raise DrotError(rc, "drot_get_profile")
         return ms.value, cnt.value
+
+    def profile_sweeps(self) -> list:
+        """[(ms, kind)] of the sweeps the last solve timed in profile mode, in launch order; kind as
+        drot_get_profile_sweeps reports it (0 reads X and C, 1 also stores X - rho*C, 2 reads no C)."""
+        buf = (ctypes.c_float * 256)()
+        kinds = (ctypes.c_int * 256)()
+        cnt = ctypes.c_int()
+        rc = self._lib.drot_get_profile_sweeps(self._h, buf, kinds, 256, ctypes.byref(cnt))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_profile_sweeps")
+        return [(float(buf[e]), int(kinds[e])) for e in range(min(cnt.value, 256))]
 
     def solve(self, C: torch.Tensor, p: torch.Tensor, q: torch.Tensor, *, stepsize: float = 0.0,
               reg_kind: int = DROT_REG_NONE, lam: float = 0.0, mu: float = 0.0,

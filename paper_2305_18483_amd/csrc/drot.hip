@@ -1224,7 +1224,7 @@ struct drot_handle_s {
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
-  int skip_cost = 0;      // even/odd scheme: C is read only every second sweep
+  int skip_cost = -1;     // even/odd scheme (C read every second sweep): -1 where it applies unless the update is fused, 0 never, 1 where it applies
   bool solved = false;
   int last_m = 0, last_n = 0;
   long long iters_done = 0;  // iterations applied to the state held by this handle
@@ -1232,6 +1232,8 @@ struct drot_handle_s {
   hipEvent_t prof_ev[2 * kMaxProfiled] = {};
   int prof_count = 0;
   double prof_sweep_ms = 0.0;
+  float prof_ms[kMaxProfiled] = {};  // per sweep, in launch order
+  int prof_kind[kMaxProfiled] = {};  // 0: reads X and C, 1: the same and stores X - rho*C, 2: reads the shifted X only
   // device workspace
   float *phi = nullptr, *varphi = nullptr;
   // a, b, rowpart, colpart, tilesum are double buffers (two halves), indexed by iteration parity
@@ -1411,9 +1413,9 @@ int drot_set_fused_update(drot_handle h, int mode) {
   return DROT_OK;
 }
 
-int drot_set_skip_cost(drot_handle h, int enable) {
-  if (!h) return DROT_ERR_INVALID_ARG;
-  h->skip_cost = enable ? 1 : 0;
+int drot_set_skip_cost(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 1) return DROT_ERR_INVALID_ARG;
+  h->skip_cost = mode;
   return DROT_OK;
 }
 
@@ -1434,6 +1436,17 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed) {
   if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
   *sweeps_timed = h->prof_count;
   *sweep_ms_avg = h->prof_count > 0 ? h->prof_sweep_ms / h->prof_count : 0.0;
+  return DROT_OK;
+}
+
+int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed) {
+  if (!h || !sweep_ms || capacity < 0 || !sweeps_timed) return DROT_ERR_INVALID_ARG;
+  if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
+  *sweeps_timed = h->prof_count;
+  for (int e = 0; e < h->prof_count && e < capacity; ++e) {
+    sweep_ms[e] = h->prof_ms[e];
+    if (sweep_kind) sweep_kind[e] = h->prof_kind[e];
+  }
   return DROT_OK;
 }
 
@@ -1636,7 +1649,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   const bool small = small_slab ||
                      (reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096);
   const bool fused = small && h->fused_update != 0;
-  const bool skip_cost = h->skip_cost && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
+  const bool skip_cost = (h->skip_cost == 1 || (h->skip_cost == -1 && !small)) &&
+                         reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
   auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
@@ -1673,7 +1687,10 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       const long long sw = k_base + k + 1;  // this sweep produces X_sw; its sums live in the sw-parity buffers
       const bool first = (sw == 1) && !warm;  // X_0 = 0: nothing to read
       const bool timed = h->profile && k < kMaxProfiled;
-      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
+      if (timed) {
+        DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
+        h->prof_kind[k] = 0;
+      }
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
       S.tilesum = small ? tsum(sw) : nullptr;
@@ -1712,6 +1729,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
+        if (timed) h->prof_kind[k] = mode;
         const FusedUpdateArgs none{};
         if (first) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, S, none);
@@ -1789,6 +1807,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       float ms = 0.f;
       DROT_HIP(hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]));
       h->prof_sweep_ms += (double)ms;
+      h->prof_ms[e] = ms;
     }
     h->prof_count = timed;
   }

@@ -322,7 +322,7 @@ def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
     P = drot_inputs.random_problem(700, 1300, seed=700 + K, reg_kind=kind, lam=0.3 if kind else 0.0)
     solver = drot.Solver(P.m, P.n, check_every=check_every)
     solver.set_fused_update(0)  # the scheme applies to the unfused sweep
-    solver.set_skip_cost(True)
+    solver.set_skip_cost(1)
     _say(f"even/odd K={K} check_every={check_every} kind={kind}")
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, K, tol=1e-12)  # residual checks active, never pass
     assert gres.iters == K
@@ -331,15 +331,36 @@ def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
     _say(f"even/odd: plan error / scale = {ratio:.2e}")
 
 
-def test_even_odd_full_size_sampled(drot, oracle):
-    # 10000 x 10000 (the unfused, non-temporal launch configuration the benchmark times)
+def test_plain_scheme_full_size(drot, oracle):
+    # 10000 x 10000 with C read by every sweep (the default at this size is the even/odd scheme,
+    # which the cfg3 and cfg4 cases above cover)
     P = drot_inputs.config(3)
     solver = drot.Solver(P.m, P.n)
-    solver.set_skip_cost(True)
-    _say("even/odd at 10000 x 10000, K=25")
+    solver.set_skip_cost(0)
+    _say("plain scheme at 10000 x 10000, K=25")
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 25)
     ores = pu.oracle_solve(oracle, P, 25)
-    pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="even/odd cfg3")
+    pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="plain cfg3")
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+def test_even_odd_is_the_default_beyond_the_fused_path(drot, oracle, kind):
+    # 2300 rows are more than the fused small-problem path takes: mode -1 must give the bits of
+    # mode 1, mode 0 different rounding, and both match the fp64 iteration
+    P = drot_inputs.random_problem(2300, 700, seed=720 + kind, reg_kind=kind, lam=0.3 if kind else 0.0)
+    solver = drot.Solver(P.m, P.n)
+    _say(f"even/odd default kind={kind}")
+    res_auto, X_auto, phi_auto, varphi_auto = pu.gpu_solve(solver, P, 120)
+    solver.set_skip_cost(1)
+    _, X_on, _, _ = pu.gpu_solve(solver, P, 120)
+    solver.set_skip_cost(0)
+    res_off, X_off, phi_off, varphi_off = pu.gpu_solve(solver, P, 120)
+    assert np.array_equal(X_auto, X_on)
+    ores = pu.oracle_solve(oracle, P, 120)
+    pu.assert_parity(oracle, P, res_auto, X_auto, phi_auto, varphi_auto, ores, label="even/odd (default)")
+    pu.assert_parity(oracle, P, res_off, X_off, phi_off, varphi_off, ores, label="plain")
+    with pytest.raises(drot.DrotError):
+        solver.set_skip_cost(2)
 
 
 @pytest.mark.parametrize("kind,m,n", [(0, 150, 210), (1, 2300, 700), (2, 600, 333)])
