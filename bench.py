@@ -30,7 +30,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0}  # by kind of sweep: read X, read C, write X; kind 2 reads no C
+BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0, 3: 12.0}  # by kind of sweep: read X, read C, write X; kind 2 reads no C;
+# kind 3 (resident kernel) is priced at the same 12 although nothing leaves the registers
 
 # HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # copy kernel of known size (see profiles/); None until measured for a workload.
@@ -124,7 +125,8 @@ def main() -> int:
 
     kernel_names = {0: "gl_slab_kernel" if P.reg_kind == 2 else "sweep_kernel (reads X and C, stores X)",
                     1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
-                    2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)"}
+                    2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)",
+                    3: "resident_kernel (X and C stay in registers; the time is per iteration)"}
     prof = sweep_profile()
     solver.set_continue(False)
     even_odd = 1 in prof

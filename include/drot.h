@@ -124,6 +124,15 @@ int drot_set_nontemporal(drot_handle h, int mode);
 int drot_set_fused_update(drot_handle h, int mode);
 
 /*
+ * Resident kernel [-1 = automatic].  Problems of at most 128 x 256 without group lasso, solved from
+ * a stored cost, run in a single workgroup that keeps X and C in registers: all the iterations up
+ * to the next residual check (or all of them, without a tolerance) are one kernel launch.  Results
+ * agree with the other paths to rounding (same precision, different summation order).  mode 0
+ * sends such problems down the general path.
+ */
+int drot_set_resident(drot_handle h, int mode);
+
+/*
  * Even/odd cost skipping [-1 = automatic] (Section "Quadratically Regularized DROT" of the paper's
  * GPU appendix).  Sweeps pair up: the first of a pair stores X - rho*C, the second reads that and
  * needs no C, so C is read every second sweep (20 instead of 24 bytes per element and pair).  Row
@@ -146,8 +155,9 @@ int drot_set_profile(drot_handle h, int enable);
 int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
 /* The individual durations, in launch order: sweep_ms [out] HOST, capacity floats; sweep_kind [out]
  * HOST, capacity ints or NULL: 0 = the sweep read X and C, 1 = it also stored X - rho*C (first of an
- * even/odd pair), 2 = it read the shifted X and no C (second of a pair); *sweeps_timed receives how
- * many the last solve timed (at most min(capacity, that many) entries are written). */
+ * even/odd pair), 2 = it read the shifted X and no C (second of a pair), 3 = a launch of the resident
+ * kernel (its duration divided by the iterations it ran); *sweeps_timed receives how many the last
+ * solve timed (at most min(capacity, that many) entries are written). */
 int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed);
 
 /*

@@ -65,6 +65,27 @@ __device__ __forceinline__ float wave_sum(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// The same for a double (each step moves the two halves separately).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_mov_f64(double v) {
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)b, CTRL, ROW_MASK, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+  return __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned long long)(unsigned)lo);
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+  v += dpp_mov_f64<0xB1, 0xF>(v);
+  v += dpp_mov_f64<0x4E, 0xF>(v);
+  v += dpp_mov_f64<0x141, 0xF>(v);
+  v += dpp_mov_f64<0x140, 0xF>(v);
+  v += dpp_mov_f64<0x142, 0xA>(v);
+  v += dpp_mov_f64<0x143, 0xC>(v);
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, 63);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 63);
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | (unsigned long long)lo);
+}
+
 __device__ __forceinline__ f4v load4(const float* __restrict__ ptr, int nvalid) {
   if (nvalid == 4) return *reinterpret_cast<const f4u*>(ptr);
   f4v v = {0.f, 0.f, 0.f, 0.f};
@@ -1048,6 +1069,176 @@ __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Resident solver for tiny problems (at most 128 x 256): one workgroup keeps X and C in registers
+// and runs a whole stretch of iterations (the ones between two residual checks) in one launch, so
+// an iteration costs two workgroup barriers instead of a kernel launch.  Wave w owns rows
+// w, w + 16, ...; a lane owns four columns.  The eq. (6) state lives in registers of "owner"
+// threads: thread t < m owns row t (a_t, p_t), thread 256 + j owns column j (b_j, q_j); phi and
+// varphi travel through LDS.  Per iteration: (A) every wave updates its rows (first half of
+// eq. (8) and the quadratic scaling), leaves the row sums and its column partials in LDS;
+// barrier; (B) the owners form the residuals, eta, and the new phi, varphi, a, b, theta in fp64;
+// barrier.  Arithmetic and precision are those of the multi-launch path (fp32 sweep and
+// fp32 sums over at most 256 elements of a row resp. 8 of a column, fp64 above).
+// ------------------------------------------------------------------------------------------
+struct ResidentArgs {
+  float* X;
+  const float* C;
+  const float* p;
+  const float* q;
+  VecState V;
+  const double* a_in;
+  const double* b_in;
+  double* a_out;
+  double* b_out;
+  int theta_in, theta_out;  // entries of V.theta to read and to write
+  int m, n, ldx, ldc;
+  float rho, scale;
+  int iters;  // sweeps to run (>= 1)
+  int first;  // X_0 = 0: nothing to read
+};
+
+constexpr int kResidentCols = 256, kResidentMaxRows = 128;
+
+// NW waves, R rows per wave, CPL columns per lane (n <= 64 * CPL).  128 rows of 256 columns need
+// 8 waves with twice the registers each; narrower problems use fewer columns per lane instead, so
+// that no lane sits idle, and keep 16 waves.
+template <int R, int NW, int CPL>
+__global__ __launch_bounds__(64 * NW) void resident_kernel(ResidentArgs A) {
+  static_assert(NW >= 8 && R * NW <= kResidentMaxRows && 64 * CPL <= kResidentCols, "owner waves 0, 1 and 4..7 must exist");
+  if (*A.V.done) return;
+  __shared__ float lds_phi[kResidentMaxRows];
+  __shared__ float lds_varphi[kResidentCols];
+  __shared__ float lds_row[kResidentMaxRows];
+  __shared__ float lds_col[NW][64 * CPL];
+  __shared__ double red[NW];
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int j0 = lane * CPL;
+  const float rho = A.rho, scale = A.scale;
+
+  float x[R][CPL], c[R][CPL];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = wave + NW * r;
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) {
+      c[r][e] = 0.f;
+      x[r][e] = 0.f;
+      if (row < A.m && j0 + e < A.n) {
+        c[r][e] = A.C[(size_t)row * A.ldc + j0 + e];
+        if (!A.first) x[r][e] = A.X[(size_t)row * A.ldx + j0 + e];
+      }
+    }
+  }
+  const bool row_owner = t < A.m;  // (m <= 128: waves 0 and 1)
+  const int jc = t - 256;          // waves 4..7
+  const bool col_owner = jc >= 0 && jc < A.n;
+  double state = 0.0, target = 0.0;  // a_t and p_t of a row owner, b_j and q_j of a column owner
+  if (row_owner) { state = A.a_in[t]; target = (double)A.p[t]; }
+  if (col_owner) { state = A.b_in[jc]; target = (double)A.q[jc]; }
+  double theta = A.V.theta[A.theta_in];
+  const double sum_p = *A.V.sum_p;
+  // (divisions by m + n, n and m as multiplications by the fp64 reciprocals: one more rounding of 1e-16)
+  const double inv_mn = 1.0 / ((double)A.m + (double)A.n), inv_n = 1.0 / (double)A.n, inv_m = 1.0 / (double)A.m;
+  // rows and columns that do not exist get a huge negative dual value: the clamp zeroes them
+  if (t < kResidentMaxRows) {
+    lds_phi[t] = row_owner ? A.V.phi[t] : kMaskedOut;
+    lds_row[t] = 0.f;
+  }
+  if (jc >= 0 && jc < kResidentCols) lds_varphi[jc] = col_owner ? A.V.varphi[jc] : kMaskedOut;
+  __syncthreads();
+
+  const bool owner_wave = wave < 2 || (wave >= 4 && wave < 8);
+  double res = 0.0;  // the owner's residual after the latest sweep
+  float dual = 0.f;  // the owner's phi_t resp. varphi_j
+  for (int it = 0; it < A.iters; ++it) {
+    // (A) sweep
+    float vp[CPL], colacc[CPL];
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) {
+      vp[e] = lds_varphi[j0 + e];
+      colacc[e] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int row = wave + NW * r;
+      const float ph = lds_phi[row];
+      float rowacc = 0.f;
+#pragma unroll
+      for (int e = 0; e < CPL; ++e) {
+        const float v = fmaxf(fmaf(-rho, c[r][e], x[r][e] + (vp[e] + ph)), 0.f) * scale;
+        x[r][e] = v;
+        colacc[e] += v;
+        rowacc += v;
+      }
+      const float tot = wave_sum(rowacc);
+      if (lane == 0) lds_row[row] = tot;
+    }
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) lds_col[wave][j0 + e] = colacc[e];
+    __syncthreads();
+    // (B) eq. (6)
+    if (owner_wave) {
+      // 1^T X 1, the same bits in every owner wave
+      const double tot = wave_sum_f64((double)lds_row[lane] + (double)lds_row[lane + 64]);
+      const double eta = (tot - sum_p) * inv_mn;
+      const double cst = 2.0 * eta - theta;
+      theta -= eta;
+      if (wave < 2) {
+        res = (double)lds_row[t] - target;
+        dual = (float)((state - 2.0 * res + cst) * inv_n);
+        state -= res;
+        if (row_owner) lds_phi[t] = dual;
+      } else if (jc < 64 * CPL) {
+        double sj = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sj += (double)lds_col[w][jc];
+        res = sj - target;
+        dual = (float)((state - 2.0 * res + cst) * inv_m);
+        state -= res;
+        if (col_owner) lds_varphi[jc] = dual;
+      }
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = wave + NW * r;
+#pragma unroll
+    for (int e = 0; e < CPL; ++e)
+      if (row < A.m && j0 + e < A.n) A.X[(size_t)row * A.ldx + j0 + e] = x[r][e];
+  }
+  if (row_owner) {
+    A.V.phi[t] = dual;
+    A.a_out[t] = state;
+    A.V.r[t] = res;
+  }
+  if (col_owner) {
+    A.V.varphi[jc] = dual;
+    A.b_out[jc] = state;
+    A.V.s[jc] = res;
+  }
+  const double r2 = block_sum_f64(row_owner ? res * res : 0.0, red);
+  const double s2 = block_sum_f64(col_owner ? res * res : 0.0, red);
+  if (t == 0) {
+    A.V.theta[A.theta_out] = theta;
+    A.V.resid[0] = r2;
+    A.V.resid[1] = s2;
+  }
+}
+
+template <int CPL>
+void launch_resident(const ResidentArgs& RS, hipStream_t stream) {
+  const int m = RS.m;
+  if (m <= 16) hipLaunchKernelGGL((resident_kernel<1, 16, CPL>), dim3(1), dim3(1024), 0, stream, RS);
+  else if (m <= 32) hipLaunchKernelGGL((resident_kernel<2, 16, CPL>), dim3(1), dim3(1024), 0, stream, RS);
+  else if (m <= 64) hipLaunchKernelGGL((resident_kernel<4, 16, CPL>), dim3(1), dim3(1024), 0, stream, RS);
+  else if constexpr (CPL < 4) hipLaunchKernelGGL((resident_kernel<8, 16, CPL>), dim3(1), dim3(1024), 0, stream, RS);
+  else hipLaunchKernelGGL((resident_kernel<16, 8, CPL>), dim3(1), dim3(512), 0, stream, RS);
+}
+
 // S6: r_primal of Appendix C; raises the stop flag at the first check that passes so that every
 // later kernel of the solve returns at once.
 __global__ void status_kernel(VecState V, int iters, double tol) {
@@ -1223,6 +1414,7 @@ struct drot_handle_s {
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
+  int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
   int skip_cost = -1;     // even/odd scheme (C read every second sweep): -1 where it applies unless the update is fused, 0 never, 1 where it applies
   bool solved = false;
@@ -1233,7 +1425,9 @@ struct drot_handle_s {
   int prof_count = 0;
   double prof_sweep_ms = 0.0;
   float prof_ms[kMaxProfiled] = {};  // per sweep, in launch order
-  int prof_kind[kMaxProfiled] = {};  // 0: reads X and C, 1: the same and stores X - rho*C, 2: reads the shifted X only
+  int prof_kind[kMaxProfiled] = {};  // 0: reads X and C, 1: the same and stores X - rho*C, 2: reads the shifted X only, 3: resident stretch
+  int prof_iters[kMaxProfiled] = {}; // iterations the timed launch covers (1 unless resident)
+  int prof_used = 0;
   // device workspace
   float *phi = nullptr, *varphi = nullptr;
   // a, b, rowpart, colpart, tilesum are double buffers (two halves), indexed by iteration parity
@@ -1413,6 +1607,12 @@ int drot_set_fused_update(drot_handle h, int mode) {
   return DROT_OK;
 }
 
+int drot_set_resident(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 0) return DROT_ERR_INVALID_ARG;
+  h->resident = mode;
+  return DROT_OK;
+}
+
 int drot_set_skip_cost(drot_handle h, int mode) {
   if (!h || mode < -1 || mode > 1) return DROT_ERR_INVALID_ARG;
   h->skip_cost = mode;
@@ -1507,8 +1707,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   const bool nt = h->nontemporal < 0 ? use_nontemporal(m, n) : h->nontemporal != 0;
   // Rows that do not start on 128-byte lines are slow to stream: work on padded copies then.
   const int ld_pad = ceil_div(n, kAlignElems) * kAlignElems;
-  const bool pad_c = !from_points && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0));
-  const bool pad_x = (n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(X_out) % 128 != 0);
+  // Tiny problems: one workgroup holds X and C in registers for a whole stretch of iterations.
+  const bool resident = h->resident != 0 && reg_kind != DROT_REG_GROUP_LASSO && !from_points &&
+                        m <= kResidentMaxRows && n <= kResidentCols;
+  const bool pad_c = !resident && !from_points && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0));
+  const bool pad_x = !resident && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(X_out) % 128 != 0));
   auto grow = [&](float** buf, size_t* len) -> int {
     const size_t need = (size_t)m * (size_t)ld_pad;
     if (*len >= need) return DROT_OK;
@@ -1681,15 +1884,38 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   int k = 0, slot = 0, checks = 0;
   bool converged = false;
   bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
+  h->prof_used = 0;
   while (k < max_iters && !converged) {
     const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
-    for (int c = 0; c < chunk; ++c, ++k) {
+    if (resident) {
+      const long long sw = k_base + k + 1;         // first sweep of the stretch
+      const long long last = sw + chunk - 1;       // its last one: the state leaves in that generation's buffers
+      const bool timed = h->profile && h->prof_used < kMaxProfiled;
+      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * h->prof_used], stream));
+      const ResidentArgs RS{Xw, Cw, p, q, V, a_buf(sw - 1), b_buf(sw - 1), a_buf(last), b_buf(last),
+                            (int)((sw - 1) & 1), (int)(last & 1), m, n, ldx, ldc, rho, S.scale, chunk,
+                            (sw == 1 && !warm) ? 1 : 0};
+      if (n <= 64) launch_resident<1>(RS, stream);
+      else if (n <= 128) launch_resident<2>(RS, stream);
+      else launch_resident<4>(RS, stream);
+      if (timed) {
+        DROT_HIP(hipEventRecord(h->prof_ev[2 * h->prof_used + 1], stream));
+        h->prof_kind[h->prof_used] = 3;
+        h->prof_iters[h->prof_used] = chunk;
+        ++h->prof_used;
+      }
+      k += chunk;
+    }
+    for (int c = 0; !resident && c < chunk; ++c, ++k) {
       const long long sw = k_base + k + 1;  // this sweep produces X_sw; its sums live in the sw-parity buffers
       const bool first = (sw == 1) && !warm;  // X_0 = 0: nothing to read
-      const bool timed = h->profile && k < kMaxProfiled;
+      const bool timed = h->profile && h->prof_used < kMaxProfiled;
+      const int pe = h->prof_used;
       if (timed) {
-        DROT_HIP(hipEventRecord(h->prof_ev[2 * k], stream));
-        h->prof_kind[k] = 0;
+        DROT_HIP(hipEventRecord(h->prof_ev[2 * pe], stream));
+        h->prof_kind[pe] = 0;
+        h->prof_iters[pe] = 1;
+        ++h->prof_used;
       }
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
@@ -1729,7 +1955,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
-        if (timed) h->prof_kind[k] = mode;
+        if (timed) h->prof_kind[pe] = mode;
         const FusedUpdateArgs none{};
         if (first) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, S, none);
@@ -1744,7 +1970,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         }
       }
-      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * k + 1], stream));
+      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
       if (!fused || c == chunk - 1) {
         // complete the state in memory: update sw from the sums of X_sw
         RA.rowpart = rowp(sw);
@@ -1802,10 +2028,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->prof_count = 0;
   h->prof_sweep_ms = 0.0;
   if (h->profile) {
-    const int timed = k < kMaxProfiled ? k : kMaxProfiled;
+    const int timed = h->prof_used;
     for (int e = 0; e < timed; ++e) {
       float ms = 0.f;
       DROT_HIP(hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]));
+      ms /= (float)h->prof_iters[e];  // per iteration (a resident stretch is one launch)
       h->prof_sweep_ms += (double)ms;
       h->prof_ms[e] = ms;
     }

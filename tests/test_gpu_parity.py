@@ -314,6 +314,48 @@ def test_group_lasso_fused_and_separate_vector_updates_give_the_same_bits(drot, 
     pu.assert_parity(oracle, P, res, X_chk, phi_chk, varphi_fused, ores, check_gap=False, label="fused group lasso")
 
 
+@pytest.mark.parametrize("m,n", [(1, 1), (1, 256), (128, 1), (16, 256), (17, 33), (33, 200), (64, 255), (65, 130),
+                                 (100, 100), (128, 256)])
+@pytest.mark.parametrize("kind", [0, 1])
+def test_resident_kernel_for_tiny_problems(drot, oracle, m, n, kind):
+    # at most 128 x 256: one workgroup runs all the iterations between two residual checks in one
+    # launch; same tolerance against the fp64 iteration, and the general path agrees with it
+    P = drot_inputs.random_problem(m, n, seed=900 + 7 * m + n, reg_kind=kind, lam=0.4 if kind else 0.0)
+    solver = drot.Solver(m, n, check_every=13)
+    _say(f"resident {m}x{n} kind={kind}")
+    K = 200
+    tol = 1e-12 if m * n > 1 else 0.0  # checks every 13 iterations, never passes (1 x 1 is solved exactly)
+    res, X_res, phi_res, varphi_res = pu.gpu_solve(solver, P, K, tol=tol)
+    assert res.iters == K
+    ores = pu.oracle_solve(oracle, P, K)
+    pu.assert_parity(oracle, P, res, X_res, phi_res, varphi_res, ores, label="resident")
+    solver.set_resident(0)
+    res_gen, X_gen, phi_gen, varphi_gen = pu.gpu_solve(solver, P, K, tol=tol)
+    solver.set_resident(-1)
+    pu.assert_parity(oracle, P, res_gen, X_gen, phi_gen, varphi_gen, ores, label="general path, tiny problem")
+    # continuation: 77 + 123 iterations land where 200 do (resident stretches are deterministic)
+    X = torch.empty((m, n), device="cuda:0")
+    pu.gpu_solve(solver, P, 77, X_out=X)
+    solver.set_continue(True)
+    _, X_two, phi_two, _ = pu.gpu_solve(solver, P, 123, X_out=X)
+    solver.set_continue(False)
+    _, X_one, phi_one, _ = pu.gpu_solve(solver, P, K)
+    assert np.array_equal(X_two, X_one) and np.array_equal(phi_two, phi_one)
+
+
+def test_resident_kernel_stops_at_the_same_check_as_the_oracle(drot, oracle):
+    P = drot_inputs.config(1)
+    solver = drot.Solver(P.m, P.n, check_every=10)
+    _say("resident, stopping rule at cfg1")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 100000, tol=1e-5)
+    ores = pu.oracle_solve(oracle, P, 100000, tol=1e-5, check_every=10)
+    assert gres.converged and abs(gres.iters - ores.iters) <= 10
+    if gres.iters == ores.iters:
+        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="resident stopping")
+    r, s = pu.residuals(P, Xg)
+    assert max(r, s) <= 1e-5 + 1e-7
+
+
 @pytest.mark.parametrize("K,check_every", [(150, 100), (151, 100), (37, 7)])
 @pytest.mark.parametrize("kind", [0, 1])
 def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
@@ -363,7 +405,7 @@ def test_even_odd_is_the_default_beyond_the_fused_path(drot, oracle, kind):
         solver.set_skip_cost(2)
 
 
-@pytest.mark.parametrize("kind,m,n", [(0, 150, 210), (1, 2300, 700), (2, 600, 333)])
+@pytest.mark.parametrize("kind,m,n", [(0, 150, 210), (1, 2300, 700), (2, 600, 333), (1, 90, 120)])
 def test_warm_start_matches_the_oracle_from_the_same_point(drot, oracle, kind, m, n):
     # start from an arbitrary (X_0, phi_0, varphi_0): Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T, eq. (5)
     P = drot_inputs.random_problem(m, n, seed=800 + kind, reg_kind=kind, lam=0.2 if kind else 0.0,
