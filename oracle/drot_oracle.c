@@ -13,7 +13,8 @@
  * Pins (tests/test_oracle_*.py): closed-form affine projection vs. a dense least-squares solve;
  * unregularized optimum vs. brute force over permutations and vs. an LP solver; quadratic case
  * vs. its KKT system and an L-BFGS solve of the smooth dual; group-lasso prox vs. a numerical
- * minimiser and its textbook special cases; the O(m+n) vector recursion the paper prints as
+ * minimiser and its textbook special cases; the entrywise terms (weighted l1, constrained OT)
+ * vs. a numerical minimiser of the prox objective and vs. LPs with shifted cost resp. fixed zeros; the O(m+n) vector recursion the paper prints as
  * eq. (6) vs. the explicit iteration here; feasibility, nonnegativity, duality gap -> 0.
  * The exact iterates after K steps have no printed example in the paper: that part of parity is
  * "unpinned by the paper" and rests on this file being the definition written out.
@@ -141,6 +142,34 @@ void oracle_prox_h(double* Xbar, int m, int n, double rho, int reg_kind, double 
 }
 
 /*
+ * The two further members of the class of Section 2 that act entry by entry, applied to a
+ * nonnegative matrix Xbar in place, before oracle_prox_h:
+ *   weighted l1, h = sum w_ij |X_ij| with w >= 0 (W != NULL): the soft-threshold
+ *       sign(x) max(|x| - rho w, 0), which for x >= 0 is max(x - rho w, 0);
+ *   constrained OT, h = indicator{X_ij = 0 for (i,j) in S} (forbidden != NULL, nonzero marks S):
+ *       the projection, X_ij = 0 on S.
+ * Both leave the matrix nonnegative, and the prox of their sum with the quadratic or the
+ * group-lasso term is the composition in this order (entrywise shrinkage first, then the group
+ * shrinkage and scaling); a test checks that against a numerical minimiser.
+ */
+void oracle_prox_entrywise(double* Xbar, int m, int n, double rho, const float* W,
+                           const unsigned char* forbidden) {
+  if (!W && !forbidden) return;
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < m; ++i)
+    for (int j = 0; j < n; ++j) {
+      const size_t e = (size_t)i * n + j;
+      double x = Xbar[e];
+      if (W) {
+        x -= rho * (double)W[e];
+        if (x < 0.0) x = 0.0;
+      }
+      if (forbidden && forbidden[e]) x = 0.0;
+      Xbar[e] = x;
+    }
+}
+
+/*
  * The iteration, eq. (4) with the split of eq. (7):
  *     X_{k+1} = prox_{rho f}(Y_k) = prox_{rho h}([Y_k - rho C]_+)         (Lemma 3.1, eq. (8))
  *     Z_{k+1} = P(2 X_{k+1} - Y_k)                                         (projection above)
@@ -152,10 +181,12 @@ void oracle_prox_h(double* Xbar, int m, int n, double rho, int reg_kind, double 
  * Stopping (Appendix C): r = X 1 - p, s = X^T 1 - q, stop when max(||r||_2, ||s||_2) <= tol,
  * tested only at iterations that are multiples of check_every (tol <= 0: never).
  * res_trace (optional, 2*max_iters doubles): ||r||_2, ||s||_2 of every iterate.
+ * W, forbidden (optional): the entrywise terms of oracle_prox_entrywise, added to h.
  * Returns the number of iterations done, or -1 if memory ran out.
  */
 int oracle_drot_solve(const float* C, const double* p, const double* q, int m, int n, double rho,
                       int reg_kind, double lambda, double mu, const int* row_class, int num_classes,
+                      const float* W, const unsigned char* forbidden,
                       const double* X0, const double* phi0, const double* varphi0,
                       int max_iters, double tol, int check_every,
                       double* X_out, double* Y_out, double* phi_out, double* varphi_out,
@@ -194,6 +225,7 @@ int oracle_drot_solve(const float* C, const double* p, const double* q, int m, i
         const double v = Y[e] - rho * (double)C[e];
         X[e] = v > 0.0 ? v : 0.0;
       }
+    oracle_prox_entrywise(X, m, n, rho, W, forbidden);
     oracle_prox_h(X, m, n, rho, reg_kind, lambda, mu, row_class, num_classes, gscratch);
     /* z-update */
 #pragma omp parallel for schedule(static)
@@ -254,14 +286,20 @@ void oracle_sqdist_cost(const float* xs, const float* xt, int m, int n, int d, d
  *   quadratic, lambda>0:  h*(W) = ||W||_F^2 / (2 lambda) -> dual_res = 0
  *   group lasso, lambda>0: h*(W) = sum_g max(||W_g||-mu,0)^2/(2 lambda), dual_res = 0
  *   group lasso, lambda=0: h* = indicator{||W_g|| <= mu} -> dual_res = ||(max(||W_g||-mu,0))_g||_2
+ * The entrywise terms (Wl1 = weights of the l1 term, forbidden = the set S of constrained OT)
+ * enter through their conjugates, which are indicators composed with h*'s argument: with them
+ *   W = [u 1^T + 1 v^T - C - Wl1]_+ outside S and W = 0 on S
+ * (the l1 term shifts the cost; entries of S are free in the dual), h(X) gains <Wl1, X>, and
+ * entries of S are left out of <C,X> (X vanishes there, whatever C holds).
  * out[0] = <C,X>, out[1] = h(X), out[2] = p^T u + q^T v, out[3] = h*(W) term, out[4] = gap,
  * out[5] = dual_res.
  */
 void oracle_objective_gap(const float* C, const double* X, const double* p, const double* q,
                           const double* phi, const double* varphi, int m, int n, double rho,
                           int reg_kind, double lambda, double mu, const int* row_class,
-                          int num_classes, double* out) {
-  double cx = 0.0, xx = 0.0, ww = 0.0;
+                          int num_classes, const float* Wl1, const unsigned char* forbidden,
+                          double* out) {
+  double cx = 0.0, xx = 0.0, ww = 0.0, l1 = 0.0;
   double* gx = NULL;
   double* gw = NULL;
   if (reg_kind == ORACLE_REG_GROUP_LASSO) {
@@ -272,10 +310,13 @@ void oracle_objective_gap(const float* C, const double* X, const double* p, cons
     const int c = gx ? row_class[i] : 0;
     for (int j = 0; j < n; ++j) {
       const size_t e = (size_t)i * n + j;
+      if (forbidden && forbidden[e]) continue; /* x = 0 and w = 0 there */
       const double x = X[e], cc = (double)C[e];
-      double w = (phi[i] + varphi[j]) / rho - cc;
+      const double wl = Wl1 ? (double)Wl1[e] : 0.0;
+      double w = (phi[i] + varphi[j]) / rho - cc - wl;
       if (w < 0.0) w = 0.0;
       cx += cc * x;
+      l1 += wl * x;
       xx += x * x;
       ww += w * w;
       if (gx) { gx[(size_t)c * n + j] += x * x; gw[(size_t)c * n + j] += w * w; }
@@ -303,6 +344,7 @@ void oracle_objective_gap(const float* C, const double* X, const double* p, cons
     if (lambda > 0.0) hstar = hs / (2.0 * lambda);
     else dres = sqrt(viol2);
   }
+  hX += l1;
   out[0] = cx; out[1] = hX; out[2] = dual_lin; out[3] = hstar;
   out[4] = cx + hX - dual_lin + hstar;
   out[5] = dres;

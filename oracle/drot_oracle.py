@@ -24,6 +24,7 @@ REG_NONE, REG_QUADRATIC, REG_GROUP_LASSO = 0, 1, 2
 _c_double_p = ctypes.POINTER(ctypes.c_double)
 _c_float_p = ctypes.POINTER(ctypes.c_float)
 _c_int_p = ctypes.POINTER(ctypes.c_int)
+_c_ubyte_p = ctypes.POINTER(ctypes.c_ubyte)
 
 
 def build(force: bool = False) -> str:
@@ -49,9 +50,13 @@ def _load():
         lib.oracle_prox_h.argtypes = [_c_double_p, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
                                       ctypes.c_double, ctypes.c_double, _c_int_p, ctypes.c_int, _c_double_p]
         lib.oracle_prox_h.restype = None
+        lib.oracle_prox_entrywise.argtypes = [_c_double_p, ctypes.c_int, ctypes.c_int, ctypes.c_double, _c_float_p,
+                                              _c_ubyte_p]
+        lib.oracle_prox_entrywise.restype = None
         lib.oracle_drot_solve.argtypes = [
             _c_float_p, _c_double_p, _c_double_p, ctypes.c_int, ctypes.c_int, ctypes.c_double,
             ctypes.c_int, ctypes.c_double, ctypes.c_double, _c_int_p, ctypes.c_int,
+            _c_float_p, _c_ubyte_p,
             _c_double_p, _c_double_p, _c_double_p,
             ctypes.c_int, ctypes.c_double, ctypes.c_int,
             _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p]
@@ -59,7 +64,7 @@ def _load():
         lib.oracle_objective_gap.argtypes = [
             _c_float_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_double, ctypes.c_double,
-            _c_int_p, ctypes.c_int, _c_double_p]
+            _c_int_p, ctypes.c_int, _c_float_p, _c_ubyte_p, _c_double_p]
         lib.oracle_objective_gap.restype = None
         lib.oracle_sqdist_cost.argtypes = [_c_float_p, _c_float_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_double, _c_float_p]
@@ -76,6 +81,23 @@ def _dp(a: Optional[np.ndarray]):
 
 def _ip(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(_c_int_p)
+
+
+def _fp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_c_float_p)
+
+
+def _bp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_c_ubyte_p)
+
+
+def _entrywise(weights, forbidden, shape):
+    """fp32 weights and a uint8 mask, contiguous, of the cost's shape (or None)."""
+    W = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
+    S = None if forbidden is None else np.ascontiguousarray(np.asarray(forbidden) != 0, dtype=np.uint8)
+    assert W is None or (W.shape == shape and (W >= 0).all())
+    assert S is None or S.shape == shape
+    return W, S
 
 
 def _f64(a) -> np.ndarray:
@@ -145,12 +167,21 @@ class OracleResult:
     Y: Optional[np.ndarray] = None
 
 
+def prox_entrywise(Xbar, rho, weights=None, forbidden=None):
+    """Weighted-l1 soft-threshold and/or zeroing of the forbidden entries of a nonnegative matrix."""
+    X = _f64(Xbar).copy()
+    W, S = _entrywise(weights, forbidden, X.shape)
+    _load().oracle_prox_entrywise(_dp(X), X.shape[0], X.shape[1], float(rho), _fp(W), _bp(S))
+    return X
+
+
 def solve(C, p, q, rho=None, reg_kind=REG_NONE, lam=0.0, mu=0.0, row_class=None, num_classes=0,
           max_iters=1000, tol=0.0, check_every=1, X0=None, phi0=None, varphi0=None,
-          return_Y=False) -> OracleResult:
+          return_Y=False, weights=None, forbidden=None) -> OracleResult:
     """Run the plain three-update iteration; see oracle_drot_solve in the C file."""
     C = np.ascontiguousarray(C, dtype=np.float32)
     m, n = C.shape
+    W, S = _entrywise(weights, forbidden, (m, n))
     p, q = _f64(p), _f64(q)
     rho = default_stepsize(m, n) if rho is None or rho <= 0 else float(rho)
     d_phi0, d_varphi0 = initial_vectors(m, n)
@@ -167,7 +198,7 @@ def solve(C, p, q, rho=None, reg_kind=REG_NONE, lam=0.0, mu=0.0, row_class=None,
     trace = np.zeros(2 * max(1, max_iters))
     it = _load().oracle_drot_solve(
         C.ctypes.data_as(_c_float_p), _dp(p), _dp(q), m, n, rho, int(reg_kind), float(lam), float(mu),
-        _ip(rc), int(num_classes), _dp(X0), _dp(phi0), _dp(varphi0), int(max_iters), float(tol),
+        _ip(rc), int(num_classes), _fp(W), _bp(S), _dp(X0), _dp(phi0), _dp(varphi0), int(max_iters), float(tol),
         int(check_every), _dp(X), _dp(Y), _dp(phi), _dp(varphi), _dp(trace))
     if it < 0:
         raise MemoryError("oracle ran out of memory")
@@ -190,13 +221,14 @@ class GapTerms:
 
 
 def objective_gap(C, X, p, q, phi, varphi, rho, reg_kind=REG_NONE, lam=0.0, mu=0.0, row_class=None,
-                  num_classes=0) -> GapTerms:
+                  num_classes=0, weights=None, forbidden=None) -> GapTerms:
     C = np.ascontiguousarray(C, dtype=np.float32)
     m, n = C.shape
+    W, S = _entrywise(weights, forbidden, (m, n))
     X, p, q, phi, varphi = _f64(X), _f64(p), _f64(q), _f64(phi), _f64(varphi)
     rc = None if row_class is None else np.ascontiguousarray(row_class, dtype=np.int32)
     out = np.zeros(6)
     _load().oracle_objective_gap(C.ctypes.data_as(_c_float_p), _dp(X), _dp(p), _dp(q), _dp(phi), _dp(varphi),
                                  m, n, float(rho), int(reg_kind), float(lam), float(mu), _ip(rc),
-                                 int(num_classes), _dp(out))
+                                 int(num_classes), _fp(W), _bp(S), _dp(out))
     return GapTerms(*[float(v) for v in out])

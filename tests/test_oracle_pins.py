@@ -433,3 +433,136 @@ def test_point_cloud_cost_matches_numpy_and_scipy(oracle):
     assert C.dtype == np.float32 and C.shape == (13, 9)
     assert np.abs(C - 0.25 * ref).max() <= 1e-6 * (0.25 * ref).max()
     assert (oracle.sqdist_cost(xs, xs, 1.0).diagonal() == 0).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# entrywise members of the class of Section 2: weighted l1 and constrained OT
+# ---------------------------------------------------------------------------------------------
+def _marginal_constraints(m, n):
+    A_eq = np.zeros((m + n, m * n))
+    for i in range(m):
+        A_eq[i, i * n:(i + 1) * n] = 1.0
+    for j in range(n):
+        A_eq[m + j, j::n] = 1.0
+    return A_eq
+
+
+def test_weighted_l1_prox_is_the_scalar_minimiser(oracle):
+    # argmin_x rho*w*|x| + (x - v)^2/2 for v >= 0, by a bounded scalar minimiser
+    rng = np.random.default_rng(21)
+    V = np.abs(rng.normal(size=(6, 5)))
+    W = rng.uniform(0.0, 2.0, size=(6, 5)).astype(np.float32)
+    rho = 0.7
+    out = oracle.prox_entrywise(V, rho, weights=W)
+    hit_zero = 0
+    for v, w, x in zip(V.ravel(), W.ravel().astype(np.float64), out.ravel()):
+        ref = sopt.minimize_scalar(lambda z: rho * w * abs(z) + 0.5 * (z - v) ** 2, bounds=(-5.0, 5.0), method="bounded",
+                                   options=dict(xatol=1e-12)).x
+        assert abs(x - ref) < 1e-6
+        assert x == max(v - rho * w, 0.0)
+        hit_zero += int(x == 0.0)
+    assert 0 < hit_zero < V.size
+    # forbidden entries are projected to zero, the rest is untouched
+    S = rng.uniform(size=V.shape) < 0.3
+    out = oracle.prox_entrywise(V, rho, forbidden=S)
+    assert not out[S].any() and np.array_equal(out[~S], V[~S])
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.6])
+def test_entrywise_terms_compose_with_the_group_lasso_prox(oracle, lam):
+    # prox of rho*(<W,X> + indicator{X_S = 0} + mu*sum_g ||X_g|| + lam/2 ||X||^2) at a nonnegative
+    # point, computed as entrywise step then group step, against a numerical minimiser per group
+    rng = np.random.default_rng(22)
+    m, n, ncls = 6, 4, 2
+    row_class = np.array([0, 1, 0, 1, 1, 0], dtype=np.int32)
+    V = np.abs(rng.normal(size=(m, n)))
+    W = rng.uniform(0.0, 0.8, size=(m, n)).astype(np.float32)
+    S = rng.uniform(size=(m, n)) < 0.25
+    rho, mu = 0.5, 0.7
+    out = oracle.prox_h(oracle.prox_entrywise(V, rho, weights=W, forbidden=S), rho, reg_kind=oracle.REG_GROUP_LASSO,
+                        lam=lam, mu=mu, row_class=row_class, num_classes=ncls)
+    assert not out[S].any() and out.min() >= 0.0
+    for c in range(ncls):
+        rows = np.where(row_class == c)[0]
+        for j in range(n):
+            free = ~S[rows, j]
+            v, w, x = V[rows, j][free], W[rows, j][free].astype(np.float64), out[rows, j][free]
+            if v.size == 0:
+                continue
+
+            def f(z):
+                return (w @ np.abs(z)) + mu * np.linalg.norm(z) + 0.5 * lam * (z @ z) + ((z - v) @ (z - v)) / (2 * rho)
+
+            best = min(sopt.minimize(f, z0, method="Nelder-Mead", options=dict(xatol=1e-10, fatol=1e-14, maxiter=40000)).fun
+                       for z0 in (v, 0.5 * v, 1e-3 * np.ones_like(v)))
+            assert f(x) <= best + 1e-9
+
+
+@pytest.mark.parametrize("m,n,seed", [(6, 9, 5), (10, 10, 6)])
+def test_weighted_l1_solution_equals_lp_with_shifted_cost(oracle, m, n, seed):
+    # on X >= 0 the l1 term is linear: min <C,X> + <W,X> over the transport polytope
+    C, p, q = _rand_problem(m, n, seed)
+    W = np.random.default_rng(seed + 50).uniform(0.0, 0.7, size=(m, n)).astype(np.float32)
+    A_eq = _marginal_constraints(m, n)
+    lp = sopt.linprog((C.astype(np.float64) + W.astype(np.float64)).ravel(), A_eq=A_eq[:-1],
+                      b_eq=np.concatenate([p, q])[:-1], bounds=(0, None), method="highs")
+    assert lp.status == 0
+    rho = oracle.default_stepsize(m, n)
+    res = oracle.solve(C, p, q, max_iters=60000, weights=W)
+    g = oracle.objective_gap(C, res.X, p, q, res.phi, res.varphi, rho, weights=W)
+    assert abs(g.objective - lp.fun) < 1e-9
+    assert abs(g.h - float((W.astype(np.float64) * res.X).sum())) < 1e-12
+    assert abs(g.gap) < 1e-9 and g.dual_res < 1e-9
+    # the plain problem with the same C has a different optimum: the weights matter here
+    lp0 = sopt.linprog(C.astype(np.float64).ravel(), A_eq=A_eq[:-1], b_eq=np.concatenate([p, q])[:-1], bounds=(0, None),
+                       method="highs")
+    assert lp0.fun < lp.fun - 1e-3
+
+
+@pytest.mark.parametrize("n", [4, 5, 6])
+def test_constrained_optimum_equals_best_allowed_permutation(oracle, n):
+    # uniform marginals: the optimum over plans that vanish on S is a permutation avoiding S
+    C, p, q = _rand_problem(n, n, 300 + n, uniform=True)
+    best_perm = min(itertools.permutations(range(n)), key=lambda s: sum(float(C[i, s[i]]) for i in range(n)))
+    S = np.zeros((n, n), dtype=bool)
+    for i in range(0, n, 2):
+        S[i, best_perm[i]] = True  # forbid half of the unconstrained optimum
+    allowed = [s for s in itertools.permutations(range(n)) if not any(S[i, s[i]] for i in range(n))]
+    best = min(sum(float(C[i, s[i]]) for i in range(n)) for s in allowed) / n
+    rho = oracle.default_stepsize(n, n)
+    res = oracle.solve(C, p, q, max_iters=40000, forbidden=S)
+    g = oracle.objective_gap(C, res.X, p, q, res.phi, res.varphi, rho, forbidden=S)
+    assert not res.X[S].any()
+    assert abs(g.objective - best) < 1e-9 and abs(g.gap) < 1e-9 and g.dual_res < 1e-9
+    assert max(res.res_row[-1], res.res_col[-1]) < 1e-9
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.05])
+def test_constrained_solution_equals_constrained_program(oracle, lam):
+    # general marginals: LP (lam = 0) resp. QP (lam > 0, SLSQP) with the entries of S fixed at zero
+    m, n = 7, 6
+    C, p, q = _rand_problem(m, n, 77)
+    S = np.random.default_rng(78).uniform(size=(m, n)) < 0.3
+    S[np.arange(m), np.arange(m) % n] = False  # keep the problem feasible with room to spare
+    A_eq = _marginal_constraints(m, n)
+    b_eq = np.concatenate([p, q])
+    bounds = [(0, 0) if s else (0, None) for s in S.ravel()]
+    c64 = C.astype(np.float64).ravel()
+    lp = sopt.linprog(c64, A_eq=A_eq[:-1], b_eq=b_eq[:-1], bounds=bounds, method="highs")
+    assert lp.status == 0
+    rho = oracle.default_stepsize(m, n)
+    kind = oracle.REG_QUADRATIC if lam > 0 else oracle.REG_NONE
+    res = oracle.solve(C, p, q, reg_kind=kind, lam=lam, max_iters=80000, forbidden=S)
+    g = oracle.objective_gap(C, res.X, p, q, res.phi, res.varphi, rho, reg_kind=kind, lam=lam, forbidden=S)
+    assert not res.X[S].any() and max(res.res_row[-1], res.res_col[-1]) < 1e-9
+    if lam == 0.0:
+        assert abs(g.objective - lp.fun) < 1e-9
+    else:
+        qp = sopt.minimize(lambda x: c64 @ x + 0.5 * lam * (x @ x), lp.x, jac=lambda x: c64 + lam * x, method="SLSQP",
+                           bounds=bounds, constraints=[dict(type="eq", fun=lambda x: A_eq[:-1] @ x - b_eq[:-1],
+                                                            jac=lambda x: A_eq[:-1])],
+                           options=dict(ftol=1e-14, maxiter=500))
+        assert qp.success
+        assert abs(g.objective - qp.fun) < 1e-7
+        assert np.abs(res.X.ravel() - qp.x).max() < 1e-5
+    assert abs(g.gap) < 1e-8
