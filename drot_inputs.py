@@ -11,6 +11,7 @@ random parameters, so the shapes and distributions below are a synthetic recipe 
 """
 from __future__ import annotations
 
+import dataclasses
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -39,6 +40,8 @@ class Problem:
     xs: Optional[np.ndarray] = None  # (m, d) float32 source points
     xt: Optional[np.ndarray] = None  # (n, d) float32 target points
     cmax: float = 1.0  # the max squared distance C was divided by
+    weights: Optional[np.ndarray] = None  # (m, n) float32 >= 0: weights of an added l1 term, or None
+    forbidden: Optional[np.ndarray] = None  # (m, n) bool: pairs that must carry no mass (constrained OT), or None
     meta: dict = field(default_factory=dict)
 
     @property
@@ -175,3 +178,19 @@ def random_problem(m: int, n: int, seed: int, d: int = 3, reg_kind: int = REG_NO
             row_class = np.sort(row_class)
     return point_cloud_problem(f"rand_{m}x{n}_s{seed}", xs, xt, p, q, reg_kind=reg_kind, lam=lam, mu=mu,
                                row_class=row_class, num_classes=num_classes)
+
+
+def with_entrywise_terms(P: Problem, seed: int, weight_scale: float = 0.0, forbid_frac: float = 0.0) -> Problem:
+    """Copy of P with random l1 weights in [0, weight_scale) and/or a random set of forbidden pairs.
+
+    Pairs with (i + j) % 3 == 0 are never forbidden, so every row and column keeps allowed partners.
+    """
+    rng = np.random.default_rng(seed)
+    m, n = P.m, P.n
+    W = rng.uniform(0.0, weight_scale, size=(m, n)).astype(np.float32) if weight_scale > 0 else None
+    S = None
+    if forbid_frac > 0:
+        S = rng.uniform(size=(m, n)) < forbid_frac
+        ii, jj = np.meshgrid(np.arange(m), np.arange(n), indexing="ij")
+        S &= (ii + jj) % 3 != 0
+    return dataclasses.replace(P, name=P.name + "_entrywise", weights=W, forbidden=S)

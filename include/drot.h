@@ -57,7 +57,19 @@ typedef struct {
   float mu;              /* group-lasso weight, >= 0; GROUP_LASSO only                              */
   int num_classes;       /* GROUP_LASSO only: number of row classes, >= 1                           */
   const int* row_class;  /* GROUP_LASSO only: DEVICE pointer, m labels in [0, num_classes)          */
+  const float* weights;  /* any kind (stored cost only): NULL, or DEVICE pointer to m*n weights
+                            w_ij >= 0, row-major, of an added weighted l1 term sum w_ij |X_ij|
+                            (Section 2, list of sparsity promoting regularizers)                     */
 } drot_reg_params;
+
+/*
+ * Constrained OT (same list: h = indicator{X_ij = 0 for (i,j) in S}) needs no parameter: set
+ * C_ij = +INFINITY for the pairs of S.  Every sweep then leaves X_ij = 0 there, the pair adds
+ * nothing to <C,X>, and its dual constraint is vacuous.  Combines with every regularizer kind.
+ * Weighted l1: on X >= 0 the term equals <W,X>, so the solve runs on a working copy C + W that the
+ * library forms once per call (one extra pass, m*n floats of workspace); drot_info.objective
+ * counts <W,X> as part of h.  Not available with drot_solve_points.
+ */
 
 /* Result of the last solve on a handle (host struct). */
 typedef struct {

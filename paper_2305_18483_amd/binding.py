@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = (
 
 class drot_reg_params(ctypes.Structure):
     _fields_ = [("lambda_", ctypes.c_float), ("mu", ctypes.c_float), ("num_classes", ctypes.c_int),
-                ("row_class", ctypes.c_void_p)]
+                ("row_class", ctypes.c_void_p), ("weights", ctypes.c_void_p)]
 
 
 class drot_info(ctypes.Structure):
@@ -195,17 +195,20 @@ class Solver:
               row_class: Optional[torch.Tensor] = None, num_classes: int = 0, max_iters: int = 1000,
               tol: float = 0.0, X_out: Optional[torch.Tensor] = None,
               stream: Optional[torch.cuda.Stream] = None, phi0: Optional[torch.Tensor] = None,
-              varphi0: Optional[torch.Tensor] = None) -> SolveResult:
+              varphi0: Optional[torch.Tensor] = None, weights: Optional[torch.Tensor] = None) -> SolveResult:
         """drot_solve (or drot_solve_warm when phi0 and varphi0 are given: X_out then holds X_0 on entry);
-        raises DrotError on a negative return code."""
+        raises DrotError on a negative return code.  weights: m x n device tensor of the weighted l1 term."""
         m, n = C.shape
         warm = phi0 is not None or varphi0 is not None
         if X_out is None:
             if warm:
                 raise ValueError("a warm start needs X_out holding the starting plan")
             X_out = torch.empty_like(C)
+        if weights is not None and tuple(weights.shape) != (m, n):
+            raise ValueError("weights must have the shape of C")
         params = drot_reg_params(float(lam), float(mu), int(num_classes),
-                                 None if row_class is None else row_class.data_ptr())
+                                 None if row_class is None else row_class.data_ptr(),
+                                 None if weights is None else _ptr(weights, torch.float32, "weights").value)
         if row_class is not None:
             _ptr(row_class, torch.int32, "row_class")
         stream = stream if stream is not None else torch.cuda.current_stream(C.device)
@@ -234,7 +237,7 @@ class Solver:
             raise ValueError("xs and xt must have the same number of columns")
         if X_out is None:
             X_out = torch.empty((m, n), dtype=torch.float32, device=xs.device)
-        params = drot_reg_params(float(lam), 0.0, 0, None)
+        params = drot_reg_params(float(lam), 0.0, 0, None, None)
         stream = stream if stream is not None else torch.cuda.current_stream(xs.device)
         rc = self._lib.drot_solve_points(self._h, _ptr(xs, torch.float32, "xs"), _ptr(xt, torch.float32, "xt"), int(d),
                                          float(cost_scale), _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"),

@@ -1239,6 +1239,16 @@ void launch_resident(const ResidentArgs& RS, hipStream_t stream) {
   else hipLaunchKernelGGL((resident_kernel<16, 8, CPL>), dim3(1), dim3(512), 0, stream, RS);
 }
 
+// Working copy of the cost for the weighted l1 term: out[i][j] = C[i][j] + W[i][j] (pitch ld; the
+// pad columns keep their zeros).  +inf entries of C (forbidden pairs) stay +inf.
+__global__ __launch_bounds__(256) void add_weights_kernel(float* __restrict__ out, const float* __restrict__ C,
+                                                          const float* __restrict__ W, int m, int n, int ld) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n) return;
+  for (int i = blockIdx.y; i < m; i += gridDim.y)
+    out[(size_t)i * ld + j] = C[(size_t)i * n + j] + W[(size_t)i * n + j];
+}
+
 // S6: r_primal of Appendix C; raises the stop flag at the first check that passes so that every
 // later kernel of the solve returns at once.
 __global__ void status_kernel(VecState V, int iters, double tol) {
@@ -1290,7 +1300,10 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
     const f4v c = A.C ? load4(A.C + (size_t)i * A.ldc + j0, nvalid) : cost4_from_points(A.pts, i, j0, nvalid);
     const f4v x = load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c, vp + A.phi[i], A.rho);
-    const f4v x2 = x * x, w2 = w * w, cxv = c * x;
+    const f4v x2 = x * x, w2 = w * w;
+    // (a forbidden pair carries c = +inf and x = 0: it adds nothing to <C,X>)
+    const f4v cxv = {x.x > 0.f ? c.x * x.x : 0.f, x.y > 0.f ? c.y * x.y : 0.f, x.z > 0.f ? c.z * x.z : 0.f,
+                     x.w > 0.f ? c.w * x.w : 0.f};
     cx += (cxv.x + cxv.y) + (cxv.z + cxv.w);
     xx += (x2.x + x2.y) + (x2.z + x2.w);
     ww += (w2.x + w2.y) + (w2.z + w2.w);
@@ -1688,6 +1701,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       if (!(mu >= 0.f) || num_classes < 1 || !row_class) return DROT_ERR_INVALID_ARG;
     }
   }
+  // weighted l1 term <W, X>: on X >= 0 it shifts the cost, so the solve runs on a working copy C + W
+  const float* weights = reg_params ? reg_params->weights : nullptr;
+  if (weights && (from_points || reinterpret_cast<uintptr_t>(weights) % 4)) return DROT_ERR_INVALID_ARG;
   int cur_dev = -1;
   DROT_HIP(hipGetDevice(&cur_dev));
   if (cur_dev != h->device) return DROT_ERR_INVALID_ARG;  // the workspace lives on the creating device
@@ -1710,7 +1726,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // Tiny problems: one workgroup holds X and C in registers for a whole stretch of iterations.
   const bool resident = h->resident != 0 && reg_kind != DROT_REG_GROUP_LASSO && !from_points &&
                         m <= kResidentMaxRows && n <= kResidentCols;
-  const bool pad_c = !resident && !from_points && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0));
+  const bool pad_c = weights != nullptr ||
+                     (!resident && !from_points && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(C) % 128 != 0)));
   const bool pad_x = !resident && ((n % kAlignElems != 0) || (reinterpret_cast<uintptr_t>(X_out) % 128 != 0));
   auto grow = [&](float** buf, size_t* len) -> int {
     const size_t need = (size_t)m * (size_t)ld_pad;
@@ -1797,8 +1814,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     if (rc != DROT_OK) return rc;
     Cw = h->cpad;
     ldc = ld_pad;
-    DROT_HIP(hipMemcpy2DAsync(h->cpad, sizeof(float) * (size_t)ld_pad, C, sizeof(float) * (size_t)n,
-                              sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
+    if (weights)
+      hipLaunchKernelGGL(add_weights_kernel, dim3(ceil_div(n, 256), m < 65535 ? m : 65535), dim3(256), 0, stream,
+                         h->cpad, C, weights, m, n, ld_pad);
+    else
+      DROT_HIP(hipMemcpy2DAsync(h->cpad, sizeof(float) * (size_t)ld_pad, C, sizeof(float) * (size_t)n,
+                                sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
   }
   if (pad_x) {
     const int rc = grow(&h->xpad, &h->xpad_len);

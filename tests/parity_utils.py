@@ -20,6 +20,8 @@ RES_TOL = 1e-6
 def to_dev(P):
     dev = torch.device("cuda:0")
     C = torch.from_numpy(P.C).to(dev)
+    if P.forbidden is not None:  # the library's convention for constrained OT: +inf cost on the forbidden pairs
+        C = torch.where(torch.from_numpy(P.forbidden).to(dev), torch.full_like(C, float("inf")), C)
     p = torch.from_numpy(P.p).to(dev)
     q = torch.from_numpy(P.q).to(dev)
     rc = None if P.row_class is None else torch.from_numpy(P.row_class).to(dev)
@@ -28,8 +30,9 @@ def to_dev(P):
 
 def gpu_solve(solver, P, max_iters, tol=0.0, stepsize=0.0, stream=None, X_out=None):
     C, p, q, rc = to_dev(P)
+    W = None if P.weights is None else torch.from_numpy(P.weights).to(C.device)
     res = solver.solve(C, p, q, stepsize=stepsize, reg_kind=P.reg_kind, lam=P.lam, mu=P.mu, row_class=rc,
-                       num_classes=P.num_classes, max_iters=max_iters, tol=tol, stream=stream, X_out=X_out)
+                       num_classes=P.num_classes, max_iters=max_iters, tol=tol, stream=stream, X_out=X_out, weights=W)
     phi, varphi = solver.duals(P.m, P.n, C.device)
     torch.cuda.synchronize()
     return res, res.X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy()
@@ -39,14 +42,15 @@ def oracle_solve(oracle, P, max_iters, tol=0.0, check_every=1, stepsize=None):
     rho = float(P.rho) if stepsize is None else float(np.float32(stepsize))
     return oracle.solve(P.C, P.p, P.q, rho=rho, reg_kind=P.reg_kind, lam=float(np.float32(P.lam)),
                         mu=float(np.float32(P.mu)), row_class=P.row_class, num_classes=P.num_classes,
-                        max_iters=max_iters, tol=tol, check_every=check_every)
+                        max_iters=max_iters, tol=tol, check_every=check_every, weights=P.weights,
+                        forbidden=P.forbidden)
 
 
 def fp64_terms(oracle, P, X, phi, varphi, stepsize=None):
     rho = float(P.rho) if stepsize is None else float(np.float32(stepsize))
     return oracle.objective_gap(P.C, X, P.p, P.q, phi, varphi, rho, reg_kind=P.reg_kind,
                                 lam=float(np.float32(P.lam)), mu=float(np.float32(P.mu)), row_class=P.row_class,
-                                num_classes=P.num_classes)
+                                num_classes=P.num_classes, weights=P.weights, forbidden=P.forbidden)
 
 
 def residuals(P, X):

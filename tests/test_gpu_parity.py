@@ -405,6 +405,29 @@ def test_even_odd_is_the_default_beyond_the_fused_path(drot, oracle, kind):
         solver.set_skip_cost(2)
 
 
+@pytest.mark.parametrize("terms", ["weights", "forbidden", "both"])
+@pytest.mark.parametrize("kind,m,n", [(0, 90, 120), (1, 128, 256), (0, 333, 517), (1, 700, 90), (2, 333, 517),
+                                      (0, 2300, 700), (1, 2300, 700), (2, 2300, 700)])
+def test_weighted_l1_and_constrained_ot(drot, oracle, kind, m, n, terms):
+    # the entrywise members of the regularizer class: l1 weights (the library solves on C + W) and
+    # forbidden pairs (C = +inf), alone, together and on top of the quadratic and group-lasso terms;
+    # the shapes cover the resident, the fused small-problem, the even/odd and the group-resident paths
+    base = drot_inputs.random_problem(m, n, seed=1100 + m + kind, reg_kind=kind, lam=0.3 if kind else 0.0,
+                                      mu=0.03 if kind == 2 else 0.0, num_classes=4)
+    P = drot_inputs.with_entrywise_terms(base, seed=1200 + n, weight_scale=0.5 if terms != "forbidden" else 0.0,
+                                         forbid_frac=0.3 if terms != "weights" else 0.0)
+    gres, Xg, ores = _run_case(drot, oracle, P, 150, f"{terms} kind={kind} {m}x{n}")
+    if P.forbidden is not None:
+        assert not Xg[P.forbidden].any() and not ores.X[P.forbidden].any()
+        assert np.isfinite(gres.objective) and np.isfinite(gres.gap)
+
+
+def test_constrained_ot_on_the_two_pass_group_lasso_path(drot, oracle):
+    base = drot_inputs.random_problem(300, 413, seed=1301, reg_kind=2, lam=0.1, mu=0.05, num_classes=5, sorted_classes=False)
+    P = drot_inputs.with_entrywise_terms(base, seed=1302, weight_scale=0.4, forbid_frac=0.25)
+    _run_case(drot, oracle, P, 200, "entrywise terms, unsorted labels")
+
+
 @pytest.mark.parametrize("kind,m,n", [(0, 150, 210), (1, 2300, 700), (2, 600, 333), (1, 90, 120)])
 def test_warm_start_matches_the_oracle_from_the_same_point(drot, oracle, kind, m, n):
     # start from an arbitrary (X_0, phi_0, varphi_0): Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T, eq. (5)
@@ -472,3 +495,33 @@ def test_cost_from_point_clouds(drot, oracle, m, n, d, kind):
     ratio = pu.assert_parity(oracle, P, res, res.X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores,
                              label="points")
     _say(f"point-cloud cost: plan error / scale = {ratio:.2e}")
+
+
+def test_ot_cost_gradient_is_the_plan(drot, oracle):
+    # Section "Backpropagation through regularized OT-costs": grad_C OT_h(C) = X* when the
+    # solution is unique (quadratic term).  Checked against the oracle's plan at convergence and
+    # against central differences of the value along a random direction.
+    # (lambda is large so that the plan varies smoothly over the finite-difference step: with a weak
+    # quadratic term OT_h is nearly piecewise linear in C and a central difference straddles kinks)
+    P = drot_inputs.random_problem(40, 50, seed=1400, reg_kind=1, lam=50.0)
+    dev = torch.device("cuda:0")
+    C, p, q, _ = pu.to_dev(P)
+    solver = drot.Solver(P.m, P.n, check_every=50)
+    kw = dict(reg_kind=1, lam=P.lam, max_iters=200000, tol=1e-7)
+    _say("ot_cost value and gradient")
+    Cg = C.clone().requires_grad_(True)
+    value = drot.ot_cost(solver, Cg, p, q, **kw)
+    (3.0 * value).backward()
+    grad = Cg.grad.cpu().numpy() / 3.0
+    ores = oracle.solve(P.C, P.p, P.q, rho=float(P.rho), reg_kind=1, lam=float(np.float32(P.lam)), max_iters=200000,
+                        tol=1e-9, check_every=50)
+    assert np.abs(grad - ores.X).max() <= 1e-4 * ores.X.max()
+    t = oracle.objective_gap(P.C, ores.X, P.p, P.q, ores.phi, ores.varphi, float(P.rho), reg_kind=1,
+                             lam=float(np.float32(P.lam)))
+    assert abs(float(value.detach()) - t.objective) <= 1e-5 * abs(t.objective)
+    E = torch.from_numpy(np.random.default_rng(1401).uniform(-1.0, 1.0, size=(P.m, P.n)).astype(np.float32)).to(dev)
+    eps = 2e-3
+    up = float(drot.ot_cost(solver, C + eps * E, p, q, **kw))
+    down = float(drot.ot_cost(solver, C - eps * E, p, q, **kw))
+    directional = float((E.cpu().numpy().astype(np.float64) * grad).sum())
+    assert abs((up - down) / (2 * eps) - directional) <= 1e-2 * abs(directional)

@@ -54,11 +54,12 @@ def test_argument_validation_without_a_gpu(lib):
 def test_struct_layouts_match_the_header():
     from paper_2305_18483_amd import binding
 
-    # drot_info: int, int, float, float, double x3 ; drot_reg_params: float, float, int, pointer
+    # drot_info: int, int, float, float, double x3 ; drot_reg_params: float, float, int, pointer, pointer
     assert ctypes.sizeof(binding.drot_info) == 40
     assert binding.drot_info.objective.offset == 16
-    assert ctypes.sizeof(binding.drot_reg_params) == 24
+    assert ctypes.sizeof(binding.drot_reg_params) == 32
     assert binding.drot_reg_params.row_class.offset == 16
+    assert binding.drot_reg_params.weights.offset == 24
 
 
 def test_input_generators_are_seeded_and_normalised():
