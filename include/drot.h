@@ -136,6 +136,16 @@ int drot_set_nontemporal(drot_handle h, int mode);
 int drot_set_fused_update(drot_handle h, int mode);
 
 /*
+ * Unchanged segments [-1 = on].  A sweep that reads X and C and stores X (not the pair of the
+ * even/odd scheme) compares the 256 new values of a row segment with the ones it loaded and
+ * skips the store when all are equal bit for bit: transport plans are sparse, so once the support
+ * has settled most segments are zero and stay zero, and the write (4 of the 12 bytes per
+ * element) disappears for them.  The memory contents are the same either way.  mode 0 stores
+ * every segment.
+ */
+int drot_set_skip_unchanged(drot_handle h, int mode);
+
+/*
  * Resident kernel [-1 = automatic].  Problems of at most 128 x 256 without group lasso, solved from
  * a stored cost, run in a single workgroup that keeps X and C in registers: all the iterations up
  * to the next residual check (or all of them, without a tolerance) are one kernel launch.  Results

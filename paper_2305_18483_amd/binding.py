@@ -23,7 +23,7 @@ DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
-    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_resident", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_resident", "drot_set_skip_unchanged", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
 )
 
 
@@ -67,6 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.drot_set_nontemporal.argtypes = [vp, ci]
     lib.drot_set_fused_update.argtypes = [vp, ci]
     lib.drot_set_resident.argtypes = [vp, ci]
+    lib.drot_set_skip_unchanged.argtypes = [vp, ci]
     lib.drot_set_skip_cost.argtypes = [vp, ci]
     lib.drot_set_profile.argtypes = [vp, ci]
     lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
@@ -160,6 +161,11 @@ class Solver:
         rc = self._lib.drot_set_resident(self._h, int(mode))
         if rc != DROT_OK:
             raise DrotError(rc, "drot_set_resident")
+
+    def set_skip_unchanged(self, mode: int) -> None:
+        rc = self._lib.drot_set_skip_unchanged(self._h, int(mode))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_skip_unchanged")
 
     def set_skip_cost(self, mode: int) -> None:
         rc = self._lib.drot_set_skip_cost(self._h, int(mode))

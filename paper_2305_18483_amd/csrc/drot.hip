@@ -54,6 +54,10 @@ __device__ __forceinline__ float dpp_mov(float v) {
       float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
 }
 
+// Bits of a float.  (By value on purpose: __builtin_bit_cast applied directly to an element of a
+// vector, as in bit_cast(int, v.y), reads the vector's first element.)
+__device__ __forceinline__ int fbits(float f) { return __builtin_bit_cast(int, f); }
+
 // Sum over the 64 lanes of a wave; the result is wave-uniform (read back from lane 63).
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_mov<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
@@ -166,6 +170,9 @@ struct SweepArgs {
   int n_mem;             // columns the sweep may touch in memory: n, or the pitch when X and C are both the
                          // library's padded copies (their pad columns are kept at zero), so that the last
                          // lanes of a row can use full 128-bit accesses
+  int skip_same;         // plain sweep: do not write back row segments whose values did not change
+  const float* rowpart_prev;  // plain sweep: the row-segment sums of the X in memory (layout of rowpart), or null
+                              // when they are not known; a segment whose sum is zero is all zero and is not read
 };
 
 // Inputs of the vector update when it is fused into the head of the next sweep (small problems):
@@ -333,28 +340,44 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   __syncthreads();
 }
 
-template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE>
+template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE, int U>
 __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdateArgs& F, int lane, int wave, int seg,
                                            int tr, float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
-  constexpr int U = kSweepRows;
+  static_assert(!PRO || U == kSweepRows, "the fused update is written for 32-row tiles");
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;      // columns of this lane that exist
   // columns of this lane that may be accessed (the plain sums of MODE 3 have no mask: existing columns only)
   const int nmem = EDGE ? min(max((MODE == 3 ? A.n : A.n_mem) - j0, 0), 4) : 4;
-  const int r0 = tr * kTileRows + wave * U;
+  const int r0 = (tr * kSweepWaves + wave) * U;  // a tile has 16 * U rows
   const int nrows = min(max(A.m - r0, 0), U);
   const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
   const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
   float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
   const float rho = A.rho, scale = A.scale;
 
+  // X >= 0, so a row segment whose sum after the previous sweep was zero holds nothing but zeros:
+  // it need not be read (lane u fetches the old sum of row r0 + u; rows read it with a scalar lane read)
+  bool readx[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) readx[u] = true;
+  if (MODE == 0 && !FIRST && !PRO && A.rowpart_prev) {
+    float prev = 1.f;
+    if (lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.m + r0 + lane];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      readx[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, prev), u)) != 0.f;
+  }
+
   // the one batch of loads of this wave
   f4v x[U], c[U];
   if (nrows == U) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < U; ++u)
       c[u] = MODE >= 2 ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Cp + u * ldc, nmem);
-      x[u] = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : ld4<EDGE, NT>(Xp + u * ldx, nmem);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+      if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
     }
   } else {
 #pragma unroll
@@ -363,7 +386,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
       x[u] = f4v{0.f, 0.f, 0.f, 0.f};
       if (u < nrows) {
         if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
-        if (!FIRST) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+        if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
       }
     }
   }
@@ -392,6 +415,13 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
           sh.z = fmaf(-rho, c[u].z, v.z);
           sh.w = fmaf(-rho, c[u].w, v.w);
           st4<EDGE, NT>(Xp + u * ldx, sh, nmem);
+        } else if (MODE == 0 && !FIRST && A.skip_same) {
+          // a row segment whose 256 new values equal the stored ones bit for bit is not written back
+          // (plans are sparse: most segments are zero and stay zero)
+          const int diff = (fbits(v.x) ^ fbits(x[u].x)) | (fbits(v.y) ^ fbits(x[u].y)) |
+                           (fbits(v.z) ^ fbits(x[u].z)) | (fbits(v.w) ^ fbits(x[u].w));
+          const bool changed = diff != 0;
+          if (__builtin_amdgcn_ballot_w64(changed) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
         } else {
           st4<EDGE, NT>(Xp + u * ldx, v, nmem);
         }
@@ -417,7 +447,10 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
   }
 }
 
-template <bool FIRST, bool NT, bool PRO, int MODE = 0>
+// U rows per wave: 2 (32-row tiles) everywhere except the plain sweep of large problems, which takes
+// 8 (128-row tiles): with most of X known to be zero that sweep is a read-only stream of C, which
+// runs best with more loads in flight per wave and leaves a quarter of the column partials.
+template <bool FIRST, bool NT, bool PRO, int MODE = 0, int U = kSweepRows>
 __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, FusedUpdateArgs F) {
   if (*A.done) return;
   __shared__ float lds_phi[kTileRows];
@@ -425,8 +458,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
-  else sweep_body<FIRST, true, false, PRO, MODE>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE, U>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, false, PRO, MODE, U>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1427,6 +1460,7 @@ struct drot_handle_s {
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
+  int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
   int skip_cost = -1;     // even/odd scheme (C read every second sweep): -1 where it applies unless the update is fused, 0 never, 1 where it applies
@@ -1617,6 +1651,12 @@ int drot_set_nontemporal(drot_handle h, int mode) {
 int drot_set_fused_update(drot_handle h, int mode) {
   if (!h || mode < -1 || mode > 0) return DROT_ERR_INVALID_ARG;
   h->fused_update = mode;
+  return DROT_OK;
+}
+
+int drot_set_skip_unchanged(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 1) return DROT_ERR_INVALID_ARG;
+  h->skip_unchanged = mode;
   return DROT_OK;
 }
 
@@ -1832,7 +1872,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   }
   SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, nullptr, h->done,
               m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale,
-              (pad_x && (pad_c || from_points)) ? ld_pad : n};
+              (pad_x && (pad_c || from_points)) ? ld_pad : n, h->skip_unchanged != 0 ? 1 : 0, nullptr};
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
   PointArgs PT{};
   if (from_points) {
@@ -1873,8 +1913,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   const bool small = small_slab ||
                      (reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096);
   const bool fused = small && h->fused_update != 0;
-  const bool skip_cost = (h->skip_cost == 1 || (h->skip_cost == -1 && !small)) &&
-                         reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
+  const bool skip_cost = h->skip_cost == 1 && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
+  // plain sweeps of large problems with the zero-segment skipping on: 128-row tiles (8 rows per wave)
+  constexpr int kTallRows = 8;
+  const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
+  const int ntr_tall = ceil_div(m, kSweepWaves * kTallRows);
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
   auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
@@ -1906,6 +1949,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   bool converged = false;
   bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
   h->prof_used = 0;
+  // generation whose row-segment sums (tile layout) describe the plain X in memory, if any: lets the
+  // plain sweep skip reading all-zero segments
+  long long sums_gen = warm ? 0 : -1;
   while (k < max_iters && !converged) {
     const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
     if (resident) {
@@ -1966,8 +2012,10 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         const FusedUpdateArgs F{rowp(sw - 1), colp(sw - 1), tsum(sw - 1), p, q, a_buf(sw - 2), b_buf(sw - 2),
                                 a_buf(sw - 1), b_buf(sw - 1), h->theta + ((sw - 2) & 1), h->theta + ((sw - 1) & 1),
                                 h->sum_p, h->phi, h->varphi, nseg, ntr};
+        S.rowpart_prev = nullptr;
         if (nt) hipLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, S, F);
         else hipLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, S, F);
+        sums_gen = sw;
       } else {
         // even/odd scheme: inside a chunk the sweeps pair up as (store X - rho*C, then read it
         // without C); an odd chunk starts with one plain sweep, so X is plain at every chunk end
@@ -1978,18 +2026,24 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         }
         if (timed) h->prof_kind[pe] = mode;
         const FusedUpdateArgs none{};
+        S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
+        sums_gen = mode == 1 ? -1 : sw;
         if (first) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         } else if (nt) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, S, none);
           else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, S, none);
+          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, true, false, 0, kTallRows>), dim3(nseg, ntr_tall), sweep_block, 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, S, none);
         } else {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, S, none);
           else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, S, none);
+          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, false, false, 0, kTallRows>), dim3(nseg, ntr_tall), sweep_block, 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         }
+        // (the tall tiles leave fewer rows of column partials for the reduction)
+        if (!slab_k) RA.ntr = (tall && !first && mode == 0) ? ntr_tall : ntr;
       }
       if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
       if (!fused || c == chunk - 1) {

@@ -386,23 +386,54 @@ def test_plain_scheme_full_size(drot, oracle):
 
 
 @pytest.mark.parametrize("kind", [0, 1])
-def test_even_odd_is_the_default_beyond_the_fused_path(drot, oracle, kind):
-    # 2300 rows are more than the fused small-problem path takes: mode -1 must give the bits of
-    # mode 1, mode 0 different rounding, and both match the fp64 iteration
-    P = drot_inputs.random_problem(2300, 700, seed=720 + kind, reg_kind=kind, lam=0.3 if kind else 0.0)
+def test_sweep_schemes_beyond_the_fused_path(drot, oracle, kind):
+    # 2300 rows are more than the fused small-problem path takes.  Default: plain sweeps on 128-row
+    # tiles that neither read nor write back all-zero row segments; mode 1 of skip_cost: the even/odd
+    # scheme; skip_unchanged 0: plain sweeps on 32-row tiles touching everything.  All three match
+    # the fp64 iteration (they differ in rounding and summation order only).
+    P = drot_inputs.random_problem(2300, 2500, seed=720 + kind, reg_kind=kind, lam=0.3 if kind else 0.0)
     solver = drot.Solver(P.m, P.n)
-    _say(f"even/odd default kind={kind}")
-    res_auto, X_auto, phi_auto, varphi_auto = pu.gpu_solve(solver, P, 120)
-    solver.set_skip_cost(1)
-    _, X_on, _, _ = pu.gpu_solve(solver, P, 120)
-    solver.set_skip_cost(0)
-    res_off, X_off, phi_off, varphi_off = pu.gpu_solve(solver, P, 120)
-    assert np.array_equal(X_auto, X_on)
+    _say(f"sweep schemes kind={kind}")
     ores = pu.oracle_solve(oracle, P, 120)
-    pu.assert_parity(oracle, P, res_auto, X_auto, phi_auto, varphi_auto, ores, label="even/odd (default)")
-    pu.assert_parity(oracle, P, res_off, X_off, phi_off, varphi_off, ores, label="plain")
+    res, X, phi, varphi = pu.gpu_solve(solver, P, 120)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="zero segments skipped (default)")
+    zero_segments = [X[:, j:j + 256].max(axis=1) == 0 for j in range(0, P.n, 256)]
+    assert float(np.mean(zero_segments)) > 0.1  # the case really exercises the skipping
+    solver.set_skip_cost(1)
+    res, X, phi, varphi = pu.gpu_solve(solver, P, 120)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="even/odd")
+    solver.set_skip_cost(0)
+    solver.set_skip_unchanged(0)
+    res, X, phi, varphi = pu.gpu_solve(solver, P, 120)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="plain, everything read and written")
     with pytest.raises(drot.DrotError):
         solver.set_skip_cost(2)
+    with pytest.raises(drot.DrotError):
+        solver.set_skip_unchanged(2)
+
+
+@pytest.mark.parametrize("m,n,kind", [(200, 512, 1), (200, 500, 0), (1000, 1024, 1), (77, 300, 0)])
+def test_skipping_zero_segments_changes_no_bit(drot, m, n, kind):
+    # with the same tiles (fused update off keeps a small problem on the plain 32-row sweep) leaving out the
+    # loads and stores of unchanged / all-zero row segments must give the very same X, phi, varphi,
+    # from the dense first iterations to the sparse ones, also across a residual check and a continuation
+    P = drot_inputs.random_problem(m, n, seed=5, reg_kind=kind, lam=0.01 if kind else 0.0)
+    solver = drot.Solver(m, n, check_every=7)
+    solver.set_fused_update(0)
+    solver.set_resident(0)
+    _say(f"zero-segment skipping, bitwise, {m}x{n}")
+    for K in (1, 2, 9, 10, 30, 120):
+        solver.set_skip_unchanged(0)
+        _, X_all, phi_all, varphi_all = pu.gpu_solve(solver, P, K, tol=1e-12)
+        solver.set_skip_unchanged(1)
+        _, X_skip, phi_skip, varphi_skip = pu.gpu_solve(solver, P, K, tol=1e-12)
+        assert np.array_equal(X_all, X_skip) and np.array_equal(phi_all, phi_skip) and np.array_equal(varphi_all, varphi_skip), K
+    X = torch.empty((m, n), device="cuda:0")
+    pu.gpu_solve(solver, P, 50, X_out=X)
+    solver.set_continue(True)
+    _, X_two, _, _ = pu.gpu_solve(solver, P, 70, X_out=X)
+    solver.set_continue(False)
+    assert np.array_equal(X_two, X_skip)
 
 
 @pytest.mark.parametrize("terms", ["weights", "forbidden", "both"])
