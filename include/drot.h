@@ -136,12 +136,13 @@ int drot_set_nontemporal(drot_handle h, int mode);
 int drot_set_fused_update(drot_handle h, int mode);
 
 /*
- * Unchanged segments [-1 = on].  A sweep that reads X and C and stores X (not the pair of the
- * even/odd scheme) compares the 256 new values of a row segment with the ones it loaded and
- * skips the store when all are equal bit for bit: transport plans are sparse, so once the support
- * has settled most segments are zero and stay zero, and the write (4 of the 12 bytes per
- * element) disappears for them.  The memory contents are the same either way.  mode 0 stores
- * every segment.
+ * Zero segments [-1 = on].  X >= 0, so a row segment (256 consecutive columns of a row) whose sum
+ * after the previous sweep was zero holds only zeros.  A sweep that reads X and C and stores X (not
+ * the pair of the even/odd scheme) then does not read that segment of X, and does not write it
+ * back if its new values are zero again.  Transport plans are sparse: once the support has settled
+ * nearly every segment is of this kind, and the sweep turns into a read-only stream of C (4 instead
+ * of 12 bytes per element).  On problems beyond the fused small-problem path this sweep runs on
+ * 64-row tiles.  The memory contents are the same either way.  mode 0 reads and stores everything.
  */
 int drot_set_skip_unchanged(drot_handle h, int mode);
 

@@ -170,9 +170,9 @@ struct SweepArgs {
   int n_mem;             // columns the sweep may touch in memory: n, or the pitch when X and C are both the
                          // library's padded copies (their pad columns are kept at zero), so that the last
                          // lanes of a row can use full 128-bit accesses
-  int skip_same;         // plain sweep: do not write back row segments whose values did not change
   const float* rowpart_prev;  // plain sweep: the row-segment sums of the X in memory (layout of rowpart), or null
-                              // when they are not known; a segment whose sum is zero is all zero and is not read
+                              // when they are not known or not to be used; a segment whose sum is zero is all
+                              // zero: it is not read, and not written back if it stays zero
 };
 
 // Inputs of the vector update when it is fused into the head of the next sweep (small problems):
@@ -340,15 +340,15 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   __syncthreads();
 }
 
-template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE, int U>
+template <bool FIRST, bool EDGE, bool NT, bool PRO, int MODE, int U, int NW>
 __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdateArgs& F, int lane, int wave, int seg,
                                            int tr, float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
-  static_assert(!PRO || U == kSweepRows, "the fused update is written for 32-row tiles");
+  static_assert(!PRO || (U == kSweepRows && NW == kSweepWaves), "the fused update is written for 32-row tiles");
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;      // columns of this lane that exist
   // columns of this lane that may be accessed (the plain sums of MODE 3 have no mask: existing columns only)
   const int nmem = EDGE ? min(max((MODE == 3 ? A.n : A.n_mem) - j0, 0), 4) : 4;
-  const int r0 = (tr * kSweepWaves + wave) * U;  // a tile has 16 * U rows
+  const int r0 = (tr * NW + wave) * U;  // a tile has NW * U rows
   const int nrows = min(max(A.m - r0, 0), U);
   const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
   const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
@@ -395,71 +395,73 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
 
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
   float wave_total = 0.f;
-  if (nrows > 0) {
+  {
     const f4v vp = PRO ? *reinterpret_cast<const f4v*>(lds_varphi + lane * 4) : load_varphi(A.varphi, j0, nvalid);
-    // lane u holds phi of row r0 + u; rows read it back with a scalar lane read
-    const float phi_lane = (lane < nrows) ? (PRO ? lds_phi[wave * U + lane] : A.phi[r0 + lane]) : 0.f;
+    // lane u holds phi of row r0 + u; rows read it back with a scalar lane read.  Rows past the end of
+    // the matrix get the huge negative value: with x = c = 0 they come out as exact zeros, so the loop
+    // below needs no per-row branches (only the stores are guarded).
+    const float phi_lane = (lane < nrows) ? (PRO ? lds_phi[wave * U + lane] : A.phi[r0 + lane]) : kMaskedOut;
     float rowkeep = 0.f;  // lane u keeps the sum of row r0 + u
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (u < nrows) {
-        const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
-        // (in MODE 2 the stored value already carries - rho*C and c is zero)
-        const f4v v = MODE == 3 ? x[u] : xbar4(x[u], c[u], vp + ph, rho) * scale;
-        if (MODE == 3) {
-          // sums only
-        } else if (MODE == 1) {
-          f4v sh;
-          sh.x = fmaf(-rho, c[u].x, v.x);
-          sh.y = fmaf(-rho, c[u].y, v.y);
-          sh.z = fmaf(-rho, c[u].z, v.z);
-          sh.w = fmaf(-rho, c[u].w, v.w);
-          st4<EDGE, NT>(Xp + u * ldx, sh, nmem);
-        } else if (MODE == 0 && !FIRST && A.skip_same) {
-          // a row segment whose 256 new values equal the stored ones bit for bit is not written back
-          // (plans are sparse: most segments are zero and stay zero)
-          const int diff = (fbits(v.x) ^ fbits(x[u].x)) | (fbits(v.y) ^ fbits(x[u].y)) |
-                           (fbits(v.z) ^ fbits(x[u].z)) | (fbits(v.w) ^ fbits(x[u].w));
-          const bool changed = diff != 0;
-          if (__builtin_amdgcn_ballot_w64(changed) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
-        } else {
-          st4<EDGE, NT>(Xp + u * ldx, v, nmem);
-        }
-        colacc += v;
-        const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
-        rowkeep = (lane == u) ? tot : rowkeep;
-        wave_total += tot;
+      const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, phi_lane), u));
+      // (in MODE 2 the stored value already carries - rho*C and c is zero)
+      const f4v v = MODE == 3 ? x[u] : xbar4(x[u], c[u], vp + ph, rho) * scale;
+      if (MODE == 3) {
+        // sums only
+      } else if (MODE == 1) {
+        f4v sh;
+        sh.x = fmaf(-rho, c[u].x, v.x);
+        sh.y = fmaf(-rho, c[u].y, v.y);
+        sh.z = fmaf(-rho, c[u].z, v.z);
+        sh.w = fmaf(-rho, c[u].w, v.w);
+        if (u < nrows) st4<EDGE, NT>(Xp + u * ldx, sh, nmem);
+      } else if (MODE == 0 && !FIRST && !PRO) {
+        // a row segment that was all zero (known from its old sum) and stays all zero is not written
+        // back: plans are sparse, so once the support has settled that is nearly every segment
+        const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+        if (u < nrows && (readx[u] || __builtin_amdgcn_ballot_w64(nonzero) != 0)) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+      } else {
+        if (u < nrows) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
       }
+      colacc += v;
+      const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+      rowkeep = (lane == u) ? tot : rowkeep;
+      wave_total += tot;
     }
     if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
   }
-  write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
   if (A.tilesum) {  // total of the tile, for the fused update of the next sweep
-    __shared__ float wt[kSweepWaves];
+    __shared__ float wt[NW];
     if (lane == 0) wt[wave] = wave_total;
     __syncthreads();
     if (threadIdx.x == 0) {
       float tot = 0.f;
 #pragma unroll
-      for (int k = 0; k < kSweepWaves; ++k) tot += wt[k];
+      for (int k = 0; k < NW; ++k) tot += wt[k];
       A.tilesum[tr * gridDim.x + seg] = tot;
     }
   }
 }
 
-// U rows per wave: 2 (32-row tiles) everywhere except the plain sweep of large problems, which takes
-// 8 (128-row tiles): with most of X known to be zero that sweep is a read-only stream of C, which
-// runs best with more loads in flight per wave and leaves a quarter of the column partials.
-template <bool FIRST, bool NT, bool PRO, int MODE = 0, int U = kSweepRows>
+// NW waves of U rows each: 16 x 2 (32-row tiles) everywhere except the plain sweep of large problems,
+// which takes 8 x 8 (64-row tiles): with most of X known to be zero that sweep is a read-only stream
+// of C, which runs best with more loads in flight per wave, and the smaller workgroups let two or
+// three of them share a compute unit so that one computes while another waits for memory.
+template <bool FIRST, bool NT, bool PRO, int MODE = 0, int U = kSweepRows, int NW = kSweepWaves>
+// (the register budget is that of 1024 threads for every NW: given more, the compiler's scheduler
+// stretches live ranges until it spills)
 __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, FusedUpdateArgs F) {
+  static_assert(NW <= kSweepWaves, "launch bound");
   if (*A.done) return;
   __shared__ float lds_phi[kTileRows];
   __shared__ float lds_varphi[kSegCols];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
-  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE, U>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
-  else sweep_body<FIRST, true, false, PRO, MODE, U>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, false, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1872,7 +1874,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   }
   SweepArgs S{Xw, Cw, h->phi, h->varphi, h->rowpart, h->colpart, nullptr, h->done,
               m, n, ldx, ldc, rho, reg_kind == DROT_REG_NONE ? 1.0f : qscale,
-              (pad_x && (pad_c || from_points)) ? ld_pad : n, h->skip_unchanged != 0 ? 1 : 0, nullptr};
+              (pad_x && (pad_c || from_points)) ? ld_pad : n, nullptr};
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
   PointArgs PT{};
   if (from_points) {
@@ -1915,9 +1917,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   const bool fused = small && h->fused_update != 0;
   const bool skip_cost = h->skip_cost == 1 && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
   // plain sweeps of large problems with the zero-segment skipping on: 128-row tiles (8 rows per wave)
-  constexpr int kTallRows = 8;
+  constexpr int kTallRows = 8, kTallWaves = 8;
   const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
-  const int ntr_tall = ceil_div(m, kSweepWaves * kTallRows);
+  const int ntr_tall = ceil_div(m, kTallWaves * kTallRows);
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
   auto rowp = [&](long long g) { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; };
@@ -2034,12 +2036,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         } else if (nt) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, S, none);
           else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, S, none);
-          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, true, false, 0, kTallRows>), dim3(nseg, ntr_tall), sweep_block, 0, stream, S, none);
+          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, true, false, 0, kTallRows, kTallWaves>), dim3(nseg, ntr_tall), dim3(64 * kTallWaves), 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, S, none);
         } else {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, S, none);
           else if (mode == 2) hipLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, S, none);
-          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, false, false, 0, kTallRows>), dim3(nseg, ntr_tall), sweep_block, 0, stream, S, none);
+          else if (tall) hipLaunchKernelGGL((sweep_kernel<false, false, false, 0, kTallRows, kTallWaves>), dim3(nseg, ntr_tall), dim3(64 * kTallWaves), 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         }
         // (the tall tiles leave fewer rows of column partials for the reduction)
