@@ -12,10 +12,13 @@ prints one JSON line: iterations/s, the HBM roofline of the dominant sweep kerne
 per launch over the kernel time from HIP events recorded on the launch stream), the time to a
 marginal residual of 1e-4, and the CPU oracle timed on a bounded sample on this machine's host cores.
 
-At this size the library pairs its sweeps (even/odd scheme of the paper's GPU appendix): the first
-of a pair reads X and C and stores X - rho*C (12 bytes per element), the second reads that and
-stores X (8 bytes per element).  The roofline object is that of the first, which takes the longer;
-the second and the pair are reported beside it, and so is a run with C read by every sweep.
+The default sweep at this size neither reads nor writes back row segments of X that are zero and
+stay zero.  Transport plans are sparse, so after the first few dozen iterations the sweep streams C
+(4 bytes per element) plus the few nonzero segments of X (8 bytes per element of those); its
+algorithmic bytes are counted that way, from the fraction of nonzero row segments in the plan the
+timed run ends with.  Two further legs time the same iterations with the even/odd scheme of the
+paper's GPU appendix (20 bytes per element and pair) and with every byte moved (12 bytes per
+element): that last one is the dense streaming rate of the sweep kernel.
 """
 from __future__ import annotations
 
@@ -31,12 +34,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0, 3: 12.0}  # by kind of sweep: read X, read C, write X; kind 2 reads no C;
-# kind 3 (resident kernel) is priced at the same 12 although nothing leaves the registers
+# kind 3 (resident kernel) is priced at the same 12 although nothing leaves the registers; kind 4 (zero segments
+# skipped) is priced from the plan's density, see sparse_sweep_bytes
 
 # HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # copy kernel of known size (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {  # (workload, kind of sweep); profiles/sweep_kernel_cfg4_20000.md
     ("cfg4_quad_20000", 0): 4.8564e9, ("cfg4_quad_20000", 1): 4.8564e9, ("cfg4_quad_20000", 2): 3.2564e9}
+SEG_COLS = 256  # columns of a row segment, the unit of the zero-segment skipping
 
 
 def log(msg: str) -> None:
@@ -47,7 +52,8 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed cold-start iterations (the support of the plan settles within the first 100 or so)")
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: 20000 x 20000)")
     ap.add_argument("--size", type=int, default=0, help="override m = n (same recipe)")
     ap.add_argument("--tol", type=float, default=1e-4, help="residual of the time-to-tolerance leg")
@@ -56,6 +62,7 @@ def main() -> int:
     ap.add_argument("--nontemporal", type=int, default=-1, help="-1: library default, 0/1: force off/on")
     ap.add_argument("--skip-cost", type=int, default=-1,
                     help="even/odd scheme (C read every second sweep): -1 library default, 0 never, 1 wherever it applies")
+    ap.add_argument("--skip-unchanged", type=int, default=-1, help="zero-segment skipping: -1/1 on, 0 off")
     ap.add_argument("--points", action="store_true", help="on-the-fly cost from the point clouds (drot_solve_points)")
     ap.add_argument("--skip-tol", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -90,6 +97,7 @@ def main() -> int:
     solver = drot.Solver(m, n, check_every=args.check_every, compute_gap=False)
     solver.set_nontemporal(args.nontemporal)
     solver.set_skip_cost(args.skip_cost)
+    solver.set_skip_unchanged(args.skip_unchanged)
     torch.cuda.synchronize()
 
     # ---- warm-up (cold start), then exactly K steady-state iterations continuing from it --------------
@@ -115,8 +123,21 @@ def main() -> int:
         solver.set_profile(False)
         return {kind: (sum(v) / len(v), len(v)) for kind, v in per_kind.items()}
 
-    def kernel_entry(kind, ms, launches):
-        nbytes = BYTES_PER_ELEMENT[kind] * m * n
+    def nonzero_segment_fraction():
+        """Fraction of row segments (256 columns of one row) of X that hold a nonzero."""
+        nz = 0
+        for j0 in range(0, n, SEG_COLS):
+            nz += int((X[:, j0:j0 + SEG_COLS] != 0).any(dim=1).sum().item())
+        return nz / (m * ((n + SEG_COLS - 1) // SEG_COLS))
+
+    def sparse_sweep_bytes(frac):
+        # C once; X read and written back only on the nonzero segments (an upper bound: a segment is
+        # charged as a whole); the old and the new row sums per segment
+        nseg = (n + SEG_COLS - 1) // SEG_COLS
+        return 4.0 * m * n + 8.0 * frac * m * n + 8.0 * m * nseg
+
+    def kernel_entry(kind, ms, launches, nbytes=None):
+        nbytes = BYTES_PER_ELEMENT[kind] * m * n if nbytes is None else nbytes
         gbs = nbytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((P.name, kind)),
@@ -126,45 +147,51 @@ def main() -> int:
     kernel_names = {0: "gl_slab_kernel" if P.reg_kind == 2 else "sweep_kernel (reads X and C, stores X)",
                     1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
                     2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)",
-                    3: "resident_kernel (X and C stay in registers; the time is per iteration)"}
+                    3: "resident_kernel (X and C stay in registers; the time is per iteration)",
+                    4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)"}
     prof = sweep_profile()
-    solver.set_continue(False)
-    even_odd = 1 in prof
-    dominant = max(prof, key=lambda kind: prof[kind][0])
-    roofline = kernel_entry(dominant, *prof[dominant])
-    bytes_per_iteration = sum(BYTES_PER_ELEMENT[k] * m * n * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
+    frac_nz = nonzero_segment_fraction()
+    kind_bytes = {k: (sparse_sweep_bytes(frac_nz) if k == 4 else BYTES_PER_ELEMENT[k] * m * n) for k in prof}
+    dominant = max(prof, key=lambda kind: prof[kind][0] * prof[kind][1])
+    roofline = kernel_entry(dominant, *prof[dominant], nbytes=kind_bytes[dominant])
+    bytes_per_iteration = sum(kind_bytes[k] * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
-    if even_odd:
-        other = kernel_entry(2, *prof[2])
-        pair_ms = prof[1][0] + prof[2][0]
-        pair_gbs = 20.0 * m * n / (pair_ms * 1e-3) / 1e9
-        roofline["paired_kernel"] = other
-        roofline["pair"] = {"algorithmic_bytes": 20.0 * m * n, "kernel_ms": round(pair_ms, 5), "achieved": round(pair_gbs, 1),
-                            "frac": round(pair_gbs / HBM_PEAK_GBS, 4)}
-        log(f"second sweep of a pair: {other['kernel_ms']:.4f} ms -> {other['achieved']:.0f} GB/s ({other['frac']:.1%}); "
-            f"pair: {pair_gbs:.0f} GB/s ({pair_gbs / HBM_PEAK_GBS:.1%})")
+    if dominant == 4:
+        roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
+        roofline["dense_model_bytes"] = 12.0 * m * n
+        roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
+        log(f"nonzero row segments of X: {frac_nz:.3%}; the same sweep priced at 12 B/element would read "
+            f"{roofline['dense_model_gbs']:.0f} GB/s")
 
-    # ---- the same K iterations with C read by every sweep (12 B/element every iteration) ---------------
-    plain_leg = None
-    if even_odd:
-        solver.set_skip_cost(0)
-        solver.solve(C, p, q, max_iters=W, **kw)
+    def timed_leg(label):
+        """K more iterations from the current state with the solver's current settings, then a profile."""
         solver.set_continue(True)
+        solver.solve(C, p, q, max_iters=2, **kw)  # (settle the scheme's first-sweep special cases)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         solver.solve(C, p, q, max_iters=K, **kw)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        pprof = sweep_profile()
+        lprof = sweep_profile()
         solver.set_continue(False)
+        leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
+               "kernels": [kernel_entry(k, *lprof[k]) for k in sorted(lprof)]}
+        log(f"{label}: {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; " +
+            "; ".join(f"{e['kernel_ms']:.4f} ms = {e['achieved']:.0f} GB/s ({e['frac']:.1%})" for e in leg["kernels"]))
+        return leg
+
+    # ---- the same K iterations with the even/odd scheme, and with every byte moved ----------------------
+    even_odd_leg = dense_leg = None
+    if dominant == 4:
+        solver.set_skip_cost(1)
+        even_odd_leg = timed_leg("even/odd scheme (20 B/element and pair)")
+        solver.set_skip_cost(0)
+        solver.set_skip_unchanged(0)
+        dense_leg = timed_leg("every byte moved (12 B/element)")
         solver.set_skip_cost(args.skip_cost)
-        plain_leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
-                     "algorithmic_bytes_per_iteration": 12.0 * m * n,
-                     "hbm_gbs_whole_iteration": round(12.0 * m * n / (dt / K) / 1e9, 1),
-                     "roofline": kernel_entry(0, *pprof[0])}
-        log(f"C read by every sweep: {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; sweep {pprof[0][0]:.4f} ms "
-            f"= {plain_leg['roofline']['achieved']:.0f} GB/s ({plain_leg['roofline']['frac']:.1%})")
+        solver.set_skip_unchanged(args.skip_unchanged)
+    solver.set_continue(False)
 
     # ---- the same K iterations with the cost recomputed from the point clouds (8 B/element) ------------
     points_leg = None
@@ -218,11 +245,11 @@ def main() -> int:
         okw = dict(rho=float(P.rho), reg_kind=P.reg_kind, lam=float(np.float32(P.lam)), mu=float(np.float32(P.mu)),
                    row_class=P.row_class, num_classes=P.num_classes)
         iters = args.cpu_iters
-        if not iters:  # two iterations to size the sample for about 15 s
+        if not iters:  # a first call to size the sample for about 20 s (its first iteration pays the page faults)
             t0 = time.perf_counter()
-            drot_oracle.solve(P.C, P.p, P.q, max_iters=2, **okw)
-            per_iter = (time.perf_counter() - t0) / 2
-            iters = max(2, min(20000, int(15.0 / per_iter)))
+            drot_oracle.solve(P.C, P.p, P.q, max_iters=4, **okw)
+            per_iter = (time.perf_counter() - t0) / 4
+            iters = max(2, min(20000, int(25.0 / per_iter)))
         t0 = time.perf_counter()
         drot_oracle.solve(P.C, P.p, P.q, max_iters=iters, **okw)
         dt = time.perf_counter() - t0
@@ -239,10 +266,10 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": P.name, "m": m, "n": n, "reg_kind": int(P.reg_kind), "lambda": P.lam, "mu": P.mu,
                    "stepsize": float(P.rho), "check_every": args.check_every},
-        "even_odd_cost_skipping": even_odd, "algorithmic_bytes_per_iteration": bytes_per_iteration,
+        "algorithmic_bytes_per_iteration": bytes_per_iteration,
         "hbm_gbs_whole_iteration": round(bytes_per_iteration / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "time_to_tol": tol_leg, "cost_read_every_sweep": plain_leg, "cost_from_points": points_leg,
-        "cpu_baseline": cpu,
+        "roofline": roofline, "time_to_tol": tol_leg, "even_odd_scheme": even_odd_leg, "every_byte_moved": dense_leg,
+        "cost_from_points": points_leg, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0

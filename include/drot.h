@@ -162,9 +162,13 @@ int drot_set_resident(drot_handle h, int mode);
  * and column sums are always those of X itself, and X_out is the plain plan on return and at every
  * residual check.  The rounding differs slightly from the plain scheme (same tolerance against the
  * fp64 iteration).  The scheme applies to the none/quadratic sweeps over a stored cost whose vector
- * update is not fused into the sweep.  mode -1 uses it for every such problem too large for the
- * fused small-problem path, mode 1 also for small problems whose fusion has been switched off,
- * mode 0 never (C read by every sweep).
+ * update is not fused into the sweep.  It is the better scheme for dense plans; for sparse ones the
+ * zero-segment skipping above wins.  mode -1 (with the zero-segment skipping on) follows the plan:
+ * problems beyond the fused small-problem path start on the skipping sweeps; the reduction counts
+ * the nonzero row segments, the host reads the count with the status of every stretch of
+ * check_every iterations (one stretch late, without waiting), and switches to the pairs while more
+ * than 70 % of the segments are nonzero and back below 50 %.  With a switch the result depends,
+ * within rounding, on check_every.  mode 1: pairs wherever they apply; mode 0: never.
  */
 int drot_set_skip_cost(drot_handle h, int mode);
 
@@ -179,7 +183,8 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
 /* The individual durations, in launch order: sweep_ms [out] HOST, capacity floats; sweep_kind [out]
  * HOST, capacity ints or NULL: 0 = the sweep read X and C, 1 = it also stored X - rho*C (first of an
  * even/odd pair), 2 = it read the shifted X and no C (second of a pair), 3 = a launch of the resident
- * kernel (its duration divided by the iterations it ran); *sweeps_timed receives how many the last
+ * kernel (its duration divided by the iterations it ran), 4 = as 0 but on 64-row tiles with the
+ * zero-segment skipping (the default sweep of large problems); *sweeps_timed receives how many the last
  * solve timed (at most min(capacity, that many) entries are written). */
 int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed);
 

@@ -151,6 +151,7 @@ __device__ __forceinline__ double block_sum_f64(double v, double* red) {
 struct DeviceStatus {
   double r2, s2;                 // ||X1-p||^2, ||X^T1-q||^2 of the last checked iterate
   double cost, h, dual_lin, h_conj, gap, dual_res;
+  double nz_segments;            // row partial sums of the last reduction that were not zero (density of the plan)
   int iters;                     // iteration the residuals belong to
   int converged;
 };
@@ -913,8 +914,8 @@ struct VecState {
   double* sum_p;   // [1] sum of p
   double* r;       // [m] row residuals X 1 - p of the last sweep
   double* s;       // [n] column residuals
-  double* part;    // [2][nbm + nbn]: per-workgroup sum of residuals, sum of squared residuals
-  double* resid;   // [2]: ||r||^2, ||s||^2
+  double* part;    // [3][nbm + nbn]: per-workgroup sum of residuals, sum of squared residuals, nonzero row partials
+  double* resid;   // [3]: ||r||^2, ||s||^2, number of nonzero row partial sums
   int* done;
   DeviceStatus* status;
 };
@@ -1015,12 +1016,16 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   const int len = rows ? A.m : A.n;
   const int nparts = rows ? A.nseg : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
+  __shared__ int nzw[kReduceThreads / 64];
   double acc = 0.0;
-  if (idx < len) {
-#pragma unroll 4
-    for (int k = sub; k < nparts; k += kReduceThreads / 64) acc += (double)part[(size_t)k * len + idx];
+  int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
+  for (int k = sub; k < nparts; k += kReduceThreads / 64) {  // (nparts and sub are wave-uniform)
+    const float v = idx < len ? part[(size_t)k * len + idx] : 0.f;
+    acc += (double)v;
+    nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v != 0.f));
   }
   red[t] = acc;
+  if (l == 0) nzw[sub] = nz;
   __syncthreads();
   for (int h = kReduceThreads / 2; h >= 64; h >>= 1) {  // fold the 16 waves' partials, lane by lane
     if (t < h) red[t] += red[t + h];
@@ -1042,6 +1047,9 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   if (t == 0) {
     A.V.part[blockIdx.x] = red[0];
     A.V.part[A.nbm + A.nbn + blockIdx.x] = red[64];
+    int cnt = 0;
+    for (int w = 0; w < kReduceThreads / 64; ++w) cnt += nzw[w];
+    A.V.part[2 * (A.nbm + A.nbn) + blockIdx.x] = (double)cnt;
   }
 }
 
@@ -1094,12 +1102,17 @@ __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
     const double* sq = A.V.part + A.nbm + A.nbn;
     for (int e = t; e < A.nbm; e += kReduceThreads) r2 += sq[e];
     for (int e = t; e < A.nbn; e += kReduceThreads) s2 += sq[A.nbm + e];
+    double nzs = 0.0;
+    const double* cnt = A.V.part + 2 * (A.nbm + A.nbn);
+    for (int e = t; e < A.nbm; e += kReduceThreads) nzs += cnt[e];
     r2 = block_sum_f64(r2, red);
     s2 = block_sum_f64(s2, red);
+    nzs = block_sum_f64(nzs, red);
     if (t == 0) {
       A.V.theta[A.par ^ 1] = theta - eta;
       A.V.resid[0] = r2;
       A.V.resid[1] = s2;
+      A.V.resid[2] = nzs;
     }
   }
 }
@@ -1261,6 +1274,7 @@ __global__ __launch_bounds__(64 * NW) void resident_kernel(ResidentArgs A) {
     A.V.theta[A.theta_out] = theta;
     A.V.resid[0] = r2;
     A.V.resid[1] = s2;
+    A.V.resid[2] = 0.0;
   }
 }
 
@@ -1291,6 +1305,7 @@ __global__ void status_kernel(VecState V, int iters, double tol) {
   const double r2 = V.resid[0], s2 = V.resid[1];
   V.status->r2 = r2;
   V.status->s2 = s2;
+  V.status->nz_segments = V.resid[2];
   V.status->iters = iters;
   if (tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol) {
     V.status->converged = 1;
@@ -1463,6 +1478,7 @@ struct drot_handle_s {
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
   int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
+  bool dense_plan = false;  // what the last solve's density feedback ended on
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
   int skip_cost = -1;     // even/odd scheme (C read every second sweep): -1 where it applies unless the update is fused, 0 never, 1 where it applies
@@ -1474,7 +1490,7 @@ struct drot_handle_s {
   int prof_count = 0;
   double prof_sweep_ms = 0.0;
   float prof_ms[kMaxProfiled] = {};  // per sweep, in launch order
-  int prof_kind[kMaxProfiled] = {};  // 0: reads X and C, 1: the same and stores X - rho*C, 2: reads the shifted X only, 3: resident stretch
+  int prof_kind[kMaxProfiled] = {};  // 0: reads X and C, 1: the same and stores X - rho*C, 2: reads the shifted X only, 3: resident stretch, 4: as 0 on 64-row tiles with the zero-segment skipping
   int prof_iters[kMaxProfiled] = {}; // iterations the timed launch covers (1 unless resident)
   int prof_used = 0;
   // device workspace
@@ -1582,8 +1598,8 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->sum_p, 1));
   take(dev_alloc(&h->r, (size_t)max_m));
   take(dev_alloc(&h->s, (size_t)max_n));
-  take(dev_alloc(&h->part, 2 * nb));
-  take(dev_alloc(&h->resid, 2));
+  take(dev_alloc(&h->part, 3 * nb));
+  take(dev_alloc(&h->resid, 3));
   h->rowpart_half = (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m;  // 32-column strips (group-resident path) are the finest
   h->colpart_half = ntr * (size_t)max_n;
   h->tilesum_half = nseg * ntr > 4096 ? nseg * ntr : 4096;  // (the group-resident path has up to 4096 slabs)
@@ -1915,10 +1931,15 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   const bool small = small_slab ||
                      (reg_kind != DROT_REG_GROUP_LASSO && !from_points && ntr <= 64 && ntiles <= 4096);
   const bool fused = small && h->fused_update != 0;
-  const bool skip_cost = h->skip_cost == 1 && reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
-  // plain sweeps of large problems with the zero-segment skipping on: 128-row tiles (8 rows per wave)
+  // Two schemes for the none/quadratic sweeps of large problems.  Sparse plan (the usual case):
+  // plain sweeps on 64-row tiles (8 waves of 8 rows) that skip the all-zero row segments of X.
+  // Dense plan (strong quadratic term): the even/odd pairs.  With both options on automatic the
+  // choice follows the density of the plan, which the reduction counts (nonzero row-segment sums)
+  // and the host reads with the status of every stretch of check_every iterations, one stretch late.
+  const bool can_pair = reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
+  const bool adaptive = can_pair && !small && h->skip_cost == -1 && h->skip_unchanged != 0;
+  bool dense_plan = resume && h->dense_plan;  // (a continued solve keeps what the last one found)
   constexpr int kTallRows = 8, kTallWaves = 8;
-  const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
   const int ntr_tall = ceil_div(m, kTallWaves * kTallRows);
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
   auto b_buf = [&](long long g) { return h->b + (size_t)(g & 1) * (size_t)h->max_n; };
@@ -1955,7 +1976,10 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // plain sweep skip reading all-zero segments
   long long sums_gen = warm ? 0 : -1;
   while (k < max_iters && !converged) {
-    const int chunk = checking ? (h->check_every < max_iters - k ? h->check_every : max_iters - k) : max_iters - k;
+    const int chunk = (checking || adaptive) ? (h->check_every < max_iters - k ? h->check_every : max_iters - k)
+                                             : max_iters - k;
+    const bool skip_cost = can_pair && (h->skip_cost == 1 || (adaptive && dense_plan));
+    const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
     if (resident) {
       const long long sw = k_base + k + 1;         // first sweep of the stretch
       const long long last = sw + chunk - 1;       // its last one: the state leaves in that generation's buffers
@@ -2026,7 +2050,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
-        if (timed) h->prof_kind[pe] = mode;
+        if (timed) h->prof_kind[pe] = (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
         sums_gen = mode == 1 ? -1 : sw;
@@ -2066,14 +2090,19 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         materialized = false;
       }
     }
-    if (checking) {
+    if (checking || adaptive) {
       // the test runs on the device; the host reads it one chunk late so the queue never drains
-      hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, (double)tol);
+      hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, checking ? (double)tol : 0.0);
       DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
       DROT_HIP(hipEventRecord(h->ev[slot], stream));
       if (checks > 0) {
         DROT_HIP(hipEventSynchronize(h->ev[slot ^ 1]));
         if (h->host_status[slot ^ 1].converged) converged = true;
+        if (adaptive) {  // (hysteresis: the break-even is at about three quarters of the segments nonzero)
+          const double density = h->host_status[slot ^ 1].nz_segments / ((double)m * (double)nseg);
+          if (density > 0.7) dense_plan = true;
+          else if (density < 0.5) dense_plan = false;
+        }
       }
       slot ^= 1;
       ++checks;
@@ -2124,6 +2153,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->info.objective = h->compute_gap ? st.cost + st.h : 0.0;
   h->info.gap = h->compute_gap ? st.gap : 0.0;
   h->info.dual_res = h->compute_gap ? st.dual_res : 0.0;
+  h->dense_plan = dense_plan;
   h->solved = true;
   h->last_m = m;
   h->last_n = n;

@@ -412,6 +412,24 @@ def test_sweep_schemes_beyond_the_fused_path(drot, oracle, kind):
         solver.set_skip_unchanged(2)
 
 
+def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
+    # a strong quadratic term keeps the plan dense: the density the reduction reports must move the
+    # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
+    P = drot_inputs.random_problem(2300, 1500, seed=740, reg_kind=1, lam=3000.0)
+    solver = drot.Solver(P.m, P.n, check_every=10)
+    solver.set_profile(True)
+    _say("dense plan, adaptive scheme")
+    res, X, phi, varphi = pu.gpu_solve(solver, P, 90)
+    kinds = [kind for _, kind in solver.profile_sweeps()]
+    solver.set_profile(False)
+    nonzero_segments = [X[:, j:j + 256].max(axis=1) > 0 for j in range(0, P.n, 256)]
+    assert float(np.mean(nonzero_segments)) > 0.9  # (a tenth of the entries is enough for that)
+    assert kinds[:10] == [0] + [4] * 9          # first stretch: the default scheme (sweep 1 has nothing to read)
+    assert set(kinds[30:]) == {1, 2}, kinds     # switched after the first status came back, one stretch late
+    ores = pu.oracle_solve(oracle, P, 90)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="dense plan")
+
+
 @pytest.mark.parametrize("m,n,kind", [(200, 512, 1), (200, 500, 0), (1000, 1024, 1), (77, 300, 0)])
 def test_skipping_zero_segments_changes_no_bit(drot, m, n, kind):
     # with the same tiles (fused update off keeps a small problem on the plain 32-row sweep) leaving out the
