@@ -40,7 +40,8 @@ BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0, 3: 12.0}  # by kind of sweep: rea
 # HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
 # copy kernel of known size (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {  # (workload, kind of sweep); profiles/sweep_kernel_cfg4_20000.md
-    ("cfg4_quad_20000", 0): 4.8564e9, ("cfg4_quad_20000", 1): 4.8564e9, ("cfg4_quad_20000", 2): 3.2564e9}
+    ("cfg4_quad_20000", 0): 4.8565e9, ("cfg4_quad_20000", 1): 4.8565e9, ("cfg4_quad_20000", 2): 3.2565e9,
+    ("cfg4_quad_20000", 4): 1.7707e9}
 SEG_COLS = 256  # columns of a row segment, the unit of the zero-segment skipping
 
 
@@ -132,9 +133,9 @@ def main() -> int:
 
     def sparse_sweep_bytes(frac):
         # C once; X read and written back only on the nonzero segments (an upper bound: a segment is
-        # charged as a whole); the old and the new row sums per segment
+        # charged as a whole); the old and the new row sums per segment; the column sums per 64-row tile
         nseg = (n + SEG_COLS - 1) // SEG_COLS
-        return 4.0 * m * n + 8.0 * frac * m * n + 8.0 * m * nseg
+        return 4.0 * m * n + 8.0 * frac * m * n + 8.0 * m * nseg + 4.0 * n * ((m + 63) // 64)
 
     def kernel_entry(kind, ms, launches, nbytes=None):
         nbytes = BYTES_PER_ELEMENT[kind] * m * n if nbytes is None else nbytes
