@@ -1019,6 +1019,7 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   __shared__ int nzw[kReduceThreads / 64];
   double acc = 0.0;
   int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
+#pragma unroll 4
   for (int k = sub; k < nparts; k += kReduceThreads / 64) {  // (nparts and sub are wave-uniform)
     const float v = idx < len ? part[(size_t)k * len + idx] : 0.f;
     acc += (double)v;
