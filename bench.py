@@ -115,13 +115,17 @@ def main() -> int:
     log(f"{K} iterations in {elapsed:.3f} s -> {K / elapsed:.1f} it/s, {ms_per_step:.4f} ms/iteration")
 
     # ---- sweep kernel durations from HIP events on the launch stream (profile mode, separate solve) ----
+    c_read = {}  # kind of sweep -> mean fraction of the row segments of C it read (screened kinds: counted by the kernel)
+
     def sweep_profile():
         solver.set_profile(True)
         solver.solve(C, p, q, max_iters=min(K, 256), **kw)
-        per_kind = {}
-        for ms, kind in solver.profile_sweeps():
+        per_kind, reads = {}, {}
+        for (ms, kind), frac in zip(solver.profile_sweeps(), solver.profile_reads()):
             per_kind.setdefault(kind, []).append(ms)
+            reads.setdefault(kind, []).append(frac)
         solver.set_profile(False)
+        c_read.update({kind: sum(v) / len(v) for kind, v in reads.items()})
         return {kind: (sum(v) / len(v), len(v)) for kind, v in per_kind.items()}
 
     def nonzero_segment_fraction():
@@ -131,14 +135,21 @@ def main() -> int:
             nz += int((X[:, j0:j0 + SEG_COLS] != 0).any(dim=1).sum().item())
         return nz / (m * ((n + SEG_COLS - 1) // SEG_COLS))
 
-    def sparse_sweep_bytes(frac):
-        # C once; X read and written back only on the nonzero segments (an upper bound: a segment is
-        # charged as a whole); the old and the new row sums per segment; the column sums per 64-row tile
+    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False):
+        # C on the fraction c_frac of its row segments; X read and written back only on the nonzero
+        # segments (an upper bound: a segment is charged as a whole); the old and the new row sums per
+        # segment (and the bound M of the screening); the column sums per 64-row tile
         nseg = (n + SEG_COLS - 1) // SEG_COLS
-        return 4.0 * m * n + 8.0 * frac * m * n + 8.0 * m * nseg + 4.0 * n * ((m + 63) // 64)
+        return (4.0 * c_frac * m * n + 8.0 * frac * m * n + (12.0 if screened else 8.0) * m * nseg +
+                4.0 * n * ((m + 63) // 64))
+
+    def bytes_of(kind, frac):
+        if kind in (4, 5, 6):
+            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4)
+        return BYTES_PER_ELEMENT[kind] * m * n
 
     def kernel_entry(kind, ms, launches, nbytes=None):
-        nbytes = BYTES_PER_ELEMENT[kind] * m * n if nbytes is None else nbytes
+        nbytes = bytes_of(kind, nonzero_segment_fraction()) if nbytes is None else nbytes
         gbs = nbytes / (ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((P.name, kind)),
@@ -149,21 +160,27 @@ def main() -> int:
                     1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
                     2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)",
                     3: "resident_kernel (X and C stay in registers; the time is per iteration)",
-                    4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)"}
+                    4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)",
+                    5: "screened_sweep_kernel (reads C only where a bound does not certify zeros; nonzero row segments of X)",
+                    6: "screened_sweep_kernel, refresh (reads all of C, records the bounds)"}
     prof = sweep_profile()
     frac_nz = nonzero_segment_fraction()
-    kind_bytes = {k: (sparse_sweep_bytes(frac_nz) if k == 4 else BYTES_PER_ELEMENT[k] * m * n) for k in prof}
+    kind_bytes = {k: bytes_of(k, frac_nz) for k in prof}
     dominant = max(prof, key=lambda kind: prof[kind][0] * prof[kind][1])
     roofline = kernel_entry(dominant, *prof[dominant], nbytes=kind_bytes[dominant])
     bytes_per_iteration = sum(kind_bytes[k] * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
-    if dominant == 4:
+    if dominant in (4, 5, 6):
         roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
+        roofline["c_row_segments_read_fraction"] = round(c_read.get(dominant, 1.0), 5)
+        roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]
         roofline["dense_model_bytes"] = 12.0 * m * n
         roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
-        log(f"nonzero row segments of X: {frac_nz:.3%}; the same sweep priced at 12 B/element would read "
-            f"{roofline['dense_model_gbs']:.0f} GB/s")
+        log(f"nonzero row segments of X: {frac_nz:.3%}; row segments of C read: {c_read.get(dominant, 1.0):.3%}; "
+            f"the same sweep priced at 12 B/element would read {roofline['dense_model_gbs']:.0f} GB/s")
+        for e in roofline["other_kernels"]:
+            log(f"  also [{e['kernel']}]: {e['kernel_ms']:.4f} ms over {e['launches_timed']} launches -> {e['achieved']:.0f} GB/s ({e['frac']:.1%})")
 
     def timed_leg(label):
         """K more iterations from the current state with the solver's current settings, then a profile."""
@@ -184,7 +201,12 @@ def main() -> int:
 
     # ---- the same K iterations with the even/odd scheme, and with every byte moved ----------------------
     even_odd_leg = dense_leg = None
-    if dominant == 4:
+    unscreened_leg = None
+    if dominant in (5, 6):
+        solver.set_screening(0)
+        unscreened_leg = timed_leg("zero segments skipped, all of C read")
+        solver.set_screening(-1)
+    if dominant in (4, 5, 6):
         solver.set_skip_cost(1)
         even_odd_leg = timed_leg("even/odd scheme (20 B/element and pair)")
         solver.set_skip_cost(0)
@@ -269,7 +291,8 @@ def main() -> int:
                    "stepsize": float(P.rho), "check_every": args.check_every},
         "algorithmic_bytes_per_iteration": bytes_per_iteration,
         "hbm_gbs_whole_iteration": round(bytes_per_iteration / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "time_to_tol": tol_leg, "even_odd_scheme": even_odd_leg, "every_byte_moved": dense_leg,
+        "roofline": roofline, "time_to_tol": tol_leg, "unscreened": unscreened_leg, "even_odd_scheme": even_odd_leg,
+        "every_byte_moved": dense_leg,
         "cost_from_points": points_leg, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -23,7 +23,7 @@ DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
-    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_resident", "drot_set_skip_unchanged", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_resident", "drot_set_screening", "drot_set_skip_unchanged", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_get_profile_reads", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
 )
 
 
@@ -68,10 +68,12 @@ def load_library() -> ctypes.CDLL:
     lib.drot_set_fused_update.argtypes = [vp, ci]
     lib.drot_set_resident.argtypes = [vp, ci]
     lib.drot_set_skip_unchanged.argtypes = [vp, ci]
+    lib.drot_set_screening.argtypes = [vp, ci]
     lib.drot_set_skip_cost.argtypes = [vp, ci]
     lib.drot_set_profile.argtypes = [vp, ci]
     lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     lib.drot_get_profile_sweeps.argtypes = [vp, ctypes.POINTER(cf), ctypes.POINTER(ci), ci, ctypes.POINTER(ci)]
+    lib.drot_get_profile_reads.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ci, ctypes.POINTER(ci)]
     lib.drot_solve.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp]
     lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_solve_points.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf,
@@ -162,6 +164,11 @@ class Solver:
         if rc != DROT_OK:
             raise DrotError(rc, "drot_set_resident")
 
+    def set_screening(self, mode: int) -> None:
+        rc = self._lib.drot_set_screening(self._h, int(mode))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_set_screening")
+
     def set_skip_unchanged(self, mode: int) -> None:
         rc = self._lib.drot_set_skip_unchanged(self._h, int(mode))
         if rc != DROT_OK:
@@ -195,6 +202,15 @@ class Solver:
         if rc != DROT_OK:
             raise DrotError(rc, "drot_get_profile_sweeps")
         return [(float(buf[e]), int(kinds[e])) for e in range(min(cnt.value, 256))]
+
+    def profile_reads(self) -> list:
+        """Fraction of the row segments of C that each sweep timed by the last solve read (drot_get_profile_reads)."""
+        buf = (ctypes.c_double * 256)()
+        cnt = ctypes.c_int()
+        rc = self._lib.drot_get_profile_reads(self._h, buf, 256, ctypes.byref(cnt))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_profile_reads")
+        return [float(buf[e]) for e in range(min(cnt.value, 256))]
 
     def solve(self, C: torch.Tensor, p: torch.Tensor, q: torch.Tensor, *, stepsize: float = 0.0,
               reg_kind: int = DROT_REG_NONE, lam: float = 0.0, mu: float = 0.0,

@@ -90,6 +90,20 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | (unsigned long long)lo);
 }
 
+// Maximum over the 64 lanes of a wave, wave-uniform: the steps of wave_sum with max in place of +.
+// (The two broadcast steps hand 0 to the lanes they do not reach; lane 63, the one read back, is
+// reached by both, and the lanes it reads are read before they are touched: the result is exact
+// whatever the signs.)
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_mov<0xB1, 0xF>(v));
+  v = fmaxf(v, dpp_mov<0x4E, 0xF>(v));
+  v = fmaxf(v, dpp_mov<0x141, 0xF>(v));
+  v = fmaxf(v, dpp_mov<0x140, 0xF>(v));
+  v = fmaxf(v, dpp_mov<0x142, 0xA>(v));
+  v = fmaxf(v, dpp_mov<0x143, 0xC>(v));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 __device__ __forceinline__ f4v load4(const float* __restrict__ ptr, int nvalid) {
   if (nvalid == 4) return *reinterpret_cast<const f4u*>(ptr);
   f4v v = {0.f, 0.f, 0.f, 0.f};
@@ -463,6 +477,143 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
   const int seg = blockIdx.x, tr = blockIdx.y;
   if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
   else sweep_body<FIRST, true, false, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+}
+
+// ------------------------------------------------------------------------------------------
+// Screened sweep (large sparse problems).  On top of skipping the all-zero row segments of X, most
+// of C need not be read either: a row segment with x = 0 comes out as zero again whenever
+// phi_i + varphi_j - rho C_ij <= 0 for its 256 columns, and that can be certified from one number.
+// A "refresh" sweep, which reads all of C, records for every row segment
+//     M_is = max_j ( varphi0_j - rho C_ij )            (varphi0 = the varphi of that sweep).
+// Later sweeps form, per column segment, delta_s = max_j (varphi_j - varphi0_j) and, per row,
+//     S = M_is + delta_s + phi_i  >=  max_j ( phi_i + varphi_j - rho C_ij ).
+// If S plus a rounding margin is <= 0 and the segment of X is zero, the segment stays zero: its C is
+// not read, nothing is computed, its row sum is 0.  The result is the one the plain sweep would
+// produce (the margin dominates the handful of fp32 roundings between the two evaluations).  As
+// varphi drifts away from varphi0 fewer segments certify; the host refreshes every so many sweeps.
+// Tiles: 8 waves x 8 rows x 256 columns, as the unscreened sweep for sparse plans.
+// ------------------------------------------------------------------------------------------
+struct ScreenArgs {
+  const float* mprime_in;   // [nseg][m] M_is of the current epoch (screening sweeps)
+  float* mprime_out;        // [nseg][m] written by a refresh sweep
+  const float* varphi0;     // [n] varphi of the epoch
+  int* wave_reads;          // profiling only (else null): [workgroup][wave] row segments of C this wave read
+};
+
+constexpr int kScreenRows = 8, kScreenWaves = 8;
+
+template <bool EDGE, bool NT, bool REFRESH>
+__device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int wave, int seg, int tr) {
+  constexpr int U = kScreenRows, NW = kScreenWaves;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
+  const int r0 = (tr * NW + wave) * U;
+  const int nrows = min(max(A.m - r0, 0), U);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const float rho = A.rho, scale = A.scale;
+  const size_t ridx = (size_t)seg * A.m + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
+
+  // lane u: old sum, phi and M of row r0 + u
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  if (lane < nrows) {
+    prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
+    ph = A.phi[r0 + lane];
+    if (!REFRESH) mpr = SC.mprime_in[ridx];
+  }
+  bool certified = lane >= nrows;  // rows past the end of the matrix: nothing to do
+  if (!REFRESH) {
+    const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+    // drift of varphi since the epoch and its magnitude over this wave's columns (columns past n: both
+    // carry the same mask value, their difference is 0; they are left out of the magnitude)
+    float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+    float a = 0.f;
+    if (nvalid > 0) a = fabsf(vp.x);
+    if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
+    if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
+    if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+    const float delta = wave_max(d), mag = wave_max(a);
+    // S bounds every phi_i + varphi_j - rho C_ij of the row segment from above; the margin, 8 units in
+    // the last place of the largest term, covers the roundings of M, of delta, of this sum and of the
+    // sweep's own evaluation (each at most half a unit of a term no larger than these)
+    const float bound = (mpr + delta) + ph;
+    const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);  // 2^-21
+    const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;  // (-inf: every pair of the segment is forbidden)
+    certified = certified || (fbits(prev) == 0 && below);
+  }
+  const unsigned skipmask = (unsigned)__builtin_amdgcn_ballot_w64(certified) & 0xffu;
+  const unsigned nzmask = (unsigned)__builtin_amdgcn_ballot_w64(fbits(prev) != 0) & 0xffu;
+
+  f4v x[U], c[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+    c[u] = f4v{0.f, 0.f, 0.f, 0.f};
+  }
+  if (nrows == U && skipmask == 0) {
+    // nothing certified (always so in a refresh sweep, and while the plan is dense): straight-line loads
+#pragma unroll
+    for (int u = 0; u < U; ++u) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (!((skipmask >> u) & 1)) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+  }
+  if (nzmask != 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if ((nzmask >> u) & 1) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+  }
+
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float rowkeep = 0.f, mkeep = 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!((skipmask >> u) & 1)) {
+      const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+      const f4v v = xbar4(x[u], c[u], vp + phu, rho) * scale;
+      const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+      if (((nzmask >> u) & 1) || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+      colacc += v;
+      const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+      rowkeep = (lane == u) ? tot : rowkeep;
+      if (REFRESH) {
+        const float mx = fmaxf(fmaxf(fmaf(-rho, c[u].x, vp.x), fmaf(-rho, c[u].y, vp.y)),
+                               fmaxf(fmaf(-rho, c[u].z, vp.z), fmaf(-rho, c[u].w, vp.w)));
+        const float mm = wave_max(mx);
+        mkeep = (lane == u) ? mm : mkeep;
+      }
+    }
+  }
+  if (lane < nrows) {
+    A.rowpart[ridx] = rowkeep;
+    if (REFRESH) SC.mprime_out[ridx] = mkeep;
+  }
+  if (SC.wave_reads && lane == 0)
+    SC.wave_reads[(tr * gridDim.x + seg) * NW + wave] = __builtin_popcount(~skipmask & 0xffu);
+  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+}
+
+// Profiling: total of the per-wave read counts of one screened sweep.
+__global__ __launch_bounds__(1024) void sum_reads_kernel(const int* __restrict__ wave_reads, int count, double* out) {
+  __shared__ double red[1024 / 64];
+  double acc = 0.0;
+  for (int e = threadIdx.x; e < count; e += 1024) acc += (double)wave_reads[e];
+  const double tot = block_sum_f64(acc, red);
+  if (threadIdx.x == 0) *out = tot;
+}
+
+template <bool NT, bool REFRESH>
+__global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepArgs A, ScreenArgs SC) {
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  if ((seg + 1) * kSegCols <= A.n) screened_body<false, NT, REFRESH>(A, SC, lane, wave, seg, tr);
+  else screened_body<true, false, REFRESH>(A, SC, lane, wave, seg, tr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1019,7 +1170,6 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   __shared__ int nzw[kReduceThreads / 64];
   double acc = 0.0;
   int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
-#pragma unroll 4
   for (int k = sub; k < nparts; k += kReduceThreads / 64) {  // (nparts and sub are wave-uniform)
     const float v = idx < len ? part[(size_t)k * len + idx] : 0.f;
     acc += (double)v;
@@ -1478,6 +1628,8 @@ struct drot_handle_s {
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
+  int screening = -1;       // sparse plans also skip the reads of C that a bound certifies useless: -1/1 with the
+                            // bounds refreshed every 64 sweeps, k >= 2 every k sweeps, 0 never
   int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
   bool dense_plan = false;  // what the last solve's density feedback ended on
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
@@ -1501,6 +1653,11 @@ struct drot_handle_s {
          *resid = nullptr;
   float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
   size_t rowpart_half = 0, colpart_half = 0, tilesum_half = 0;
+  float *mprime = nullptr, *varphi0 = nullptr;  // screened sweep: per-row-segment bounds and the epoch's varphi
+  int* wave_reads = nullptr;      // profiling: per-wave read counts of a screened sweep (allocated with the events)
+  size_t wave_reads_len = 0;
+  double* prof_reads = nullptr;   // profiling: [kMaxProfiled] row segments of C read by each timed sweep (device)
+  double prof_reads_host[kMaxProfiled] = {};
   float* gbuf = nullptr;  // group-lasso accumulators, grown on demand
   size_t gbuf_len = 0;
   // padded working copies of C and X (pitch rounded up to 32 elements), made when the caller's
@@ -1542,7 +1699,7 @@ int dev_alloc(T** ptr, size_t count) {
 }
 
 void free_all(drot_handle h) {
-  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf};
+  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf, h->mprime, h->varphi0};
   double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid};
   for (float* b : fbufs) (void)hipFree(b);
   for (double* b : dbufs) (void)hipFree(b);
@@ -1557,6 +1714,8 @@ void free_all(drot_handle h) {
     if (e) (void)hipEventDestroy(e);
   for (auto& e : h->prof_ev)
     if (e) (void)hipEventDestroy(e);
+  (void)hipFree(h->wave_reads);
+  (void)hipFree(h->prof_reads);
 }
 
 }  // namespace
@@ -1607,6 +1766,8 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->rowpart, 2 * h->rowpart_half));
   take(dev_alloc(&h->colpart, 2 * h->colpart_half));
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
+  take(dev_alloc(&h->mprime, nseg * (size_t)max_m));
+  take(dev_alloc(&h->varphi0, (size_t)max_n));
   h->max_runs = (int)ntr;
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));
   take(dev_alloc(&h->done, 1));
@@ -1679,6 +1840,12 @@ int drot_set_skip_unchanged(drot_handle h, int mode) {
   return DROT_OK;
 }
 
+int drot_set_screening(drot_handle h, int mode) {
+  if (!h || mode < -1 || mode > 100000) return DROT_ERR_INVALID_ARG;
+  h->screening = mode;
+  return DROT_OK;
+}
+
 int drot_set_resident(drot_handle h, int mode) {
   if (!h || mode < -1 || mode > 0) return DROT_ERR_INVALID_ARG;
   h->resident = mode;
@@ -1699,6 +1866,13 @@ int drot_set_profile(drot_handle h, int enable) {
         e = nullptr;
         return DROT_ERR_HIP;
       }
+  if (enable && !h->prof_reads) {
+    // read counts of the screened sweeps: one int per wave of the largest grid, one total per timed sweep
+    const size_t waves = (size_t)ceil_div(h->max_n, kSegCols) * (size_t)ceil_div(h->max_m, kScreenRows * kScreenWaves) * kScreenWaves;
+    if (hipMalloc(reinterpret_cast<void**>(&h->wave_reads), sizeof(int) * waves) != hipSuccess) return DROT_ERR_ALLOC;
+    h->wave_reads_len = waves;
+    if (hipMalloc(reinterpret_cast<void**>(&h->prof_reads), sizeof(double) * kMaxProfiled) != hipSuccess) return DROT_ERR_ALLOC;
+  }
   h->profile = enable ? 1 : 0;
   return DROT_OK;
 }
@@ -1719,6 +1893,17 @@ int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int
     sweep_ms[e] = h->prof_ms[e];
     if (sweep_kind) sweep_kind[e] = h->prof_kind[e];
   }
+  return DROT_OK;
+}
+
+int drot_get_profile_reads(drot_handle h, double* c_fraction, int capacity, int* sweeps_timed) {
+  if (!h || !c_fraction || capacity < 0 || !sweeps_timed) return DROT_ERR_INVALID_ARG;
+  if (!h->solved) return DROT_ERR_NOT_INITIALIZED;
+  *sweeps_timed = h->prof_count;
+  const double segments = (double)h->last_m * (double)ceil_div(h->last_n, kSegCols);
+  for (int e = 0; e < h->prof_count && e < capacity; ++e)
+    c_fraction[e] = (h->prof_kind[e] == 5 || h->prof_kind[e] == 6) ? h->prof_reads_host[e] / segments
+                    : (h->prof_kind[e] == 2 ? 0.0 : 1.0);
   return DROT_OK;
 }
 
@@ -1976,6 +2161,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // generation whose row-segment sums (tile layout) describe the plain X in memory, if any: lets the
   // plain sweep skip reading all-zero segments
   long long sums_gen = warm ? 0 : -1;
+  // screened sweeps: the sweep that last recorded the bounds M (with its varphi as varphi0), if any
+  long long epoch_gen = -1;
+  const int kRefreshEvery = h->screening >= 2 ? h->screening : 64;
   while (k < max_iters && !converged) {
     const int chunk = (checking || adaptive) ? (h->check_every < max_iters - k ? h->check_every : max_iters - k)
                                              : max_iters - k;
@@ -2051,11 +2239,27 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
-        if (timed) h->prof_kind[pe] = (mode == 0 && tall && !first) ? 4 : mode;
+        const bool screened = mode == 0 && tall && !first && h->screening != 0;
+        const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= kRefreshEvery);
+        if (timed) h->prof_kind[pe] = screened ? (refresh ? 6 : 5) : (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
         sums_gen = mode == 1 ? -1 : sw;
-        if (first) {
+        if (screened) {
+          const dim3 sgrid(nseg, ceil_div(m, kScreenRows * kScreenWaves)), sblock(64 * kScreenWaves);
+          if (refresh) {
+            DROT_HIP(hipMemcpyAsync(h->varphi0, h->varphi, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, stream));
+            epoch_gen = sw;
+          }
+          const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr};
+          if (refresh) {
+            if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, S, SC);
+            else hipLaunchKernelGGL((screened_sweep_kernel<false, true>), sgrid, sblock, 0, stream, S, SC);
+          } else {
+            if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, false>), sgrid, sblock, 0, stream, S, SC);
+            else hipLaunchKernelGGL((screened_sweep_kernel<false, false>), sgrid, sblock, 0, stream, S, SC);
+          }
+        } else if (first) {
           if (mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         } else if (nt) {
@@ -2072,7 +2276,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         // (the tall tiles leave fewer rows of column partials for the reduction)
         if (!slab_k) RA.ntr = (tall && !first && mode == 0) ? ntr_tall : ntr;
       }
-      if (timed) DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
+      if (timed) {
+        DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
+        if (h->prof_kind[pe] == 5 || h->prof_kind[pe] == 6)
+          hipLaunchKernelGGL(sum_reads_kernel, dim3(1), dim3(1024), 0, stream, (const int*)h->wave_reads,
+                             nseg * ceil_div(m, kScreenRows * kScreenWaves) * kScreenWaves, h->prof_reads + pe);
+      }
       if (!fused || c == chunk - 1) {
         // complete the state in memory: update sw from the sums of X_sw
         RA.rowpart = rowp(sw);
@@ -2136,6 +2345,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->prof_sweep_ms = 0.0;
   if (h->profile) {
     const int timed = h->prof_used;
+    if (timed > 0) DROT_HIP(hipMemcpy(h->prof_reads_host, h->prof_reads, sizeof(double) * (size_t)timed, hipMemcpyDeviceToHost));
     for (int e = 0; e < timed; ++e) {
       float ms = 0.f;
       DROT_HIP(hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]));

@@ -412,6 +412,29 @@ def test_sweep_schemes_beyond_the_fused_path(drot, oracle, kind):
         solver.set_skip_unchanged(2)
 
 
+@pytest.mark.parametrize("kind,m,n", [(0, 2300, 2500), (1, 2100, 3000), (0, 2049, 257), (1, 4000, 1500)])
+def test_screening_changes_no_bit(drot, oracle, kind, m, n):
+    # leaving out the reads of C that the bound certifies useless must give the very iterates of the
+    # unscreened sweeps (same tiles, same summation order), over several refresh periods, across
+    # residual checks, and with forbidden pairs (C = +inf) in the picture
+    base = drot_inputs.random_problem(m, n, seed=1500 + m, reg_kind=kind, lam=0.05 if kind else 0.0)
+    P = drot_inputs.with_entrywise_terms(base, seed=1501, forbid_frac=0.2 if kind else 0.0)
+    solver = drot.Solver(m, n, check_every=37)
+    _say(f"screening, bitwise, {m}x{n} kind={kind}")
+    K = 300
+    solver.set_screening(0)
+    res_plain, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
+    solver.set_screening(-1)
+    solver.set_profile(True)
+    res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
+    kinds = [kind_ for _, kind_ in solver.profile_sweeps()]
+    solver.set_profile(False)
+    assert 5 in kinds and 6 in kinds  # screened and refresh sweeps both ran
+    assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
+    ores = pu.oracle_solve(oracle, P, K)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="screened")
+
+
 def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     # a strong quadratic term keeps the plan dense: the density the reduction reports must move the
     # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
@@ -424,7 +447,7 @@ def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     solver.set_profile(False)
     nonzero_segments = [X[:, j:j + 256].max(axis=1) > 0 for j in range(0, P.n, 256)]
     assert float(np.mean(nonzero_segments)) > 0.9  # (a tenth of the entries is enough for that)
-    assert kinds[:10] == [0] + [4] * 9          # first stretch: the default scheme (sweep 1 has nothing to read)
+    assert kinds[:10] == [0, 6] + [5] * 8       # first stretch: the default scheme (sweep 1 has nothing to read, sweep 2 records the bounds)
     assert set(kinds[30:]) == {1, 2}, kinds     # switched after the first status came back, one stretch late
     ores = pu.oracle_solve(oracle, P, 90)
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="dense plan")
