@@ -144,7 +144,7 @@ def main() -> int:
                 4.0 * n * ((m + 63) // 64))
 
     def bytes_of(kind, frac):
-        if kind in (4, 5, 6):
+        if kind in (4, 5, 6, 7):
             return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4)
         return BYTES_PER_ELEMENT[kind] * m * n
 
@@ -162,7 +162,8 @@ def main() -> int:
                     3: "resident_kernel (X and C stay in registers; the time is per iteration)",
                     4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)",
                     5: "screened_sweep_kernel (reads C only where a bound does not certify zeros; nonzero row segments of X)",
-                    6: "screened_sweep_kernel, refresh (reads all of C, records the bounds)"}
+                    6: "screened_sweep_kernel, refresh (reads all of C, records the bounds)",
+                    7: "screened_lean_kernel (one wave per 64 x 256 tile; reads C only where a bound does not certify zeros)"}
     prof = sweep_profile()
     frac_nz = nonzero_segment_fraction()
     kind_bytes = {k: bytes_of(k, frac_nz) for k in prof}
@@ -171,7 +172,7 @@ def main() -> int:
     bytes_per_iteration = sum(kind_bytes[k] * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
-    if dominant in (4, 5, 6):
+    if dominant in (4, 5, 6, 7):
         roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
         roofline["c_row_segments_read_fraction"] = round(c_read.get(dominant, 1.0), 5)
         roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]
@@ -202,11 +203,11 @@ def main() -> int:
     # ---- the same K iterations with the even/odd scheme, and with every byte moved ----------------------
     even_odd_leg = dense_leg = None
     unscreened_leg = None
-    if dominant in (5, 6):
+    if dominant in (5, 6, 7):
         solver.set_screening(0)
         unscreened_leg = timed_leg("zero segments skipped, all of C read")
         solver.set_screening(-1)
-    if dominant in (4, 5, 6):
+    if dominant in (4, 5, 6, 7):
         solver.set_skip_cost(1)
         even_odd_leg = timed_leg("even/odd scheme (20 B/element and pair)")
         solver.set_skip_cost(0)

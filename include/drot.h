@@ -148,11 +148,12 @@ int drot_set_skip_unchanged(drot_handle h, int mode);
 
 /*
  * Screening [-1 = on].  With the zero-segment skipping on, sweeps over large sparse plans also leave
- * out most reads of C.  Every 64th sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
+ * out most reads of C.  Every 256th sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
  * until the next one, a row segment whose X is zero and whose bound M + max_j (drift of varphi_j
  * since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is known to
  * stay zero: nothing of it is read, computed or written.  The iterates are those of the unscreened
- * sweeps, bit for bit.  mode 0 reads C in full every sweep.
+ * sweeps, bit for bit.  mode 0 reads C in full every sweep; mode k >= 2 records the bounds every
+ * k-th sweep instead.
  */
 int drot_set_screening(drot_handle h, int mode);
 
@@ -194,13 +195,14 @@ int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
  * HOST, capacity ints or NULL: 0 = the sweep read X and C, 1 = it also stored X - rho*C (first of an
  * even/odd pair), 2 = it read the shifted X and no C (second of a pair), 3 = a launch of the resident
  * kernel (its duration divided by the iterations it ran), 4 = as 0 but on 64-row tiles with the
- * zero-segment skipping, 5 = the same with screening (the default sweep of large problems), 6 = a
- * screening sweep that reads all of C and records the bounds; *sweeps_timed receives how many the last
+ * zero-segment skipping, 5 = the same with screening, 6 = a screening sweep that reads all of C and
+ * records the bounds, 7 = the screened sweep for plans known to be sparse (one wave per tile; the
+ * default sweep of large problems once the first status has come back); *sweeps_timed receives how many the last
  * solve timed (at most min(capacity, that many) entries are written). */
 int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed);
 /* For the same sweeps: the fraction of the row segments of C (256 columns of one row) each of them
  * read; c_fraction [out] HOST, capacity doubles.  1 for the kinds that read all of C, 0 for kind 2,
- * counted by the kernel for the screened kinds 5 and 6. */
+ * counted by the kernel for the screened kinds 5, 6 and 7. */
 int drot_get_profile_reads(drot_handle h, double* c_fraction, int capacity, int* sweeps_timed);
 
 /*

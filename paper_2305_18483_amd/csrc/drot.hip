@@ -616,6 +616,95 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
   else screened_body<true, false, REFRESH>(A, SC, lane, wave, seg, tr);
 }
 
+// The screened sweep for plans known to be sparse (a few percent of the row segments left to
+// process): one wave owns a whole 64 x 256 tile, lane l holding the old sum, phi and M of row l.
+// It decides all 64 rows at once and then walks through the rows left over, one at a time.  No
+// LDS, no barrier; 8 times fewer waves than the tile of 8 waves x 8 rows, and the same bits: the
+// rows of every group of 8 are added up in order and the 8 groups in order, which is what that
+// tile's waves and its LDS fold do (rows and groups that contribute nothing add +0).
+template <bool EDGE, bool NT>
+__device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr) {
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
+  const int r0 = tr * 64;
+  const int nrows = min(A.m - r0, 64);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const float rho = A.rho, scale = A.scale;
+  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  if (lane < nrows) {
+    prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
+    ph = A.phi[r0 + lane];
+    mpr = SC.mprime_in[ridx];
+  }
+  float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  float a = 0.f;
+  if (nvalid > 0) a = fabsf(vp.x);
+  if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
+  if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
+  if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+  const float delta = wave_max(d), mag = wave_max(a);
+  const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
+  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
+  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool certified = lane >= nrows || (fbits(prev) == 0 && below);
+  unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
+  const unsigned long long nzmask = __builtin_amdgcn_ballot_w64(fbits(prev) != 0);
+  if (SC.wave_reads && lane == 0) SC.wave_reads[tr * gridDim.x + seg] = __builtin_popcountll(todo);
+
+  f4v tile_acc = {0.f, 0.f, 0.f, 0.f}, group_acc = {0.f, 0.f, 0.f, 0.f};
+  int group = -1;
+  float rowkeep = 0.f;
+  while (todo != 0) {
+    const int u = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    if ((u >> 3) != group) {
+      if (group >= 0) tile_acc += group_acc;
+      group_acc = f4v{0.f, 0.f, 0.f, 0.f};
+      group = u >> 3;
+    }
+    const bool nz = (nzmask >> u) & 1;
+    const f4v c = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+    f4v x = {0.f, 0.f, 0.f, 0.f};
+    if (nz) x = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+    const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+    const f4v v = xbar4(x, c, vp + phu, rho) * scale;
+    const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+    if (nz || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+    group_acc += v;
+    const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+    rowkeep = (lane == u) ? tot : rowkeep;
+  }
+  if (group >= 0) tile_acc += group_acc;
+  if (lane < nrows) A.rowpart[ridx] = rowkeep;
+  float* __restrict__ cp = A.colpart + (size_t)tr * A.n + j0;
+  if (nvalid == 4) *reinterpret_cast<f4u*>(cp) = tile_acc;
+  else {
+    if (nvalid > 0) cp[0] = tile_acc.x;
+    if (nvalid > 1) cp[1] = tile_acc.y;
+    if (nvalid > 2) cp[2] = tile_acc.z;
+  }
+}
+
+constexpr int kLeanWaves = 4;  // independent waves per workgroup
+
+template <bool NT>
+__global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
+  if (tr >= ntiles_rows) return;
+  if ((seg + 1) * kSegCols <= A.n) screened_lean_body<false, NT>(A, SC, lane, seg, tr);
+  else screened_lean_body<true, false>(A, SC, lane, seg, tr);
+}
+
 // ------------------------------------------------------------------------------------------
 // On-the-fly cost: C_ij = cost_scale * ||xs_i - xt_j||^2 recomputed from the two point clouds in
 // every sweep instead of being read (8 bytes per element of HBM traffic instead of 12, plus
@@ -1157,9 +1246,7 @@ struct ReduceArgs {
 
 constexpr int kReduceThreads = 1024;
 
-__global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
-  if (*A.V.done) return;
-  __shared__ double red[kReduceThreads];
+__device__ __forceinline__ void reduce_body(const ReduceArgs& A, double* red, int* nzw) {
   const int t = threadIdx.x;
   const int sub = t >> 6, l = t & 63;
   const bool rows = (int)blockIdx.x < A.nbm;
@@ -1167,7 +1254,6 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   const int len = rows ? A.m : A.n;
   const int nparts = rows ? A.nseg : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
-  __shared__ int nzw[kReduceThreads / 64];
   double acc = 0.0;
   int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
   for (int k = sub; k < nparts; k += kReduceThreads / 64) {  // (nparts and sub are wave-uniform)
@@ -1204,6 +1290,13 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   }
 }
 
+__global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
+  if (*A.V.done) return;
+  __shared__ double red[kReduceThreads];
+  __shared__ int nzw[kReduceThreads / 64];
+  reduce_body(A, red, nzw);
+}
+
 // ------------------------------------------------------------------------------------------
 // S5, second half: eq. (6) with f = 1_m, e = 1_n.  eta = 1^T r/(m+n); phi+ = (a - 2r + (2 eta -
 // theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m, a -= r, b -= s, theta -= eta.  fp64; phi and
@@ -1221,9 +1314,9 @@ struct UpdateArgs {
   int m, n, nbm, nbn, par;
 };
 
-__global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
-  if (*A.V.done) return;
-  __shared__ double red[kReduceThreads];
+// The update for all m + n entries by one workgroup (all = true: it strides over them) or for the
+// 1024 entries of workgroup `vb` (all = false); the arithmetic per entry is the same either way.
+__device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, bool all, double* red) {
   const int t = threadIdx.x;
   double acc = 0.0;
   if (A.tilesum) {
@@ -1237,18 +1330,22 @@ __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
   const double eta = sum_r / mn;
   const double theta = A.V.theta[A.par];
   const double cst = 2.0 * eta - theta;
-  const long long g = (long long)blockIdx.x * kReduceThreads + t;
-  if (g < A.m) {
-    const double r = A.V.r[g], ai = A.a_in[g];
-    A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
-    A.a_out[g] = ai - r;
-  } else if (g < (long long)A.m + A.n) {
-    const long long j = g - A.m;
-    const double sj = A.V.s[j], bj = A.b_in[j];
-    A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
-    A.b_out[j] = bj - sj;
+  const long long total = (long long)A.m + A.n;
+  const long long first = all ? t : (long long)vb * kReduceThreads + t;
+  const long long step = all ? kReduceThreads : total;  // (all = false: one entry per thread)
+  for (long long g = first; g < total; g += step) {
+    if (g < A.m) {
+      const double r = A.V.r[g], ai = A.a_in[g];
+      A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
+      A.a_out[g] = ai - r;
+    } else {
+      const long long j = g - A.m;
+      const double sj = A.V.s[j], bj = A.b_in[j];
+      A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
+      A.b_out[j] = bj - sj;
+    }
   }
-  if (blockIdx.x == 0) {
+  if (all || vb == 0) {
     double r2 = 0.0, s2 = 0.0;
     const double* sq = A.V.part + A.nbm + A.nbn;
     for (int e = t; e < A.nbm; e += kReduceThreads) r2 += sq[e];
@@ -1266,6 +1363,12 @@ __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
       A.V.resid[2] = nzs;
     }
   }
+}
+
+__global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
+  if (*A.V.done) return;
+  __shared__ double red[kReduceThreads];
+  update_body(A, (int)blockIdx.x, false, red);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1632,6 +1735,9 @@ struct drot_handle_s {
                             // bounds refreshed every 64 sweeps, k >= 2 every k sweeps, 0 never
   int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
   bool dense_plan = false;  // what the last solve's density feedback ended on
+  double plan_density = -1.0;
+  long long epoch_gen = -1;  // screening: sweep that recorded the bounds in mprime (continued solves)
+  int refresh_period = 8;
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
   int skip_cost = -1;     // even/odd scheme (C read every second sweep): -1 where it applies unless the update is fused, 0 never, 1 where it applies
@@ -1902,7 +2008,7 @@ int drot_get_profile_reads(drot_handle h, double* c_fraction, int capacity, int*
   *sweeps_timed = h->prof_count;
   const double segments = (double)h->last_m * (double)ceil_div(h->last_n, kSegCols);
   for (int e = 0; e < h->prof_count && e < capacity; ++e)
-    c_fraction[e] = (h->prof_kind[e] == 5 || h->prof_kind[e] == 6) ? h->prof_reads_host[e] / segments
+    c_fraction[e] = h->prof_kind[e] >= 5 ? h->prof_reads_host[e] / segments
                     : (h->prof_kind[e] == 2 ? 0.0 : 1.0);
   return DROT_OK;
 }
@@ -2122,9 +2228,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // Dense plan (strong quadratic term): the even/odd pairs.  With both options on automatic the
   // choice follows the density of the plan, which the reduction counts (nonzero row-segment sums)
   // and the host reads with the status of every stretch of check_every iterations, one stretch late.
+  const dim3 update_grid(ceil_div(m + n, kReduceThreads));
   const bool can_pair = reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
   const bool adaptive = can_pair && !small && h->skip_cost == -1 && h->skip_unchanged != 0;
   bool dense_plan = resume && h->dense_plan;  // (a continued solve keeps what the last one found)
+  double plan_density = resume ? h->plan_density : -1.0;  // fraction of nonzero row segments, once a status has come back
   constexpr int kTallRows = 8, kTallWaves = 8;
   const int ntr_tall = ceil_div(m, kTallWaves * kTallRows);
   auto a_buf = [&](long long g) { return h->a + (size_t)(g & 1) * (size_t)h->max_m; };
@@ -2133,7 +2241,6 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   auto colp = [&](long long g) { return h->colpart + (size_t)(g & 1) * h->colpart_half; };
   auto tsum = [&](long long g) { return h->tilesum + (size_t)(g & 1) * h->tilesum_half; };
   const dim3 grid(nseg, ntr), block(kBlock), sweep_block(64 * kSweepWaves);
-  const dim3 update_grid(ceil_div(m + n, kReduceThreads));
 
   if (warm) {
     // sums of X_0 (a sweep that only adds up), residuals, then the eq. (6) state of the starting point
@@ -2162,8 +2269,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // plain sweep skip reading all-zero segments
   long long sums_gen = warm ? 0 : -1;
   // screened sweeps: the sweep that last recorded the bounds M (with its varphi as varphi0), if any
-  long long epoch_gen = -1;
-  const int kRefreshEvery = h->screening >= 2 ? h->screening : 64;
+  // (varphi moves fast at first: the bounds are renewed after 8 sweeps, then 16, 32, ... up to the
+  // period; a continued solve carries on with the bounds and the schedule of the last one)
+  const int refresh_max = h->screening >= 2 ? h->screening : 256;
+  long long epoch_gen = resume ? h->epoch_gen : -1;
+  int refresh_period = resume ? h->refresh_period : 8;
+  if (refresh_period > refresh_max) refresh_period = refresh_max;
   while (k < max_iters && !converged) {
     const int chunk = (checking || adaptive) ? (h->check_every < max_iters - k ? h->check_every : max_iters - k)
                                              : max_iters - k;
@@ -2240,7 +2351,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
         const bool screened = mode == 0 && tall && !first && h->screening != 0;
-        const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= kRefreshEvery);
+        const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= refresh_period);
         if (timed) h->prof_kind[pe] = screened ? (refresh ? 6 : 5) : (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
@@ -2249,10 +2360,19 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const dim3 sgrid(nseg, ceil_div(m, kScreenRows * kScreenWaves)), sblock(64 * kScreenWaves);
           if (refresh) {
             DROT_HIP(hipMemcpyAsync(h->varphi0, h->varphi, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, stream));
+            if (epoch_gen >= 0) refresh_period = refresh_period * 2 < refresh_max ? refresh_period * 2 : refresh_max;
             epoch_gen = sw;
           }
           const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr};
-          if (refresh) {
+          // once the plan is known to be sparse: one wave per tile, walking through the few rows left
+          const bool lean = !refresh && S.rowpart_prev != nullptr && plan_density >= 0.0 && plan_density < 0.25;
+          if (lean) {
+            const int ntr64 = ceil_div(m, 64);
+            const dim3 lgrid(nseg, ceil_div(ntr64, kLeanWaves)), lblock(64 * kLeanWaves);
+            if (nt) hipLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, S, SC, ntr64);
+            else hipLaunchKernelGGL((screened_lean_kernel<false>), lgrid, lblock, 0, stream, S, SC, ntr64);
+            if (timed) h->prof_kind[pe] = 7;
+          } else if (refresh) {
             if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, S, SC);
             else hipLaunchKernelGGL((screened_sweep_kernel<false, true>), sgrid, sblock, 0, stream, S, SC);
           } else {
@@ -2278,9 +2398,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       }
       if (timed) {
         DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
-        if (h->prof_kind[pe] == 5 || h->prof_kind[pe] == 6)
+        if (h->prof_kind[pe] >= 5)  // (one count per wave: 8 per 64-row tile, or one in the lean kernel)
           hipLaunchKernelGGL(sum_reads_kernel, dim3(1), dim3(1024), 0, stream, (const int*)h->wave_reads,
-                             nseg * ceil_div(m, kScreenRows * kScreenWaves) * kScreenWaves, h->prof_reads + pe);
+                             nseg * ceil_div(m, 64) * (h->prof_kind[pe] == 7 ? 1 : kScreenWaves), h->prof_reads + pe);
       }
       if (!fused || c == chunk - 1) {
         // complete the state in memory: update sw from the sums of X_sw
@@ -2310,6 +2430,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         if (h->host_status[slot ^ 1].converged) converged = true;
         if (adaptive) {  // (hysteresis: the break-even is at about three quarters of the segments nonzero)
           const double density = h->host_status[slot ^ 1].nz_segments / ((double)m * (double)nseg);
+          plan_density = density;
           if (density > 0.7) dense_plan = true;
           else if (density < 0.5) dense_plan = false;
         }
@@ -2365,6 +2486,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->info.gap = h->compute_gap ? st.gap : 0.0;
   h->info.dual_res = h->compute_gap ? st.dual_res : 0.0;
   h->dense_plan = dense_plan;
+  h->plan_density = plan_density;
+  h->epoch_gen = epoch_gen;
+  h->refresh_period = refresh_period;
   h->solved = true;
   h->last_m = m;
   h->last_n = n;

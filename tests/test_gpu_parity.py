@@ -435,6 +435,28 @@ def test_screening_changes_no_bit(drot, oracle, kind, m, n):
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="screened")
 
 
+def test_lean_screened_sweep_changes_no_bit(drot, oracle):
+    # wide rows: after the first status reports a sparse plan the solver moves to the one-wave-per-tile
+    # screened sweep; iterates must still be those of the unscreened sweeps, bit for bit
+    P = drot_inputs.random_problem(2100, 8192 + 40, seed=1600, d=8, reg_kind=1, lam=0.01)
+    solver = drot.Solver(P.m, P.n, check_every=25)
+    _say("lean screened sweep, bitwise")
+    K = 260
+    solver.set_screening(0)
+    _, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
+    solver.set_screening(-1)
+    solver.set_profile(True)
+    res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
+    kinds = [k for _, k in solver.profile_sweeps()]
+    reads = solver.profile_reads()
+    solver.set_profile(False)
+    assert kinds.count(7) > 50, kinds
+    assert min(r for r, k in zip(reads, kinds) if k == 7) < 0.5  # and it does leave most of C unread
+    assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
+    ores = pu.oracle_solve(oracle, P, K)
+    pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="lean screened")
+
+
 def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     # a strong quadratic term keeps the plan dense: the density the reduction reports must move the
     # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
@@ -447,7 +469,8 @@ def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     solver.set_profile(False)
     nonzero_segments = [X[:, j:j + 256].max(axis=1) > 0 for j in range(0, P.n, 256)]
     assert float(np.mean(nonzero_segments)) > 0.9  # (a tenth of the entries is enough for that)
-    assert kinds[:10] == [0, 6] + [5] * 8       # first stretch: the default scheme (sweep 1 has nothing to read, sweep 2 records the bounds)
+    # first stretch: the default scheme (sweep 1 has nothing to read, sweeps 2 and 10 record the bounds)
+    assert kinds[:10] == [0, 6] + [5] * 7 + [6]
     assert set(kinds[30:]) == {1, 2}, kinds     # switched after the first status came back, one stretch late
     ores = pu.oracle_solve(oracle, P, 90)
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="dense plan")
