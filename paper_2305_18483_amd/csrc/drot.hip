@@ -1256,10 +1256,21 @@ __device__ __forceinline__ void reduce_body(const ReduceArgs& A, double* red, in
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
   double acc = 0.0;
   int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
-  for (int k = sub; k < nparts; k += kReduceThreads / 64) {  // (nparts and sub are wave-uniform)
-    const float v = idx < len ? part[(size_t)k * len + idx] : 0.f;
-    acc += (double)v;
-    nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v != 0.f));
+  constexpr int kStride = kReduceThreads / 64, kBatch = 8;
+  for (int k0 = sub; k0 < nparts; k0 += kStride * kBatch) {  // (nparts and sub are wave-uniform)
+    // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
+    // trip would wait for memory once per partial sum)
+    float v[kBatch];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int k = k0 + b * kStride;
+      v[b] = (idx < len && k < nparts) ? part[(size_t)k * len + idx] : 0.f;
+    }
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      if (k0 + b * kStride < nparts) acc += (double)v[b];
+      nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f));
+    }
   }
   red[t] = acc;
   if (l == 0) nzw[sub] = nz;
