@@ -187,7 +187,9 @@ int drot_set_skip_cost(drot_handle h, int mode);
  * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
  * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
  * how many were timed (with even/odd cost skipping the two kinds of sweep alternate, starting with
- * the one that reads C when the number of iterations between checks is even).  Costs two event records per iteration, so leave it off when timing a solve.
+ * the one that reads C when the number of iterations between checks is even).  The reading of an
+ * empty event pair (the smallest of four recorded at the start of the solve, a few microseconds) is
+ * subtracted from every duration.  Costs two event records per iteration, so leave it off when timing a solve.
  */
 int drot_set_profile(drot_handle h, int enable);
 int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);

@@ -1757,6 +1757,8 @@ struct drot_handle_s {
   long long iters_done = 0;  // iterations applied to the state held by this handle
   // sweep timing (profile mode): event pairs recorded on the solve's stream
   hipEvent_t prof_ev[2 * kMaxProfiled] = {};
+  hipEvent_t cal_ev[8] = {};  // four empty event pairs per profiled solve: what a pair costs without a kernel between
+  double prof_overhead_ms = 0.0;
   int prof_count = 0;
   double prof_sweep_ms = 0.0;
   float prof_ms[kMaxProfiled] = {};  // per sweep, in launch order
@@ -1830,6 +1832,8 @@ void free_all(drot_handle h) {
   for (auto& e : h->ev)
     if (e) (void)hipEventDestroy(e);
   for (auto& e : h->prof_ev)
+    if (e) (void)hipEventDestroy(e);
+  for (auto& e : h->cal_ev)
     if (e) (void)hipEventDestroy(e);
   (void)hipFree(h->wave_reads);
   (void)hipFree(h->prof_reads);
@@ -1979,6 +1983,12 @@ int drot_set_profile(drot_handle h, int enable) {
   if (!h) return DROT_ERR_INVALID_ARG;
   if (enable)
     for (auto& e : h->prof_ev)
+      if (!e && hipEventCreate(&e) != hipSuccess) {
+        e = nullptr;
+        return DROT_ERR_HIP;
+      }
+  if (enable)
+    for (auto& e : h->cal_ev)
       if (!e && hipEventCreate(&e) != hipSuccess) {
         e = nullptr;
         return DROT_ERR_HIP;
@@ -2276,6 +2286,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   bool converged = false;
   bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
   h->prof_used = 0;
+  if (h->profile)  // empty event pairs: the time a pair reports with nothing between its two records
+    for (auto& e : h->cal_ev) DROT_HIP(hipEventRecord(e, stream));
   // generation whose row-segment sums (tile layout) describe the plain X in memory, if any: lets the
   // plain sweep skip reading all-zero segments
   long long sums_gen = warm ? 0 : -1;
@@ -2478,9 +2490,19 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   if (h->profile) {
     const int timed = h->prof_used;
     if (timed > 0) DROT_HIP(hipMemcpy(h->prof_reads_host, h->prof_reads, sizeof(double) * (size_t)timed, hipMemcpyDeviceToHost));
+    // What an event pair reports for an empty interval (the smallest of four) is taken off every
+    // measurement: for kernels of tens of microseconds it is a third of the reading.
+    float overhead = 1e30f;
+    for (int c = 0; c < 4; ++c) {
+      float ms = 0.f;
+      DROT_HIP(hipEventElapsedTime(&ms, h->cal_ev[2 * c], h->cal_ev[2 * c + 1]));
+      if (ms < overhead) overhead = ms;
+    }
+    h->prof_overhead_ms = (double)overhead;
     for (int e = 0; e < timed; ++e) {
       float ms = 0.f;
       DROT_HIP(hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]));
+      ms = ms > overhead ? ms - overhead : 0.f;
       ms /= (float)h->prof_iters[e];  // per iteration (a resident stretch is one launch)
       h->prof_sweep_ms += (double)ms;
       h->prof_ms[e] = ms;
