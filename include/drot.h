@@ -152,8 +152,9 @@ int drot_set_skip_unchanged(drot_handle h, int mode);
  * until the next one, a row segment whose X is zero and whose bound M + max_j (drift of varphi_j
  * since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is known to
  * stay zero: nothing of it is read, computed or written.  The iterates are those of the unscreened
- * sweeps, bit for bit.  mode 0 reads C in full every sweep; mode k >= 2 records the bounds every
- * k-th sweep instead.
+ * sweeps, bit for bit.  mode -1 screens problems of 2^24 entries and more (smaller ones stream all
+ * of C from the caches just as fast), mode 1 every problem the skipping applies to, mode k >= 2 the
+ * same with the bounds recorded at least every k-th sweep; mode 0 reads C in full every sweep.
  */
 int drot_set_screening(drot_handle h, int mode);
 

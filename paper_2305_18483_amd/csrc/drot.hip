@@ -661,25 +661,41 @@ __device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const Scr
   f4v tile_acc = {0.f, 0.f, 0.f, 0.f}, group_acc = {0.f, 0.f, 0.f, 0.f};
   int group = -1;
   float rowkeep = 0.f;
+  constexpr int kWalk = 4;  // rows fetched together: their loads overlap, the arithmetic stays in row order
   while (todo != 0) {
-    const int u = __builtin_ctzll(todo);
-    todo &= todo - 1;
-    if ((u >> 3) != group) {
-      if (group >= 0) tile_acc += group_acc;
-      group_acc = f4v{0.f, 0.f, 0.f, 0.f};
-      group = u >> 3;
+    int row[kWalk];
+    f4v c[kWalk], x[kWalk];
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      row[b] = -1;
+      c[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      x[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      if (todo != 0) {
+        row[b] = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        c[b] = ld4<EDGE, NT>(Cp + row[b] * ldc, nmem);
+        if ((nzmask >> row[b]) & 1) x[b] = ld4<EDGE, NT>(Xp + row[b] * ldx, nmem);
+      }
     }
-    const bool nz = (nzmask >> u) & 1;
-    const f4v c = ld4<EDGE, NT>(Cp + u * ldc, nmem);
-    f4v x = {0.f, 0.f, 0.f, 0.f};
-    if (nz) x = ld4<EDGE, NT>(Xp + u * ldx, nmem);
-    const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
-    const f4v v = xbar4(x, c, vp + phu, rho) * scale;
-    const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
-    if (nz || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
-    group_acc += v;
-    const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
-    rowkeep = (lane == u) ? tot : rowkeep;
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      const int u = row[b];
+      if (u >= 0) {
+        if ((u >> 3) != group) {
+          if (group >= 0) tile_acc += group_acc;
+          group_acc = f4v{0.f, 0.f, 0.f, 0.f};
+          group = u >> 3;
+        }
+        const bool nz = (nzmask >> u) & 1;
+        const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+        const f4v v = xbar4(x[b], c[b], vp + phu, rho) * scale;
+        const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+        if (nz || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+        group_acc += v;
+        const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+        rowkeep = (lane == u) ? tot : rowkeep;
+      }
+    }
   }
   if (group >= 0) tile_acc += group_acc;
   if (lane < nrows) A.rowpart[ridx] = rowkeep;
@@ -1742,8 +1758,9 @@ struct drot_handle_s {
   int profile = 0;        // record HIP events around every sweep launch
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
-  int screening = -1;       // sparse plans also skip the reads of C that a bound certifies useless: -1/1 with the
-                            // bounds refreshed every 64 sweeps, k >= 2 every k sweeps, 0 never
+  int screening = -1;       // sparse plans also skip the reads of C that a bound certifies useless: -1 for problems
+                            // of 16 M entries and more, 1 always, k >= 2 always and with the bounds renewed at
+                            // least every k sweeps (default 256), 0 never
   int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
   bool dense_plan = false;  // what the last solve's density feedback ended on
   double plan_density = -1.0;
@@ -2373,7 +2390,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
-        const bool screened = mode == 0 && tall && !first && h->screening != 0;
+        // (automatic: from 16 M entries up; below that the whole of C streams from the caches as fast)
+        const bool screened = mode == 0 && tall && !first &&
+                              (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= ((size_t)1 << 24)));
         const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= refresh_period);
         if (timed) h->prof_kind[pe] = screened ? (refresh ? 6 : 5) : (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};

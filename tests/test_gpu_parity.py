@@ -424,7 +424,7 @@ def test_screening_changes_no_bit(drot, oracle, kind, m, n):
     K = 300
     solver.set_screening(0)
     res_plain, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
-    solver.set_screening(-1)
+    solver.set_screening(1)  # (automatic mode starts at 2^24 entries)
     solver.set_profile(True)
     res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
     kinds = [kind_ for _, kind_ in solver.profile_sweeps()]
@@ -462,6 +462,7 @@ def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
     P = drot_inputs.random_problem(2300, 1500, seed=740, reg_kind=1, lam=3000.0)
     solver = drot.Solver(P.m, P.n, check_every=10)
+    solver.set_screening(1)
     solver.set_profile(True)
     _say("dense plan, adaptive scheme")
     res, X, phi, varphi = pu.gpu_solve(solver, P, 90)
