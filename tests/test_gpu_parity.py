@@ -435,6 +435,56 @@ def test_screening_changes_no_bit(drot, oracle, kind, m, n):
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="screened")
 
 
+def test_screening_across_calls_and_starts(drot, oracle):
+    # the bounds outlive a call: a continued solve goes on screening with them, and lands on the
+    # bits of one long unscreened solve; a warm start begins a new epoch; l1 weights just shift C
+    base = drot_inputs.random_problem(2110, 2600, seed=1700, d=6, reg_kind=1, lam=0.02)
+    P = drot_inputs.with_entrywise_terms(base, seed=1701, weight_scale=0.3)
+    solver = drot.Solver(P.m, P.n, check_every=20)
+    _say("screening across calls")
+    solver.set_screening(0)
+    res_plain, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, 240, tol=1e-12)
+    solver.set_screening(1)
+    X = torch.empty((P.m, P.n), device="cuda:0")
+    pu.gpu_solve(solver, P, 100, tol=1e-12, X_out=X)
+    solver.set_continue(True)
+    solver.set_profile(True)
+    res, X_two, phi_two, varphi_two = pu.gpu_solve(solver, P, 140, tol=1e-12, X_out=X)
+    kinds = [k for _, k in solver.profile_sweeps()]
+    solver.set_profile(False)
+    solver.set_continue(False)
+    assert kinds[0] != 6 and (5 in kinds or 7 in kinds)  # no new epoch at the start of the continued call
+    assert np.array_equal(X_two, X_plain) and np.array_equal(phi_two, phi_plain) and np.array_equal(varphi_two, varphi_plain)
+    ores = pu.oracle_solve(oracle, P, 240)
+    pu.assert_parity(oracle, P, res_plain, X_plain, phi_plain, varphi_plain, ores, label="screening, weights")
+    # warm start from that point, screened against unscreened
+    C, p, q, _ = pu.to_dev(P)
+    W = torch.from_numpy(P.weights).to(C.device)
+    outs = []
+    for mode in (0, 1):
+        solver.set_screening(mode)
+        Xw = torch.from_numpy(X_plain).to(C.device)
+        r = solver.solve(C, p, q, reg_kind=1, lam=P.lam, max_iters=120, X_out=Xw, weights=W,
+                         phi0=torch.from_numpy(phi_plain).to(C.device), varphi0=torch.from_numpy(varphi_plain).to(C.device))
+        outs.append(r.X.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("m,n", [(2049, 257), (2111, 300), (4000, 1000)])
+def test_screening_on_ragged_shapes(drot, m, n):
+    # last tile with 1 ... 63 rows, last column segment with 1 ... 255 columns, padded working copies
+    P = drot_inputs.random_problem(m, n, seed=1800 + m, d=4, reg_kind=0)
+    solver = drot.Solver(m, n, check_every=15)
+    _say(f"screening, ragged {m}x{n}")
+    outs = []
+    for mode in (0, 1):
+        solver.set_screening(mode)
+        _, X, phi, varphi = pu.gpu_solve(solver, P, 200, tol=1e-12)
+        outs.append((X, phi, varphi))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
 def test_lean_screened_sweep_changes_no_bit(drot, oracle):
     # wide rows: after the first status reports a sparse plan the solver moves to the one-wave-per-tile
     # screened sweep; iterates must still be those of the unscreened sweeps, bit for bit
