@@ -173,6 +173,9 @@ def main() -> int:
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
     if dominant in (4, 5, 6, 7):
+        roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the nonzero row segments of X "
+                                   "(counted on the final plan) + 8-12 B per row segment (old and new sums, bound) + column partials; "
+                                   "dense_model_* prices the same launch at 12 B per element")
         roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
         roofline["c_row_segments_read_fraction"] = round(c_read.get(dominant, 1.0), 5)
         roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]

@@ -2246,7 +2246,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   SlabArgs SL{S, h->runbuf, h->runbuf ? h->runbuf + nruns : nullptr, rho * mu};
   const dim3 slab_grid(ceil_div(n, kSlabCols), nruns > 0 ? nruns : 1);
   // the partial sums the reduction reads: per 256-column segment and 32-row tile, or, on the
-  // group-resident path, per 64-column strip and label run
+  // group-resident path, per 32-column strip and label run
   ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, slab_k ? ceil_div(n, kSlabCols) : nseg,
                 slab_k ? nruns : ntr, nbm, nbn};
   UpdateArgs UA{V, nullptr, 0, nullptr, nullptr, nullptr, nullptr, m, n, nbm, nbn, 0};
