@@ -135,17 +135,18 @@ def main() -> int:
             nz += int((X[:, j0:j0 + SEG_COLS] != 0).any(dim=1).sum().item())
         return nz / (m * ((n + SEG_COLS - 1) // SEG_COLS))
 
-    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False):
+    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False, tile_rows=64):
         # C on the fraction c_frac of its row segments; X read and written back only on the nonzero
         # segments (an upper bound: a segment is charged as a whole); the old and the new row sums per
-        # segment (and the bound M of the screening); the column sums per 64-row tile
+        # segment (and the bound M of the screening); the column sums per 64-row tile (per four of
+        # them in the lean kernel)
         nseg = (n + SEG_COLS - 1) // SEG_COLS
         return (4.0 * c_frac * m * n + 8.0 * frac * m * n + (12.0 if screened else 8.0) * m * nseg +
-                4.0 * n * ((m + 63) // 64))
+                4.0 * n * ((m + tile_rows - 1) // tile_rows))
 
     def bytes_of(kind, frac):
         if kind in (4, 5, 6, 7):
-            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4)
+            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 256 if kind == 7 else 64)
         return BYTES_PER_ELEMENT[kind] * m * n
 
     def kernel_entry(kind, ms, launches, nbytes=None):

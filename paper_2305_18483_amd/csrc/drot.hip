@@ -253,6 +253,21 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
   }
 }
 
+// Total of a tile from the totals of its NW waves, in wave order.
+template <int NW>
+__device__ __forceinline__ void write_tile_total(float wave_total, int lane, int wave, int seg, int tr,
+                                                 float* __restrict__ tilesum) {
+  __shared__ float wt[NW];
+  if (lane == 0) wt[wave] = wave_total;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) tot += wt[k];
+    tilesum[tr * gridDim.x + seg] = tot;
+  }
+}
+
 // MODE selects the paper's even/odd scheme (Section "Quadratically Regularized DROT"): 0 = plain
 // (read X and C, store X); 1 = read X and C, store X - rho*C; 2 = read the shifted X only (no C)
 // and store the plain X.  A 1-sweep followed by a 2-sweep moves 20 bytes per element instead of 24.
@@ -447,17 +462,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
     if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
   }
   write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
-  if (A.tilesum) {  // total of the tile, for the fused update of the next sweep
-    __shared__ float wt[NW];
-    if (lane == 0) wt[wave] = wave_total;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      float tot = 0.f;
-#pragma unroll
-      for (int k = 0; k < NW; ++k) tot += wt[k];
-      A.tilesum[tr * gridDim.x + seg] = tot;
-    }
-  }
+  // total of the tile, for the vector update that forms eta from these
+  if (A.tilesum) write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
 }
 
 // NW waves of U rows each: 16 x 2 (32-row tiles) everywhere except the plain sweep of large problems,
@@ -569,7 +575,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   }
 
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
-  float rowkeep = 0.f, mkeep = 0.f;
+  float rowkeep = 0.f, mkeep = 0.f, wave_total = 0.f;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (!((skipmask >> u) & 1)) {
@@ -580,6 +586,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
       colacc += v;
       const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
       rowkeep = (lane == u) ? tot : rowkeep;
+      wave_total += tot;
       if (REFRESH) {
         const float mx = fmaxf(fmaxf(fmaf(-rho, c[u].x, vp.x), fmaf(-rho, c[u].y, vp.y)),
                                fmaxf(fmaf(-rho, c[u].z, vp.z), fmaf(-rho, c[u].w, vp.w)));
@@ -595,6 +602,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   if (SC.wave_reads && lane == 0)
     SC.wave_reads[(tr * gridDim.x + seg) * NW + wave] = __builtin_popcount(~skipmask & 0xffu);
   write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
 }
 
 // Profiling: total of the per-wave read counts of one screened sweep.
@@ -623,7 +631,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
 // rows of every group of 8 are added up in order and the 8 groups in order, which is what that
 // tile's waves and its LDS fold do (rows and groups that contribute nothing add +0).
 template <bool EDGE, bool NT>
-__device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr) {
+__device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
+                                                  int stop, float& tile_total) {
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
@@ -654,11 +663,14 @@ __device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const Scr
   const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
   const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
   const bool certified = lane >= nrows || (fbits(prev) == 0 && below);
+  tile_total = 0.f;
+  if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
   unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
   const unsigned long long nzmask = __builtin_amdgcn_ballot_w64(fbits(prev) != 0);
   if (SC.wave_reads && lane == 0) SC.wave_reads[tr * gridDim.x + seg] = __builtin_popcountll(todo);
 
   f4v tile_acc = {0.f, 0.f, 0.f, 0.f}, group_acc = {0.f, 0.f, 0.f, 0.f};
+  float tile_tot = 0.f, group_tot = 0.f;  // the total of the tile, added up in the same order
   int group = -1;
   float rowkeep = 0.f;
   constexpr int kWalk = 4;  // rows fetched together: their loads overlap, the arithmetic stays in row order
@@ -682,8 +694,12 @@ __device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const Scr
       const int u = row[b];
       if (u >= 0) {
         if ((u >> 3) != group) {
-          if (group >= 0) tile_acc += group_acc;
+          if (group >= 0) {
+            tile_acc += group_acc;
+            tile_tot += group_tot;
+          }
           group_acc = f4v{0.f, 0.f, 0.f, 0.f};
+          group_tot = 0.f;
           group = u >> 3;
         }
         const bool nz = (nzmask >> u) & 1;
@@ -694,31 +710,48 @@ __device__ __forceinline__ void screened_lean_body(const SweepArgs& A, const Scr
         group_acc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
+        group_tot += tot;
       }
     }
   }
-  if (group >= 0) tile_acc += group_acc;
-  if (lane < nrows) A.rowpart[ridx] = rowkeep;
-  float* __restrict__ cp = A.colpart + (size_t)tr * A.n + j0;
-  if (nvalid == 4) *reinterpret_cast<f4u*>(cp) = tile_acc;
-  else {
-    if (nvalid > 0) cp[0] = tile_acc.x;
-    if (nvalid > 1) cp[1] = tile_acc.y;
-    if (nvalid > 2) cp[2] = tile_acc.z;
+  if (group >= 0) {
+    tile_acc += group_acc;
+    tile_tot += group_tot;
   }
+  if (lane < nrows) A.rowpart[ridx] = rowkeep;
+  tile_total = tile_tot;
+  return tile_acc;  // column sums of the tile (columns past n: 0)
 }
 
-constexpr int kLeanWaves = 4;  // independent waves per workgroup
+// Four waves per workgroup, stacked along the rows: they work independently and meet once, at the
+// end, to add their tiles' column sums in the order tile 0, 1, 2, 3 (kColGroup in the reduction:
+// the sweeps that store one row of column sums per 64-row tile are added up in that order too).
+constexpr int kLeanWaves = 4;
+constexpr int kColGroup = kLeanWaves;
+static_assert(64 * kLeanWaves == kSegCols, "one thread per column of the segment in the final fold");
 
 template <bool NT>
 __global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
-  if (*A.done) return;
+  // (the stop flag is fetched along with a wave's first loads and tested before its first store)
+  const int stop = *A.done;
+  __shared__ float fold[kLeanWaves][kSegCols];
+  __shared__ float totals[kLeanWaves];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
-  if (tr >= ntiles_rows) return;
-  if ((seg + 1) * kSegCols <= A.n) screened_lean_body<false, NT>(A, SC, lane, seg, tr);
-  else screened_lean_body<true, false>(A, SC, lane, seg, tr);
+  f4v acc = {0.f, 0.f, 0.f, 0.f};
+  float total = 0.f;
+  if (tr < ntiles_rows) {
+    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, total);
+    else acc = screened_lean_body<true, false>(A, SC, lane, seg, tr, stop, total);
+  }
+  if (stop) return;
+  *reinterpret_cast<f4v*>(&fold[wave][lane * 4]) = acc;
+  if (lane == 0) totals[wave] = total;
+  __syncthreads();
+  const int t = threadIdx.x, j = seg * kSegCols + t;
+  if (j < A.n) A.colpart[(size_t)blockIdx.y * A.n + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
+  if (t == 0) A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1258,70 +1291,119 @@ struct ReduceArgs {
   const float* p;
   const float* q;
   int m, n, nseg, ntr, nbm, nbn;
+  int cgroup;  // 1, or kColGroup: consecutive rows of colpart are first added up in fp32, in groups of that many
 };
 
 constexpr int kReduceThreads = 1024;
 
-__device__ __forceinline__ void reduce_body(const ReduceArgs& A, double* red, int* nzw) {
+// First part: the partial sums of 64 entries split 16 ways (share c takes the partials c, c + 16,
+// ...), each share added up in order.  NW waves: wave w forms the shares w, w + NW, ... of entry
+// idx and leaves them in red[share][lane]; nz_out counts the nonzero partials this wave saw.
+template <int NW>
+__device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, int& nz_out) {
+  static_assert(16 % NW == 0, "the 16 shares are dealt out to the waves");
   const int t = threadIdx.x;
   const int sub = t >> 6, l = t & 63;
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
   const int len = rows ? A.m : A.n;
-  const int nparts = rows ? A.nseg : A.ntr;
+  const bool grouped = !rows && A.cgroup == kColGroup;
+  const int nparts = rows ? A.nseg : grouped ? (A.ntr + kColGroup - 1) / kColGroup : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
-  double acc = 0.0;
-  int nz = 0;  // partial sums of this wave that are not zero (wave-uniform)
-  constexpr int kStride = kReduceThreads / 64, kBatch = 8;
-  for (int k0 = sub; k0 < nparts; k0 += kStride * kBatch) {  // (nparts and sub are wave-uniform)
-    // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
-    // trip would wait for memory once per partial sum)
-    float v[kBatch];
+  int nz = 0;
+  constexpr int kStride = 16, kBatch = 8;
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b) {
-      const int k = k0 + b * kStride;
-      v[b] = (idx < len && k < nparts) ? part[(size_t)k * len + idx] : 0.f;
-    }
+  for (int share = sub; share < 16; share += NW) {
+    double acc = 0.0;
+    if (grouped) {
+      // column sums stored per 64-row tile: tiles 4k .. 4k+3 are added first, in fp32 and in order, as
+      // the workgroups of the lean sweep do before they store (a tile past the end adds +0)
+      constexpr int kGroups = kBatch / 2;
+      for (int k0 = share; k0 < nparts; k0 += kStride * kGroups) {
+        float v[kGroups][kColGroup];
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b) {
-      if (k0 + b * kStride < nparts) acc += (double)v[b];
-      nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f));
+        for (int b = 0; b < kGroups; ++b)
+#pragma unroll
+          for (int g = 0; g < kColGroup; ++g) {
+            const int k = (k0 + b * kStride) * kColGroup + g;
+            v[b][g] = (idx < len && k < A.ntr) ? part[(size_t)k * len + idx] : 0.f;
+          }
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b)
+          if (k0 + b * kStride < nparts) acc += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
+      }
     }
+    for (int k0 = share; !grouped && k0 < nparts; k0 += kStride * kBatch) {  // (nparts and share are wave-uniform)
+      // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
+      // trip would wait for memory once per partial sum)
+      float v[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int k = k0 + b * kStride;
+        v[b] = (idx < len && k < nparts) ? part[(size_t)k * len + idx] : 0.f;
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        if (k0 + b * kStride < nparts) acc += (double)v[b];
+        nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f));
+      }
+    }
+    red[share * 64 + l] = acc;
   }
-  red[t] = acc;
-  if (l == 0) nzw[sub] = nz;
-  __syncthreads();
-  for (int h = kReduceThreads / 2; h >= 64; h >>= 1) {  // fold the 16 waves' partials, lane by lane
-    if (t < h) red[t] += red[t + h];
-    __syncthreads();
-  }
+  nz_out = nz;
+}
+
+// Second part, after the one barrier that follows the first: wave 0 adds the 16 shares of its 64
+// entries (a fixed tree, the one sum_partials_16 ends with), forms the residuals and leaves the
+// workgroup's sum, sum of squares and count.  Returns the residual of entry idx in threads
+// 0 .. 63 (0 elsewhere).  pq: p_idx or q_idx, fetched by the caller along with the partial sums
+// (reduce_entry_pq) so that no second trip to memory follows the barrier.
+__device__ __forceinline__ float reduce_entry_pq(const ReduceArgs& A) {
+  const int t = threadIdx.x;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  return (t < 64 && idx < (rows ? A.m : A.n)) ? (rows ? A.p[idx] : A.q[idx]) : 0.f;
+}
+
+template <int NW>
+__device__ __forceinline__ double reduce_finish(const ReduceArgs& A, const double* red, const int* nzw, float pq) {
+  const int t = threadIdx.x;
+  if (t >= 64) return 0.0;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  const int len = rows ? A.m : A.n;
+  double w[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) w[k] = red[k * 64 + t];
+  const double total = (((w[0] + w[8]) + (w[4] + w[12])) + ((w[2] + w[10]) + (w[6] + w[14]))) +
+                       (((w[1] + w[9]) + (w[5] + w[13])) + ((w[3] + w[11]) + (w[7] + w[15])));
   double res = 0.0;
-  if (t < 64 && idx < len) {
-    res = red[t] - (double)(rows ? A.p[idx] : A.q[idx]);
+  if (idx < len) {
+    res = total - (double)pq;
     (rows ? A.V.r : A.V.s)[idx] = res;
   }
-  __syncthreads();
-  // sum and sum of squares over the 64 residuals of this workgroup
-  if (t < 64) { red[t] = res; red[64 + t] = res * res; }
-  __syncthreads();
-  for (int h = 32; h > 0; h >>= 1) {
-    if (t < h) { red[t] += red[t + h]; red[64 + t] += red[64 + t + h]; }
-    __syncthreads();
-  }
+  const double sum = wave_sum_f64(res), sumsq = wave_sum_f64(res * res);
   if (t == 0) {
-    A.V.part[blockIdx.x] = red[0];
-    A.V.part[A.nbm + A.nbn + blockIdx.x] = red[64];
+    A.V.part[blockIdx.x] = sum;
+    A.V.part[A.nbm + A.nbn + blockIdx.x] = sumsq;
     int cnt = 0;
-    for (int w = 0; w < kReduceThreads / 64; ++w) cnt += nzw[w];
+    for (int k = 0; k < NW; ++k) cnt += nzw[k];
     A.V.part[2 * (A.nbm + A.nbn) + blockIdx.x] = (double)cnt;
   }
+  return res;
 }
 
 __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
   if (*A.V.done) return;
-  __shared__ double red[kReduceThreads];
-  __shared__ int nzw[kReduceThreads / 64];
-  reduce_body(A, red, nzw);
+  constexpr int NW = kReduceThreads / 64;
+  __shared__ double red[16 * 64];
+  __shared__ int nzw[NW];
+  int nz;
+  const float pq = reduce_entry_pq(A);
+  reduce_gather<NW>(A, red, nz);
+  if ((threadIdx.x & 63) == 0) nzw[threadIdx.x >> 6] = nz;
+  __syncthreads();
+  reduce_finish<NW>(A, red, nzw, pq);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1340,6 +1422,26 @@ struct UpdateArgs {
   double* b_out;
   int m, n, nbm, nbn, par;
 };
+
+// ||r||^2, ||s||^2 and the number of nonzero row-segment sums from the per-workgroup sums of the reduction.
+__device__ __forceinline__ void sum_residual_norms(const VecState& V, int nbm, int nbn, double* red) {
+  const int t = threadIdx.x;
+  double r2 = 0.0, s2 = 0.0;
+  const double* sq = V.part + nbm + nbn;
+  for (int e = t; e < nbm; e += kReduceThreads) r2 += sq[e];
+  for (int e = t; e < nbn; e += kReduceThreads) s2 += sq[nbm + e];
+  double nzs = 0.0;
+  const double* cnt = V.part + 2 * (nbm + nbn);
+  for (int e = t; e < nbm; e += kReduceThreads) nzs += cnt[e];
+  r2 = block_sum_f64(r2, red);
+  s2 = block_sum_f64(s2, red);
+  nzs = block_sum_f64(nzs, red);
+  if (t == 0) {
+    V.resid[0] = r2;
+    V.resid[1] = s2;
+    V.resid[2] = nzs;
+  }
+}
 
 // The update for all m + n entries by one workgroup (all = true: it strides over them) or for the
 // 1024 entries of workgroup `vb` (all = false); the arithmetic per entry is the same either way.
@@ -1372,30 +1474,122 @@ __device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, bool al
       A.b_out[j] = bj - sj;
     }
   }
-  if (all || vb == 0) {
-    double r2 = 0.0, s2 = 0.0;
-    const double* sq = A.V.part + A.nbm + A.nbn;
-    for (int e = t; e < A.nbm; e += kReduceThreads) r2 += sq[e];
-    for (int e = t; e < A.nbn; e += kReduceThreads) s2 += sq[A.nbm + e];
-    double nzs = 0.0;
-    const double* cnt = A.V.part + 2 * (A.nbm + A.nbn);
-    for (int e = t; e < A.nbm; e += kReduceThreads) nzs += cnt[e];
-    r2 = block_sum_f64(r2, red);
-    s2 = block_sum_f64(s2, red);
-    nzs = block_sum_f64(nzs, red);
-    if (t == 0) {
-      A.V.theta[A.par ^ 1] = theta - eta;
-      A.V.resid[0] = r2;
-      A.V.resid[1] = s2;
-      A.V.resid[2] = nzs;
-    }
-  }
+  if ((all || vb == 0) && t == 0) A.V.theta[A.par ^ 1] = theta - eta;
 }
 
 __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
   if (*A.V.done) return;
   __shared__ double red[kReduceThreads];
   update_body(A, (int)blockIdx.x, false, red);
+}
+
+// What the stopping test and the host's choice of scheme read, after a reduce_update_kernel (which
+// leaves the per-workgroup sums only).  One workgroup; launched before a status_kernel.
+__global__ __launch_bounds__(kReduceThreads) void residual_norms_kernel(VecState V, int nbm, int nbn) {
+  if (*V.done) return;
+  __shared__ double red[kReduceThreads];
+  sum_residual_norms(V, nbm, nbn, red);
+}
+
+// Both halves of S5 in one launch, for the sweeps on 64-row tiles of large problems.  What stands
+// between the two halves is one number, eta = (1^T X 1 - 1^T p)/(m+n); with the totals of the tiles
+// at hand (the sweep stores them) every workgroup forms it by itself, then reduces its 64 rows or
+// columns and updates them on the spot.  Tile totals: rows in groups of 8 in order, the 8 groups
+// in order (fp32), then four tiles stacked along the rows in order (in the lean sweep's workgroups,
+// or here: tgroup), then all of it in fp64 in a fixed order.
+struct TileTotals {
+  const float* tilesum;  // [tile_rows][nseg], or one entry per kColGroup tile rows (tgroup = 1)
+  int tile_rows;         // rows of tilesum
+  int nseg;
+  int tgroup;            // kColGroup: add tile rows 4k .. 4k+3 first; 1: stored that way
+};
+
+// (8 waves: every workgroup of a 40000-entry problem is resident at once.  The tile totals are dealt
+// out to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...)
+constexpr int kMergedWaves = 8;
+
+__global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T) {
+  // (the stop flag travels with the other loads and is tested before the first store: a test up
+  // front would put one more trip to memory ahead of everything)
+  const int stop = *A.V.done;
+  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW);
+  __shared__ double red[16 * 64];
+  __shared__ double eta_part[kShares / 64];
+  __shared__ int nzw[NW];
+  const int t = threadIdx.x;
+  // eq. (6) inputs of this thread's entry, fetched early
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  const bool owner = t < 64 && idx < (rows ? A.m : A.n);
+  const double ab_in = owner ? (rows ? U.a_in[idx] : U.b_in[idx]) : 0.0;
+  const double theta = A.V.theta[U.par], sum_p = *A.V.sum_p;
+  const float pq = reduce_entry_pq(A);
+  // the shares of the tile totals: batches of independent loads, added in index order
+  double acc[kPerThread];
+#pragma unroll
+  for (int s = 0; s < kPerThread; ++s) {
+    acc[s] = 0.0;
+    const int v0 = t + s * 64 * NW;
+    if (T.tgroup == kColGroup) {
+      constexpr int kGroups = 4;
+      const int ngroups = ((T.tile_rows + kColGroup - 1) / kColGroup) * T.nseg;
+      for (int e0 = v0; e0 < ngroups; e0 += kShares * kGroups) {
+        float v[kGroups][kColGroup];
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b) {
+          const int e = e0 + b * kShares;
+          const int k = e / T.nseg, sg = e - k * T.nseg;
+#pragma unroll
+          for (int g = 0; g < kColGroup; ++g) {
+            const int tr = k * kColGroup + g;
+            v[b][g] = (e < ngroups && tr < T.tile_rows) ? T.tilesum[tr * T.nseg + sg] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b) acc[s] += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
+      }
+    } else {
+      constexpr int kBatch = 8;
+      const int ngroups = T.tile_rows * T.nseg;
+      for (int e0 = v0; e0 < ngroups; e0 += kShares * kBatch) {
+        float v[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+          const int e = e0 + b * kShares;
+          v[b] = e < ngroups ? T.tilesum[e] : 0.f;
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) acc[s] += (double)v[b];
+      }
+    }
+  }
+  int nz;
+  reduce_gather<NW>(A, red, nz);
+#pragma unroll
+  for (int s = 0; s < kPerThread; ++s) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[s] += __shfl_xor(acc[s], off, 64);
+    if ((t & 63) == 0) eta_part[(t >> 6) + s * NW] = acc[s];
+  }
+  if ((t & 63) == 0) nzw[t >> 6] = nz;
+  __syncthreads();
+  if (stop) return;
+  const double res = reduce_finish<NW>(A, red, nzw, pq);
+  if (t >= 64) return;
+  double total = 0.0;
+  for (int k = 0; k < kShares / 64; ++k) total += eta_part[k];
+  const double eta = (total - sum_p) / ((double)A.m + (double)A.n);
+  const double cst = 2.0 * eta - theta;
+  if (owner) {
+    if (rows) {
+      A.V.phi[idx] = (float)((ab_in - 2.0 * res + cst) / (double)A.n);
+      U.a_out[idx] = ab_in - res;
+    } else {
+      A.V.varphi[idx] = (float)((ab_in - 2.0 * res + cst) / (double)A.m);
+      U.b_out[idx] = ab_in - res;
+    }
+  }
+  if (blockIdx.x == 0 && t == 0) A.V.theta[U.par ^ 1] = theta - eta;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2248,7 +2442,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // the partial sums the reduction reads: per 256-column segment and 32-row tile, or, on the
   // group-resident path, per 32-column strip and label run
   ReduceArgs RA{V, h->rowpart, h->colpart, p, q, m, n, slab_k ? ceil_div(n, kSlabCols) : nseg,
-                slab_k ? nruns : ntr, nbm, nbn};
+                slab_k ? nruns : ntr, nbm, nbn, 1};
   UpdateArgs UA{V, nullptr, 0, nullptr, nullptr, nullptr, nullptr, m, n, nbm, nbn, 0};
   // Small problems: the vector update of iteration s-1 is computed at the head of sweep s by every
   // workgroup for its own rows and columns (one launch per iteration instead of three); the
@@ -2302,6 +2496,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   int k = 0, slot = 0, checks = 0;
   bool converged = false;
   bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
+  bool norms_pending = false;  // the last vector update left the residual norms as per-workgroup sums
   h->prof_used = 0;
   if (h->profile)  // empty event pairs: the time a pair reports with nothing between its two records
     for (auto& e : h->cal_ev) DROT_HIP(hipEventRecord(e, stream));
@@ -2353,6 +2548,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
       S.tilesum = small ? tsum(sw) : nullptr;
+      bool tiles64 = false, lean = false;
       if (from_points) {
         if (first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, S, PT);
         else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
@@ -2396,8 +2592,13 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= refresh_period);
         if (timed) h->prof_kind[pe] = screened ? (refresh ? 6 : 5) : (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};
+        // the sweeps on 64-row tiles also store the totals of their tiles: one launch then does both
+        // halves of the vector update
+        tiles64 = tall && !first && mode == 0;
+        if (tiles64) S.tilesum = tsum(sw);
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
         sums_gen = mode == 1 ? -1 : sw;
+        lean = false;
         if (screened) {
           const dim3 sgrid(nseg, ceil_div(m, kScreenRows * kScreenWaves)), sblock(64 * kScreenWaves);
           if (refresh) {
@@ -2407,7 +2608,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           }
           const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr};
           // once the plan is known to be sparse: one wave per tile, walking through the few rows left
-          const bool lean = !refresh && S.rowpart_prev != nullptr && plan_density >= 0.0 && plan_density < 0.25;
+          lean = !refresh && S.rowpart_prev != nullptr && plan_density >= 0.0 && plan_density < 0.25;
           if (lean) {
             const int ntr64 = ceil_div(m, 64);
             const dim3 lgrid(nseg, ceil_div(ntr64, kLeanWaves)), lblock(64 * kLeanWaves);
@@ -2435,8 +2636,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           else if (tall) hipLaunchKernelGGL((sweep_kernel<false, false, false, 0, kTallRows, kTallWaves>), dim3(nseg, ntr_tall), dim3(64 * kTallWaves), 0, stream, S, none);
           else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, S, none);
         }
-        // (the tall tiles leave fewer rows of column partials for the reduction)
-        if (!slab_k) RA.ntr = (tall && !first && mode == 0) ? ntr_tall : ntr;
+        // (the 64-row tiles leave fewer rows of column partials for the reduction, which adds them up in
+        // groups of four; the lean sweep stores one row per group)
+        if (!slab_k) {
+          RA.ntr = lean ? ceil_div(ntr_tall, kColGroup) : tiles64 ? ntr_tall : ntr;
+          RA.cgroup = (tiles64 && !lean) ? kColGroup : 1;
+        }
       }
       if (timed) {
         DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
@@ -2455,8 +2660,14 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         UA.par = (int)((sw - 1) & 1);
         UA.tilesum = small ? tsum(sw) : nullptr;
         UA.ntiles = small_slab ? nstrips * nruns : ntiles;
-        hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
-        hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
+        if (tiles64) {
+          const TileTotals TT{tsum(sw), lean ? ceil_div(ntr_tall, kColGroup) : ntr_tall, nseg, lean ? 1 : kColGroup};
+          hipLaunchKernelGGL(reduce_update_kernel, dim3(nbm + nbn), dim3(64 * kMergedWaves), 0, stream, RA, UA, TT);
+        } else {
+          hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
+          hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
+        }
+        norms_pending = true;
         materialized = true;
       } else {
         materialized = false;
@@ -2464,6 +2675,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     }
     if (checking || adaptive) {
       // the test runs on the device; the host reads it one chunk late so the queue never drains
+      if (norms_pending) hipLaunchKernelGGL(residual_norms_kernel, dim3(1), dim3(kReduceThreads), 0, stream, V, nbm, nbn);
+      norms_pending = false;
       hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, checking ? (double)tol : 0.0);
       DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
       DROT_HIP(hipEventRecord(h->ev[slot], stream));
@@ -2482,8 +2695,10 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     }
   }
   // final state: residuals of the returned iterate (no-op if the stop flag is already up)
-  if (k > 0)
+  if (k > 0) {
+    if (norms_pending) hipLaunchKernelGGL(residual_norms_kernel, dim3(1), dim3(kReduceThreads), 0, stream, V, nbm, nbn);
     hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, checking ? (double)tol : 0.0);
+  }
   if (h->compute_gap) {
     float* gx = h->gbuf;
     float* gw = h->gbuf ? h->gbuf + ngroups : nullptr;
