@@ -2496,6 +2496,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   int k = 0, slot = 0, checks = 0;
   bool converged = false;
   bool materialized = true;  // phi, varphi, a, b, theta in memory are complete for the sweeps done so far
+  bool was_probe[2] = {false, false};
   bool norms_pending = false;  // the last vector update left the residual norms as per-workgroup sums
   h->prof_used = 0;
   if (h->profile)  // empty event pairs: the time a pair reports with nothing between its two records
@@ -2511,8 +2512,22 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   int refresh_period = resume ? h->refresh_period : 8;
   if (refresh_period > refresh_max) refresh_period = refresh_max;
   while (k < max_iters && !converged) {
-    const int chunk = (checking || adaptive) ? (h->check_every < max_iters - k ? h->check_every : max_iters - k)
-                                             : max_iters - k;
+    int chunk = max_iters - k;
+    bool probe = false;  // this stretch ends with a status for the host's choice of sweep only (no stopping test)
+    if (checking || adaptive) {
+      const int to_check = h->check_every - k % h->check_every;  // the tests stay at multiples of check_every
+      if (to_check < chunk) chunk = to_check;
+      if (adaptive && !(plan_density >= 0.0 && plan_density < 0.25)) {
+        // how sparse the plan is decides the sweep: until it is known to be sparse, have a look after
+        // 16, 32 and 64 iterations too (a plan is dense in its first iterations, whatever it becomes:
+        // these early readings can move the solver to the lean sweep, never to the even/odd pairs)
+        const int next = k < 16 ? 16 : k < 32 ? 32 : k < 64 ? 64 : 0;
+        if (next > 0 && next - k < chunk) {
+          chunk = next - k;
+          probe = true;
+        }
+      }
+    }
     const bool skip_cost = can_pair && (h->skip_cost == 1 || (adaptive && dense_plan));
     const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
     if (resident) {
@@ -2677,16 +2692,17 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       // the test runs on the device; the host reads it one chunk late so the queue never drains
       if (norms_pending) hipLaunchKernelGGL(residual_norms_kernel, dim3(1), dim3(kReduceThreads), 0, stream, V, nbm, nbn);
       norms_pending = false;
-      hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, checking ? (double)tol : 0.0);
+      hipLaunchKernelGGL(status_kernel, dim3(1), dim3(1), 0, stream, V, k, (checking && !probe) ? (double)tol : 0.0);
       DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
       DROT_HIP(hipEventRecord(h->ev[slot], stream));
+      was_probe[slot] = probe;
       if (checks > 0) {
         DROT_HIP(hipEventSynchronize(h->ev[slot ^ 1]));
         if (h->host_status[slot ^ 1].converged) converged = true;
         if (adaptive) {  // (hysteresis: the break-even is at about three quarters of the segments nonzero)
           const double density = h->host_status[slot ^ 1].nz_segments / ((double)m * (double)nseg);
           plan_density = density;
-          if (density > 0.7) dense_plan = true;
+          if (density > 0.7 && !was_probe[slot ^ 1]) dense_plan = true;
           else if (density < 0.5) dense_plan = false;
         }
       }

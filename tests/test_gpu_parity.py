@@ -507,6 +507,25 @@ def test_lean_screened_sweep_changes_no_bit(drot, oracle):
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="lean screened")
 
 
+def test_early_looks_at_the_density_start_the_lean_sweep_before_the_first_check(drot):
+    # residual checks 1000 iterations apart: the host would learn how sparse the plan is after 2000
+    # iterations; the extra status readings after 16, 32 and 64 iterations (no stopping test in them)
+    # let it move to the lean sweep within the first 100 or so, and no bit of the result changes
+    P = drot_inputs.random_problem(2100, 8192 + 40, seed=1600, d=8, reg_kind=1, lam=0.01)
+    solver = drot.Solver(P.m, P.n, check_every=1000)
+    _say("early density readings")
+    K = 300
+    solver.set_screening(0)
+    _, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
+    solver.set_screening(1)
+    solver.set_profile(True)
+    res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
+    kinds = [k for _, k in solver.profile_sweeps()]
+    solver.set_profile(False)
+    assert res.iters == K and 7 in kinds[:200], kinds
+    assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
+
+
 def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     # a strong quadratic term keeps the plan dense: the density the reduction reports must move the
     # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
