@@ -1959,6 +1959,7 @@ struct drot_handle_s {
   bool dense_plan = false;  // what the last solve's density feedback ended on
   double plan_density = -1.0;
   long long epoch_gen = -1;  // screening: sweep that recorded the bounds in mprime (continued solves)
+  bool sums_valid = false;   // rowpart of the last generation describes the X the solve returned
   int refresh_period = 8;
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
@@ -2503,7 +2504,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     for (auto& e : h->cal_ev) DROT_HIP(hipEventRecord(e, stream));
   // generation whose row-segment sums (tile layout) describe the plain X in memory, if any: lets the
   // plain sweep skip reading all-zero segments
-  long long sums_gen = warm ? 0 : -1;
+  // (a continued solve starts from the X the last one returned, so its row-segment sums still hold)
+  long long sums_gen = warm ? 0 : (resume && h->sums_valid) ? k_base : -1;
+  h->sums_valid = false;  // (until this solve has returned)
   // screened sweeps: the sweep that last recorded the bounds M (with its varphi as varphi0), if any
   // (varphi moves fast at first: the bounds are renewed after 8 sweeps, then 16, 32, ... up to the
   // period; a continued solve carries on with the bounds and the schedule of the last one)
@@ -2772,6 +2775,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->plan_density = plan_density;
   h->epoch_gen = epoch_gen;
   h->refresh_period = refresh_period;
+  // (after an early stop the sweeps launched past it did nothing: be conservative)
+  h->sums_valid = !st.converged && max_iters > 0 && sums_gen == k_base + k;
   h->solved = true;
   h->last_m = m;
   h->last_n = n;
