@@ -135,18 +135,33 @@ def main() -> int:
             nz += int((X[:, j0:j0 + SEG_COLS] != 0).any(dim=1).sum().item())
         return nz / (m * ((n + SEG_COLS - 1) // SEG_COLS))
 
-    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False, tile_rows=64):
-        # C on the fraction c_frac of its row segments; X read and written back only on the nonzero
-        # segments (an upper bound: a segment is charged as a whole); the old and the new row sums per
-        # segment (and the bound M of the screening); the column sums per 64-row tile (per four of
-        # them in the lean kernel)
+    def nonzero_line_fraction():
+        """Fraction of the 128-byte lines (32 columns of one row, counted from the segment's start) of X that hold a nonzero."""
+        nz = total = 0
+        for j0 in range(0, n, 32):
+            nz += int((X[:, j0:j0 + 32] != 0).any(dim=1).sum().item())
+            total += m
+        return nz / total
+
+    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False, tile_rows=64, per_segment=8.0):
+        # C on the fraction c_frac of its row segments; X read and written back only on the fraction
+        # frac of its entries that lie in nonzero row segments (lean kernel: in nonzero 128-byte
+        # lines) -- an upper bound, a piece is charged as a whole; per row segment the old and the
+        # new row sum (+ the bound M of the screening, + two bytes of line flags in the lean kernel);
+        # the column sums per 64-row tile (per four of them in the lean kernel)
         nseg = (n + SEG_COLS - 1) // SEG_COLS
-        return (4.0 * c_frac * m * n + 8.0 * frac * m * n + (12.0 if screened else 8.0) * m * nseg +
+        return (4.0 * c_frac * m * n + 8.0 * frac * m * n + per_segment * m * nseg +
                 4.0 * n * ((m + tile_rows - 1) // tile_rows))
 
+    line_frac = {}
+
     def bytes_of(kind, frac):
-        if kind in (4, 5, 6, 7):
-            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 256 if kind == 7 else 64)
+        if kind == 7:
+            if "v" not in line_frac:
+                line_frac["v"] = nonzero_line_fraction()
+            return sparse_sweep_bytes(line_frac["v"], c_read.get(kind, 1.0), True, 256, 14.0)
+        if kind in (4, 5, 6):
+            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 64, 12.0 if kind != 4 else 8.0)
         return BYTES_PER_ELEMENT[kind] * m * n
 
     def kernel_entry(kind, ms, launches, nbytes=None):
@@ -174,15 +189,18 @@ def main() -> int:
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
     if dominant in (4, 5, 6, 7):
-        roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the nonzero row segments of X "
-                                   "(counted on the final plan) + 8-12 B per row segment (old and new sums, bound) + column partials; "
-                                   "dense_model_* prices the same launch at 12 B per element")
+        roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the entries of X in nonzero row segments "
+                                   "(lean kernel: in nonzero 128-byte lines; counted on the final plan) + 8-14 B per row segment (old and new "
+                                   "sums, bound, line flags) + column sums; dense_model_* prices the same launch at 12 B per element")
         roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
+        if "v" in line_frac:
+            roofline["nonzero_line_fraction"] = round(line_frac["v"], 6)
         roofline["c_row_segments_read_fraction"] = round(c_read.get(dominant, 1.0), 5)
         roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]
         roofline["dense_model_bytes"] = 12.0 * m * n
         roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
-        log(f"nonzero row segments of X: {frac_nz:.3%}; row segments of C read: {c_read.get(dominant, 1.0):.3%}; "
+        log(f"nonzero row segments of X: {frac_nz:.3%}" + (f" (128-byte lines: {line_frac['v']:.4%})" if "v" in line_frac else "") +
+            f"; row segments of C read: {c_read.get(dominant, 1.0):.3%}; "
             f"the same sweep priced at 12 B/element would read {roofline['dense_model_gbs']:.0f} GB/s")
         for e in roofline["other_kernels"]:
             log(f"  also [{e['kernel']}]: {e['kernel_ms']:.4f} ms over {e['launches_timed']} launches -> {e['achieved']:.0f} GB/s ({e['frac']:.1%})")

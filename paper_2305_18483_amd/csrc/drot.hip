@@ -503,8 +503,27 @@ struct ScreenArgs {
   const float* mprime_in;   // [nseg][m] M_is of the current epoch (screening sweeps)
   float* mprime_out;        // [nseg][m] written by a refresh sweep
   const float* varphi0;     // [n] varphi of the epoch
-  int* wave_reads;          // profiling only (else null): [workgroup][wave] row segments of C this wave read
+  int* wave_reads;          // 8-wave tiles, profiling only (else null): [workgroup][wave] row segments of C this wave read
+  // lean sweep only: it renews the bounds by itself when the vector update before it has raised ctl[0]
+  float* varphi0_out;       // [n]
+  const int* ctl;           // kCtl... words, see ScreenCtl
+  int* wg_reads;            // [workgroup] row segments of C the workgroup read (always written)
+  // lean sweep only: which of the eight 128-byte lines of a row segment of X hold a nonzero
+  const unsigned char* lines_in;  // [nseg][m] as left by the previous sweep if that was a lean one, else null
+  unsigned char* lines_out;       // [nseg][m]
 };
+
+// Control words of the lean sweep's own refresh schedule (device memory, updated by
+// reduce_update_kernel after every lean sweep): the classic rent-or-buy rule.  Reading the C of a
+// row segment the bounds fail to certify is the rent, renewing the bounds (all of C once) the
+// purchase: renew when the rent paid since the last renewal, counted from the level right after
+// it, has reached the price.  That stays within a factor 2 of the best schedule in hindsight,
+// whatever the drift of varphi does, and needs no model of it.
+constexpr int kCtlRenew = 0;   // the next lean sweep renews the bounds
+constexpr int kCtlSince = 1;   // lean sweeps since the last renewal
+constexpr int kCtlFloor = 2;   // row segments of C read by the first sweep after it (-1: not known yet)
+constexpr int kCtlPaid = 3;    // reads above that floor accumulated since
+constexpr int kCtlWords = 4;
 
 constexpr int kScreenRows = 8, kScreenWaves = 8;
 
@@ -632,7 +651,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
 // tile's waves and its LDS fold do (rows and groups that contribute nothing add +0).
 template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
-                                                  int stop, float& tile_total) {
+                                                  int stop, bool renew, float& tile_total, int& reads) {
   const int j0 = seg * kSegCols + lane * 4;
   const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
@@ -647,11 +666,16 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
   const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
   float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  unsigned oldlines = 0;  // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31)
   if (lane < nrows) {
     prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
     ph = A.phi[r0 + lane];
     mpr = SC.mprime_in[ridx];
+    oldlines = SC.lines_in ? SC.lines_in[ridx] : 0xffu;
   }
+  if (fbits(prev) == 0) oldlines = 0;
+  // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
+  // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
   float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
   float a = 0.f;
   if (nvalid > 0) a = fabsf(vp.x);
@@ -662,12 +686,15 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
   const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
   const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
-  const bool certified = lane >= nrows || (fbits(prev) == 0 && below);
+  const bool certified = lane >= nrows || (!renew && fbits(prev) == 0 && below);
   tile_total = 0.f;
+  reads = 0;
   if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
   unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
-  const unsigned long long nzmask = __builtin_amdgcn_ballot_w64(fbits(prev) != 0);
-  if (SC.wave_reads && lane == 0) SC.wave_reads[tr * gridDim.x + seg] = __builtin_popcountll(todo);
+  reads = __builtin_popcountll(todo);
+  float mkeep = 0.f;  // renew: lane u keeps the new bound of row u
+  unsigned newlines = 0;  // lane u keeps the nonzero lines of the new row u
+  const unsigned myline = (unsigned)lane >> 3;  // 8 lanes x 16 bytes: one 128-byte line
 
   f4v tile_acc = {0.f, 0.f, 0.f, 0.f}, group_acc = {0.f, 0.f, 0.f, 0.f};
   float tile_tot = 0.f, group_tot = 0.f;  // the total of the tile, added up in the same order
@@ -686,7 +713,9 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
         row[b] = __builtin_ctzll(todo);
         todo &= todo - 1;
         c[b] = ld4<EDGE, NT>(Cp + row[b] * ldc, nmem);
-        if ((nzmask >> row[b]) & 1) x[b] = ld4<EDGE, NT>(Xp + row[b] * ldx, nmem);
+        // of X only the lines that hold something (a plan has about one nonzero per nonzero row segment)
+        const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)oldlines, row[b]);
+        if ((ol >> myline) & 1) x[b] = ld4<EDGE, NT>(Xp + row[b] * ldx, nmem);
       }
     }
 #pragma unroll
@@ -702,15 +731,29 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
           group_tot = 0.f;
           group = u >> 3;
         }
-        const bool nz = (nzmask >> u) & 1;
         const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
         const f4v v = xbar4(x[b], c[b], vp + phu, rho) * scale;
         const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
-        if (nz || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+        // lines with a nonzero now (bit g: any of lanes 8g .. 8g+7); those and the ones that held one
+        // before are written, the others are zero in memory and stay so
+        unsigned long long nzb = __builtin_amdgcn_ballot_w64(nonzero);
+        nzb |= nzb >> 4;
+        nzb |= nzb >> 2;
+        nzb |= nzb >> 1;
+        const unsigned nl = (unsigned)(((nzb & 0x0101010101010101ull) * 0x0102040810204080ull) >> 56);
+        const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)oldlines, u);
+        if (((ol | nl) >> myline) & 1) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+        newlines = (lane == u) ? nl : newlines;
         group_acc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
         group_tot += tot;
+        if (renew) {
+          const float mx = fmaxf(fmaxf(fmaf(-rho, c[b].x, vp.x), fmaf(-rho, c[b].y, vp.y)),
+                                 fmaxf(fmaf(-rho, c[b].z, vp.z), fmaf(-rho, c[b].w, vp.w)));
+          const float mm = wave_max(mx);
+          mkeep = (lane == u) ? mm : mkeep;
+        }
       }
     }
   }
@@ -718,7 +761,22 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
     tile_acc += group_acc;
     tile_tot += group_tot;
   }
-  if (lane < nrows) A.rowpart[ridx] = rowkeep;
+  if (lane < nrows) {
+    A.rowpart[ridx] = rowkeep;
+    SC.lines_out[ridx] = (unsigned char)newlines;
+  }
+  if (renew) {
+    if (lane < nrows) SC.mprime_out[ridx] = mkeep;
+    if (tr == 0) {  // the first tile of the column segment also stores the epoch's varphi
+      float* __restrict__ v0 = SC.varphi0_out + j0;
+      if (nvalid == 4) *reinterpret_cast<f4u*>(v0) = vp;
+      else {
+        if (nvalid > 0) v0[0] = vp.x;
+        if (nvalid > 1) v0[1] = vp.y;
+        if (nvalid > 2) v0[2] = vp.z;
+      }
+    }
+  }
   tile_total = tile_tot;
   return tile_acc;  // column sums of the tile (columns past n: 0)
 }
@@ -734,24 +792,33 @@ template <bool NT>
 __global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
   // (the stop flag is fetched along with a wave's first loads and tested before its first store)
   const int stop = *A.done;
+  const bool renew = SC.ctl[kCtlRenew] != 0;
   __shared__ float fold[kLeanWaves][kSegCols];
   __shared__ float totals[kLeanWaves];
+  __shared__ int nreads[kLeanWaves];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   float total = 0.f;
+  int reads = 0;
   if (tr < ntiles_rows) {
-    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, total);
-    else acc = screened_lean_body<true, false>(A, SC, lane, seg, tr, stop, total);
+    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
+    else acc = screened_lean_body<true, false>(A, SC, lane, seg, tr, stop, renew, total, reads);
   }
   if (stop) return;
   *reinterpret_cast<f4v*>(&fold[wave][lane * 4]) = acc;
-  if (lane == 0) totals[wave] = total;
+  if (lane == 0) {
+    totals[wave] = total;
+    nreads[wave] = reads;
+  }
   __syncthreads();
   const int t = threadIdx.x, j = seg * kSegCols + t;
   if (j < A.n) A.colpart[(size_t)blockIdx.y * A.n + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
-  if (t == 0) A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
+  if (t == 0) {
+    A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
+    SC.wg_reads[blockIdx.y * gridDim.x + seg] = (nreads[0] + nreads[1]) + (nreads[2] + nreads[3]);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1504,11 +1571,22 @@ struct TileTotals {
   int tgroup;            // kColGroup: add tile rows 4k .. 4k+3 first; 1: stored that way
 };
 
+// The lean sweep's refresh schedule rides along (last workgroup): see ScreenCtl above.
+struct ScreenCtlArgs {
+  int* ctl;              // the control words
+  const int* wg_reads;   // [nwg] what the lean sweep's workgroups read
+  int nwg;
+  int mode;              // 0: nothing; 1: the sweep was a refresh ordered by the host: start afresh; 2: account for a lean sweep
+  int price;             // rent that buys a renewal, in row segments of C
+  int max_since;         // renew after this many lean sweeps at the latest
+};
+
 // (8 waves: every workgroup of a 40000-entry problem is resident at once.  The tile totals are dealt
 // out to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...)
 constexpr int kMergedWaves = 8;
 
-__global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T) {
+__global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T,
+                                                                          ScreenCtlArgs K) {
   // (the stop flag travels with the other loads and is tested before the first store: a test up
   // front would put one more trip to memory ahead of everything)
   const int stop = *A.V.done;
@@ -1516,7 +1594,25 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   __shared__ double red[16 * 64];
   __shared__ double eta_part[kShares / 64];
   __shared__ int nzw[NW];
+  __shared__ int readw[NW];
   const int t = threadIdx.x;
+  // the schedule keeper adds up what the lean sweep read (its loads leave with everybody else's)
+  const bool keeper = K.mode == 2 && blockIdx.x == gridDim.x - 1;
+  int nread = 0, renewed = 0;
+  if (keeper) {
+    renewed = K.ctl[kCtlRenew];
+    constexpr int kBatch = 8;
+    for (int e0 = t; e0 < K.nwg; e0 += 64 * NW * kBatch) {
+      int v[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b * 64 * NW;
+        v[b] = e < K.nwg ? K.wg_reads[e] : 0;
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) nread += v[b];
+    }
+  }
   // eq. (6) inputs of this thread's entry, fetched early
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
@@ -1571,9 +1667,35 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
     for (int off = 32; off > 0; off >>= 1) acc[s] += __shfl_xor(acc[s], off, 64);
     if ((t & 63) == 0) eta_part[(t >> 6) + s * NW] = acc[s];
   }
-  if ((t & 63) == 0) nzw[t >> 6] = nz;
+  if (keeper) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nread += __shfl_xor(nread, off, 64);
+  }
+  if ((t & 63) == 0) {
+    nzw[t >> 6] = nz;
+    readw[t >> 6] = nread;
+  }
   __syncthreads();
   if (stop) return;
+  if (t == 0 && blockIdx.x == gridDim.x - 1 && K.mode != 0) {
+    if (K.mode == 1 || renewed) {  // new bounds: nothing paid yet, the floor is what the next sweep reads
+      K.ctl[kCtlRenew] = 0;
+      K.ctl[kCtlSince] = 0;
+      K.ctl[kCtlFloor] = -1;
+      K.ctl[kCtlPaid] = 0;
+    } else {
+      int total = 0;
+      for (int k = 0; k < NW; ++k) total += readw[k];
+      const int since = K.ctl[kCtlSince] + 1;
+      int floor_reads = K.ctl[kCtlFloor], paid = K.ctl[kCtlPaid];
+      if (floor_reads < 0) floor_reads = total;
+      else if (total > floor_reads) paid += total - floor_reads;
+      K.ctl[kCtlSince] = since;
+      K.ctl[kCtlFloor] = floor_reads;
+      K.ctl[kCtlPaid] = paid;
+      if (paid >= K.price || since >= K.max_since) K.ctl[kCtlRenew] = 1;
+    }
+  }
   const double res = reduce_finish<NW>(A, red, nzw, pq);
   if (t >= 64) return;
   double total = 0.0;
@@ -1985,6 +2107,10 @@ struct drot_handle_s {
   float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
   size_t rowpart_half = 0, colpart_half = 0, tilesum_half = 0;
   float *mprime = nullptr, *varphi0 = nullptr;  // screened sweep: per-row-segment bounds and the epoch's varphi
+  int* screen_ctl = nullptr;      // control words of the lean sweep's refresh schedule
+  unsigned char* xlines = nullptr;  // [nseg][m] nonzero 128-byte lines of every row segment of X (lean sweep)
+  bool lines_valid = false;       // xlines describes the X the last solve returned
+  int* wg_reads = nullptr;        // per-workgroup read counts of the lean sweep
   int* wave_reads = nullptr;      // profiling: per-wave read counts of a screened sweep (allocated with the events)
   size_t wave_reads_len = 0;
   double* prof_reads = nullptr;   // profiling: [kMaxProfiled] row segments of C read by each timed sweep (device)
@@ -2049,6 +2175,9 @@ void free_all(drot_handle h) {
     if (e) (void)hipEventDestroy(e);
   (void)hipFree(h->wave_reads);
   (void)hipFree(h->prof_reads);
+  (void)hipFree(h->screen_ctl);
+  (void)hipFree(h->xlines);
+  (void)hipFree(h->wg_reads);
 }
 
 }  // namespace
@@ -2101,6 +2230,9 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
   take(dev_alloc(&h->mprime, nseg * (size_t)max_m));
   take(dev_alloc(&h->varphi0, (size_t)max_n));
+  take(dev_alloc(&h->screen_ctl, (size_t)kCtlWords));
+  take(dev_alloc(&h->xlines, nseg * (size_t)max_m));
+  take(dev_alloc(&h->wg_reads, nseg * (size_t)ceil_div(ceil_div(max_m, 64), kLeanWaves)));
   h->max_runs = (int)ntr;
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));
   take(dev_alloc(&h->done, 1));
@@ -2506,7 +2638,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // plain sweep skip reading all-zero segments
   // (a continued solve starts from the X the last one returned, so its row-segment sums still hold)
   long long sums_gen = warm ? 0 : (resume && h->sums_valid) ? k_base : -1;
-  h->sums_valid = false;  // (until this solve has returned)
+  long long lines_gen = (resume && h->lines_valid && sums_gen >= 0) ? k_base : -1;  // the same for the lean sweep's line masks
+  h->sums_valid = h->lines_valid = false;  // (until this solve has returned)
   // screened sweeps: the sweep that last recorded the bounds M (with its varphi as varphi0), if any
   // (varphi moves fast at first: the bounds are renewed after 8 sweeps, then 16, 32, ... up to the
   // period; a continued solve carries on with the bounds and the schedule of the last one)
@@ -2566,7 +2699,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
       S.tilesum = small ? tsum(sw) : nullptr;
-      bool tiles64 = false, lean = false;
+      bool tiles64 = false, lean = false, refresh = false;
       if (from_points) {
         if (first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, S, PT);
         else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
@@ -2607,16 +2740,18 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         // (automatic: from 16 M entries up; below that the whole of C streams from the caches as fast)
         const bool screened = mode == 0 && tall && !first &&
                               (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= ((size_t)1 << 24)));
-        const bool refresh = screened && (epoch_gen < 0 || sw - epoch_gen >= refresh_period);
+        S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
+        sums_gen = mode == 1 ? -1 : sw;
+        // once the plan is known to be sparse (and bounds exist): one wave per tile, walking through the few
+        // rows left; that sweep renews the bounds by itself, on a schedule kept on the device
+        lean = screened && epoch_gen >= 0 && S.rowpart_prev != nullptr && plan_density >= 0.0 && plan_density < 0.25;
+        refresh = screened && !lean && (epoch_gen < 0 || sw - epoch_gen >= refresh_period);
         if (timed) h->prof_kind[pe] = screened ? (refresh ? 6 : 5) : (mode == 0 && tall && !first) ? 4 : mode;
         const FusedUpdateArgs none{};
         // the sweeps on 64-row tiles also store the totals of their tiles: one launch then does both
         // halves of the vector update
         tiles64 = tall && !first && mode == 0;
         if (tiles64) S.tilesum = tsum(sw);
-        S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
-        sums_gen = mode == 1 ? -1 : sw;
-        lean = false;
         if (screened) {
           const dim3 sgrid(nseg, ceil_div(m, kScreenRows * kScreenWaves)), sblock(64 * kScreenWaves);
           if (refresh) {
@@ -2624,10 +2759,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
             if (epoch_gen >= 0) refresh_period = refresh_period * 2 < refresh_max ? refresh_period * 2 : refresh_max;
             epoch_gen = sw;
           }
-          const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr};
-          // once the plan is known to be sparse: one wave per tile, walking through the few rows left
-          lean = !refresh && S.rowpart_prev != nullptr && plan_density >= 0.0 && plan_density < 0.25;
+          const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr,
+                              h->varphi0, h->screen_ctl, h->wg_reads,
+                              (lean && lines_gen == sw - 1) ? h->xlines : nullptr, h->xlines};
           if (lean) {
+            lines_gen = sw;
             const int ntr64 = ceil_div(m, 64);
             const dim3 lgrid(nseg, ceil_div(ntr64, kLeanWaves)), lblock(64 * kLeanWaves);
             if (nt) hipLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, S, SC, ntr64);
@@ -2663,9 +2799,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       }
       if (timed) {
         DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
-        if (h->prof_kind[pe] >= 5)  // (one count per wave: 8 per 64-row tile, or one in the lean kernel)
-          hipLaunchKernelGGL(sum_reads_kernel, dim3(1), dim3(1024), 0, stream, (const int*)h->wave_reads,
-                             nseg * ceil_div(m, 64) * (h->prof_kind[pe] == 7 ? 1 : kScreenWaves), h->prof_reads + pe);
+        if (h->prof_kind[pe] >= 5)  // (one count per wave of the 8-wave tiles, one per workgroup of the lean kernel)
+          hipLaunchKernelGGL(sum_reads_kernel, dim3(1), dim3(1024), 0, stream,
+                             (const int*)(h->prof_kind[pe] == 7 ? h->wg_reads : h->wave_reads),
+                             h->prof_kind[pe] == 7 ? nseg * ceil_div(ceil_div(m, 64), kLeanWaves)
+                                                   : nseg * ceil_div(m, 64) * kScreenWaves,
+                             h->prof_reads + pe);
       }
       if (!fused || c == chunk - 1) {
         // complete the state in memory: update sw from the sums of X_sw
@@ -2680,7 +2819,13 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         UA.ntiles = small_slab ? nstrips * nruns : ntiles;
         if (tiles64) {
           const TileTotals TT{tsum(sw), lean ? ceil_div(ntr_tall, kColGroup) : ntr_tall, nseg, lean ? 1 : kColGroup};
-          hipLaunchKernelGGL(reduce_update_kernel, dim3(nbm + nbn), dim3(64 * kMergedWaves), 0, stream, RA, UA, TT);
+          // (the price of a renewal: all row segments of C, read by a sweep that streams them better than
+          // the scattered reads it saves)
+          const double price = 0.75 * (double)m * (double)nseg;
+          const ScreenCtlArgs KA{h->screen_ctl, h->wg_reads, nseg * ceil_div(ntr_tall, kLeanWaves),
+                                 lean ? 2 : refresh ? 1 : 0, price < 1.0e9 ? (int)price : 1000000000,
+                                 h->screening >= 2 ? h->screening : 1024};
+          hipLaunchKernelGGL(reduce_update_kernel, dim3(nbm + nbn), dim3(64 * kMergedWaves), 0, stream, RA, UA, TT, KA);
         } else {
           hipLaunchKernelGGL(reduce_kernel, dim3(nbm + nbn), dim3(kReduceThreads), 0, stream, RA);
           hipLaunchKernelGGL(update_kernel, update_grid, dim3(kReduceThreads), 0, stream, UA);
@@ -2777,6 +2922,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->refresh_period = refresh_period;
   // (after an early stop the sweeps launched past it did nothing: be conservative)
   h->sums_valid = !st.converged && max_iters > 0 && sums_gen == k_base + k;
+  h->lines_valid = h->sums_valid && lines_gen == k_base + k;
   h->solved = true;
   h->last_m = m;
   h->last_n = n;
