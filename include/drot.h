@@ -148,13 +148,16 @@ int drot_set_skip_unchanged(drot_handle h, int mode);
 
 /*
  * Screening [-1 = on].  With the zero-segment skipping on, sweeps over large sparse plans also leave
- * out most reads of C.  Every 256th sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
- * until the next one, a row segment whose X is zero and whose bound M + max_j (drift of varphi_j
- * since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is known to
- * stay zero: nothing of it is read, computed or written.  The iterates are those of the unscreened
- * sweeps, bit for bit.  mode -1 screens problems of 2^24 entries and more (smaller ones stream all
- * of C from the caches just as fast), mode 1 every problem the skipping applies to, mode k >= 2 the
- * same with the bounds recorded at least every k-th sweep; mode 0 reads C in full every sweep.
+ * out most reads of C.  Now and then a sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
+ * until the next such sweep, a row segment whose X is zero and whose bound M + max_j (drift of
+ * varphi_j since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is
+ * known to stay zero: nothing of it is read, computed or written.  The iterates are those of the
+ * unscreened sweeps, bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first, at
+ * most 256 apart; once the plan is known to be sparse the sweep itself decides, on the device, when
+ * the reads that weakened bounds cost it have added up to the price of new ones.  mode -1 screens
+ * problems of 2^24 entries and more (smaller ones stream all of C from the caches just as fast),
+ * mode 1 every problem the skipping applies to, mode k >= 2 the same with the bounds renewed at
+ * least every k-th sweep; mode 0 reads C in full every sweep.
  */
 int drot_set_screening(drot_handle h, int mode);
 
