@@ -485,23 +485,29 @@ def test_screening_on_ragged_shapes(drot, m, n):
         assert np.array_equal(a, b)
 
 
-def test_lean_screened_sweep_changes_no_bit(drot, oracle):
+@pytest.mark.parametrize("mode", [-1, 7])
+def test_lean_screened_sweep_changes_no_bit(drot, oracle, mode):
     # wide rows: after the first status reports a sparse plan the solver moves to the one-wave-per-tile
-    # screened sweep; iterates must still be those of the unscreened sweeps, bit for bit
+    # screened sweep, which keeps its own refresh schedule and line flags for X; iterates must still be
+    # those of the unscreened sweeps, bit for bit.  mode 7: new bounds at least every 7th sweep, so the
+    # sweep's own renewals (everything read, nothing certified) come up many times.
     P = drot_inputs.random_problem(2100, 8192 + 40, seed=1600, d=8, reg_kind=1, lam=0.01)
     solver = drot.Solver(P.m, P.n, check_every=25)
-    _say("lean screened sweep, bitwise")
+    _say(f"lean screened sweep, bitwise, screening mode {mode}")
     K = 260
     solver.set_screening(0)
     _, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
-    solver.set_screening(-1)
+    solver.set_screening(mode)
     solver.set_profile(True)
     res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
     kinds = [k for _, k in solver.profile_sweeps()]
     reads = solver.profile_reads()
     solver.set_profile(False)
     assert kinds.count(7) > 50, kinds
-    assert min(r for r, k in zip(reads, kinds) if k == 7) < 0.5  # and it does leave most of C unread
+    lean_reads = [r for r, k in zip(reads, kinds) if k == 7]
+    assert min(lean_reads) < 0.5  # it does leave most of C unread
+    renewals = sum(1 for r in lean_reads if r > 0.999)
+    assert renewals >= (len(lean_reads) // 10 if mode == 7 else 0), (renewals, len(lean_reads))  # (7 sweeps, then the renewal)
     assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
     ores = pu.oracle_solve(oracle, P, K)
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="lean screened")
