@@ -162,6 +162,12 @@ def main() -> int:
             return sparse_sweep_bytes(line_frac["v"], c_read.get(kind, 1.0), True, 256, 14.0)
         if kind in (4, 5, 6):
             return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 64, 12.0 if kind != 4 else 8.0)
+        if kind == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
+            # group-resident group lasso: all of C; of X the 128-byte lines (32 columns of a row) that hold
+            # a nonzero; per line the old and the new sum; the column sums per class
+            if "v" not in line_frac:
+                line_frac["v"] = nonzero_line_fraction()
+            return (4.0 + 8.0 * line_frac["v"]) * m * n + 8.0 * m * ((n + 31) // 32) + 4.0 * n * max(1, P.num_classes)
         return BYTES_PER_ELEMENT[kind] * m * n
 
     def kernel_entry(kind, ms, launches, nbytes=None):
@@ -188,6 +194,12 @@ def main() -> int:
     bytes_per_iteration = sum(kind_bytes[k] * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
     log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
         f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
+    if dominant == 0 and P.reg_kind == 2 and "v" in line_frac:
+        roofline["bytes_model"] = ("4 B per element (C) + 8 B x the entries of X in nonzero 128-byte lines (counted on the final plan) "
+                                   "+ 8 B per line (old and new sums) + column sums; the working set fits the 256 MB memory-side cache")
+        roofline["nonzero_line_fraction"] = round(line_frac["v"], 6)
+        roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
+        log(f"nonzero 128-byte lines of X: {line_frac['v']:.3%}; priced at 12 B/element the sweep would read {roofline['dense_model_gbs']:.0f} GB/s")
     if dominant in (4, 5, 6, 7):
         roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the entries of X in nonzero row segments "
                                    "(lean kernel: in nonzero 128-byte lines; counted on the final plan) + 8-14 B per row segment (old and new "
@@ -205,7 +217,7 @@ def main() -> int:
         for e in roofline["other_kernels"]:
             log(f"  also [{e['kernel']}]: {e['kernel_ms']:.4f} ms over {e['launches_timed']} launches -> {e['achieved']:.0f} GB/s ({e['frac']:.1%})")
 
-    def timed_leg(label):
+    def timed_leg(label, nbytes=None):
         """K more iterations from the current state with the solver's current settings, then a profile."""
         solver.set_continue(True)
         solver.solve(C, p, q, max_iters=2, **kw)  # (settle the scheme's first-sweep special cases)
@@ -217,7 +229,7 @@ def main() -> int:
         lprof = sweep_profile()
         solver.set_continue(False)
         leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
-               "kernels": [kernel_entry(k, *lprof[k]) for k in sorted(lprof)]}
+               "kernels": [kernel_entry(k, *lprof[k], nbytes=nbytes) for k in sorted(lprof)]}
         log(f"{label}: {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; " +
             "; ".join(f"{e['kernel_ms']:.4f} ms = {e['achieved']:.0f} GB/s ({e['frac']:.1%})" for e in leg["kernels"]))
         return leg
@@ -236,6 +248,10 @@ def main() -> int:
         solver.set_skip_unchanged(0)
         dense_leg = timed_leg("every byte moved (12 B/element)")
         solver.set_skip_cost(args.skip_cost)
+        solver.set_skip_unchanged(args.skip_unchanged)
+    if dominant == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
+        solver.set_skip_unchanged(0)
+        dense_leg = timed_leg("every byte moved (12 B/element)", nbytes=12.0 * m * n)
         solver.set_skip_unchanged(args.skip_unchanged)
     solver.set_continue(False)
 

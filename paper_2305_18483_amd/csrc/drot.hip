@@ -1127,6 +1127,17 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
 
   f4v x[K], c[K];
   float ph[K];
+  // X >= 0: a row's 32 columns of this strip (one 128-byte line, the 8 lanes of a row) are all zero
+  // exactly when their sum after the previous sweep was zero; such a line is not read, and not
+  // written back if it comes out as zero again (the memory contents are the same either way)
+  bool held[K];
+  const bool flags = !FIRST && !PRO && A.rowpart_prev != nullptr;
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int r = ry + RL * k;
+    held[k] = true;
+    if (flags && r < len) held[k] = fbits(A.rowpart_prev[(size_t)strip * A.m + start + r]) != 0;
+  }
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int r = ry + RL * k;
@@ -1135,7 +1146,7 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     ph[k] = kMaskedOut;  // rows past the run: the clamp zeroes them
     if (r < len) {
       c[k] = load4(Cp + (size_t)(RL * k) * ldc, nvalid);
-      if (!FIRST) x[k] = load4(Xp + (size_t)(RL * k) * ldx, nvalid);
+      if (!FIRST && held[k]) x[k] = load4(Xp + (size_t)(RL * k) * ldx, nvalid);
       if (!PRO) ph[k] = A.phi[start + r];
     }
   }
@@ -1234,7 +1245,7 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     const float rs = rowlanes_sum<CX>((v.x + v.y) + (v.z + v.w));
     colacc += v;
     if (r < len) {
-      store4(Xp + (size_t)(RL * k) * ldx, v, nvalid);
+      if (held[k] || fbits(rs) != 0) store4(Xp + (size_t)(RL * k) * ldx, v, nvalid);
       if (cx == 0) A.rowpart[(size_t)strip * A.m + start + r] = rs;
     }
   }
@@ -2082,6 +2093,7 @@ struct drot_handle_s {
   double plan_density = -1.0;
   long long epoch_gen = -1;  // screening: sweep that recorded the bounds in mprime (continued solves)
   bool sums_valid = false;   // rowpart of the last generation describes the X the solve returned
+  int sums_strip = 0;        // ... in pieces of this many columns (256, or 32 on the group-resident path)
   int refresh_period = 8;
   int resident = -1;      // -1: tiny problems run in the one-workgroup resident kernel, 0: never
   int fused_update = -1;  // -1: for small problems, 0: never (always separate reduce + update kernels)
@@ -2637,7 +2649,9 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // generation whose row-segment sums (tile layout) describe the plain X in memory, if any: lets the
   // plain sweep skip reading all-zero segments
   // (a continued solve starts from the X the last one returned, so its row-segment sums still hold)
-  long long sums_gen = warm ? 0 : (resume && h->sums_valid) ? k_base : -1;
+  const int sums_strip = slab_k ? kSlabCols : kSegCols;
+  // (the warm start's sums are those of 256-column segments)
+  long long sums_gen = warm ? (slab_k ? -1 : 0) : (resume && h->sums_valid && h->sums_strip == sums_strip) ? k_base : -1;
   long long lines_gen = (resume && h->lines_valid && sums_gen >= 0) ? k_base : -1;  // the same for the lean sweep's line masks
   h->sums_valid = h->lines_valid = false;  // (until this solve has returned)
   // screened sweeps: the sweep that last recorded the bounds M (with its varphi as varphi0), if any
@@ -2699,16 +2713,21 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       S.rowpart = SL.S.rowpart = G.S.rowpart = rowp(sw);
       S.colpart = SL.S.colpart = G.S.colpart = colp(sw);
       S.tilesum = small ? tsum(sw) : nullptr;
-      bool tiles64 = false, lean = false, refresh = false;
+      bool tiles64 = false, lean = false, refresh = false, slab_totals = false;
       if (from_points) {
         if (first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, S, PT);
         else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
         else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, S, PT);
       } else if (slab_k) {
+        // (large problems: the slab totals give eta, one launch then does the whole vector update)
+        slab_totals = !small && (size_t)nstrips * (size_t)nruns <= h->tilesum_half;
+        if (slab_totals) S.tilesum = tsum(sw);
         SL.S.tilesum = S.tilesum;
         const FusedUpdateArgs F{rowp(sw - 1), colp(sw - 1), tsum(sw - 1), p, q, a_buf(sw - 2), b_buf(sw - 2),
                                 a_buf(sw - 1), b_buf(sw - 1), h->theta + ((sw - 2) & 1), h->theta + ((sw - 1) & 1),
                                 h->sum_p, h->phi, h->varphi, nstrips, nruns};
+        SL.S.rowpart_prev = (sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
+        sums_gen = sw;
         launch_slab(first, !materialized, slab_k, slab_grid, stream, SL, F);
       } else if (reg_kind == DROT_REG_GROUP_LASSO) {
         hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((ngroups + 255) / 256), 4)), dim3(256), 0, stream,
@@ -2817,7 +2836,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         UA.par = (int)((sw - 1) & 1);
         UA.tilesum = small ? tsum(sw) : nullptr;
         UA.ntiles = small_slab ? nstrips * nruns : ntiles;
-        if (tiles64) {
+        if (slab_totals) {
+          const TileTotals TT{tsum(sw), nruns, nstrips, 1};
+          const ScreenCtlArgs KA{nullptr, nullptr, 0, 0, 0, 0};
+          hipLaunchKernelGGL(reduce_update_kernel, dim3(nbm + nbn), dim3(64 * kMergedWaves), 0, stream, RA, UA, TT, KA);
+        } else if (tiles64) {
           const TileTotals TT{tsum(sw), lean ? ceil_div(ntr_tall, kColGroup) : ntr_tall, nseg, lean ? 1 : kColGroup};
           // (the price of a renewal: all row segments of C, read by a sweep that streams them better than
           // the scattered reads it saves)
@@ -2923,6 +2946,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // (after an early stop the sweeps launched past it did nothing: be conservative)
   h->sums_valid = !st.converged && max_iters > 0 && sums_gen == k_base + k;
   h->lines_valid = h->sums_valid && lines_gen == k_base + k;
+  h->sums_strip = sums_strip;
   h->solved = true;
   h->last_m = m;
   h->last_n = n;

@@ -576,6 +576,35 @@ def test_skipping_zero_segments_changes_no_bit(drot, m, n, kind):
     assert np.array_equal(X_two, X_skip)
 
 
+@pytest.mark.parametrize("m,n,classes", [(600, 2100, 3), (1203, 2600, 5), (1800, 2100, 2)])
+def test_group_lasso_skipping_zero_lines_changes_no_bit(drot, m, n, classes):
+    # group-resident group lasso beyond the fused small-problem path: leaving out the loads and stores
+    # of the all-zero 128-byte lines of X (known from the strip row sums) must give the very same
+    # iterates, from the dense first iterations on, across a residual check, a continuation and a
+    # warm start (whose sums come in another layout and must not be taken for flags)
+    P = drot_inputs.random_problem(m, n, seed=1900 + m, reg_kind=2, lam=0.01, mu=0.1, num_classes=classes)
+    solver = drot.Solver(m, n, check_every=9)
+    _say(f"group lasso, zero-line skipping, bitwise, {m}x{n}")
+    outs = {}
+    for mode in (0, 1):
+        solver.set_skip_unchanged(mode)
+        for K in (1, 2, 10, 60):
+            outs[(mode, K)] = pu.gpu_solve(solver, P, K, tol=1e-12)[1:]
+        X = torch.empty((m, n), device="cuda:0")
+        pu.gpu_solve(solver, P, 25, X_out=X)
+        solver.set_continue(True)
+        outs[(mode, "two")] = pu.gpu_solve(solver, P, 35, X_out=X)[1:]
+        solver.set_continue(False)
+    for key in [k for k in outs if k[0] == 0]:
+        for a, b in zip(outs[key], outs[(1, key[1])]):
+            assert np.array_equal(a, b), key
+    for a, b in zip(outs[(1, "two")], outs[(1, 60)]):
+        assert np.array_equal(a, b)
+    Xz = outs[(1, 60)][0]
+    zero_lines = [Xz[:, j:j + 32].max(axis=1) == 0 for j in range(0, n, 32)]
+    assert float(np.mean(zero_lines)) > 0.1  # the case really exercises the skipping
+
+
 @pytest.mark.parametrize("terms", ["weights", "forbidden", "both"])
 @pytest.mark.parametrize("kind,m,n", [(0, 90, 120), (1, 128, 256), (0, 333, 517), (1, 700, 90), (2, 333, 517),
                                       (0, 2300, 700), (1, 2300, 700), (2, 2300, 700)])
