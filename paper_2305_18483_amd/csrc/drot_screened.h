@@ -1,0 +1,338 @@
+// Screened sweeps: the 8-wave tile and the lean one-wave-per-tile kernel.
+// Part of drot.hip (included there, inside its anonymous namespace, in this order); not a stand-alone header.
+
+// ------------------------------------------------------------------------------------------
+// Screened sweep (large sparse problems).  On top of skipping the all-zero row segments of X, most
+// of C need not be read either: a row segment with x = 0 comes out as zero again whenever
+// phi_i + varphi_j - rho C_ij <= 0 for its 256 columns, and that can be certified from one number.
+// A "refresh" sweep, which reads all of C, records for every row segment
+//     M_is = max_j ( varphi0_j - rho C_ij )            (varphi0 = the varphi of that sweep).
+// Later sweeps form, per column segment, delta_s = max_j (varphi_j - varphi0_j) and, per row,
+//     S = M_is + delta_s + phi_i  >=  max_j ( phi_i + varphi_j - rho C_ij ).
+// If S plus a rounding margin is <= 0 and the segment of X is zero, the segment stays zero: its C is
+// not read, nothing is computed, its row sum is 0.  The result is the one the plain sweep would
+// produce (the margin dominates the handful of fp32 roundings between the two evaluations).  As
+// varphi drifts away from varphi0 fewer segments certify; the host refreshes every so many sweeps.
+// Tiles: 8 waves x 8 rows x 256 columns, as the unscreened sweep for sparse plans.
+// ------------------------------------------------------------------------------------------
+struct ScreenArgs {
+  const float* mprime_in;   // [nseg][m] M_is of the current epoch (screening sweeps)
+  float* mprime_out;        // [nseg][m] written by a refresh sweep
+  const float* varphi0;     // [n] varphi of the epoch
+  int* wave_reads;          // 8-wave tiles, profiling only (else null): [workgroup][wave] row segments of C this wave read
+  // lean sweep only: it renews the bounds by itself when the vector update before it has raised ctl[0]
+  float* varphi0_out;       // [n]
+  const int* ctl;           // kCtl... words, see ScreenCtl
+  int* wg_reads;            // [workgroup] row segments of C the workgroup read (always written)
+  // lean sweep only: which of the eight 128-byte lines of a row segment of X hold a nonzero
+  const unsigned char* lines_in;  // [nseg][m] as left by the previous sweep if that was a lean one, else null
+  unsigned char* lines_out;       // [nseg][m]
+};
+
+// Control words of the lean sweep's own refresh schedule (device memory, updated by
+// reduce_update_kernel after every lean sweep): the classic rent-or-buy rule.  Reading the C of a
+// row segment the bounds fail to certify is the rent, renewing the bounds (all of C once) the
+// purchase: renew when the rent paid since the last renewal, counted from the level right after
+// it, has reached the price.  That stays within a factor 2 of the best schedule in hindsight,
+// whatever the drift of varphi does, and needs no model of it.
+constexpr int kCtlRenew = 0;   // the next lean sweep renews the bounds
+constexpr int kCtlSince = 1;   // lean sweeps since the last renewal
+constexpr int kCtlFloor = 2;   // row segments of C read by the first sweep after it (-1: not known yet)
+constexpr int kCtlPaid = 3;    // reads above that floor accumulated since
+constexpr int kCtlWords = 4;
+
+constexpr int kScreenRows = 8, kScreenWaves = 8;
+
+template <bool EDGE, bool NT, bool REFRESH>
+__device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int wave, int seg, int tr) {
+  constexpr int U = kScreenRows, NW = kScreenWaves;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
+  const int r0 = (tr * NW + wave) * U;
+  const int nrows = min(max(A.m - r0, 0), U);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const float rho = A.rho, scale = A.scale;
+  const size_t ridx = (size_t)seg * A.m + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
+
+  // lane u: old sum, phi and M of row r0 + u
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  if (lane < nrows) {
+    prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
+    ph = A.phi[r0 + lane];
+    if (!REFRESH) mpr = SC.mprime_in[ridx];
+  }
+  bool certified = lane >= nrows;  // rows past the end of the matrix: nothing to do
+  if (!REFRESH) {
+    const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+    // drift of varphi since the epoch and its magnitude over this wave's columns (columns past n: both
+    // carry the same mask value, their difference is 0; they are left out of the magnitude)
+    float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+    float a = 0.f;
+    if (nvalid > 0) a = fabsf(vp.x);
+    if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
+    if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
+    if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+    const float delta = wave_max(d), mag = wave_max(a);
+    // S bounds every phi_i + varphi_j - rho C_ij of the row segment from above; the margin, 8 units in
+    // the last place of the largest term, covers the roundings of M, of delta, of this sum and of the
+    // sweep's own evaluation (each at most half a unit of a term no larger than these)
+    const float bound = (mpr + delta) + ph;
+    const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);  // 2^-21
+    const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;  // (-inf: every pair of the segment is forbidden)
+    certified = certified || (fbits(prev) == 0 && below);
+  }
+  const unsigned skipmask = (unsigned)__builtin_amdgcn_ballot_w64(certified) & 0xffu;
+  const unsigned nzmask = (unsigned)__builtin_amdgcn_ballot_w64(fbits(prev) != 0) & 0xffu;
+
+  f4v x[U], c[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    x[u] = f4v{0.f, 0.f, 0.f, 0.f};
+    c[u] = f4v{0.f, 0.f, 0.f, 0.f};
+  }
+  if (nrows == U && skipmask == 0) {
+    // nothing certified (always so in a refresh sweep, and while the plan is dense): straight-line loads
+#pragma unroll
+    for (int u = 0; u < U; ++u) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (!((skipmask >> u) & 1)) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
+  }
+  if (nzmask != 0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if ((nzmask >> u) & 1) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+  }
+
+  f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float rowkeep = 0.f, mkeep = 0.f, wave_total = 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (!((skipmask >> u) & 1)) {
+      const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+      const f4v v = xbar4(x[u], c[u], vp + phu, rho) * scale;
+      const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+      if (((nzmask >> u) & 1) || __builtin_amdgcn_ballot_w64(nonzero) != 0) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+      colacc += v;
+      const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+      rowkeep = (lane == u) ? tot : rowkeep;
+      wave_total += tot;
+      if (REFRESH) {
+        const float mx = fmaxf(fmaxf(fmaf(-rho, c[u].x, vp.x), fmaf(-rho, c[u].y, vp.y)),
+                               fmaxf(fmaf(-rho, c[u].z, vp.z), fmaf(-rho, c[u].w, vp.w)));
+        const float mm = wave_max(mx);
+        mkeep = (lane == u) ? mm : mkeep;
+      }
+    }
+  }
+  if (lane < nrows) {
+    A.rowpart[ridx] = rowkeep;
+    if (REFRESH) SC.mprime_out[ridx] = mkeep;
+  }
+  if (SC.wave_reads && lane == 0)
+    SC.wave_reads[(tr * gridDim.x + seg) * NW + wave] = __builtin_popcount(~skipmask & 0xffu);
+  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
+}
+
+// Profiling: total of the per-wave read counts of one screened sweep.
+__global__ __launch_bounds__(1024) void sum_reads_kernel(const int* __restrict__ wave_reads, int count, double* out) {
+  __shared__ double red[1024 / 64];
+  double acc = 0.0;
+  for (int e = threadIdx.x; e < count; e += 1024) acc += (double)wave_reads[e];
+  const double tot = block_sum_f64(acc, red);
+  if (threadIdx.x == 0) *out = tot;
+}
+
+template <bool NT, bool REFRESH>
+__global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepArgs A, ScreenArgs SC) {
+  if (*A.done) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y;
+  if ((seg + 1) * kSegCols <= A.n) screened_body<false, NT, REFRESH>(A, SC, lane, wave, seg, tr);
+  else screened_body<true, false, REFRESH>(A, SC, lane, wave, seg, tr);
+}
+
+// The screened sweep for plans known to be sparse (a few percent of the row segments left to
+// process): one wave owns a whole 64 x 256 tile, lane l holding the old sum, phi and M of row l.
+// It decides all 64 rows at once and then walks through the rows left over, one at a time.  No
+// LDS, no barrier; 8 times fewer waves than the tile of 8 waves x 8 rows, and the same bits: the
+// rows of every group of 8 are added up in order and the 8 groups in order, which is what that
+// tile's waves and its LDS fold do (rows and groups that contribute nothing add +0).
+template <bool EDGE, bool NT>
+__device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
+                                                  int stop, bool renew, float& tile_total, int& reads) {
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
+  const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
+  const int r0 = tr * 64;
+  const int nrows = min(A.m - r0, 64);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const float rho = A.rho, scale = A.scale;
+  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+
+  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  unsigned oldlines = 0;  // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31)
+  if (lane < nrows) {
+    prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
+    ph = A.phi[r0 + lane];
+    mpr = SC.mprime_in[ridx];
+    oldlines = SC.lines_in ? SC.lines_in[ridx] : 0xffu;
+  }
+  if (fbits(prev) == 0) oldlines = 0;
+  // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
+  // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
+  float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  float a = 0.f;
+  if (nvalid > 0) a = fabsf(vp.x);
+  if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
+  if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
+  if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+  const float delta = wave_max(d), mag = wave_max(a);
+  const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
+  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
+  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool certified = lane >= nrows || (!renew && fbits(prev) == 0 && below);
+  tile_total = 0.f;
+  reads = 0;
+  if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
+  unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
+  reads = __builtin_popcountll(todo);
+  float mkeep = 0.f;  // renew: lane u keeps the new bound of row u
+  unsigned newlines = 0;  // lane u keeps the nonzero lines of the new row u
+  const unsigned myline = (unsigned)lane >> 3;  // 8 lanes x 16 bytes: one 128-byte line
+
+  f4v tile_acc = {0.f, 0.f, 0.f, 0.f}, group_acc = {0.f, 0.f, 0.f, 0.f};
+  float tile_tot = 0.f, group_tot = 0.f;  // the total of the tile, added up in the same order
+  int group = -1;
+  float rowkeep = 0.f;
+  constexpr int kWalk = 4;  // rows fetched together: their loads overlap, the arithmetic stays in row order
+  while (todo != 0) {
+    int row[kWalk];
+    f4v c[kWalk], x[kWalk];
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      row[b] = -1;
+      c[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      x[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      if (todo != 0) {
+        row[b] = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        c[b] = ld4<EDGE, NT>(Cp + row[b] * ldc, nmem);
+        // of X only the lines that hold something (a plan has about one nonzero per nonzero row segment)
+        const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)oldlines, row[b]);
+        if ((ol >> myline) & 1) x[b] = ld4<EDGE, NT>(Xp + row[b] * ldx, nmem);
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      const int u = row[b];
+      if (u >= 0) {
+        if ((u >> 3) != group) {
+          if (group >= 0) {
+            tile_acc += group_acc;
+            tile_tot += group_tot;
+          }
+          group_acc = f4v{0.f, 0.f, 0.f, 0.f};
+          group_tot = 0.f;
+          group = u >> 3;
+        }
+        const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+        const f4v v = xbar4(x[b], c[b], vp + phu, rho) * scale;
+        const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+        // lines with a nonzero now (bit g: any of lanes 8g .. 8g+7); those and the ones that held one
+        // before are written, the others are zero in memory and stay so
+        unsigned long long nzb = __builtin_amdgcn_ballot_w64(nonzero);
+        nzb |= nzb >> 4;
+        nzb |= nzb >> 2;
+        nzb |= nzb >> 1;
+        const unsigned nl = (unsigned)(((nzb & 0x0101010101010101ull) * 0x0102040810204080ull) >> 56);
+        const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)oldlines, u);
+        if (((ol | nl) >> myline) & 1) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+        newlines = (lane == u) ? nl : newlines;
+        group_acc += v;
+        const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+        rowkeep = (lane == u) ? tot : rowkeep;
+        group_tot += tot;
+        if (renew) {
+          const float mx = fmaxf(fmaxf(fmaf(-rho, c[b].x, vp.x), fmaf(-rho, c[b].y, vp.y)),
+                                 fmaxf(fmaf(-rho, c[b].z, vp.z), fmaf(-rho, c[b].w, vp.w)));
+          const float mm = wave_max(mx);
+          mkeep = (lane == u) ? mm : mkeep;
+        }
+      }
+    }
+  }
+  if (group >= 0) {
+    tile_acc += group_acc;
+    tile_tot += group_tot;
+  }
+  if (lane < nrows) {
+    A.rowpart[ridx] = rowkeep;
+    SC.lines_out[ridx] = (unsigned char)newlines;
+  }
+  if (renew) {
+    if (lane < nrows) SC.mprime_out[ridx] = mkeep;
+    if (tr == 0) {  // the first tile of the column segment also stores the epoch's varphi
+      float* __restrict__ v0 = SC.varphi0_out + j0;
+      if (nvalid == 4) *reinterpret_cast<f4u*>(v0) = vp;
+      else {
+        if (nvalid > 0) v0[0] = vp.x;
+        if (nvalid > 1) v0[1] = vp.y;
+        if (nvalid > 2) v0[2] = vp.z;
+      }
+    }
+  }
+  tile_total = tile_tot;
+  return tile_acc;  // column sums of the tile (columns past n: 0)
+}
+
+// Four waves per workgroup, stacked along the rows: they work independently and meet once, at the
+// end, to add their tiles' column sums in the order tile 0, 1, 2, 3 (kColGroup in the reduction:
+// the sweeps that store one row of column sums per 64-row tile are added up in that order too).
+constexpr int kLeanWaves = 4;
+constexpr int kColGroup = kLeanWaves;
+static_assert(64 * kLeanWaves == kSegCols, "one thread per column of the segment in the final fold");
+
+template <bool NT>
+__global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
+  // (the stop flag is fetched along with a wave's first loads and tested before its first store)
+  const int stop = *A.done;
+  const bool renew = SC.ctl[kCtlRenew] != 0;
+  __shared__ float fold[kLeanWaves][kSegCols];
+  __shared__ float totals[kLeanWaves];
+  __shared__ int nreads[kLeanWaves];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
+  f4v acc = {0.f, 0.f, 0.f, 0.f};
+  float total = 0.f;
+  int reads = 0;
+  if (tr < ntiles_rows) {
+    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
+    else acc = screened_lean_body<true, false>(A, SC, lane, seg, tr, stop, renew, total, reads);
+  }
+  if (stop) return;
+  *reinterpret_cast<f4v*>(&fold[wave][lane * 4]) = acc;
+  if (lane == 0) {
+    totals[wave] = total;
+    nreads[wave] = reads;
+  }
+  __syncthreads();
+  const int t = threadIdx.x, j = seg * kSegCols + t;
+  if (j < A.n) A.colpart[(size_t)blockIdx.y * A.n + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
+  if (t == 0) {
+    A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
+    SC.wg_reads[blockIdx.y * gridDim.x + seg] = (nreads[0] + nreads[1]) + (nreads[2] + nreads[3]);
+  }
+}

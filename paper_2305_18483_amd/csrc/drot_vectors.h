@@ -1,0 +1,461 @@
+// Start state, reduction of the partial sums and the eq. (6) update of the dual vectors.
+// Part of drot.hip (included there, inside its anonymous namespace, in this order); not a stand-alone header.
+
+// ------------------------------------------------------------------------------------------
+// S0: starting point of the Initialization paragraph: X_0 = 0 (never materialised: the first
+// sweep does not read X), phi_0, varphi_0 constants, and a_0 = Y_0 1 - p, b_0 = Y_0^T 1 - q,
+// theta_0 = 1^T a_0/(m+n) with Y_0 = phi_0 1^T + 1 varphi_0^T, the values that make eq. (6)
+// reproduce eq. (4).  One workgroup.
+// ------------------------------------------------------------------------------------------
+struct VecState {
+  float* phi;
+  float* varphi;
+  double* a;
+  double* b;
+  double* theta;   // [2], indexed by iteration parity
+  double* sum_p;   // [1] sum of p
+  double* r;       // [m] row residuals X 1 - p of the last sweep
+  double* s;       // [n] column residuals
+  double* part;    // [3][nbm + nbn]: per-workgroup sum of residuals, sum of squared residuals, nonzero row partials
+  double* resid;   // [3]: ||r||^2, ||s||^2, number of nonzero row partial sums
+  int* done;
+  DeviceStatus* status;
+};
+
+__global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __restrict__ p,
+                                                    const float* __restrict__ q, int m, int n) {
+  __shared__ double red[1024];
+  const int t = threadIdx.x;
+  const double mn = (double)m + (double)n;
+  const double phi0 = (1.0 + (double)m / mn) / (3.0 * mn);
+  const double varphi0 = (1.0 + (double)n / mn) / (3.0 * mn);
+  double sp = 0.0;
+  for (int i = t; i < m; i += blockDim.x) {
+    const double pi = (double)p[i];
+    sp += pi;
+    V.phi[i] = (float)phi0;
+    V.a[i] = (double)n * (phi0 + varphi0) - pi;
+  }
+  for (int j = t; j < n; j += blockDim.x) {
+    V.varphi[j] = (float)varphi0;
+    V.b[j] = (double)m * (phi0 + varphi0) - (double)q[j];
+  }
+  const double sum_p = block_sum_f64(sp, red);
+  if (t == 0) {
+    *V.sum_p = sum_p;
+    V.theta[0] = ((double)m * (double)n * (phi0 + varphi0) - sum_p) / mn;
+    V.theta[1] = 0.0;
+    *V.done = 0;
+    *V.status = DeviceStatus{};
+  }
+}
+
+// Re-arms the stop flag and the status block when a solve continues from the handle's state.
+__global__ void reset_kernel(VecState V) {
+  *V.done = 0;
+  *V.status = DeviceStatus{};
+}
+
+// Warm start: state of eq. (6) for a caller-supplied starting point (X_0, phi_0, varphi_0), i.e.
+// Y_0 = X_0 + phi_0 1^T + 1 varphi_0^T (eq. (5)): a_0 = Y_0 1 - p = (X_0 1 - p) + n phi_0 + (1^T varphi_0) 1,
+// b_0 = (X_0^T 1 - q) + m varphi_0 + (1^T phi_0) 1, theta_0 = 1^T a_0 / (m+n).  The residuals
+// X_0 1 - p and X_0^T 1 - q come from reduce_kernel (V.r, V.s).  One workgroup.
+__global__ __launch_bounds__(1024) void warm_init_kernel(VecState V, const float* __restrict__ p,
+                                                         const float* __restrict__ phi0,
+                                                         const float* __restrict__ varphi0, int m, int n) {
+  __shared__ double red[1024];
+  const int t = threadIdx.x;
+  double sp = 0.0, sphi = 0.0, svarphi = 0.0;
+  for (int i = t; i < m; i += blockDim.x) { sp += (double)p[i]; sphi += (double)phi0[i]; }
+  for (int j = t; j < n; j += blockDim.x) svarphi += (double)varphi0[j];
+  sp = block_sum_f64(sp, red);
+  sphi = block_sum_f64(sphi, red);
+  svarphi = block_sum_f64(svarphi, red);
+  double sa = 0.0;
+  for (int i = t; i < m; i += blockDim.x) {
+    const double f = (double)phi0[i];
+    const double ai = V.r[i] + (double)n * f + svarphi;
+    V.a[i] = ai;
+    V.phi[i] = phi0[i];
+    sa += ai;
+  }
+  for (int j = t; j < n; j += blockDim.x) {
+    const double f = (double)varphi0[j];
+    V.b[j] = V.s[j] + (double)m * f + sphi;
+    V.varphi[j] = varphi0[j];
+  }
+  sa = block_sum_f64(sa, red);
+  if (t == 0) {
+    *V.sum_p = sp;
+    V.theta[0] = sa / ((double)m + (double)n);
+    V.theta[1] = 0.0;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// S5, first half: r = X1 - p and s = X^T1 - q from the partial sums, in fp64.  A workgroup owns
+// 64 rows or 64 columns; its 16 waves split the partials.  Leaves per workgroup the sum and the
+// sum of squares of its residuals (for eta and for the stopping test, S6).
+// ------------------------------------------------------------------------------------------
+struct ReduceArgs {
+  VecState V;
+  const float* rowpart;
+  const float* colpart;
+  const float* p;
+  const float* q;
+  int m, n, nseg, ntr, nbm, nbn;
+  int cgroup;  // 1, or kColGroup: consecutive rows of colpart are first added up in fp32, in groups of that many
+};
+
+constexpr int kReduceThreads = 1024;
+
+// First part: the partial sums of 64 entries split 16 ways (share c takes the partials c, c + 16,
+// ...), each share added up in order.  NW waves: wave w forms the shares w, w + NW, ... of entry
+// idx and leaves them in red[share][lane]; nz_out counts the nonzero partials this wave saw.
+template <int NW>
+__device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, int& nz_out) {
+  static_assert(16 % NW == 0, "the 16 shares are dealt out to the waves");
+  const int t = threadIdx.x;
+  const int sub = t >> 6, l = t & 63;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
+  const int len = rows ? A.m : A.n;
+  const bool grouped = !rows && A.cgroup == kColGroup;
+  const int nparts = rows ? A.nseg : grouped ? (A.ntr + kColGroup - 1) / kColGroup : A.ntr;
+  const float* __restrict__ part = rows ? A.rowpart : A.colpart;
+  int nz = 0;
+  constexpr int kStride = 16, kBatch = 8;
+#pragma unroll
+  for (int share = sub; share < 16; share += NW) {
+    double acc = 0.0;
+    if (grouped) {
+      // column sums stored per 64-row tile: tiles 4k .. 4k+3 are added first, in fp32 and in order, as
+      // the workgroups of the lean sweep do before they store (a tile past the end adds +0)
+      constexpr int kGroups = kBatch / 2;
+      for (int k0 = share; k0 < nparts; k0 += kStride * kGroups) {
+        float v[kGroups][kColGroup];
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b)
+#pragma unroll
+          for (int g = 0; g < kColGroup; ++g) {
+            const int k = (k0 + b * kStride) * kColGroup + g;
+            v[b][g] = (idx < len && k < A.ntr) ? part[(size_t)k * len + idx] : 0.f;
+          }
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b)
+          if (k0 + b * kStride < nparts) acc += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
+      }
+    }
+    for (int k0 = share; !grouped && k0 < nparts; k0 += kStride * kBatch) {  // (nparts and share are wave-uniform)
+      // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
+      // trip would wait for memory once per partial sum)
+      float v[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int k = k0 + b * kStride;
+        v[b] = (idx < len && k < nparts) ? part[(size_t)k * len + idx] : 0.f;
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        if (k0 + b * kStride < nparts) acc += (double)v[b];
+        nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f));
+      }
+    }
+    red[share * 64 + l] = acc;
+  }
+  nz_out = nz;
+}
+
+// Second part, after the one barrier that follows the first: wave 0 adds the 16 shares of its 64
+// entries (a fixed tree, the one sum_partials_16 ends with), forms the residuals and leaves the
+// workgroup's sum, sum of squares and count.  Returns the residual of entry idx in threads
+// 0 .. 63 (0 elsewhere).  pq: p_idx or q_idx, fetched by the caller along with the partial sums
+// (reduce_entry_pq) so that no second trip to memory follows the barrier.
+__device__ __forceinline__ float reduce_entry_pq(const ReduceArgs& A) {
+  const int t = threadIdx.x;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  return (t < 64 && idx < (rows ? A.m : A.n)) ? (rows ? A.p[idx] : A.q[idx]) : 0.f;
+}
+
+template <int NW>
+__device__ __forceinline__ double reduce_finish(const ReduceArgs& A, const double* red, const int* nzw, float pq) {
+  const int t = threadIdx.x;
+  if (t >= 64) return 0.0;
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  const int len = rows ? A.m : A.n;
+  double w[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) w[k] = red[k * 64 + t];
+  const double total = (((w[0] + w[8]) + (w[4] + w[12])) + ((w[2] + w[10]) + (w[6] + w[14]))) +
+                       (((w[1] + w[9]) + (w[5] + w[13])) + ((w[3] + w[11]) + (w[7] + w[15])));
+  double res = 0.0;
+  if (idx < len) {
+    res = total - (double)pq;
+    (rows ? A.V.r : A.V.s)[idx] = res;
+  }
+  const double sum = wave_sum_f64(res), sumsq = wave_sum_f64(res * res);
+  if (t == 0) {
+    A.V.part[blockIdx.x] = sum;
+    A.V.part[A.nbm + A.nbn + blockIdx.x] = sumsq;
+    int cnt = 0;
+    for (int k = 0; k < NW; ++k) cnt += nzw[k];
+    A.V.part[2 * (A.nbm + A.nbn) + blockIdx.x] = (double)cnt;
+  }
+  return res;
+}
+
+__global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
+  if (*A.V.done) return;
+  constexpr int NW = kReduceThreads / 64;
+  __shared__ double red[16 * 64];
+  __shared__ int nzw[NW];
+  int nz;
+  const float pq = reduce_entry_pq(A);
+  reduce_gather<NW>(A, red, nz);
+  if ((threadIdx.x & 63) == 0) nzw[threadIdx.x >> 6] = nz;
+  __syncthreads();
+  reduce_finish<NW>(A, red, nzw, pq);
+}
+
+// ------------------------------------------------------------------------------------------
+// S5, second half: eq. (6) with f = 1_m, e = 1_n.  eta = 1^T r/(m+n); phi+ = (a - 2r + (2 eta -
+// theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m, a -= r, b -= s, theta -= eta.  fp64; phi and
+// varphi are rounded to fp32 for the sweep.  Every workgroup re-derives eta from the per-workgroup
+// sums (a few hundred doubles); workgroup 0 also stores theta+ and the squared residual norms.
+// ------------------------------------------------------------------------------------------
+struct UpdateArgs {
+  VecState V;
+  const float* tilesum;  // non-null: eta from the tile totals, exactly as the fused update computes it
+  int ntiles;
+  const double* a_in;  // a, b before the update and after it (the two halves of a double buffer)
+  const double* b_in;
+  double* a_out;
+  double* b_out;
+  int m, n, nbm, nbn, par;
+};
+
+// ||r||^2, ||s||^2 and the number of nonzero row-segment sums from the per-workgroup sums of the reduction.
+__device__ __forceinline__ void sum_residual_norms(const VecState& V, int nbm, int nbn, double* red) {
+  const int t = threadIdx.x;
+  double r2 = 0.0, s2 = 0.0;
+  const double* sq = V.part + nbm + nbn;
+  for (int e = t; e < nbm; e += kReduceThreads) r2 += sq[e];
+  for (int e = t; e < nbn; e += kReduceThreads) s2 += sq[nbm + e];
+  double nzs = 0.0;
+  const double* cnt = V.part + 2 * (nbm + nbn);
+  for (int e = t; e < nbm; e += kReduceThreads) nzs += cnt[e];
+  r2 = block_sum_f64(r2, red);
+  s2 = block_sum_f64(s2, red);
+  nzs = block_sum_f64(nzs, red);
+  if (t == 0) {
+    V.resid[0] = r2;
+    V.resid[1] = s2;
+    V.resid[2] = nzs;
+  }
+}
+
+// The update for all m + n entries by one workgroup (all = true: it strides over them) or for the
+// 1024 entries of workgroup `vb` (all = false); the arithmetic per entry is the same either way.
+__device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, bool all, double* red) {
+  const int t = threadIdx.x;
+  double acc = 0.0;
+  if (A.tilesum) {
+    for (int e = t; e < A.ntiles; e += kReduceThreads) acc += (double)A.tilesum[e];
+  } else {
+    for (int e = t; e < A.nbm; e += kReduceThreads) acc += A.V.part[e];
+  }
+  double sum_r = block_sum_f64(acc, red);
+  if (A.tilesum) sum_r -= *A.V.sum_p;
+  const double mn = (double)A.m + (double)A.n;
+  const double eta = sum_r / mn;
+  const double theta = A.V.theta[A.par];
+  const double cst = 2.0 * eta - theta;
+  const long long total = (long long)A.m + A.n;
+  const long long first = all ? t : (long long)vb * kReduceThreads + t;
+  const long long step = all ? kReduceThreads : total;  // (all = false: one entry per thread)
+  for (long long g = first; g < total; g += step) {
+    if (g < A.m) {
+      const double r = A.V.r[g], ai = A.a_in[g];
+      A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
+      A.a_out[g] = ai - r;
+    } else {
+      const long long j = g - A.m;
+      const double sj = A.V.s[j], bj = A.b_in[j];
+      A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
+      A.b_out[j] = bj - sj;
+    }
+  }
+  if ((all || vb == 0) && t == 0) A.V.theta[A.par ^ 1] = theta - eta;
+}
+
+__global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
+  if (*A.V.done) return;
+  __shared__ double red[kReduceThreads];
+  update_body(A, (int)blockIdx.x, false, red);
+}
+
+// What the stopping test and the host's choice of scheme read, after a reduce_update_kernel (which
+// leaves the per-workgroup sums only).  One workgroup; launched before a status_kernel.
+__global__ __launch_bounds__(kReduceThreads) void residual_norms_kernel(VecState V, int nbm, int nbn) {
+  if (*V.done) return;
+  __shared__ double red[kReduceThreads];
+  sum_residual_norms(V, nbm, nbn, red);
+}
+
+// Both halves of S5 in one launch, for the sweeps on 64-row tiles of large problems.  What stands
+// between the two halves is one number, eta = (1^T X 1 - 1^T p)/(m+n); with the totals of the tiles
+// at hand (the sweep stores them) every workgroup forms it by itself, then reduces its 64 rows or
+// columns and updates them on the spot.  Tile totals: rows in groups of 8 in order, the 8 groups
+// in order (fp32), then four tiles stacked along the rows in order (in the lean sweep's workgroups,
+// or here: tgroup), then all of it in fp64 in a fixed order.
+struct TileTotals {
+  const float* tilesum;  // [tile_rows][nseg], or one entry per kColGroup tile rows (tgroup = 1)
+  int tile_rows;         // rows of tilesum
+  int nseg;
+  int tgroup;            // kColGroup: add tile rows 4k .. 4k+3 first; 1: stored that way
+};
+
+// The lean sweep's refresh schedule rides along (last workgroup): see ScreenCtl above.
+struct ScreenCtlArgs {
+  int* ctl;              // the control words
+  const int* wg_reads;   // [nwg] what the lean sweep's workgroups read
+  int nwg;
+  int mode;              // 0: nothing; 1: the sweep was a refresh ordered by the host: start afresh; 2: account for a lean sweep
+  int price;             // rent that buys a renewal, in row segments of C
+  int max_since;         // renew after this many lean sweeps at the latest
+};
+
+// (8 waves: every workgroup of a 40000-entry problem is resident at once.  The tile totals are dealt
+// out to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...)
+constexpr int kMergedWaves = 8;
+
+__global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T,
+                                                                          ScreenCtlArgs K) {
+  // (the stop flag travels with the other loads and is tested before the first store: a test up
+  // front would put one more trip to memory ahead of everything)
+  const int stop = *A.V.done;
+  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW);
+  __shared__ double red[16 * 64];
+  __shared__ double eta_part[kShares / 64];
+  __shared__ int nzw[NW];
+  __shared__ int readw[NW];
+  const int t = threadIdx.x;
+  // the schedule keeper adds up what the lean sweep read (its loads leave with everybody else's)
+  const bool keeper = K.mode == 2 && blockIdx.x == gridDim.x - 1;
+  int nread = 0, renewed = 0;
+  if (keeper) {
+    renewed = K.ctl[kCtlRenew];
+    constexpr int kBatch = 8;
+    for (int e0 = t; e0 < K.nwg; e0 += 64 * NW * kBatch) {
+      int v[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b * 64 * NW;
+        v[b] = e < K.nwg ? K.wg_reads[e] : 0;
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) nread += v[b];
+    }
+  }
+  // eq. (6) inputs of this thread's entry, fetched early
+  const bool rows = (int)blockIdx.x < A.nbm;
+  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
+  const bool owner = t < 64 && idx < (rows ? A.m : A.n);
+  const double ab_in = owner ? (rows ? U.a_in[idx] : U.b_in[idx]) : 0.0;
+  const double theta = A.V.theta[U.par], sum_p = *A.V.sum_p;
+  const float pq = reduce_entry_pq(A);
+  // the shares of the tile totals: batches of independent loads, added in index order
+  double acc[kPerThread];
+#pragma unroll
+  for (int s = 0; s < kPerThread; ++s) {
+    acc[s] = 0.0;
+    const int v0 = t + s * 64 * NW;
+    if (T.tgroup == kColGroup) {
+      constexpr int kGroups = 4;
+      const int ngroups = ((T.tile_rows + kColGroup - 1) / kColGroup) * T.nseg;
+      for (int e0 = v0; e0 < ngroups; e0 += kShares * kGroups) {
+        float v[kGroups][kColGroup];
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b) {
+          const int e = e0 + b * kShares;
+          const int k = e / T.nseg, sg = e - k * T.nseg;
+#pragma unroll
+          for (int g = 0; g < kColGroup; ++g) {
+            const int tr = k * kColGroup + g;
+            v[b][g] = (e < ngroups && tr < T.tile_rows) ? T.tilesum[tr * T.nseg + sg] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int b = 0; b < kGroups; ++b) acc[s] += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
+      }
+    } else {
+      constexpr int kBatch = 8;
+      const int ngroups = T.tile_rows * T.nseg;
+      for (int e0 = v0; e0 < ngroups; e0 += kShares * kBatch) {
+        float v[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+          const int e = e0 + b * kShares;
+          v[b] = e < ngroups ? T.tilesum[e] : 0.f;
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) acc[s] += (double)v[b];
+      }
+    }
+  }
+  int nz;
+  reduce_gather<NW>(A, red, nz);
+#pragma unroll
+  for (int s = 0; s < kPerThread; ++s) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc[s] += __shfl_xor(acc[s], off, 64);
+    if ((t & 63) == 0) eta_part[(t >> 6) + s * NW] = acc[s];
+  }
+  if (keeper) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nread += __shfl_xor(nread, off, 64);
+  }
+  if ((t & 63) == 0) {
+    nzw[t >> 6] = nz;
+    readw[t >> 6] = nread;
+  }
+  __syncthreads();
+  if (stop) return;
+  if (t == 0 && blockIdx.x == gridDim.x - 1 && K.mode != 0) {
+    if (K.mode == 1 || renewed) {  // new bounds: nothing paid yet, the floor is what the next sweep reads
+      K.ctl[kCtlRenew] = 0;
+      K.ctl[kCtlSince] = 0;
+      K.ctl[kCtlFloor] = -1;
+      K.ctl[kCtlPaid] = 0;
+    } else {
+      int total = 0;
+      for (int k = 0; k < NW; ++k) total += readw[k];
+      const int since = K.ctl[kCtlSince] + 1;
+      int floor_reads = K.ctl[kCtlFloor], paid = K.ctl[kCtlPaid];
+      if (floor_reads < 0) floor_reads = total;
+      else if (total > floor_reads) paid += total - floor_reads;
+      K.ctl[kCtlSince] = since;
+      K.ctl[kCtlFloor] = floor_reads;
+      K.ctl[kCtlPaid] = paid;
+      if (paid >= K.price || since >= K.max_since) K.ctl[kCtlRenew] = 1;
+    }
+  }
+  const double res = reduce_finish<NW>(A, red, nzw, pq);
+  if (t >= 64) return;
+  double total = 0.0;
+  for (int k = 0; k < kShares / 64; ++k) total += eta_part[k];
+  const double eta = (total - sum_p) / ((double)A.m + (double)A.n);
+  const double cst = 2.0 * eta - theta;
+  if (owner) {
+    if (rows) {
+      A.V.phi[idx] = (float)((ab_in - 2.0 * res + cst) / (double)A.n);
+      U.a_out[idx] = ab_in - res;
+    } else {
+      A.V.varphi[idx] = (float)((ab_in - 2.0 * res + cst) / (double)A.m);
+      U.b_out[idx] = ab_in - res;
+    }
+  }
+  if (blockIdx.x == 0 && t == 0) A.V.theta[U.par ^ 1] = theta - eta;
+}

@@ -31,7 +31,7 @@ def _rand_problem(m, n, seed, uniform=False):
 
 
 # ---------------------------------------------------------------------------------------------
-# projection onto the marginal constraints (Section 2.1: "the projection onto X is easy")
+# projection onto the marginal constraints (Section 2.1, the closed form of eq. (5))
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("m,n", [(3, 5), (4, 4), (7, 2), (1, 6), (5, 1)])
 def test_projection_equals_dense_least_squares(oracle, m, n):
