@@ -8,7 +8,7 @@
 // segment when n is not a multiple of 256: only there do lanes check how many of their 4
 // columns exist.  NT marks the accesses non-temporal (used when X and C cannot stay in cache).
 //
-// Alignment (what the paper's "shifted work areas" of Section "General Optimization" are for):
+// Alignment (what the shifted work areas of the paper's Section "General Optimization" are for):
 // row segments that straddle 128-byte lines cost 10-28 % here, so the host hands this kernel
 // rows that start on a line: the caller's arrays when n % 32 == 0 and the base is aligned, else
 // working copies with the pitch rounded up to 32 elements (ldx, ldc).
