@@ -147,7 +147,8 @@ def main() -> int:
         # C on the fraction c_frac of its row segments; X read and written back only on the fraction
         # frac of its entries that lie in nonzero row segments (lean kernel: in nonzero 128-byte
         # lines) -- an upper bound, a piece is charged as a whole; per row segment the old and the
-        # new row sum (+ the bound M of the screening, + two bytes of line flags in the lean kernel);
+        # new row sum and the bound M of the screening (lean kernel: the new sum, the bound and two
+        # bytes of line flags, which stand in for the old sum);
         # the column sums per 64-row tile (per four of them in the lean kernel)
         nseg = (n + SEG_COLS - 1) // SEG_COLS
         return (4.0 * c_frac * m * n + 8.0 * frac * m * n + per_segment * m * nseg +
@@ -159,7 +160,7 @@ def main() -> int:
         if kind == 7:
             if "v" not in line_frac:
                 line_frac["v"] = nonzero_line_fraction()
-            return sparse_sweep_bytes(line_frac["v"], c_read.get(kind, 1.0), True, 256, 14.0)
+            return sparse_sweep_bytes(line_frac["v"], c_read.get(kind, 1.0), True, 256, 10.0)
         if kind in (4, 5, 6):
             return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 64, 12.0 if kind != 4 else 8.0)
         if kind == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:

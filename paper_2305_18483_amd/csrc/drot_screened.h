@@ -181,15 +181,17 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
 
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
   const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
-  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
-  unsigned oldlines = 0;  // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31)
+  float ph = kMaskedOut, mpr = 0.f;
+  // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31).  From
+  // the flags the previous lean sweep left; after any other sweep from the row sums (nonzero sum:
+  // any line may hold something)
+  unsigned oldlines = 0;
   if (lane < nrows) {
-    prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
     ph = A.phi[r0 + lane];
     mpr = SC.mprime_in[ridx];
-    oldlines = SC.lines_in ? SC.lines_in[ridx] : 0xffu;
+    if (SC.lines_in) oldlines = SC.lines_in[ridx];
+    else oldlines = (A.rowpart_prev == nullptr || fbits(A.rowpart_prev[ridx]) != 0) ? 0xffu : 0u;
   }
-  if (fbits(prev) == 0) oldlines = 0;
   // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
   // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
   float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
@@ -202,7 +204,7 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
   const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
   const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
-  const bool certified = lane >= nrows || (!renew && fbits(prev) == 0 && below);
+  const bool certified = lane >= nrows || (!renew && oldlines == 0 && below);
   tile_total = 0.f;
   reads = 0;
   if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
