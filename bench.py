@@ -203,7 +203,7 @@ def main() -> int:
         log(f"nonzero 128-byte lines of X: {line_frac['v']:.3%}; priced at 12 B/element the sweep would read {roofline['dense_model_gbs']:.0f} GB/s")
     if dominant in (4, 5, 6, 7):
         roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the entries of X in nonzero row segments "
-                                   "(lean kernel: in nonzero 128-byte lines; counted on the final plan) + 8-14 B per row segment (old and new "
+                                   "(lean kernel: in nonzero 128-byte lines; counted on the final plan) + 8-12 B per row segment (old and new "
                                    "sums, bound, line flags) + column sums; dense_model_* prices the same launch at 12 B per element")
         roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
         if "v" in line_frac:
