@@ -88,6 +88,25 @@ def test_cfg4_quadratic_20000_reduced_K(drot, oracle):
     _run_case(drot, oracle, drot_inputs.config(4), 12, "cfg4")
 
 
+@pytest.mark.parametrize("cfg,K", [(3, 200), (4, 130)])
+def test_full_size_lean_sweeps_against_the_oracle(drot, oracle, cfg, K):
+    # long enough for the solver to have moved to the lean screened sweep (line flags, its own
+    # renewals), in the launch configuration the benchmark times; the oracle needs half a minute
+    P = drot_inputs.config(cfg)
+    solver = drot.Solver(P.m, P.n)
+    solver.set_profile(True)
+    gres, Xg, ores = _run_case(drot, oracle, P, K, f"cfg{cfg}, lean sweeps", solver=solver)
+    kinds = [k for _, k in solver.profile_sweeps()]
+    solver.set_profile(False)
+    assert kinds.count(7) >= 20, kinds
+    # fp64 properties of the returned plan that hold at any size
+    X = torch.from_numpy(Xg).to("cuda:0").double()
+    r = float((X.sum(dim=1) - torch.from_numpy(P.p).to("cuda:0").double()).norm())
+    s_ = float((X.sum(dim=0) - torch.from_numpy(P.q).to("cuda:0").double()).norm())
+    assert float(X.min()) >= 0.0
+    assert abs(r - gres.r_row) <= 1e-6 and abs(s_ - gres.r_col) <= 1e-6, (r, gres.r_row, s_, gres.r_col)
+
+
 def test_cfg5_group_lasso_5000_reduced_K(drot, oracle):
     _run_case(drot, oracle, drot_inputs.config(5), 150, "cfg5")
 
