@@ -107,7 +107,9 @@ int drot_set_compute_gap(drot_handle h, int enable);
  * iteration from the state the previous solve on this handle left (phi, varphi and the running
  * sums of eq. (6) in the workspace, the plan in X_out, which must still hold that solve's output;
  * same m, n, C, p, q and regularizer are the caller's responsibility).  Running K1 then K2
- * iterations this way gives bit-for-bit the iterate of one K1+K2 solve.  INVALID_ARG at the next
+ * iterations this way gives bit-for-bit the iterate of one K1+K2 solve, unless the automatic
+ * even/odd scheme (drot_set_skip_cost) comes into play: when it starts depends on where the
+ * calls and their stretches of check_every iterations begin.  INVALID_ARG at the next
  * solve if no solve has run or the sizes differ.  drot_info.iters counts the iterations of the call.
  */
 int drot_set_continue(drot_handle h, int enable);
@@ -185,7 +187,8 @@ int drot_set_resident(drot_handle h, int mode);
  * the nonzero row segments, the host reads the count with the status of every stretch of
  * check_every iterations (one stretch late, without waiting), and switches to the pairs while more
  * than 70 % of the segments are nonzero and back below 50 %.  With a switch the result depends,
- * within rounding, on check_every.  mode 1: pairs wherever they apply; mode 0: never.
+ * within rounding, on check_every and on how a solve is cut into continued calls.  mode 1: pairs
+ * wherever they apply; mode 0: never.
  */
 int drot_set_skip_cost(drot_handle h, int mode);
 
