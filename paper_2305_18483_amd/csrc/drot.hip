@@ -604,7 +604,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // and the host reads with the status of every stretch of check_every iterations, one stretch late.
   const dim3 update_grid(ceil_div(m + n, kReduceThreads));
   const bool can_pair = reg_kind != DROT_REG_GROUP_LASSO && !fused && !from_points;
-  const bool adaptive = can_pair && !small && h->skip_cost == -1 && h->skip_unchanged != 0;
+  // (two decisions hang on the density the reduction reports: pairs or not, when that is left to the
+  // library, and whether the screened sweeps may use their lean kernel)
+  const bool adaptive_pairs = can_pair && !small && h->skip_cost == -1 && h->skip_unchanged != 0;
+  const bool may_screen = can_pair && !small && h->skip_cost != 1 && h->skip_unchanged != 0 &&
+                          (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= ((size_t)1 << 24)));
+  const bool adaptive = adaptive_pairs || may_screen;
   bool dense_plan = resume && h->dense_plan;  // (a continued solve keeps what the last one found)
   double plan_density = resume ? h->plan_density : -1.0;  // fraction of nonzero row segments, once a status has come back
   constexpr int kTallRows = 8, kTallWaves = 8;
@@ -664,18 +669,19 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     if (checking || adaptive) {
       const int to_check = h->check_every - k % h->check_every;  // the tests stay at multiples of check_every
       if (to_check < chunk) chunk = to_check;
-      if (adaptive && !(plan_density >= 0.0 && plan_density < 0.25)) {
-        // how sparse the plan is decides the sweep: until it is known to be sparse, have a look after
-        // 16, 32 and 64 iterations too (a plan is dense in its first iterations, whatever it becomes:
-        // these early readings can move the solver to the lean sweep, never to the even/odd pairs)
-        const int next = k < 16 ? 16 : k < 32 ? 32 : k < 64 ? 64 : 0;
+      if (adaptive && !resume && k < 512) {
+        // how sparse the plan is decides the sweep, and a cold start goes through phases (empty, then
+        // dense, then as sparse as it will be, or not): over the first 512 iterations have a look
+        // after 16 and then every 32 iterations too.  These early readings can move the solver to the
+        // lean sweep and away from it again, never to the even/odd pairs.
+        const int next = k < 16 ? 16 : (k / 32 + 1) * 32;
         if (next > 0 && next - k < chunk) {
           chunk = next - k;
           probe = true;
         }
       }
     }
-    const bool skip_cost = can_pair && (h->skip_cost == 1 || (adaptive && dense_plan));
+    const bool skip_cost = can_pair && (h->skip_cost == 1 || (adaptive_pairs && dense_plan));
     const bool tall = !small && !skip_cost && !from_points && reg_kind != DROT_REG_GROUP_LASSO && h->skip_unchanged != 0;
     if (resident) {
       const long long sw = k_base + k + 1;         // first sweep of the stretch
@@ -754,8 +760,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
         // (automatic: from 16 M entries up; below that the whole of C streams from the caches as fast)
-        const bool screened = mode == 0 && tall && !first &&
-                              (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= ((size_t)1 << 24)));
+        const bool screened = mode == 0 && tall && !first && may_screen;
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
         sums_gen = mode == 1 ? -1 : sw;
         // once the plan is known to be sparse (and bounds exist): one wave per tile, walking through the few
@@ -870,7 +875,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         if (adaptive) {  // (hysteresis: the break-even is at about three quarters of the segments nonzero)
           const double density = h->host_status[slot ^ 1].nz_segments / ((double)m * (double)nseg);
           plan_density = density;
-          if (density > 0.7 && !was_probe[slot ^ 1]) dense_plan = true;
+          if (density > 0.7 && !was_probe[slot ^ 1]) dense_plan = adaptive_pairs;
           else if (density < 0.5) dense_plan = false;
         }
       }

@@ -551,6 +551,33 @@ def test_early_looks_at_the_density_start_the_lean_sweep_before_the_first_check(
     assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
 
 
+def test_lean_sweep_does_not_depend_on_the_even_odd_option(drot):
+    # the density readings that let the screened sweeps use their lean kernel are taken whether or not
+    # the choice of the even/odd pairs is left to the library; cut into continued calls at odd places,
+    # the solve lands on the same bits
+    P = drot_inputs.random_problem(2100, 8192 + 40, seed=1601, d=6, reg_kind=0)
+    solver = drot.Solver(P.m, P.n, check_every=50)
+    solver.set_skip_cost(0)
+    _say("lean sweep with the even/odd scheme switched off")
+    K = 240
+    solver.set_screening(0)
+    _, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
+    solver.set_screening(1)
+    solver.set_profile(True)
+    _, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
+    kinds = [k for _, k in solver.profile_sweeps()]
+    solver.set_profile(False)
+    assert kinds.count(7) > 20, kinds
+    assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
+    Xc = torch.empty((P.m, P.n), device="cuda:0")
+    pu.gpu_solve(solver, P, 97, tol=1e-12, X_out=Xc)
+    solver.set_continue(True)
+    pu.gpu_solve(solver, P, 11, tol=1e-12, X_out=Xc)
+    _, X3, phi3, varphi3 = pu.gpu_solve(solver, P, K - 108, tol=1e-12, X_out=Xc)
+    solver.set_continue(False)
+    assert np.array_equal(X3, X_plain) and np.array_equal(phi3, phi_plain) and np.array_equal(varphi3, varphi_plain)
+
+
 def test_dense_plans_switch_to_the_even_odd_scheme(drot, oracle):
     # a strong quadratic term keeps the plan dense: the density the reduction reports must move the
     # solver from the zero-segment-skipping sweeps to the even/odd pairs (and the result must not care)
