@@ -41,7 +41,7 @@ BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0, 3: 12.0}  # by kind of sweep: rea
 # copy kernel of known size (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC_BYTES = {  # (workload, kind of sweep); profiles/sweep_kernel_cfg4_20000.md
     ("cfg4_quad_20000", 0): 4.8565e9, ("cfg4_quad_20000", 1): 4.8565e9, ("cfg4_quad_20000", 2): 3.2565e9,
-    ("cfg4_quad_20000", 4): 1.6957e9, ("cfg4_quad_20000", 7): 1.0870e8}
+    ("cfg4_quad_20000", 4): 1.6957e9, ("cfg4_quad_20000", 7): 9.271e7}
 SEG_COLS = 256  # columns of a row segment, the unit of the zero-segment skipping
 
 
