@@ -12,7 +12,8 @@
 // If S plus a rounding margin is <= 0 and the segment of X is zero, the segment stays zero: its C is
 // not read, nothing is computed, its row sum is 0.  The result is the one the plain sweep would
 // produce (the margin dominates the handful of fp32 roundings between the two evaluations).  As
-// varphi drifts away from varphi0 fewer segments certify; the host refreshes every so many sweeps.
+// varphi drifts away from varphi0 fewer segments certify, so the bounds are renewed now and then: on
+// the host's schedule while this kernel is in use, on the device's own in the lean kernel below.
 // Tiles: 8 waves x 8 rows x 256 columns, as the unscreened sweep for sparse plans.
 // ------------------------------------------------------------------------------------------
 struct ScreenArgs {
@@ -22,7 +23,7 @@ struct ScreenArgs {
   int* wave_reads;          // 8-wave tiles, profiling only (else null): [workgroup][wave] row segments of C this wave read
   // lean sweep only: it renews the bounds by itself when the vector update before it has raised ctl[0]
   float* varphi0_out;       // [n]
-  const int* ctl;           // kCtl... words, see ScreenCtl
+  const int* ctl;           // the control words below (kCtlRenew ...)
   int* wg_reads;            // [workgroup] row segments of C the workgroup read (always written)
   // lean sweep only: which of the eight 128-byte lines of a row segment of X hold a nonzero
   const unsigned char* lines_in;  // [nseg][m] as left by the previous sweep if that was a lean one, else null
@@ -160,11 +161,14 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
 }
 
 // The screened sweep for plans known to be sparse (a few percent of the row segments left to
-// process): one wave owns a whole 64 x 256 tile, lane l holding the old sum, phi and M of row l.
-// It decides all 64 rows at once and then walks through the rows left over, one at a time.  No
-// LDS, no barrier; 8 times fewer waves than the tile of 8 waves x 8 rows, and the same bits: the
-// rows of every group of 8 are added up in order and the 8 groups in order, which is what that
-// tile's waves and its LDS fold do (rows and groups that contribute nothing add +0).
+// process): one wave owns a whole 64 x 256 tile, lane l holding the line flags, phi and M of row l.
+// It decides all 64 rows at once and then walks through the rows left over, four at a time (their
+// loads overlap; the arithmetic stays in row order).  The waves of a workgroup work on their own
+// and meet once, at the end (screened_lean_kernel).  8 times fewer waves than the tile of 8 waves x
+// 8 rows, and the same bits: the rows of every group of 8 are added up in order and the 8 groups in
+// order, which is what that tile's waves and its LDS fold do (rows and groups that contribute
+// nothing add +0).  Returns the tile's column sums; tile_total: its total, added up the same way;
+// reads: how many row segments of C it fetched.
 template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
                                                   int stop, bool renew, float& tile_total, int& reads) {

@@ -317,7 +317,7 @@ struct TileTotals {
   int tgroup;            // kColGroup: add tile rows 4k .. 4k+3 first; 1: stored that way
 };
 
-// The lean sweep's refresh schedule rides along (last workgroup): see ScreenCtl above.
+// The lean sweep's refresh schedule rides along (last workgroup): the control words kCtlRenew ... of the screened sweeps.
 struct ScreenCtlArgs {
   int* ctl;              // the control words
   const int* wg_reads;   // [nwg] what the lean sweep's workgroups read
