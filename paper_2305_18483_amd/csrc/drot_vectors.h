@@ -223,7 +223,8 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_kernel(ReduceArgs A) {
 // S5, second half: eq. (6) with f = 1_m, e = 1_n.  eta = 1^T r/(m+n); phi+ = (a - 2r + (2 eta -
 // theta))/n, varphi+ = (b - 2s + (2 eta - theta))/m, a -= r, b -= s, theta -= eta.  fp64; phi and
 // varphi are rounded to fp32 for the sweep.  Every workgroup re-derives eta from the per-workgroup
-// sums (a few hundred doubles); workgroup 0 also stores theta+ and the squared residual norms.
+// sums (a few hundred doubles); workgroup 0 also stores theta+.  The squared residual norms are
+// summed over the workgroups only where somebody reads them (residual_norms_kernel).
 // ------------------------------------------------------------------------------------------
 struct UpdateArgs {
   VecState V;
@@ -256,9 +257,8 @@ __device__ __forceinline__ void sum_residual_norms(const VecState& V, int nbm, i
   }
 }
 
-// The update for all m + n entries by one workgroup (all = true: it strides over them) or for the
-// 1024 entries of workgroup `vb` (all = false); the arithmetic per entry is the same either way.
-__device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, bool all, double* red) {
+// The update of the 1024 entries of workgroup vb (rows first, then columns), one per thread.
+__device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, double* red) {
   const int t = threadIdx.x;
   double acc = 0.0;
   if (A.tilesum) {
@@ -272,28 +272,24 @@ __device__ __forceinline__ void update_body(const UpdateArgs& A, int vb, bool al
   const double eta = sum_r / mn;
   const double theta = A.V.theta[A.par];
   const double cst = 2.0 * eta - theta;
-  const long long total = (long long)A.m + A.n;
-  const long long first = all ? t : (long long)vb * kReduceThreads + t;
-  const long long step = all ? kReduceThreads : total;  // (all = false: one entry per thread)
-  for (long long g = first; g < total; g += step) {
-    if (g < A.m) {
-      const double r = A.V.r[g], ai = A.a_in[g];
-      A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
-      A.a_out[g] = ai - r;
-    } else {
-      const long long j = g - A.m;
-      const double sj = A.V.s[j], bj = A.b_in[j];
-      A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
-      A.b_out[j] = bj - sj;
-    }
+  const long long g = (long long)vb * kReduceThreads + t;
+  if (g < A.m) {
+    const double r = A.V.r[g], ai = A.a_in[g];
+    A.V.phi[g] = (float)((ai - 2.0 * r + cst) / (double)A.n);
+    A.a_out[g] = ai - r;
+  } else if (g < (long long)A.m + A.n) {
+    const long long j = g - A.m;
+    const double sj = A.V.s[j], bj = A.b_in[j];
+    A.V.varphi[j] = (float)((bj - 2.0 * sj + cst) / (double)A.m);
+    A.b_out[j] = bj - sj;
   }
-  if ((all || vb == 0) && t == 0) A.V.theta[A.par ^ 1] = theta - eta;
+  if (vb == 0 && t == 0) A.V.theta[A.par ^ 1] = theta - eta;
 }
 
 __global__ __launch_bounds__(kReduceThreads) void update_kernel(UpdateArgs A) {
   if (*A.V.done) return;
   __shared__ double red[kReduceThreads];
-  update_body(A, (int)blockIdx.x, false, red);
+  update_body(A, (int)blockIdx.x, red);
 }
 
 // What the stopping test and the host's choice of scheme read, after a reduce_update_kernel (which
