@@ -159,7 +159,7 @@ int drot_set_skip_unchanged(drot_handle h, int mode);
  * unscreened sweeps, bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first, at
  * most 256 apart; once the plan is known to be sparse the sweep itself decides, on the device, when
  * the reads that weakened bounds cost it have added up to the price of new ones.  mode -1 screens
- * problems of 2^24 entries and more (smaller ones stream all of C from the caches just as fast),
+ * problems of 11.5 million entries and more (smaller ones stream all of C from the caches just as fast),
  * mode 1 every problem the skipping applies to, mode k >= 2 the same with the bounds renewed at
  * least every k-th sweep; mode 0 reads C in full every sweep.
  */

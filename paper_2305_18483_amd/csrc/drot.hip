@@ -70,6 +70,10 @@ void launch_slab(bool first, bool pro, int k, dim3 grid, hipStream_t stream, con
 }
 
 constexpr int kMaxProfiled = 256;  // sweeps timed per solve in profile mode
+// Screening on automatic: from this many entries up (about 3400 x 3400).  Measured to a residual of
+// 1e-4 on two kinds of problem: equal at 3000 x 3000, 15 % faster at 3500 x 3500, 30-40 % at
+// 4096 x 4096 and 5000 x 5000; below, the whole of C streams from the caches as fast.
+constexpr size_t kScreenFrom = (size_t)11 << 20;
 
 }  // namespace
 
@@ -83,7 +87,7 @@ struct drot_handle_s {
   int force_two_pass = 0; // group lasso: always take the general two-pass path
   int nontemporal = -1;   // -1: by problem size, 0: never, 1: always
   int screening = -1;       // sparse plans also skip the reads of C that a bound certifies useless: -1 for problems
-                            // of 16 M entries and more, 1 always, k >= 2 always and with the bounds renewed at
+                            // of kScreenFrom entries and more, 1 always, k >= 2 always and with the bounds renewed at
                             // least every k sweeps (default 256), 0 never
   int skip_unchanged = -1;  // -1/1: unchanged row segments are not written back, 0: every segment is stored
   bool dense_plan = false;  // what the last solve's density feedback ended on
@@ -608,7 +612,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   // library, and whether the screened sweeps may use their lean kernel)
   const bool adaptive_pairs = can_pair && !small && h->skip_cost == -1 && h->skip_unchanged != 0;
   const bool may_screen = can_pair && !small && h->skip_cost != 1 && h->skip_unchanged != 0 &&
-                          (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= ((size_t)1 << 24)));
+                          (h->screening > 0 || (h->screening == -1 && (size_t)m * (size_t)n >= kScreenFrom));
   const bool adaptive = adaptive_pairs || may_screen;
   bool dense_plan = resume && h->dense_plan;  // (a continued solve keeps what the last one found)
   double plan_density = resume ? h->plan_density : -1.0;  // fraction of nonzero row segments, once a status has come back
@@ -759,7 +763,6 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
           const int paired_from = chunk & 1;  // index in the chunk of the first paired sweep
           if (c >= paired_from) mode = ((c - paired_from) & 1) ? 2 : 1;
         }
-        // (automatic: from 16 M entries up; below that the whole of C streams from the caches as fast)
         const bool screened = mode == 0 && tall && !first && may_screen;
         S.rowpart_prev = (mode == 0 && sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
         sums_gen = mode == 1 ? -1 : sw;

@@ -443,7 +443,7 @@ def test_screening_changes_no_bit(drot, oracle, kind, m, n):
     K = 300
     solver.set_screening(0)
     res_plain, X_plain, phi_plain, varphi_plain = pu.gpu_solve(solver, P, K, tol=1e-12)
-    solver.set_screening(1)  # (automatic mode starts at 2^24 entries)
+    solver.set_screening(1)  # (automatic mode starts at 11.5 million entries)
     solver.set_profile(True)
     res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
     kinds = [kind_ for _, kind_ in solver.profile_sweeps()]
