@@ -107,6 +107,35 @@ def test_full_size_lean_sweeps_against_the_oracle(drot, oracle, cfg, K):
     assert abs(r - gres.r_row) <= 1e-6 and abs(s_ - gres.r_col) <= 1e-6, (r, gres.r_row, s_, gres.r_col)
 
 
+def test_beyond_the_benchmark_size(drot):
+    # 1.4e9 entries (twice the benchmark's rows, ragged, padded working copies): the indices of every
+    # array stay in range, the screened sweeps give the bits of the unscreened ones, and the residuals
+    # the library reports are those of the returned plan in fp64.  Inputs are made on the device.
+    m, n = 40000, 35007
+    gen = torch.Generator(device="cuda:0").manual_seed(77)
+    xs = torch.randn((m, 3), generator=gen, device="cuda:0")
+    xt = 0.3 + 1.2 * torch.randn((n, 3), generator=gen, device="cuda:0")
+    C = torch.cdist(xs, xt).pow_(2)
+    C /= C.max()
+    p = torch.full((m,), 1.0 / m, device="cuda:0")
+    q = torch.full((n,), 1.0 / n, device="cuda:0")
+    solver = drot.Solver(m, n, compute_gap=False)
+    _say(f"large problem {m}x{n}")
+    outs = []
+    for mode in (0, -1):
+        solver.set_screening(mode)
+        X = torch.empty_like(C)
+        res = solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=260, X_out=X)
+        phi, varphi = solver.duals(m, n, C.device)
+        outs.append((X, phi.clone(), varphi.clone(), res))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
+    X, res = outs[1][0], outs[1][3]
+    assert float(X.min()) >= 0.0
+    r = float((X.sum(dim=1, dtype=torch.float64) - p.double()).norm())
+    s_ = float((X.sum(dim=0, dtype=torch.float64) - q.double()).norm())
+    assert abs(r - res.r_row) <= 1e-6 and abs(s_ - res.r_col) <= 1e-6, (r, res.r_row, s_, res.r_col)
+
+
 def test_cfg5_group_lasso_5000_reduced_K(drot, oracle):
     _run_case(drot, oracle, drot_inputs.config(5), 150, "cfg5")
 
