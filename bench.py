@@ -212,6 +212,9 @@ def main() -> int:
         roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]
         roofline["dense_model_bytes"] = 12.0 * m * n
         roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
+        # (above 1: the sweep does not move the bytes the dense model charges; the leg every_byte_moved
+        # below is the same solver made to move them all, with its own roofline)
+        roofline["dense_model_frac"] = round(roofline["dense_model_gbs"] / HBM_PEAK_GBS, 3)
         log(f"nonzero row segments of X: {frac_nz:.3%}" + (f" (128-byte lines: {line_frac['v']:.4%})" if "v" in line_frac else "") +
             f"; row segments of C read: {c_read.get(dominant, 1.0):.3%}; "
             f"the same sweep priced at 12 B/element would read {roofline['dense_model_gbs']:.0f} GB/s")
