@@ -145,8 +145,8 @@ int drot_set_fused_update(drot_handle h, int mode);
  * nearly every segment is of this kind, and the sweep turns into a read-only stream of C (4 instead
  * of 12 bytes per element).  On problems beyond the fused small-problem path this sweep runs on
  * 64-row tiles.  The group-resident group-lasso sweep of such problems does the same with pieces of
- * 32 columns of a row (one 128-byte line).  The memory contents are the same either way.  mode 0
- * reads and stores everything.
+ * 32 columns of a row (one 128-byte line), and the sweep of drot_solve_points with row segments.
+ * The memory contents are the same either way.  mode 0 reads and stores everything.
  */
 int drot_set_skip_unchanged(drot_handle h, int mode);
 

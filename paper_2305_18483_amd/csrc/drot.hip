@@ -722,6 +722,8 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
       S.tilesum = small ? tsum(sw) : nullptr;
       bool tiles64 = false, lean = false, refresh = false, slab_totals = false;
       if (from_points) {
+        S.rowpart_prev = (sums_gen == sw - 1 && h->skip_unchanged != 0) ? rowp(sw - 1) : nullptr;
+        sums_gen = sw;
         if (first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, S, PT);
         else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, S, PT);
         else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, S, PT);

@@ -54,12 +54,17 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
   const size_t ldx = (size_t)A.ldx;
   float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
 
-  // sweep layout: start the loads of X and of the per-row / per-column vectors
+  // sweep layout: start the loads of X and of the per-row / per-column vectors.  With the old row
+  // sums at hand (X >= 0: a zero sum is an all-zero segment) the flags are fetched here and the few
+  // segments of X that hold something after the matrix phase, which hides the flags' latency.
+  const bool flags = !FIRST && A.rowpart_prev != nullptr;
+  float prev = 1.f;
+  if (flags && lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.m + r0 + lane];
   f4v x[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     x[u] = f4v{0.f, 0.f, 0.f, 0.f};
-    if (!FIRST && u < nrows) {
+    if (!FIRST && !flags && u < nrows) {
       if (NT && nvalid == 4) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(Xp + u * ldx));
       else x[u] = load4(Xp + u * ldx, nvalid);
     }
@@ -104,6 +109,15 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
     dots[R0 + 4 * kk + 2][cb + 16 + r] = acc1.z;
     dots[R0 + 4 * kk + 3][cb + 16 + r] = acc1.w;
   }
+  bool readx[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    readx[u] = __builtin_amdgcn_readlane(fbits(prev), u) != 0;
+    if (flags && u < nrows && readx[u]) {
+      if (NT && nvalid == 4) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(Xp + u * ldx));
+      else x[u] = load4(Xp + u * ldx, nvalid);
+    }
+  }
   __syncthreads();
 
   // sweep phase, as in sweep_body with the cost taken from the tile of inner products
@@ -123,8 +137,12 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
         c.z = cs * fmaxf(fmaf(-2.f, dv.z, xsq + ysq.z), 0.f);
         c.w = cs * fmaxf(fmaf(-2.f, dv.w, xsq + ysq.w), 0.f);
         const f4v v = xbar4(x[u], c, vp + ph, rho) * scale;
-        if (NT && nvalid == 4) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(Xp + u * ldx));
-        else store4(Xp + u * ldx, v, nvalid);
+        // (a segment that was all zero and comes out all zero again is not written back)
+        const bool nonzero = ((fbits(v.x) | fbits(v.y)) | (fbits(v.z) | fbits(v.w))) != 0;
+        if (readx[u] || __builtin_amdgcn_ballot_w64(nonzero) != 0) {
+          if (NT && nvalid == 4) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(Xp + u * ldx));
+          else store4(Xp + u * ldx, v, nvalid);
+        }
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;

@@ -772,6 +772,38 @@ def test_cost_from_point_clouds(drot, oracle, m, n, d, kind):
     _say(f"point-cloud cost: plan error / scale = {ratio:.2e}")
 
 
+@pytest.mark.parametrize("m,n,d,kind", [(333, 517, 3, 0), (1300, 2100, 6, 1), (900, 2300, 2, 0)])
+def test_point_cloud_sweep_skipping_zero_segments_changes_no_bit(drot, m, n, d, kind):
+    # the sweep that recomputes the cost also leaves all-zero row segments of X unread and unwritten;
+    # same bits as with everything moved, from the first iterations on and across a continuation
+    P = drot_inputs.random_problem(m, n, seed=2100 + d, d=d, reg_kind=kind, lam=0.02 if kind else 0.0)
+    scale = float(np.float32(1.0 / P.cmax))
+    dev = torch.device("cuda:0")
+    xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
+    p, q = torch.from_numpy(P.p).to(dev), torch.from_numpy(P.q).to(dev)
+    solver = drot.Solver(m, n, check_every=13)
+    _say(f"point-cloud cost, zero-segment skipping, bitwise, {m}x{n} d={d}")
+    outs = {}
+    for mode in (0, 1):
+        solver.set_skip_unchanged(mode)
+        for K in (1, 2, 40, 150):
+            r = solver.solve_points(xs, xt, scale, p, q, reg_kind=kind, lam=P.lam, max_iters=K, tol=1e-12)
+            phi, varphi = solver.duals(m, n, dev)
+            outs[(mode, K)] = (r.X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy())
+    for K in (1, 2, 40, 150):
+        for a, b in zip(outs[(0, K)], outs[(1, K)]):
+            assert np.array_equal(a, b), K
+    X = torch.empty((m, n), device=dev)
+    solver.solve_points(xs, xt, scale, p, q, reg_kind=kind, lam=P.lam, max_iters=61, tol=1e-12, X_out=X)
+    solver.set_continue(True)
+    r = solver.solve_points(xs, xt, scale, p, q, reg_kind=kind, lam=P.lam, max_iters=89, tol=1e-12, X_out=X)
+    solver.set_continue(False)
+    assert np.array_equal(r.X.cpu().numpy(), outs[(1, 150)][0])
+    Xz = outs[(1, 150)][0]
+    zero_segments = [Xz[:, j:j + 256].max(axis=1) == 0 for j in range(0, n, 256)]
+    assert float(np.mean(zero_segments)) > 0.02  # (some segments really are skipped)
+
+
 def test_ot_cost_gradient_is_the_plan(drot, oracle):
     # Section "Backpropagation through regularized OT-costs": grad_C OT_h(C) = X* when the
     # solution is unique (quadratic term).  Checked against the oracle's plan at convergence and
