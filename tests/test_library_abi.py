@@ -74,3 +74,24 @@ def test_input_generators_are_seeded_and_normalised():
     assert g.row_class.shape == (200,) and g.num_classes == 10 and (np.diff(g.row_class) >= 0).all()
     r = drot_inputs.random_problem(17, 9, seed=4, reg_kind=2, num_classes=3, sorted_classes=False)
     assert r.C.shape == (17, 9) and r.row_class.max() < 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the benchmark runs on one GPU only: any other count ends at once, before anything touches a device
+    import subprocess
+    import sys
+
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+    assert proc.returncode == 2
+    assert "one GPU" in proc.stderr and proc.stdout.strip() == ""
+
+
+def test_product_package_does_not_import_the_oracle():
+    # the oracle is test infrastructure: nothing under the package may import or name it
+    pkg = os.path.join(ROOT, "paper_2305_18483_amd")
+    for base, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".h", ".hip")):
+                text = open(os.path.join(base, name)).read()
+                assert "oracle" not in text.lower(), os.path.join(base, name)
