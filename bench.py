@@ -340,6 +340,9 @@ def main() -> int:
         "config": {"workload": P.name, "m": m, "n": n, "reg_kind": int(P.reg_kind), "lambda": P.lam, "mu": P.mu,
                    "stepsize": float(P.rho), "check_every": args.check_every},
         "algorithmic_bytes_per_iteration": bytes_per_iteration,
+        # (the dense model's 12 B per element over the iteration time: what a solver that moves every
+        # byte would have to sustain to keep up; far above the 8000 GB/s peak when the sweeps skip work)
+        "dense_model_gbs_whole_iteration": round(12.0 * m * n / (ms_per_step * 1e-3) / 1e9, 1),
         "hbm_gbs_whole_iteration": round(bytes_per_iteration / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "time_to_tol": tol_leg, "unscreened": unscreened_leg, "even_odd_scheme": even_odd_leg,
         "every_byte_moved": dense_leg,
