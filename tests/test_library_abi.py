@@ -95,3 +95,19 @@ def test_product_package_does_not_import_the_oracle():
             if name.endswith((".py", ".h", ".hip")):
                 text = open(os.path.join(base, name)).read()
                 assert "oracle" not in text.lower(), os.path.join(base, name)
+
+
+def test_public_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: include/drot.h must compile as C99 on its own, with warnings as errors
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler on this machine")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "drot.h"\nint main(void) { drot_handle h = 0; drot_info i; (void)h; (void)i; return 0; }\n')
+    proc = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "use_header.o")],
+                          stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert proc.returncode == 0, proc.stdout
