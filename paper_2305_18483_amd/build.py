@@ -8,14 +8,6 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 SOURCES = [os.path.join(_PKG, "csrc", "drot.hip")]
 LIB_PATH = os.path.join(_PKG, "libdrot.so")
-# counter-calibration probe (a plain copy kernel of known size), a stand-alone executable
-PROBE_SOURCE = os.path.join(_PKG, "csrc", "copy_probe.hip")
-PROBE_PATH = os.path.join(_PKG, "copy_probe")
-
-COMMON_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17",
-    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instructions are kept out of the generated code
@@ -39,9 +31,8 @@ def _run(cmd, verbose):
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source: libdrot.so (the product) and the copy_probe executable; returns the library path."""
+    """Compile the HIP sources into libdrot.so; returns the library path."""
     _run(["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", LIB_PATH, *SOURCES], verbose)
-    _run(["hipcc", *COMMON_FLAGS, "-o", PROBE_PATH, PROBE_SOURCE], verbose)
     return LIB_PATH
 
 

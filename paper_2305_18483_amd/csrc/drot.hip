@@ -338,24 +338,42 @@ int drot_set_skip_cost(drot_handle h, int mode) {
 
 int drot_set_profile(drot_handle h, int enable) {
   if (!h) return DROT_ERR_INVALID_ARG;
-  if (enable)
-    for (auto& e : h->prof_ev)
-      if (!e && hipEventCreate(&e) != hipSuccess) {
-        e = nullptr;
-        return DROT_ERR_HIP;
-      }
-  if (enable)
-    for (auto& e : h->cal_ev)
-      if (!e && hipEventCreate(&e) != hipSuccess) {
-        e = nullptr;
-        return DROT_ERR_HIP;
-      }
-  if (enable && !h->prof_reads) {
+  if (enable) {
+    // everything or nothing: a failure part of the way leaves the handle as it was
+    hipEvent_t made[2 * kMaxProfiled + 8] = {};
+    int nmade = 0;
+    bool ok = true;
+    auto make = [&](hipEvent_t& e) {
+      if (!ok || e) return;
+      if (hipEventCreate(&e) != hipSuccess) { e = nullptr; ok = false; return; }
+      made[nmade++] = e;
+    };
+    for (auto& e : h->prof_ev) make(e);
+    for (auto& e : h->cal_ev) make(e);
+    int* wave_reads = nullptr;
+    double* prof_reads = nullptr;
     // read counts of the screened sweeps: one int per wave of the largest grid, one total per timed sweep
     const size_t waves = (size_t)ceil_div(h->max_n, kSegCols) * (size_t)ceil_div(h->max_m, kScreenRows * kScreenWaves) * kScreenWaves;
-    if (hipMalloc(reinterpret_cast<void**>(&h->wave_reads), sizeof(int) * waves) != hipSuccess) return DROT_ERR_ALLOC;
-    h->wave_reads_len = waves;
-    if (hipMalloc(reinterpret_cast<void**>(&h->prof_reads), sizeof(double) * kMaxProfiled) != hipSuccess) return DROT_ERR_ALLOC;
+    int rc = ok ? DROT_OK : DROT_ERR_HIP;
+    if (rc == DROT_OK && !h->prof_reads) {
+      if (hipMalloc(reinterpret_cast<void**>(&wave_reads), sizeof(int) * waves) != hipSuccess ||
+          hipMalloc(reinterpret_cast<void**>(&prof_reads), sizeof(double) * kMaxProfiled) != hipSuccess)
+        rc = DROT_ERR_ALLOC;
+    }
+    if (rc != DROT_OK) {
+      (void)hipFree(wave_reads);
+      (void)hipFree(prof_reads);
+      for (int e = 0; e < nmade; ++e) (void)hipEventDestroy(made[e]);
+      for (auto& e : h->prof_ev) for (int k = 0; k < nmade; ++k) if (e == made[k]) e = nullptr;
+      for (auto& e : h->cal_ev) for (int k = 0; k < nmade; ++k) if (e == made[k]) e = nullptr;
+      (void)hipGetLastError();
+      return rc;
+    }
+    if (!h->prof_reads) {
+      h->wave_reads = wave_reads;
+      h->wave_reads_len = waves;
+      h->prof_reads = prof_reads;
+    }
   }
   h->profile = enable ? 1 : 0;
   return DROT_OK;
@@ -640,8 +658,11 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
     RA.nseg = slab_k ? ceil_div(n, kSlabCols) : nseg;
     RA.ntr = slab_k ? nruns : ntr;
   }
-  if (max_iters == 0 && !resume && !warm)
+  if (max_iters == 0 && !resume && !warm) {
     hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, X_out, (size_t)m * n, 0.f, (const int*)nullptr);
+    if (pad_x)  // (the gap pass reads the working copy, which may hold an earlier solve's plan)
+      hipLaunchKernelGGL(fill_kernel, dim3(1024), dim3(256), 0, stream, h->xpad, (size_t)m * ld_pad, 0.f, (const int*)nullptr);
+  }
 
   const bool checking = tol > 0.f;
   int k = 0, slot = 0, checks = 0;
@@ -780,8 +801,7 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
         if (tiles64) S.tilesum = tsum(sw);
         if (screened) {
           const dim3 sgrid(nseg, ceil_div(m, kScreenRows * kScreenWaves)), sblock(64 * kScreenWaves);
-          if (refresh) {
-            DROT_HIP(hipMemcpyAsync(h->varphi0, h->varphi, sizeof(float) * (size_t)n, hipMemcpyDeviceToDevice, stream));
+          if (refresh) {  // (the sweep itself stores varphi as the epoch's varphi0)
             if (epoch_gen >= 0) refresh_period = refresh_period * 2 < refresh_max ? refresh_period * 2 : refresh_max;
             epoch_gen = sw;
           }
@@ -948,8 +968,12 @@ static int solve_impl(drot_handle h, const CostSource& cost, const float* p, con
   h->info.dual_res = h->compute_gap ? st.dual_res : 0.0;
   h->dense_plan = dense_plan;
   h->plan_density = plan_density;
-  h->epoch_gen = epoch_gen;
-  h->refresh_period = refresh_period;
+  // After an early stop the sweeps queued past it did nothing, a refresh among them included: the
+  // host's record of the last refresh may then name a sweep that never ran.  The bounds in memory
+  // still belong to their varphi0 (the refresh sweep stores both), but the schedule starts afresh.
+  const bool epoch_ran = epoch_gen <= k_base + (long long)st.iters;
+  h->epoch_gen = (st.converged || !epoch_ran) ? -1 : epoch_gen;
+  h->refresh_period = (st.converged || !epoch_ran) ? 8 : refresh_period;
   // (after an early stop the sweeps launched past it did nothing: be conservative)
   h->sums_valid = !st.converged && max_iters > 0 && sums_gen == k_base + k;
   h->lines_valid = h->sums_valid && lines_gen == k_base + k;

@@ -21,8 +21,8 @@ struct ScreenArgs {
   float* mprime_out;        // [nseg][m] written by a refresh sweep
   const float* varphi0;     // [n] varphi of the epoch
   int* wave_reads;          // 8-wave tiles, profiling only (else null): [workgroup][wave] row segments of C this wave read
+  float* varphi0_out;       // [n] written by a refresh sweep, and by the lean sweep when it renews its bounds
   // lean sweep only: it renews the bounds by itself when the vector update before it has raised ctl[0]
-  float* varphi0_out;       // [n]
   const int* ctl;           // the control words below (kCtlRenew ...)
   int* wg_reads;            // [workgroup] row segments of C the workgroup read (always written)
   // lean sweep only: which of the eight 128-byte lines of a row segment of X hold a nonzero
@@ -88,6 +88,18 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   }
   const unsigned skipmask = (unsigned)__builtin_amdgcn_ballot_w64(certified) & 0xffu;
   const unsigned nzmask = (unsigned)__builtin_amdgcn_ballot_w64(fbits(prev) != 0) & 0xffu;
+  if (REFRESH && tr == 0 && wave == 0) {
+    // the first wave of every column segment stores the varphi the new bounds are recorded against
+    // (here, behind the stop flag, so that bounds and epoch always belong together; nobody reads
+    // varphi0 in a refresh sweep)
+    float* __restrict__ v0 = SC.varphi0_out + j0;
+    if (nvalid == 4) *reinterpret_cast<f4u*>(v0) = vp;
+    else {
+      if (nvalid > 0) v0[0] = vp.x;
+      if (nvalid > 1) v0[1] = vp.y;
+      if (nvalid > 2) v0[2] = vp.z;
+    }
+  }
 
   f4v x[U], c[U];
 #pragma unroll

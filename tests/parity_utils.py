@@ -6,6 +6,8 @@ Tolerances (the bar the benchmark definition states, fp32 arithmetic on the GPU,
                 cancelling terms of size rho*C, so fp32 cannot hold a relative error on the tiniest ones)
   * objective:  |obj_gpu - obj_oracle| <= 1e-5 * |obj_oracle|, both evaluated in fp64 from the plans
   * residuals:  | ||X1-p|| - ||X1-p||_oracle | <= 1e-6, same for the column residual
+  * support:    entries positive on one side and zero on the other are below 1e-5 of the plan's scale and few
+  * large entries (>= 1e-2 * max): per-entry relative error <= 1e-3
 """
 from __future__ import annotations
 
@@ -15,6 +17,16 @@ import torch
 PLAN_TOL = 1e-4
 OBJ_TOL = 1e-5
 RES_TOL = 1e-6
+# support mismatches (an entry > 0 on one side, == 0 on the other): how large such an entry may be
+# relative to the largest entry of the plan, and how many there may be
+SUPPORT_TOL = 1e-5
+SUPPORT_COUNT_FRAC = 2e-2
+SUPPORT_COUNT_MIN = 8
+# per-entry relative error on the entries >= BIG_ENTRY * max (there an absolute error of PLAN_TOL * max
+# is a relative one of at most PLAN_TOL / BIG_ENTRY; the bar asked of those entries is ten times tighter)
+BIG_ENTRY = 1e-2
+REL_TOL_BIG = 1e-3
+LAST_STATS = {}  # what the last assert_parity measured beyond its return value (for the test logs)
 
 
 def to_dev(P):
@@ -67,8 +79,26 @@ def assert_parity(oracle, P, gres, Xg, phig, varphig, ores, stepsize=None, check
     assert np.isfinite(Xg).all(), label
     assert (Xg >= 0).all(), label
     scale = np.abs(Xo).max()
-    err = np.abs(Xg.astype(np.float64) - Xo).max()
+    diff = np.abs(Xg.astype(np.float64) - Xo)
+    err = diff.max()
     assert err <= PLAN_TOL * scale, f"{label}: plan error {err:.3e} vs scale {scale:.3e} (ratio {err / scale:.2e})"
+    # support: entries that are positive on one side and exactly zero on the other.  fp32 produces an
+    # entry as the clamp of a sum of terms of size rho*|C|, |phi|, |varphi|, so one that the fp64
+    # iteration leaves within the rounding of those terms of zero may land on the other side of the
+    # clamp; such entries must be that small (far below the plan's tolerance) and few
+    sg, so = Xg > 0, Xo > 0
+    mism = sg != so
+    nmism = int(np.count_nonzero(mism))
+    nnz = max(int(np.count_nonzero(so)), 1)
+    mism_mag = float(np.maximum(Xg[mism].max(initial=0.0), Xo[mism].max(initial=0.0)))
+    assert mism_mag <= SUPPORT_TOL * scale, f"{label}: {nmism} support mismatches, largest entry {mism_mag:.3e} vs scale {scale:.3e}"
+    assert nmism <= max(SUPPORT_COUNT_MIN, SUPPORT_COUNT_FRAC * nnz), f"{label}: {nmism} support mismatches of {nnz} nonzeros"
+    # relative error where it means something: on the entries that are at least a hundredth of the largest
+    big = Xo >= BIG_ENTRY * scale
+    rel_big = float((diff[big] / Xo[big]).max()) if big.any() else 0.0
+    assert rel_big <= REL_TOL_BIG, f"{label}: relative error {rel_big:.3e} on entries >= {BIG_ENTRY:g} * max"
+    LAST_STATS.update(support_mismatches=nmism, nonzeros=nnz, largest_mismatched_entry=mism_mag / scale,
+                      rel_err_big_entries=rel_big, frob=float(np.sqrt((diff * diff).sum()) / np.sqrt((Xo * Xo).sum())))
     # dual vectors: same normalisation (they are O(rho) like the plan's increments)
     pscale = max(np.abs(ores.phi).max(), np.abs(ores.varphi).max())
     perr = max(np.abs(phig - ores.phi).max(), np.abs(varphig - ores.varphi).max())

@@ -29,73 +29,138 @@ def drot():
     return drot_mod
 
 
+_CONFIGS = {}
+
+
+def _config(k):
+    """The k-th benchmark configuration, generated once per test session (cfg4 takes a while)."""
+    if k not in _CONFIGS:
+        _say(f"generating configuration {k}")
+        _CONFIGS[k] = drot_inputs.config(k)
+    return _CONFIGS[k]
+
+
+def _stats():
+    st = pu.LAST_STATS
+    return (f"support mismatches {st.get('support_mismatches')} of {st.get('nonzeros')} nonzeros "
+            f"(largest such entry / scale {st.get('largest_mismatched_entry', 0.0):.1e}), relative error on entries "
+            f">= 1e-2 max {st.get('rel_err_big_entries', 0.0):.1e}, Frobenius {st.get('frob', 0.0):.1e}")
+
+
 def _run_case(drot, oracle, P, K, label, solver=None, **kw):
     _say(f"{label}: {P.name} m={P.m} n={P.n} reg={P.reg_kind} K={K}")
     solver = solver or drot.Solver(P.m, P.n)
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, K, **kw)
     assert gres.code == drot.DROT_OK and gres.iters == K
+    _say(f"{label}: GPU done, oracle running")
     ores = pu.oracle_solve(oracle, P, K, stepsize=kw.get("stepsize") or None)
     ratio = pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, stepsize=kw.get("stepsize") or None, label=label)
-    _say(f"{label}: plan error / scale = {ratio:.2e}")
+    _say(f"{label}: plan error / scale = {ratio:.2e}; {_stats()}")
     return gres, Xg, ores
+
+
+def _checks_of(P, X, phi, varphi):
+    """fp64 evaluation of a returned triple by the plain-torch module that shares nothing with either solver."""
+    import drot_checks
+
+    dev = X.device
+    rc = None if P.row_class is None else torch.from_numpy(P.row_class).to(dev)
+    return drot_checks.fp64_terms(torch.from_numpy(P.C).to(dev), X, torch.from_numpy(P.p).to(dev),
+                                  torch.from_numpy(P.q).to(dev), phi, varphi, float(P.rho), reg_kind=P.reg_kind,
+                                  lam=float(np.float32(P.lam)), mu=float(np.float32(P.mu)), row_class=rc,
+                                  num_classes=P.num_classes)
 
 
 # ---------------------------------------------------------------------------------------------
 # the five benchmark configurations
 # ---------------------------------------------------------------------------------------------
 def test_cfg1_unregularized_100_fixed_2000(drot, oracle):
-    _run_case(drot, oracle, drot_inputs.config(1), 2000, "cfg1")
+    _run_case(drot, oracle, _config(1), 2000, "cfg1")
 
 
 def test_cfg2_quadratic_1000_fixed_3000(drot, oracle):
-    _run_case(drot, oracle, drot_inputs.config(2), 3000, "cfg2")
+    _run_case(drot, oracle, _config(2), 3000, "cfg2")
+
+
+def _to_tolerance_against_the_oracle(drot, oracle, P, solver, tol, check_every, max_iters, label):
+    """Both sides iterate to the residual `tol`, testing every check_every iterations.  The stop checks may
+    differ by one interval (a borderline test can flip with fp32 rounding); the plans are compared element
+    by element at the earlier of the two stops, the later side re-run for exactly that many iterations."""
+    _say(f"{label}: to {tol:g}, GPU")
+    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, max_iters, tol=tol)
+    assert gres.code == drot.DROT_OK and gres.converged and gres.iters % check_every == 0
+    _say(f"{label}: GPU stopped after {gres.iters}; oracle running")
+    ores = pu.oracle_solve(oracle, P, max_iters, tol=tol, check_every=check_every)
+    _say(f"{label}: oracle stopped after {ores.iters}")
+    assert abs(gres.iters - ores.iters) <= check_every, (gres.iters, ores.iters)
+    r, s_ = pu.residuals(P, Xg)
+    assert max(r, s_) <= tol + 1e-7
+    stop_g = gres.iters
+    K = min(gres.iters, ores.iters)
+    if gres.iters > K:
+        gres, Xg, phig, varphig = pu.gpu_solve(solver, P, K)
+    if ores.iters > K:
+        ores = pu.oracle_solve(oracle, P, K)
+    ratio = pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label=label)
+    _say(f"{label}: at iteration {K}: plan error / scale = {ratio:.2e}; {_stats()}")
+    return stop_g, ores
 
 
 def test_cfg2_quadratic_1000_to_tolerance(drot, oracle):
-    # the configuration iterates to a marginal residual of 1e-5; the oracle is run to 1e-4 (a few
-    # thousand iterations) and must stop at the same check; the GPU run to 1e-5 is then verified by
-    # fp64 properties of its result (feasibility, gap)
-    P = drot_inputs.config(2)
+    # the run the configuration names: to a marginal residual of 1e-5, both sides, compared element by
+    # element where they stop (and the same at 1e-4, which takes a tenth of the iterations)
+    P = _config(2)
     solver = drot.Solver(P.m, P.n, check_every=100)
-    _say("cfg2 to 1e-4 against the oracle")
-    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 200000, tol=1e-4)
-    ores = pu.oracle_solve(oracle, P, 200000, tol=1e-4, check_every=100)
-    assert gres.code == drot.DROT_OK and gres.converged
-    # a borderline check may flip with fp32 rounding: allow one check interval
-    assert abs(gres.iters - ores.iters) <= 100, (gres.iters, ores.iters)
-    if gres.iters == ores.iters:
-        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="cfg2 tol 1e-4")
-    _say(f"cfg2 to 1e-5 (GPU iters to 1e-4: {gres.iters})")
+    _to_tolerance_against_the_oracle(drot, oracle, P, solver, 1e-4, 100, 200000, "cfg2 to 1e-4")
+    stop, _ = _to_tolerance_against_the_oracle(drot, oracle, P, solver, 1e-5, 100, 400000, "cfg2 to 1e-5")
+    # Optimality of the returned point, scaled so that nothing small is divided by.  A fixed point of the
+    # sweep satisfies rho*lambda*X = [phi + varphi - rho*C]_+ entry by entry (Section 3, quadratic
+    # regularization: X = [Y - rho C]_+ / (1 + rho*lambda), with Y - X = phi 1^T + 1 varphi^T); one sweep
+    # away from it, X_K and X_{K+1} = [X_K + t]_+ / (1 + rho*lambda) with t = phi_K + varphi_K - rho C give
+    # |rho*lambda*X_K - [t]_+| <= (1 + rho*lambda) |X_K - X_{K+1}| in every entry (case by case on the signs
+    # of t and X_K + t).  So the defect is bounded by the last change of the plan, plus the fp32 rounding of
+    # t (terms of size rho).  (The textbook form X = [u + v - C]_+ / lambda is this identity divided by
+    # rho*lambda = 1e-5: it magnifies the rounding of t a hundred thousand times and holds only in the limit.)
+    import drot_checks
+
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 400000, tol=1e-5)
-    assert gres.code == drot.DROT_OK and gres.converged and gres.iters % 100 == 0
-    r, s = pu.residuals(P, Xg)
-    assert max(r, s) <= 1e-5 + 1e-7
-    t = pu.fp64_terms(oracle, P, Xg, phig, varphig)
-    # (the KKT form X = [u (+) v - C]_+ / lambda divides by rho*lambda = 1e-5 and only holds at the
-    # exact fixed point, so it is pinned on the oracle at convergence, not here)
-    _say(f"cfg2 to 1e-5: gap={t.gap:.3e} obj={t.objective:.6f} reported gap={gres.gap:.3e}")
-    assert abs(t.gap) <= 1e-2 * abs(t.objective)
+    assert gres.iters == stop
+    dev = torch.device("cuda:0")
+    C, X_K = torch.from_numpy(P.C).to(dev), torch.from_numpy(Xg).to(dev)
+    lam, rho = float(np.float32(P.lam)), float(P.rho)
+    defect = drot_checks.fixed_point_defect(C, X_K, torch.from_numpy(phig).to(dev), torch.from_numpy(varphig).to(dev), rho, lam)
+    solver.set_continue(True)
+    _, X_next, _, _ = pu.gpu_solve(solver, P, 1, X_out=X_K.clone())
+    solver.set_continue(False)
+    change = float(np.abs(X_next.astype(np.float64) - Xg.astype(np.float64)).max())
+    rounding = 8 * 2.0 ** -24 * rho * 3.0  # phi_i, varphi_j and rho*C_ij are each below 3*rho here
+    _say(f"cfg2 at 1e-5: fixed-point defect {defect:.3e}, last change of the plan {change:.3e}, plan scale {Xg.max():.3e}")
+    assert defect <= (1.0 + rho * lam) * change + rounding
+    t = _checks_of(P, X_K, torch.from_numpy(phig).to(dev), torch.from_numpy(varphig).to(dev))
+    assert t.min_entry >= 0.0 and max(t.r_row, t.r_col) <= 1e-5 + 1e-7
+    assert abs(gres.objective - t.objective) <= 1e-5 * abs(t.objective)
     assert abs(gres.gap - t.gap) <= 2e-5 * max(abs(t.cost), abs(t.dual_linear), abs(t.h_conj))
-    _say(f"cfg2 to 1e-5: iters={gres.iters} gap={t.gap:.3e} obj={t.objective:.6f}")
 
 
 def test_cfg3_unregularized_10000_reduced_K(drot, oracle):
-    # full size, the launch configuration the benchmark times; K bounded by the oracle's speed
-    _run_case(drot, oracle, drot_inputs.config(3), 30, "cfg3")
+    # full size, the launch configuration the benchmark times: the dense first sweeps
+    _run_case(drot, oracle, _config(3), 30, "cfg3")
 
 
 def test_cfg4_quadratic_20000_reduced_K(drot, oracle):
-    _run_case(drot, oracle, drot_inputs.config(4), 12, "cfg4")
+    _run_case(drot, oracle, _config(4), 12, "cfg4")
 
 
-@pytest.mark.parametrize("cfg,K", [(3, 200), (4, 130)])
-def test_full_size_lean_sweeps_against_the_oracle(drot, oracle, cfg, K):
-    # long enough for the solver to have moved to the lean screened sweep (line flags, its own
-    # renewals), in the launch configuration the benchmark times; the oracle needs half a minute
-    P = drot_inputs.config(cfg)
+@pytest.mark.parametrize("cfg,K", [(3, 1000), (4, 500)])
+def test_full_size_fixed_iterations_against_the_oracle(drot, oracle, cfg, K):
+    # the fixed-iteration runs the configurations name (1000 resp. 500 iterations), element by element
+    # against the fp64 iteration, in the launch configuration the benchmark times: by then the solver has
+    # long moved to the lean screened sweep (line flags, its own renewals of the bounds).  The oracle
+    # needs one to two minutes for these.
+    P = _config(cfg)
     solver = drot.Solver(P.m, P.n)
     solver.set_profile(True)
-    gres, Xg, ores = _run_case(drot, oracle, P, K, f"cfg{cfg}, lean sweeps", solver=solver)
+    gres, Xg, ores = _run_case(drot, oracle, P, K, f"cfg{cfg}, {K} iterations", solver=solver)
     kinds = [k for _, k in solver.profile_sweeps()]
     solver.set_profile(False)
     assert kinds.count(7) >= 20, kinds
@@ -105,6 +170,34 @@ def test_full_size_lean_sweeps_against_the_oracle(drot, oracle, cfg, K):
     s_ = float((X.sum(dim=0) - torch.from_numpy(P.q).to("cuda:0").double()).norm())
     assert float(X.min()) >= 0.0
     assert abs(r - gres.r_row) <= 1e-6 and abs(s_ - gres.r_col) <= 1e-6, (r, gres.r_row, s_, gres.r_col)
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_size_runs_to_tolerance_hold_up_in_fp64(drot, cfg):
+    # the time-to-tolerance runs the benchmark reports (tens of thousands of iterations at cfg4, hundreds
+    # of renewals of the screening bounds): what they return is checked by fp64 code that shares nothing
+    # with the library -- nonnegativity, both residual norms, objective, duality gap (Appendix C)
+    P = _config(cfg)
+    dev = torch.device("cuda:0")
+    solver = drot.Solver(P.m, P.n, check_every=100)
+    _say(f"cfg{cfg} to a residual of 1e-4")
+    C, p, q, rc = pu.to_dev(P)
+    res = solver.solve(C, p, q, reg_kind=P.reg_kind, lam=P.lam, mu=P.mu, row_class=rc, num_classes=P.num_classes,
+                       max_iters=100000, tol=1e-4)
+    phi, varphi = solver.duals(P.m, P.n, dev)
+    torch.cuda.synchronize()
+    assert res.code == drot.DROT_OK and res.converged and res.iters % 100 == 0
+    t = _checks_of(P, res.X, phi, varphi)
+    _say(f"cfg{cfg}: {res.iters} iterations; fp64: min {t.min_entry:.1e}, residuals {t.r_row:.3e}/{t.r_col:.3e}, "
+         f"objective {t.objective:.8f} (reported {res.objective:.8f}), gap {t.gap:.4e} (reported {res.gap:.4e}), "
+         f"dual residual {t.dual_res:.3e} (reported {res.dual_res:.3e}), {t.nnz} nonzeros")
+    assert t.min_entry >= 0.0
+    assert max(t.r_row, t.r_col) <= 1e-4 + 1e-7
+    assert abs(t.r_row - res.r_row) <= 1e-6 and abs(t.r_col - res.r_col) <= 1e-6
+    assert abs(res.objective - t.objective) <= 1e-5 * abs(t.objective)
+    gap_scale = max(abs(t.cost), abs(t.dual_linear), abs(t.h_conj))
+    assert abs(res.gap - t.gap) <= 2e-5 * gap_scale
+    assert abs(res.dual_res - t.dual_res) <= 2e-5 * max(t.dual_res, gap_scale)
 
 
 def test_beyond_the_benchmark_size(drot):
@@ -136,8 +229,9 @@ def test_beyond_the_benchmark_size(drot):
     assert abs(r - res.r_row) <= 1e-6 and abs(s_ - res.r_col) <= 1e-6, (r, res.r_row, s_, res.r_col)
 
 
-def test_cfg5_group_lasso_5000_reduced_K(drot, oracle):
-    _run_case(drot, oracle, drot_inputs.config(5), 150, "cfg5")
+def test_cfg5_group_lasso_5000_fixed_1000(drot, oracle):
+    # the configuration's own run: 1000 iterations at full size
+    _run_case(drot, oracle, _config(5), 1000, "cfg5")
 
 
 def test_cfg5_recipe_1000_fixed_1000(drot, oracle):
@@ -182,15 +276,7 @@ def test_explicit_stepsize(drot, oracle):
 def test_stops_at_first_passing_check(drot, oracle):
     P = drot_inputs.random_problem(90, 110, seed=9)
     solver = drot.Solver(P.m, P.n, check_every=10)
-    _say("stopping rule")
-    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 50000, tol=1e-4)
-    ores = pu.oracle_solve(oracle, P, 50000, tol=1e-4, check_every=10)
-    assert gres.converged and gres.code == drot.DROT_OK
-    assert abs(gres.iters - ores.iters) <= 10
-    if gres.iters == ores.iters:
-        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="stopping")
-    r, s = pu.residuals(P, Xg)
-    assert max(r, s) <= 1e-4 + 1e-7
+    _to_tolerance_against_the_oracle(drot, oracle, P, solver, 1e-4, 10, 50000, "stopping rule")
     # out of iterations before the tolerance: a status, not an error
     gres2, _, _, _ = pu.gpu_solve(solver, P, 20, tol=1e-9)
     assert gres2.code == drot.DROT_MAX_ITERS and not gres2.converged and gres2.iters == 20
@@ -392,16 +478,9 @@ def test_resident_kernel_for_tiny_problems(drot, oracle, m, n, kind):
 
 
 def test_resident_kernel_stops_at_the_same_check_as_the_oracle(drot, oracle):
-    P = drot_inputs.config(1)
+    P = _config(1)
     solver = drot.Solver(P.m, P.n, check_every=10)
-    _say("resident, stopping rule at cfg1")
-    gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 100000, tol=1e-5)
-    ores = pu.oracle_solve(oracle, P, 100000, tol=1e-5, check_every=10)
-    assert gres.converged and abs(gres.iters - ores.iters) <= 10
-    if gres.iters == ores.iters:
-        pu.assert_parity(oracle, P, gres, Xg, phig, varphig, ores, label="resident stopping")
-    r, s = pu.residuals(P, Xg)
-    assert max(r, s) <= 1e-5 + 1e-7
+    _to_tolerance_against_the_oracle(drot, oracle, P, solver, 1e-5, 10, 100000, "resident, stopping rule at cfg1")
 
 
 @pytest.mark.parametrize("K,check_every", [(150, 100), (151, 100), (37, 7)])
@@ -422,11 +501,12 @@ def test_even_odd_cost_skipping(drot, oracle, K, check_every, kind):
 
 
 def test_plain_scheme_full_size(drot, oracle):
-    # 10000 x 10000 with C read by every sweep (the default at this size is the even/odd scheme,
-    # which the cfg3 and cfg4 cases above cover)
-    P = drot_inputs.config(3)
+    # 10000 x 10000 with every sweep on 32-row tiles reading all of C (the defaults at this size, the
+    # zero-segment skipping and the screened sweeps, are what the cfg3 and cfg4 cases above cover)
+    P = _config(3)
     solver = drot.Solver(P.m, P.n)
     solver.set_skip_cost(0)
+    solver.set_skip_unchanged(0)
     _say("plain scheme at 10000 x 10000, K=25")
     gres, Xg, phig, varphig = pu.gpu_solve(solver, P, 25)
     ores = pu.oracle_solve(oracle, P, 25)
@@ -481,6 +561,50 @@ def test_screening_changes_no_bit(drot, oracle, kind, m, n):
     assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
     ores = pu.oracle_solve(oracle, P, K)
     pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="screened")
+
+
+def test_continuing_after_an_early_stop_screens_with_valid_bounds(drot):
+    # A solve that converges at a check has one more stretch of sweeps queued behind the stop flag, which
+    # do nothing -- a refresh of the screening bounds among them.  A continued solve must not take that
+    # refresh for done: its iterates are those of the unscreened sweeps, bit for bit.
+    P = drot_inputs.random_problem(2300, 2500, seed=1500 + 2300, reg_kind=1, lam=0.05)
+    _say("continuation after convergence, screened against unscreened")
+    outs = []
+    for mode in (0, 1):
+        solver = drot.Solver(P.m, P.n, check_every=25)
+        solver.set_skip_cost(0)
+        solver.set_screening(mode)
+        # (host-ordered refreshes fall on sweeps 2, 10, 26, 58, 122, 250: the one at 122 sits in the stretch
+        # queued behind a stop at iteration 100)
+        probe, _, _, _ = pu.gpu_solve(solver, P, 100)
+        tol = float(np.float32(max(probe.r_row, probe.r_col) * 1.0005))
+        X = torch.empty((P.m, P.n), device="cuda:0")
+        res, _, _, _ = pu.gpu_solve(solver, P, 5000, tol=tol, X_out=X)
+        assert res.converged and res.iters <= 100, (res.iters, tol)
+        stop = res.iters
+        solver.set_continue(True)
+        solver.set_profile(True)
+        res2, X2, phi2, varphi2 = pu.gpu_solve(solver, P, 180, tol=1e-12, X_out=X)
+        kinds = [k for _, k in solver.profile_sweeps()]
+        solver.set_profile(False)
+        assert res2.iters == 180
+        if mode == 1:
+            assert 5 in kinds or 7 in kinds, kinds  # the continued call does screen
+        outs.append((stop, X2, phi2, varphi2))
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1:], outs[1][1:]):
+        assert np.array_equal(a, b)
+
+
+def test_zero_iterations_on_a_reused_padded_handle_reports_x0(drot):
+    # n % 32 != 0: the library iterates on a padded copy of X; a solve with zero iterations on a handle
+    # that still holds an earlier plan there must report X_0 = 0, not that plan
+    P = drot_inputs.random_problem(300, 333, seed=61, reg_kind=1, lam=0.2)
+    solver = drot.Solver(P.m, P.n)
+    pu.gpu_solve(solver, P, 50)
+    res, X0, _, _ = pu.gpu_solve(solver, P, 0)
+    assert res.iters == 0 and not X0.any()
+    assert res.objective == 0.0
 
 
 def test_screening_across_calls_and_starts(drot, oracle):
