@@ -93,128 +93,137 @@ int drot_create(drot_handle* out, int max_m, int max_n);
 int drot_destroy(drot_handle h);
 
 /*
- * Options (all optional; defaults in brackets).
- *   check_every [100]: the residual test of Appendix C is evaluated on the device every this many
- *       iterations; the solve stops at the first test that passes.  >= 1.
- *   compute_gap [1]: evaluate objective, duality gap and dual residual of the returned iterate
- *       (one extra read-only pass over X and C at the end of the solve).
+ * Options: drot_set_option(h, option, value); defaults in brackets.  INVALID_ARG for a null handle, an
+ * unknown option or a value outside the stated range.
+ *
+ * How the solve is run
+ *   DROT_OPT_CHECK_EVERY [100], >= 1: the residual test of Appendix C (r_primal) is evaluated on the
+ *       device every this many iterations; the solve stops at the first test that passes.
+ *   DROT_OPT_COMPUTE_GAP [1], 0/1: evaluate objective, duality gap and dual residual of the returned
+ *       iterate (Appendix C; one read-only pass over X and C at the end of the solve).
+ *   DROT_OPT_GAP_EVERY [0], >= 0: k >= 1 evaluates objective, duality gap and dual residual also during
+ *       the solve, at every k-th residual check (iterations that are multiples of k * check_every), and
+ *       records them (drot_get_checks); 0: only at the end.  See drot_set_gap_tolerance.
+ *   DROT_OPT_CONTINUE [0], 0/1: the next drot_solve / drot_solve_points does not restart from X_0 = 0: it
+ *       resumes the iteration from the state the previous solve on this handle left (phi, varphi and the
+ *       running sums of eq. (6) in the workspace, the plan in X_out, which must still hold that solve's
+ *       output; same m, n, C, p, q and regularizer are the caller's responsibility).  Running K1 then K2
+ *       iterations this way gives bit for bit the iterate of one K1+K2 solve, unless the automatic
+ *       even/odd scheme (DROT_OPT_SKIP_COST) comes into play: when it starts depends on where the calls
+ *       and their stretches of check_every iterations begin.  INVALID_ARG at the next solve if no solve
+ *       has run or the sizes differ.  drot_info.iters counts the iterations of the call.
+ *   DROT_OPT_PROFILE [0], 0/1: record HIP events on the solve's stream around every sweep launch (the
+ *       first 256 of a solve) and count what the sweep read; see drot_get_profile.  Costs two event
+ *       records and a few tiny kernels per iteration, so leave it off when timing a solve.
+ *
+ * Which kernels run (tuning; the iterates do not depend on these unless stated)
+ *   DROT_OPT_SKIP_UNCHANGED [-1 = on], -1/0/1: X >= 0, so a row segment (256 consecutive columns of a
+ *       row) whose sum after the previous sweep was zero holds only zeros; the sweep then does not read
+ *       that segment of X, and does not write it back if it stays zero.  Transport plans are sparse: once
+ *       the support has settled the sweep is a read-only stream of C (4 instead of 12 bytes per element).
+ *       Beyond the fused small-problem path these sweeps run on 64-row tiles.  The group-resident
+ *       group-lasso sweep does the same with 128-byte lines, the sweep of drot_solve_points with row
+ *       segments.  Same memory contents either way.  0 reads and stores everything.
+ *   DROT_OPT_SCREENING [-1], -1 .. 100000: with the skipping on, sweeps over large sparse plans also leave
+ *       out most reads of C.  Now and then a sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
+ *       until the next such sweep a row segment whose X is zero and whose bound M + max_j (drift of varphi_j
+ *       since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is known to stay
+ *       zero: nothing of it is read, computed or written.  The iterates are those of the unscreened sweeps,
+ *       bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first, at most 256 apart; once the
+ *       plan is known to be sparse the sweep itself decides, on the device, when the reads that weakened
+ *       bounds cost it have added up to the price of new ones.  -1 screens problems of 11.5 million entries
+ *       and more (smaller ones stream all of C from the caches just as fast), 1 every problem the skipping
+ *       applies to, k >= 2 the same with the bounds renewed at least every k-th sweep, 0 never.
+ *   DROT_OPT_SKIP_COST [-1], -1/0/1: the even/odd scheme of the paper's GPU appendix (Section
+ *       "Quadratically Regularized DROT"): sweeps pair up, the first of a pair stores X - rho*C, the second
+ *       reads that and needs no C (20 instead of 24 bytes per element and pair).  Row and column sums are
+ *       always those of X itself, and X_out is the plain plan on return and at every residual check.  The
+ *       rounding differs slightly from the plain scheme (same tolerance against the fp64 iteration).
+ *       Applies to the none/quadratic sweeps over a stored cost whose vector update is not fused into the
+ *       sweep; the better scheme for dense plans, as the skipping is for sparse ones.  -1 follows the plan:
+ *       the reduction counts the nonzero row segments, the host reads the count with the status of every
+ *       stretch (one stretch late, without waiting) and switches to the pairs above 70 % nonzero segments
+ *       and back below 50 %; with a switch the result depends, within rounding, on check_every and on how a
+ *       solve is cut into continued calls.  1: pairs wherever they apply; 0: never.
+ *   DROT_OPT_FUSED_UPDATE [-1], -1/0: small problems (at most 2048 rows and 4096 tiles of 32 x 256) compute
+ *       the O(m+n) update of eq. (6) at the head of the next sweep, one launch per iteration instead of
+ *       three; 0 always runs the separate kernels.  Same bits.
+ *   DROT_OPT_RESIDENT [-1], -1/0: problems of at most 128 x 256 without group lasso, from a stored cost, run
+ *       in a single workgroup that keeps X and C in registers: all the iterations up to the next residual
+ *       check are one launch.  Agrees with the other paths to rounding (different summation order).
+ *   DROT_OPT_GROUP_TWO_PASS [0], 0/1: a group-lasso solve uses the group-resident kernel (a whole class x
+ *       32 columns in one workgroup's registers, 12 bytes per element) when every class is one run of at
+ *       most 1024 consecutive rows, and otherwise the two-pass path (any labels, 20 bytes per element);
+ *       1 forces the two-pass path.
+ *   DROT_OPT_NONTEMPORAL [-1], -1/0/1: mark the sweep's loads and stores of X and C non-temporal (best when
+ *       they are far larger than the caches); -1 decides from 8*m*n bytes.  Same results.
  */
-int drot_set_check_every(drot_handle h, int check_every);
-int drot_set_compute_gap(drot_handle h, int enable);
+typedef enum {
+  DROT_OPT_CHECK_EVERY = 0,
+  DROT_OPT_COMPUTE_GAP = 1,
+  DROT_OPT_GAP_EVERY = 2,
+  DROT_OPT_CONTINUE = 3,
+  DROT_OPT_PROFILE = 4,
+  DROT_OPT_SKIP_UNCHANGED = 5,
+  DROT_OPT_SCREENING = 6,
+  DROT_OPT_SKIP_COST = 7,
+  DROT_OPT_FUSED_UPDATE = 8,
+  DROT_OPT_RESIDENT = 9,
+  DROT_OPT_GROUP_TWO_PASS = 10,
+  DROT_OPT_NONTEMPORAL = 11
+} drot_option;
+
+int drot_set_option(drot_handle h, drot_option option, int value);
 
 /*
- * Continuation [off].  When enabled, drot_solve does not restart from X_0 = 0: it resumes the
- * iteration from the state the previous solve on this handle left (phi, varphi and the running
- * sums of eq. (6) in the workspace, the plan in X_out, which must still hold that solve's output;
- * same m, n, C, p, q and regularizer are the caller's responsibility).  Running K1 then K2
- * iterations this way gives bit-for-bit the iterate of one K1+K2 solve, unless the automatic
- * even/odd scheme (drot_set_skip_cost) comes into play: when it starts depends on where the
- * calls and their stretches of check_every iterations begin.  INVALID_ARG at the next
- * solve if no solve has run or the sizes differ.  drot_info.iters counts the iterations of the call.
+ * Stopping on the duality gap as well [0 = off] (Section 3, "Stopping criteria"; Appendix C).  With
+ * gap_tol > 0 a check passes only if, besides the residual test, the gap was evaluated at that check
+ * (DROT_OPT_GAP_EVERY, taken as 1 if it is 0) and
+ *     |gap| <= gap_tol * |objective|   and   dual_res <= gap_tol
+ * (the dual residual, where the conjugate of h is an indicator, is a norm of a violation in units of
+ * the cost, which the stepsize default assumes normalised to max(C) = 1; it is 0 for the quadratic
+ * term).  The residual test alone says nothing about optimality: with a weak quadratic term the
+ * conjugate ||W||_F^2 / (2 lambda) magnifies any dual infeasibility left.  INVALID_ARG for a negative
+ * or NaN tolerance.
  */
-int drot_set_continue(drot_handle h, int enable);
+int drot_set_gap_tolerance(drot_handle h, float gap_tol);
 
 /*
- * Group-lasso path [automatic].  By default a group-lasso solve uses the group-resident kernel
- * (a whole class x 32 columns in one workgroup's registers, 12 bytes per element) when every class
- * is one run of at most 1024 consecutive rows, and otherwise the general two-pass path (any labels,
- * 20 bytes per element, fp32 atomics for the group norms).  enable = 1 forces the two-pass path.
+ * The residual checks of the last solve, in order: the status block of every check, as the host read
+ * it (each check once; after a stop the checks queued behind it do not run).
  */
-int drot_set_group_two_pass(drot_handle h, int enable);
+typedef struct {
+  int iters;           /* iteration of the check (counted within the call)                           */
+  int gap_evaluated;   /* 1 if objective, gap and dual_res below were evaluated at this very check     */
+  float r_row, r_col;  /* the two residual norms of Appendix C                                         */
+  double objective, gap, dual_res;
+} drot_check;
+/* out [out] HOST, capacity entries; *count receives how many checks the solve made (at most
+ * min(capacity, *count) entries are written; the library keeps the first 65536). */
+int drot_get_checks(drot_handle h, drot_check* out, int capacity, int* count);
 
 /*
- * Non-temporal accesses in the sweep [-1 = chosen by problem size].  mode 1 marks the loads and
- * stores of X and C non-temporal (best when X and C are far larger than the caches), mode 0 keeps
- * them cacheable (best when they fit), -1 decides from 8*m*n bytes.  A tuning knob: results are
- * identical in every mode.
+ * Sweep timings of the last solve in profile mode, in launch order (at most the first 256 sweeps).
+ *   ms          duration of the sweep launch from HIP events on the solve's stream, less the reading of
+ *               an empty event pair (the smallest of four recorded at the start of the solve)
+ *   kind        0 = read X and C, stored X (32-row tiles; also the group-lasso sweeps), 1 = also stored
+ *               X - rho*C (first of an even/odd pair), 2 = read the shifted X and no C (second of a pair),
+ *               3 = a launch of the resident kernel (its duration divided by the iterations it ran),
+ *               4 = as 0 on 64-row tiles with the zero-segment skipping, 5 = the same with screening,
+ *               6 = a screening sweep that reads all of C and records the bounds, 7 = the screened sweep
+ *               for plans known to be sparse (one wave per tile)
+ *   c_fraction  fraction of the row segments of C (256 columns of one row) the sweep read: counted by
+ *               the kernel for kinds 5, 6, 7; 1 for the kinds that read all of C, 0 for kind 2
+ *   x_fraction  fraction of the row segments of X that hold a nonzero after the sweep (counted by the
+ *               vector update that follows it), or -1 where that update is fused into the next sweep
  */
-int drot_set_nontemporal(drot_handle h, int mode);
-
-/*
- * Fused vector update [-1 = automatic].  For small problems (at most 2048 rows and 4096 tiles of
- * 32 x 256) the O(m+n) update of eq. (6) is computed at the head of the next sweep, so that an
- * iteration is one kernel launch instead of three; mode 0 always runs the separate kernels.
- */
-int drot_set_fused_update(drot_handle h, int mode);
-
-/*
- * Zero segments [-1 = on].  X >= 0, so a row segment (256 consecutive columns of a row) whose sum
- * after the previous sweep was zero holds only zeros.  A sweep that reads X and C and stores X (not
- * the pair of the even/odd scheme) then does not read that segment of X, and does not write it
- * back if its new values are zero again.  Transport plans are sparse: once the support has settled
- * nearly every segment is of this kind, and the sweep turns into a read-only stream of C (4 instead
- * of 12 bytes per element).  On problems beyond the fused small-problem path this sweep runs on
- * 64-row tiles.  The group-resident group-lasso sweep of such problems does the same with pieces of
- * 32 columns of a row (one 128-byte line), and the sweep of drot_solve_points with row segments.
- * The memory contents are the same either way.  mode 0 reads and stores everything.
- */
-int drot_set_skip_unchanged(drot_handle h, int mode);
-
-/*
- * Screening [-1 = on].  With the zero-segment skipping on, sweeps over large sparse plans also leave
- * out most reads of C.  Now and then a sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
- * until the next such sweep, a row segment whose X is zero and whose bound M + max_j (drift of
- * varphi_j since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is
- * known to stay zero: nothing of it is read, computed or written.  The iterates are those of the
- * unscreened sweeps, bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first, at
- * most 256 apart; once the plan is known to be sparse the sweep itself decides, on the device, when
- * the reads that weakened bounds cost it have added up to the price of new ones.  mode -1 screens
- * problems of 11.5 million entries and more (smaller ones stream all of C from the caches just as fast),
- * mode 1 every problem the skipping applies to, mode k >= 2 the same with the bounds renewed at
- * least every k-th sweep; mode 0 reads C in full every sweep.
- */
-int drot_set_screening(drot_handle h, int mode);
-
-/*
- * Resident kernel [-1 = automatic].  Problems of at most 128 x 256 without group lasso, solved from
- * a stored cost, run in a single workgroup that keeps X and C in registers: all the iterations up
- * to the next residual check (or all of them, without a tolerance) are one kernel launch.  Results
- * agree with the other paths to rounding (same precision, different summation order).  mode 0
- * sends such problems down the general path.
- */
-int drot_set_resident(drot_handle h, int mode);
-
-/*
- * Even/odd cost skipping [-1 = automatic] (Section "Quadratically Regularized DROT" of the paper's
- * GPU appendix).  Sweeps pair up: the first of a pair stores X - rho*C, the second reads that and
- * needs no C, so C is read every second sweep (20 instead of 24 bytes per element and pair).  Row
- * and column sums are always those of X itself, and X_out is the plain plan on return and at every
- * residual check.  The rounding differs slightly from the plain scheme (same tolerance against the
- * fp64 iteration).  The scheme applies to the none/quadratic sweeps over a stored cost whose vector
- * update is not fused into the sweep.  It is the better scheme for dense plans; for sparse ones the
- * zero-segment skipping above wins.  mode -1 (with the zero-segment skipping on) follows the plan:
- * problems beyond the fused small-problem path start on the skipping sweeps; the reduction counts
- * the nonzero row segments, the host reads the count with the status of every stretch of
- * check_every iterations (one stretch late, without waiting), and switches to the pairs while more
- * than 70 % of the segments are nonzero and back below 50 %.  With a switch the result depends,
- * within rounding, on check_every and on how a solve is cut into continued calls.  mode 1: pairs
- * wherever they apply; mode 0: never.
- */
-int drot_set_skip_cost(drot_handle h, int mode);
-
-/*
- * Profiling [off].  When enabled, HIP events are recorded on the solve's stream around every
- * sweep launch (the first 256 of a solve); drot_get_profile returns their mean duration in ms and
- * how many were timed (with even/odd cost skipping the two kinds of sweep alternate, starting with
- * the one that reads C when the number of iterations between checks is even).  The reading of an
- * empty event pair (the smallest of four recorded at the start of the solve, a few microseconds) is
- * subtracted from every duration.  Costs two event records per iteration, so leave it off when timing a solve.
- */
-int drot_set_profile(drot_handle h, int enable);
-int drot_get_profile(drot_handle h, double* sweep_ms_avg, int* sweeps_timed);
-/* The individual durations, in launch order: sweep_ms [out] HOST, capacity floats; sweep_kind [out]
- * HOST, capacity ints or NULL: 0 = the sweep read X and C, 1 = it also stored X - rho*C (first of an
- * even/odd pair), 2 = it read the shifted X and no C (second of a pair), 3 = a launch of the resident
- * kernel (its duration divided by the iterations it ran), 4 = as 0 but on 64-row tiles with the
- * zero-segment skipping, 5 = the same with screening, 6 = a screening sweep that reads all of C and
- * records the bounds, 7 = the screened sweep for plans known to be sparse (one wave per tile; the
- * default sweep of large problems once the first status has come back); *sweeps_timed receives how many the last
- * solve timed (at most min(capacity, that many) entries are written). */
-int drot_get_profile_sweeps(drot_handle h, float* sweep_ms, int* sweep_kind, int capacity, int* sweeps_timed);
-/* For the same sweeps: the fraction of the row segments of C (256 columns of one row) each of them
- * read; c_fraction [out] HOST, capacity doubles.  1 for the kinds that read all of C, 0 for kind 2,
- * counted by the kernel for the screened kinds 5, 6 and 7. */
-int drot_get_profile_reads(drot_handle h, double* c_fraction, int capacity, int* sweeps_timed);
+typedef struct {
+  float ms;
+  int kind;
+  double c_fraction;
+  double x_fraction;
+} drot_sweep_timing;
+int drot_get_profile(drot_handle h, drot_sweep_timing* out, int capacity, int* count);
 
 /*
  * Solve problem (1) by the iteration of eq. (8) + eq. (6), starting from X_0 = 0 and the
