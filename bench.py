@@ -8,17 +8,18 @@ residual test where one is scheduled.  Default workload: the quadratically regul
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--size N]
 
-prints one JSON line: iterations/s, the HBM roofline of the dominant sweep kernel (algorithmic bytes
-per launch over the kernel time from HIP events recorded on the launch stream), the time to a
-marginal residual of 1e-4, and the CPU oracle timed on a bounded sample on this machine's host cores.
+prints one JSON line.  `value` is K iterations timed after a cold start of W iterations.  The solver
+is deterministic, so the same W + K iterations are then run once more in profile mode (HIP events on
+the launch stream around every sweep; the kernels count what they read): `roofline` describes the
+dominant sweep kernel of exactly the timed iterations.  The leg `steady_state` does the same with a
+fixed warm-up of 200 and 500 timed iterations, whatever --steps/--warmup say: a cold start is dense
+for its first dozens of iterations and sparse afterwards, and the two regimes run different kernels.
 
-The default sweep at this size neither reads nor writes back row segments of X that are zero and
-stay zero.  Transport plans are sparse, so after the first few dozen iterations the sweep streams C
-(4 bytes per element) plus the few nonzero segments of X (8 bytes per element of those); its
-algorithmic bytes are counted that way, from the fraction of nonzero row segments in the plan the
-timed run ends with.  Two further legs time the same iterations with the even/odd scheme of the
-paper's GPU appendix (20 bytes per element and pair) and with every byte moved (12 bytes per
-element): that last one is the dense streaming rate of the sweep kernel.
+Further legs: the same 500 iterations with the screening off, with the even/odd scheme of the paper's
+GPU appendix, and with every byte moved (12 bytes per element: the dense streaming rate of the sweep
+kernel); the cost recomputed from the point clouds; time to a residual of 1e-4 and to a relative
+duality gap of 1e-3, each checked in fp64 by code that shares nothing with the library; sizes n and
+n - 1 side by side (alignment); the CPU oracle on a bounded sample, on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -32,17 +33,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-BYTES_PER_ELEMENT = {0: 12.0, 1: 12.0, 2: 8.0, 3: 12.0}  # by kind of sweep: read X, read C, write X; kind 2 reads no C;
-# kind 3 (resident kernel) is priced at the same 12 although nothing leaves the registers; kind 4 (zero segments
-# skipped) is priced from the plan's density, see sparse_sweep_bytes
-
-# HBM traffic of one sweep launch in bytes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
-# copy kernel of known size (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {  # (workload, kind of sweep); profiles/sweep_kernel_cfg4_20000.md
-    ("cfg4_quad_20000", 0): 4.8565e9, ("cfg4_quad_20000", 1): 4.8565e9, ("cfg4_quad_20000", 2): 3.2565e9,
-    ("cfg4_quad_20000", 4): 1.6957e9, ("cfg4_quad_20000", 7): 9.271e7}
-SEG_COLS = 256  # columns of a row segment, the unit of the zero-segment skipping
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+MFMA_F32_PEAK_TFLOPS = 157.3
+SEG_COLS = 256             # columns of a row segment, the unit of the zero-segment skipping
+STEADY_WARMUP, STEADY_STEPS = 200, 500
+KERNEL_NAMES = {
+    0: "sweep_kernel (reads X and C, stores X)",
+    1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
+    2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)",
+    3: "resident_kernel (X and C stay in registers; the time is per iteration)",
+    4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)",
+    5: "screened_sweep_kernel (reads C only where a bound does not certify zeros; nonzero row segments of X)",
+    6: "screened_sweep_kernel, refresh (reads all of C, records the bounds)",
+    7: "screened_lean_kernel (one wave per 64 x 256 tile; reads C only where a bound does not certify zeros)"}
+# counter-measured HBM traffic per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of
+# known size), written by profiles/ for one fixed, deterministic run; attached only to that very run
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_steady_state.json")
 
 
 def log(msg: str) -> None:
@@ -52,30 +58,44 @@ def log(msg: str) -> None:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=200,
+    ap.add_argument("--steps", type=int, default=STEADY_STEPS)
+    ap.add_argument("--warmup", type=int, default=STEADY_WARMUP,
                     help="untimed cold-start iterations (the support of the plan settles within the first 100 or so)")
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4: 20000 x 20000)")
     ap.add_argument("--size", type=int, default=0, help="override m = n (same recipe)")
     ap.add_argument("--tol", type=float, default=1e-4, help="residual of the time-to-tolerance leg")
-    ap.add_argument("--tol-max-iters", type=int, default=40000)
+    ap.add_argument("--gap-tol", type=float, default=1e-3, help="relative duality gap of the time-to-gap leg")
+    ap.add_argument("--tol-max-iters", type=int, default=400000)
     ap.add_argument("--check-every", type=int, default=100)
     ap.add_argument("--nontemporal", type=int, default=-1, help="-1: library default, 0/1: force off/on")
     ap.add_argument("--skip-cost", type=int, default=-1,
                     help="even/odd scheme (C read every second sweep): -1 library default, 0 never, 1 wherever it applies")
     ap.add_argument("--skip-unchanged", type=int, default=-1, help="zero-segment skipping: -1/1 on, 0 off")
-    ap.add_argument("--points", action="store_true", help="on-the-fly cost from the point clouds (drot_solve_points)")
-    ap.add_argument("--skip-tol", action="store_true")
-    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--only", default="", help="comma-separated legs to run besides the main measurement "
+                    "(steady,variants,points,tol,gap,alignment,cpu); default: all")
     ap.add_argument("--cpu-iters", type=int, default=0, help="oracle iterations to time (0: sized for ~20 s)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run a device copy of 1 GiB five times (to scale the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+    legs = set(args.only.split(",")) if args.only else {"steady", "variants", "points", "tol", "gap", "alignment", "cpu"}
 
     import numpy as np
     import torch
 
+    if args.calibrate:
+        # a plain elementwise kernel of known size: reads 1 GiB, writes 1 GiB per launch
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch.add(a, 1.0, out=b), 2^28 floats: 1 GiB read and 1 GiB written per launch, 5 launches"}))
+        return 0
+
+    import drot_checks
     import drot_inputs
     import paper_2305_18483_amd as drot
 
@@ -88,6 +108,7 @@ def main() -> int:
     t0 = time.time()
     P = drot_inputs.config(args.config, size=args.size or None)
     m, n = P.m, P.n
+    nseg = (n + SEG_COLS - 1) // SEG_COLS
     log(f"workload {P.name}: m={m} n={n} reg_kind={P.reg_kind} lambda={P.lam} mu={P.mu} (generated in {time.time() - t0:.1f} s)")
     C = torch.from_numpy(P.C).to(dev)
     p = torch.from_numpy(P.p).to(dev)
@@ -96,224 +117,263 @@ def main() -> int:
     X = torch.empty_like(C)
     kw = dict(reg_kind=P.reg_kind, lam=P.lam, mu=P.mu, row_class=rc, num_classes=P.num_classes, X_out=X)
     solver = drot.Solver(m, n, check_every=args.check_every, compute_gap=False)
-    solver.set_nontemporal(args.nontemporal)
-    solver.set_skip_cost(args.skip_cost)
-    solver.set_skip_unchanged(args.skip_unchanged)
+
+    def defaults():
+        solver.set_nontemporal(args.nontemporal)
+        solver.set_skip_cost(args.skip_cost)
+        solver.set_skip_unchanged(args.skip_unchanged)
+        solver.set_screening(-1)
+        solver.set_continue(False)
+
+    defaults()
     torch.cuda.synchronize()
-
-    # ---- warm-up (cold start), then exactly K steady-state iterations continuing from it --------------
-    K, W = args.steps, args.warmup
-    solver.solve(C, p, q, max_iters=W, **kw)
-    solver.set_continue(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    res = solver.solve(C, p, q, max_iters=K, **kw)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    assert res.iters == K
-    ms_per_step = elapsed / K * 1e3
-    log(f"{K} iterations in {elapsed:.3f} s -> {K / elapsed:.1f} it/s, {ms_per_step:.4f} ms/iteration")
-
-    # ---- sweep kernel durations from HIP events on the launch stream (profile mode, separate solve) ----
-    c_read = {}  # kind of sweep -> mean fraction of the row segments of C it read (screened kinds: counted by the kernel)
-
-    def sweep_profile():
-        solver.set_profile(True)
-        solver.solve(C, p, q, max_iters=min(K, 256), **kw)
-        per_kind, reads = {}, {}
-        for (ms, kind), frac in zip(solver.profile_sweeps(), solver.profile_reads()):
-            per_kind.setdefault(kind, []).append(ms)
-            reads.setdefault(kind, []).append(frac)
-        solver.set_profile(False)
-        c_read.update({kind: sum(v) / len(v) for kind, v in reads.items()})
-        return {kind: (sum(v) / len(v), len(v)) for kind, v in per_kind.items()}
-
-    def nonzero_segment_fraction():
-        """Fraction of row segments (256 columns of one row) of X that hold a nonzero."""
-        nz = 0
-        for j0 in range(0, n, SEG_COLS):
-            nz += int((X[:, j0:j0 + SEG_COLS] != 0).any(dim=1).sum().item())
-        return nz / (m * ((n + SEG_COLS - 1) // SEG_COLS))
 
     def nonzero_line_fraction():
-        """Fraction of the 128-byte lines (32 columns of one row, counted from the segment's start) of X that hold a nonzero."""
+        """Fraction of the 128-byte lines (32 columns of one row) of X that hold a nonzero."""
         nz = total = 0
         for j0 in range(0, n, 32):
             nz += int((X[:, j0:j0 + 32] != 0).any(dim=1).sum().item())
             total += m
         return nz / total
 
-    def sparse_sweep_bytes(frac, c_frac=1.0, screened=False, tile_rows=64, per_segment=8.0):
-        # C on the fraction c_frac of its row segments; X read and written back only on the fraction
-        # frac of its entries that lie in nonzero row segments (lean kernel: in nonzero 128-byte
-        # lines) -- an upper bound, a piece is charged as a whole; per row segment the old and the
-        # new row sum and the bound M of the screening (lean kernel: the new sum, the bound and two
-        # bytes of line flags, which stand in for the old sum);
-        # the column sums per 64-row tile (per four of them in the lean kernel)
-        nseg = (n + SEG_COLS - 1) // SEG_COLS
-        return (4.0 * c_frac * m * n + 8.0 * frac * m * n + per_segment * m * nseg +
-                4.0 * n * ((m + tile_rows - 1) // tile_rows))
+    def sweep_bytes(rec, x_before, line_frac):
+        """Algorithmic bytes of one profiled sweep: what it must move for the plan at hand.
 
-    line_frac = {}
-
-    def bytes_of(kind, frac):
+        C on the fraction of its row segments the kernel read (counted by the kernel); X read on the row
+        segments that held a nonzero before the sweep and written on those that did or do now (counted
+        by the vector updates; the lean kernel moves 128-byte lines instead of row segments: priced from
+        the plan the run ends with); per row segment the old and new sums, the bound, the line flags;
+        the column sums per tile row.
+        """
+        kind, c, x_after = rec.kind, rec.c_fraction, rec.x_fraction
+        mn = float(m) * n
+        if kind in (0, 1, 3):
+            if kind == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
+                # group-resident group lasso: all of C; of X the nonzero 128-byte lines; two sums per line
+                return (4.0 + 8.0 * line_frac) * mn + 8.0 * m * ((n + 31) // 32) + 4.0 * n * max(1, P.num_classes)
+            return 12.0 * mn
+        if kind == 2:
+            return 8.0 * mn
+        xb = x_after if x_before is None or x_before < 0 else x_before
+        xw = max(xb, x_after)
         if kind == 7:
-            if "v" not in line_frac:
-                line_frac["v"] = nonzero_line_fraction()
-            return sparse_sweep_bytes(line_frac["v"], c_read.get(kind, 1.0), True, 256, 10.0)
-        if kind in (4, 5, 6):
-            return sparse_sweep_bytes(frac, c_read.get(kind, 1.0), kind != 4, 64, 12.0 if kind != 4 else 8.0)
-        if kind == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
-            # group-resident group lasso: all of C; of X the 128-byte lines (32 columns of a row) that hold
-            # a nonzero; per line the old and the new sum; the column sums per class
-            if "v" not in line_frac:
-                line_frac["v"] = nonzero_line_fraction()
-            return (4.0 + 8.0 * line_frac["v"]) * m * n + 8.0 * m * ((n + 31) // 32) + 4.0 * n * max(1, P.num_classes)
-        return BYTES_PER_ELEMENT[kind] * m * n
+            return 4.0 * c * mn + 8.0 * line_frac * mn + 10.0 * m * nseg + 4.0 * n * ((m + 255) // 256)
+        per_segment = 8.0 if kind == 4 else 12.0
+        return 4.0 * c * mn + 4.0 * (xb + xw) * mn + per_segment * m * nseg + 4.0 * n * ((m + 63) // 64)
 
-    def kernel_entry(kind, ms, launches, nbytes=None):
-        nbytes = bytes_of(kind, nonzero_segment_fraction()) if nbytes is None else nbytes
-        gbs = nbytes / (ms * 1e-3) / 1e9
-        return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((P.name, kind)),
-                "kernel": kernel_names[kind], "kernel_ms": round(ms, 5), "launches_timed": launches,
-                "algorithmic_bytes": nbytes}
+    def measure(W, K, label):
+        """Cold start of W iterations, K timed; then the same W + K once more in profile mode."""
+        defaults()
+        solver.solve(C, p, q, max_iters=W, **kw)
+        solver.set_continue(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        res = solver.solve(C, p, q, max_iters=K, **kw)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        assert res.iters == K
+        checksum = (float(X.sum(dtype=torch.float64)), float(X.max()), int((X != 0).sum()))
+        # the same iterations again, profiled (the first 256 of the K)
+        solver.set_continue(False)
+        solver.solve(C, p, q, max_iters=W, **kw)
+        solver.set_continue(True)
+        solver.set_profile(True)
+        solver.solve(C, p, q, max_iters=K, **kw)
+        recs = solver.profile_records()
+        solver.set_profile(False)
+        solver.set_continue(False)
+        again = (float(X.sum(dtype=torch.float64)), float(X.max()), int((X != 0).sum()))
+        assert again == checksum, f"the profiled rerun did not reproduce the timed run: {again} vs {checksum}"
+        line_frac = nonzero_line_fraction() if (any(r.kind == 7 for r in recs) or P.reg_kind == 2) else 0.0
+        per_kind = {}
+        x_before = None
+        for r in recs:
+            b = sweep_bytes(r, x_before, line_frac)
+            e = per_kind.setdefault(r.kind, {"ms": 0.0, "bytes": 0.0, "n": 0, "c": 0.0, "x": 0.0})
+            e["ms"] += r.ms
+            e["bytes"] += b
+            e["n"] += 1
+            e["c"] += r.c_fraction
+            e["x"] += max(r.x_fraction, 0.0)
+            x_before = r.x_fraction
+        entries = {}
+        for kind, e in per_kind.items():
+            gbs = e["bytes"] / (e["ms"] * 1e-3) / 1e9
+            entries[kind] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": KERNEL_NAMES[kind]
+                             if not (kind == 0 and P.reg_kind == 2) else "gl_slab_kernel / group-lasso sweep",
+                             "kernel_ms": round(e["ms"] / e["n"], 5), "launches_timed": e["n"],
+                             "algorithmic_bytes": e["bytes"] / e["n"],
+                             "c_row_segments_read_fraction": round(e["c"] / e["n"], 5),
+                             "nonzero_row_segment_fraction": round(e["x"] / e["n"], 5)}
+            if kind in (4, 5, 6, 7):
+                entries[kind]["dense_model_gbs"] = round(12.0 * m * n / (e["ms"] / e["n"] * 1e-3) / 1e9, 1)
+        dominant = max(per_kind, key=lambda k: per_kind[k]["ms"])
+        roof = dict(entries[dominant])
+        roof["other_kernels"] = [entries[k] for k in sorted(entries) if k != dominant]
+        roof["bytes_model"] = ("per launch: 4 B x the row segments of C read (counted by the kernel) + X read on the row segments "
+                               "nonzero before and written on those nonzero before or after (counted by the vector updates; lean "
+                               "kernel: the nonzero 128-byte lines of the final plan) + 8-12 B per row segment (sums, bound, line "
+                               "flags) + column sums; dense sweeps 12 (8 without C) B per element; dense_model_gbs prices the "
+                               "launch at 12 B per element")
+        if line_frac:
+            roof["nonzero_line_fraction"] = round(line_frac, 6)
+        sweep_ms = sum(e["ms"] for e in per_kind.values()) / max(1, len(recs))
+        total_bytes = sum(e["bytes"] for e in per_kind.values()) / max(1, len(recs))
+        ms_per_step = elapsed / K * 1e3
+        out = {"value": round(K / elapsed, 2), "unit": "iterations/s", "warmup": W, "steps": K,
+               "ms_per_step": round(ms_per_step, 5), "roofline": roof,
+               "iteration_breakdown_ms": {"sweep_kernel_mean": round(sweep_ms, 5),
+                                          "vector_update_and_launch_gaps": round(max(ms_per_step - sweep_ms, 0.0), 5),
+                                          "sweeps_profiled": len(recs)},
+               "algorithmic_bytes_per_iteration": total_bytes,
+               "hbm_gbs_whole_iteration": round(total_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+               "dense_model_gbs_whole_iteration": round(12.0 * m * n / (ms_per_step * 1e-3) / 1e9, 1)}
+        # counter-measured traffic: only for the very run the counters were taken on
+        if os.path.exists(TRAFFIC_FILE):
+            tr = json.load(open(TRAFFIC_FILE))
+            if tr.get("workload") == P.name and tr.get("warmup") == W and tr.get("steps") == K:
+                key = {7: "screened_lean_kernel", 5: "screened_sweep_kernel", 4: "sweep_kernel_tall"}.get(dominant)
+                if key in tr.get("bytes_per_launch", {}):
+                    roof["traffic"] = tr["bytes_per_launch"][key]
+                    roof["traffic_source"] = tr.get("source")
+        log(f"{label}: {K} iterations after {W} in {elapsed:.4f} s -> {K / elapsed:.1f} it/s, {ms_per_step:.4f} ms/iteration "
+            f"(sweeps {sweep_ms:.4f} ms); dominant [{roof['kernel']}]: {roof['kernel_ms']:.4f} ms x {roof['launches_timed']} "
+            f"-> {roof['achieved']:.0f} GB/s algorithmic ({roof['frac']:.1%} of {HBM_PEAK_GBS:.0f})")
+        for e in roof["other_kernels"]:
+            log(f"    also [{e['kernel']}]: {e['kernel_ms']:.4f} ms x {e['launches_timed']} -> {e['achieved']:.0f} GB/s ({e['frac']:.1%})")
+        return out
 
-    kernel_names = {0: "gl_slab_kernel" if P.reg_kind == 2 else "sweep_kernel (reads X and C, stores X)",
-                    1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
-                    2: "sweep_kernel, second of a pair (reads X - rho*C, stores X)",
-                    3: "resident_kernel (X and C stay in registers; the time is per iteration)",
-                    4: "sweep_kernel on 64-row tiles (reads C; reads and stores only the nonzero row segments of X)",
-                    5: "screened_sweep_kernel (reads C only where a bound does not certify zeros; nonzero row segments of X)",
-                    6: "screened_sweep_kernel, refresh (reads all of C, records the bounds)",
-                    7: "screened_lean_kernel (one wave per 64 x 256 tile; reads C only where a bound does not certify zeros)"}
-    prof = sweep_profile()
-    frac_nz = nonzero_segment_fraction()
-    kind_bytes = {k: bytes_of(k, frac_nz) for k in prof}
-    dominant = max(prof, key=lambda kind: prof[kind][0] * prof[kind][1])
-    roofline = kernel_entry(dominant, *prof[dominant], nbytes=kind_bytes[dominant])
-    bytes_per_iteration = sum(kind_bytes[k] * cnt for k, (_, cnt) in prof.items()) / sum(c for _, c in prof.values())
-    log(f"dominant sweep kernel [{roofline['kernel']}]: {roofline['kernel_ms']:.4f} ms mean over {roofline['launches_timed']} launches "
-        f"-> {roofline['achieved']:.0f} GB/s algorithmic ({roofline['frac']:.1%} of {HBM_PEAK_GBS:.0f} GB/s)")
-    if dominant == 0 and P.reg_kind == 2 and "v" in line_frac:
-        roofline["bytes_model"] = ("4 B per element (C) + 8 B x the entries of X in nonzero 128-byte lines (counted on the final plan) "
-                                   "+ 8 B per line (old and new sums) + column sums; the working set fits the 256 MB memory-side cache")
-        roofline["nonzero_line_fraction"] = round(line_frac["v"], 6)
-        roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
-        log(f"nonzero 128-byte lines of X: {line_frac['v']:.3%}; priced at 12 B/element the sweep would read {roofline['dense_model_gbs']:.0f} GB/s")
-    if dominant in (4, 5, 6, 7):
-        roofline["bytes_model"] = ("4 B x the row segments of C read (counted by the kernel) + 8 B x the entries of X in nonzero row segments "
-                                   "(lean kernel: in nonzero 128-byte lines; counted on the final plan) + 8-12 B per row segment (old and new "
-                                   "sums, bound, line flags) + column sums; dense_model_* prices the same launch at 12 B per element")
-        roofline["nonzero_row_segment_fraction"] = round(frac_nz, 5)
-        if "v" in line_frac:
-            roofline["nonzero_line_fraction"] = round(line_frac["v"], 6)
-        roofline["c_row_segments_read_fraction"] = round(c_read.get(dominant, 1.0), 5)
-        roofline["other_kernels"] = [kernel_entry(k, *prof[k], nbytes=kind_bytes[k]) for k in sorted(prof) if k != dominant]
-        roofline["dense_model_bytes"] = 12.0 * m * n
-        roofline["dense_model_gbs"] = round(12.0 * m * n / (roofline["kernel_ms"] * 1e-3) / 1e9, 1)
-        # (above 1: the sweep does not move the bytes the dense model charges; the leg every_byte_moved
-        # below is the same solver made to move them all, with its own roofline)
-        roofline["dense_model_frac"] = round(roofline["dense_model_gbs"] / HBM_PEAK_GBS, 3)
-        log(f"nonzero row segments of X: {frac_nz:.3%}" + (f" (128-byte lines: {line_frac['v']:.4%})" if "v" in line_frac else "") +
-            f"; row segments of C read: {c_read.get(dominant, 1.0):.3%}; "
-            f"the same sweep priced at 12 B/element would read {roofline['dense_model_gbs']:.0f} GB/s")
-        for e in roofline["other_kernels"]:
-            log(f"  also [{e['kernel']}]: {e['kernel_ms']:.4f} ms over {e['launches_timed']} launches -> {e['achieved']:.0f} GB/s ({e['frac']:.1%})")
+    # ---- the timed region the command line asks for ---------------------------------------------------
+    K, W = args.steps, args.warmup
+    main_leg = measure(W, K, "timed region")
+    steady = None
+    if (W, K) == (STEADY_WARMUP, STEADY_STEPS):
+        steady = main_leg
+    elif "steady" in legs and P.m * P.n >= 1 << 22:
+        steady = measure(STEADY_WARMUP, STEADY_STEPS, "steady state")
 
-    def timed_leg(label, nbytes=None):
-        """K more iterations from the current state with the solver's current settings, then a profile."""
+    # ---- the same steady-state iterations with the screening off, in pairs, with every byte moved -------
+    def variant(label, **options):
+        defaults()
+        solver.solve(C, p, q, max_iters=STEADY_WARMUP, **kw)
+        for name, value in options.items():
+            getattr(solver, f"set_{name}")(value)
         solver.set_continue(True)
         solver.solve(C, p, q, max_iters=2, **kw)  # (settle the scheme's first-sweep special cases)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        solver.solve(C, p, q, max_iters=K, **kw)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        lprof = sweep_profile()
-        solver.set_continue(False)
-        leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
-               "kernels": [kernel_entry(k, *lprof[k], nbytes=nbytes) for k in sorted(lprof)]}
-        log(f"{label}: {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; " +
-            "; ".join(f"{e['kernel_ms']:.4f} ms = {e['achieved']:.0f} GB/s ({e['frac']:.1%})" for e in leg["kernels"]))
-        return leg
-
-    # ---- the same K iterations with the even/odd scheme, and with every byte moved ----------------------
-    even_odd_leg = dense_leg = None
-    unscreened_leg = None
-    if dominant in (5, 6, 7):
-        solver.set_screening(0)
-        unscreened_leg = timed_leg("zero segments skipped, all of C read")
-        solver.set_screening(-1)
-    if dominant in (4, 5, 6, 7):
-        solver.set_skip_cost(1)
-        even_odd_leg = timed_leg("even/odd scheme (20 B/element and pair)")
-        solver.set_skip_cost(0)
-        solver.set_skip_unchanged(0)
-        dense_leg = timed_leg("every byte moved (12 B/element)")
-        solver.set_skip_cost(args.skip_cost)
-        solver.set_skip_unchanged(args.skip_unchanged)
-    if dominant == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
-        solver.set_skip_unchanged(0)
-        dense_leg = timed_leg("every byte moved (12 B/element)", nbytes=12.0 * m * n)
-        solver.set_skip_unchanged(args.skip_unchanged)
-    solver.set_continue(False)
-
-    # ---- the same K iterations with the cost recomputed from the point clouds ------------------------
-    points_leg = None
-    if P.reg_kind != 2 and P.xs is not None and (args.points or not args.skip_tol):
-        xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
-        cs = float(np.float32(1.0 / P.cmax))
-        pkw = dict(reg_kind=P.reg_kind, lam=P.lam, X_out=X)
-        solver.solve_points(xs, xt, cs, p, q, max_iters=W, **pkw)
-        solver.set_continue(True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        solver.solve_points(xs, xt, cs, p, q, max_iters=K, **pkw)
+        solver.solve(C, p, q, max_iters=STEADY_STEPS, **kw)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         solver.set_profile(True)
-        solver.solve_points(xs, xt, cs, p, q, max_iters=min(K, 256), **pkw)
+        solver.solve(C, p, q, max_iters=256, **kw)
+        recs = solver.profile_records()
+        solver.set_profile(False)
+        line_frac = nonzero_line_fraction() if P.reg_kind == 2 else 0.0
+        kernels, x_before = {}, None
+        for r in recs:
+            e = kernels.setdefault(r.kind, {"ms": 0.0, "bytes": 0.0, "n": 0})
+            e["ms"] += r.ms
+            e["bytes"] += sweep_bytes(r, x_before, line_frac)
+            e["n"] += 1
+            x_before = r.x_fraction
+        ks = []
+        for kind in sorted(kernels):
+            e = kernels[kind]
+            gbs = e["bytes"] / (e["ms"] * 1e-3) / 1e9
+            ks.append({"kernel": KERNEL_NAMES[kind], "kernel_ms": round(e["ms"] / e["n"], 5), "launches_timed": e["n"],
+                       "algorithmic_bytes": e["bytes"] / e["n"], "achieved": round(gbs, 1), "unit": "GB/s",
+                       "frac": round(gbs / HBM_PEAK_GBS, 4), "bound": "hbm", "peak": HBM_PEAK_GBS, "traffic": None})
+        log(f"{label}: {STEADY_STEPS / dt:.1f} it/s, {dt / STEADY_STEPS * 1e3:.4f} ms/iteration; " +
+            "; ".join(f"{e['kernel_ms']:.4f} ms = {e['achieved']:.0f} GB/s ({e['frac']:.1%})" for e in ks))
+        defaults()
+        return {"value": round(STEADY_STEPS / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / STEADY_STEPS * 1e3, 5),
+                "kernels": ks}
+
+    unscreened_leg = even_odd_leg = dense_leg = None
+    if "variants" in legs and steady is not None:
+        if P.reg_kind != 2:
+            unscreened_leg = variant("zero segments skipped, all of C read", screening=0)
+            even_odd_leg = variant("even/odd scheme (20 B/element and pair)", skip_cost=1)
+            dense_leg = variant("every byte moved (12 B/element)", skip_cost=0, skip_unchanged=0)
+        else:
+            dense_leg = variant("every byte moved (12 B/element)", skip_unchanged=0)
+
+    # ---- the same iterations with the cost recomputed from the point clouds --------------------------
+    points_leg = None
+    if "points" in legs and P.reg_kind != 2 and P.xs is not None:
+        xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
+        cs = float(np.float32(1.0 / P.cmax))
+        pkw = dict(reg_kind=P.reg_kind, lam=P.lam, X_out=X)
+        defaults()
+        solver.solve_points(xs, xt, cs, p, q, max_iters=STEADY_WARMUP, **pkw)
+        solver.set_continue(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        solver.solve_points(xs, xt, cs, p, q, max_iters=STEADY_STEPS, **pkw)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        solver.set_profile(True)
+        solver.solve_points(xs, xt, cs, p, q, max_iters=256, **pkw)
         pms, _ = solver.profile()
         solver.set_profile(False)
         solver.set_continue(False)
-        # bytes: X read and written on its nonzero row segments only (with the zero-segment skipping
-        # on; every element otherwise), the old and new row sums, the column sums; the contraction is
-        # 2d flops per element on the fp32 matrix cores whatever the plan looks like
-        fnz = nonzero_segment_fraction() if args.skip_unchanged != 0 else 1.0
-        pbytes = 8.0 * fnz * m * n + 8.0 * m * ((n + SEG_COLS - 1) // SEG_COLS) + 4.0 * n * ((m + 31) // 32)
-        points_leg = {"value": round(K / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / K * 1e3, 5),
-                      "d": int(P.xs.shape[1]), "algorithmic_bytes_per_iteration": pbytes,
-                      "nonzero_row_segment_fraction": round(fnz, 5),
-                      "kernel_ms": round(pms, 5), "kernel_hbm_gbs": round(pbytes / (pms * 1e-3) / 1e9, 1),
-                      "kernel_tflops": round(2.0 * P.xs.shape[1] * m * n / (pms * 1e-3) / 1e12, 2)}
-        log(f"cost from point clouds (d={points_leg['d']}): {K / dt:.1f} it/s, {dt / K * 1e3:.4f} ms/iteration; sweep "
-            f"{pms:.4f} ms = {points_leg['kernel_tflops']} TFLOP/s fp32 MFMA, {points_leg['kernel_hbm_gbs']:.0f} GB/s of HBM "
-            f"(X on its {fnz:.1%} nonzero row segments)")
+        d = int(P.xs.shape[1])
+        tflops = 2.0 * d * m * n / (pms * 1e-3) / 1e12
+        points_leg = {"value": round(STEADY_STEPS / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / STEADY_STEPS * 1e3, 5),
+                      "d": d, "kernel_ms": round(pms, 5),
+                      "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                                   "kernel": "sweep_points_kernel (2 d flops per element on the fp32 matrix cores)"}}
+        log(f"cost from point clouds (d={d}): {STEADY_STEPS / dt:.1f} it/s, {dt / STEADY_STEPS * 1e3:.4f} ms/iteration; sweep "
+            f"{pms:.4f} ms = {tflops:.1f} TFLOP/s fp32 MFMA")
 
-    # ---- time to tolerance (cold start, residual test every check_every iterations) -------------------
-    tol_leg = None
-    if not args.skip_tol:
+    # ---- time to tolerance / to a duality gap (cold start), verified in fp64 by independent code -------
+    def to_tolerance(label, gap_tol):
+        defaults()
         solver.set_compute_gap(True)
+        solver.set_gap_tolerance(gap_tol)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         r = solver.solve(C, p, q, max_iters=args.tol_max_iters, tol=args.tol, **kw)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        tol_leg = {"tol": args.tol, "seconds": round(dt, 4), "iters": r.iters, "converged": bool(r.converged),
-                   "r_row": r.r_row, "r_col": r.r_col, "objective": r.objective, "gap": r.gap,
-                   "dual_res": r.dual_res, "check_every": args.check_every}
-        log(f"time to {args.tol:g}: {dt:.3f} s, {r.iters} iterations, converged={r.converged}, "
-            f"residuals {r.r_row:.2e}/{r.r_col:.2e}, objective {r.objective:.6f}, gap {r.gap:.3e}")
+        solver.set_gap_tolerance(0.0)
         solver.set_compute_gap(False)
+        phi, varphi = solver.duals(m, n, dev)
+        t = drot_checks.fp64_terms(C, X, p, q, phi, varphi, float(P.rho), reg_kind=P.reg_kind, lam=float(np.float32(P.lam)),
+                                   mu=float(np.float32(P.mu)), row_class=rc, num_classes=P.num_classes)
+        leg = {"tol": args.tol, "gap_tol": gap_tol or None, "seconds": round(dt, 4), "iters": r.iters,
+               "converged": bool(r.converged), "r_row": r.r_row, "r_col": r.r_col, "objective": r.objective, "gap": r.gap,
+               "dual_res": r.dual_res, "check_every": args.check_every,
+               "fp64_check": {"min_entry": t.min_entry, "r_row": t.r_row, "r_col": t.r_col, "objective": t.objective,
+                              "gap": t.gap, "dual_res": t.dual_res, "nonzeros": t.nnz,
+                              "by": "drot_checks.py (plain torch fp64; shares no code with the library or the oracle)"}}
+        log(f"{label}: {dt:.3f} s, {r.iters} iterations, converged={r.converged}, residuals {r.r_row:.2e}/{r.r_col:.2e}, "
+            f"objective {r.objective:.6f}, gap {r.gap:.3e}; fp64: min {t.min_entry:.1e}, residuals {t.r_row:.2e}/{t.r_col:.2e}, "
+            f"objective {t.objective:.6f}, gap {t.gap:.3e}")
+        return leg
+
+    tol_leg = to_tolerance(f"time to a residual of {args.tol:g}", 0.0) if "tol" in legs else None
+    gap_leg = to_tolerance(f"time to a residual of {args.tol:g} and a gap of {args.gap_tol:g} x objective", args.gap_tol) \
+        if "gap" in legs else None
+
+    # ---- sizes n and n - 1 side by side (rows on and off the 128-byte lines) -----------------------------
+    alignment_leg = None
+    if "alignment" in legs and args.config == 4 and not args.size:
+        del X, C
+        torch.cuda.empty_cache()
+        alignment_leg = alignment(torch, drot, dev)
+        C = X = None
 
     # ---- CPU oracle on the host cores of this box, bounded sample of the same workload ---------------
     cpu = None
-    if not args.skip_cpu:
+    if "cpu" in legs:
         from oracle import drot_oracle
 
         drot_oracle.build()
-        del X
+        X = C = None
         torch.cuda.empty_cache()
         okw = dict(rho=float(P.rho), reg_kind=P.reg_kind, lam=float(np.float32(P.lam)), mu=float(np.float32(P.mu)),
                    row_class=P.row_class, num_classes=P.num_classes)
@@ -322,7 +382,7 @@ def main() -> int:
             t0 = time.perf_counter()
             drot_oracle.solve(P.C, P.p, P.q, max_iters=4, **okw)
             per_iter = (time.perf_counter() - t0) / 4
-            iters = max(2, min(20000, int(25.0 / per_iter)))
+            iters = max(2, min(20000, int(20.0 / per_iter)))
         t0 = time.perf_counter()
         drot_oracle.solve(P.C, P.p, P.q, max_iters=iters, **okw)
         dt = time.perf_counter() - t0
@@ -334,22 +394,65 @@ def main() -> int:
     out = {
         "metric": "DR iterations/sec at m=n=20000 fp32" if (args.config == 4 and not args.size)
         else f"DR iterations/sec at {m}x{n} fp32",
-        "value": round(K / elapsed, 2), "unit": "iterations/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": main_leg["value"], "unit": "iterations/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": main_leg["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": P.name, "m": m, "n": n, "reg_kind": int(P.reg_kind), "lambda": P.lam, "mu": P.mu,
                    "stepsize": float(P.rho), "check_every": args.check_every},
-        "algorithmic_bytes_per_iteration": bytes_per_iteration,
-        # (the dense model's 12 B per element over the iteration time: what a solver that moves every
-        # byte would have to sustain to keep up; far above the 8000 GB/s peak when the sweeps skip work)
-        "dense_model_gbs_whole_iteration": round(12.0 * m * n / (ms_per_step * 1e-3) / 1e9, 1),
-        "hbm_gbs_whole_iteration": round(bytes_per_iteration / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": roofline, "time_to_tol": tol_leg, "unscreened": unscreened_leg, "even_odd_scheme": even_odd_leg,
-        "every_byte_moved": dense_leg,
-        "cost_from_points": points_leg, "cpu_baseline": cpu,
+        "algorithmic_bytes_per_iteration": main_leg["algorithmic_bytes_per_iteration"],
+        "hbm_gbs_whole_iteration": main_leg["hbm_gbs_whole_iteration"],
+        "dense_model_gbs_whole_iteration": main_leg["dense_model_gbs_whole_iteration"],
+        "iteration_breakdown_ms": main_leg["iteration_breakdown_ms"],
+        "roofline": main_leg["roofline"],
+        "steady_state": steady if steady is not main_leg else "the timed region above (same warm-up and steps)",
+        "time_to_tol": tol_leg, "time_to_gap": gap_leg, "unscreened": unscreened_leg, "even_odd_scheme": even_odd_leg,
+        "every_byte_moved": dense_leg, "cost_from_points": points_leg, "alignment": alignment_leg, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0
+
+
+def alignment(torch, drot, dev):
+    """Iterations per second at n and n - 1 (the paper's Table 3 sizes): rows on and off the 128-byte lines,
+    with every byte moved and with the library's defaults.  Synthetic clouds made on the device."""
+    rows = []
+    for n in (4096, 8192, 10240):
+        pair = {}
+        for size in (n, n - 1):
+            gen = torch.Generator(device=dev).manual_seed(4000 + size)
+            xs = torch.randn((size, 8), generator=gen, device=dev)
+            xt = 0.3 + 1.2 * torch.randn((size, 8), generator=gen, device=dev)
+            C = torch.cdist(xs, xt).pow_(2)
+            C /= C.max()
+            p = torch.full((size,), 1.0 / size, device=dev)
+            q = torch.full((size,), 1.0 / size, device=dev)
+            X = torch.empty_like(C)
+            solver = drot.Solver(size, size, compute_gap=False)
+            for scheme in ("every_byte_moved", "default"):
+                if scheme == "every_byte_moved":
+                    solver.set_skip_cost(0)
+                    solver.set_skip_unchanged(0)
+                else:
+                    solver.set_skip_cost(-1)
+                    solver.set_skip_unchanged(-1)
+                solver.set_continue(False)
+                solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=200, X_out=X)
+                solver.set_continue(True)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=300, X_out=X)
+                torch.cuda.synchronize()
+                pair[(size, scheme)] = 300 / (time.perf_counter() - t0)
+            solver.close()
+            del C, X
+            torch.cuda.empty_cache()
+        for scheme in ("every_byte_moved", "default"):
+            a, b = pair[(n, scheme)], pair[(n - 1, scheme)]
+            rows.append({"n": n, "scheme": scheme, "its_per_s_n": round(a, 1), "its_per_s_n_minus_1": round(b, 1),
+                         "slowdown_percent": round((a / b - 1.0) * 100.0, 2)})
+            log(f"alignment {n} vs {n - 1} [{scheme}]: {a:.0f} vs {b:.0f} it/s ({(a / b - 1.0) * 100.0:+.2f} %)")
+    return {"note": "300 iterations continuing a 200-iteration cold start, each call copying X out of the padded working copy "
+                    "when n % 32 != 0", "rows": rows}
 
 
 if __name__ == "__main__":

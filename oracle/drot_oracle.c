@@ -178,19 +178,31 @@ void oracle_prox_entrywise(double* Xbar, int m, int n, double rho, const float* 
  * Since Y_{k+1} - X_{k+1} = Z_{k+1} - (2X_{k+1} - Y_k), the vectors phi_{k+1}, varphi_{k+1}
  * of eq. (5) are the projection's two correction vectors; they are returned for the last step.
  *
- * Stopping (Appendix C): r = X 1 - p, s = X^T 1 - q, stop when max(||r||_2, ||s||_2) <= tol,
- * tested only at iterations that are multiples of check_every (tol <= 0: never).
+ * Stopping (Section 3 "Stopping criteria", Appendix C): r = X 1 - p, s = X^T 1 - q, stop when
+ * max(||r||_2, ||s||_2) <= tol, tested only at iterations that are multiples of check_every
+ * (tol <= 0: never).  With gap_every >= 1 the objective, the duality gap and the dual residual of
+ * (X_k, phi_k, varphi_k) are evaluated at every gap_every-th of those tests (oracle_objective_gap
+ * below) and written to gap_trace (optional; 4 doubles per evaluation: k, objective, gap, dual
+ * residual; capacity gap_trace_cap evaluations, *gap_trace_len receives their number); with
+ * gap_tol > 0 a test then passes only if the gap was evaluated at it and
+ * |gap| <= gap_tol * |objective| and dual residual <= gap_tol.
  * res_trace (optional, 2*max_iters doubles): ||r||_2, ||s||_2 of every iterate.
  * W, forbidden (optional): the entrywise terms of oracle_prox_entrywise, added to h.
  * Returns the number of iterations done, or -1 if memory ran out.
  */
+void oracle_objective_gap(const float* C, const double* X, const double* p, const double* q,
+                          const double* phi, const double* varphi, int m, int n, double rho,
+                          int reg_kind, double lambda, double mu, const int* row_class,
+                          int num_classes, const float* Wl1, const unsigned char* forbidden,
+                          double* out);
+
 int oracle_drot_solve(const float* C, const double* p, const double* q, int m, int n, double rho,
                       int reg_kind, double lambda, double mu, const int* row_class, int num_classes,
                       const float* W, const unsigned char* forbidden,
                       const double* X0, const double* phi0, const double* varphi0,
-                      int max_iters, double tol, int check_every,
+                      int max_iters, double tol, int check_every, int gap_every, double gap_tol,
                       double* X_out, double* Y_out, double* phi_out, double* varphi_out,
-                      double* res_trace) {
+                      double* res_trace, double* gap_trace, int gap_trace_cap, int* gap_trace_len) {
   const size_t mn = (size_t)m * n;
   double* X = X_out;
   double* Y = (double*)malloc(sizeof(double) * mn);
@@ -215,7 +227,7 @@ int oracle_drot_solve(const float* C, const double* p, const double* q, int m, i
   for (int i = 0; i < m; ++i) phi_out[i] = phi0[i];
   for (int j = 0; j < n; ++j) varphi_out[j] = varphi0[j];
 
-  int k = 0;
+  int k = 0, ngap = 0;
   while (k < max_iters) {
     /* x-update */
 #pragma omp parallel for schedule(static)
@@ -251,8 +263,26 @@ int oracle_drot_solve(const float* C, const double* p, const double* q, int m, i
     nr = sqrt(nr);
     ns = sqrt(ns);
     if (res_trace) { res_trace[2 * (size_t)(k - 1)] = nr; res_trace[2 * (size_t)(k - 1) + 1] = ns; }
-    if (tol > 0.0 && k % check_every == 0 && nr <= tol && ns <= tol) break;
+    if (k % check_every == 0) {
+      int gap_ok = gap_tol <= 0.0;
+      if (gap_every >= 1 && (k / check_every) % gap_every == 0) {
+        double t[6];
+        oracle_objective_gap(C, X, p, q, phi_out, varphi_out, m, n, rho, reg_kind, lambda, mu, row_class,
+                             num_classes, W, forbidden, t);
+        const double objective = t[0] + t[1];
+        if (gap_trace && ngap < gap_trace_cap) {
+          gap_trace[4 * (size_t)ngap] = (double)k;
+          gap_trace[4 * (size_t)ngap + 1] = objective;
+          gap_trace[4 * (size_t)ngap + 2] = t[4];
+          gap_trace[4 * (size_t)ngap + 3] = t[5];
+        }
+        ++ngap;
+        if (gap_tol > 0.0) gap_ok = fabs(t[4]) <= gap_tol * fabs(objective) && t[5] <= gap_tol;
+      }
+      if (tol > 0.0 && nr <= tol && ns <= tol && gap_ok) break;
+    }
   }
+  if (gap_trace_len) *gap_trace_len = ngap < gap_trace_cap ? ngap : gap_trace_cap;
   if (Y_out) memcpy(Y_out, Y, sizeof(double) * mn);
   free(Y); free(V); free(rs); free(cs); free(gscratch);
   return k;

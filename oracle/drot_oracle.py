@@ -58,8 +58,8 @@ def _load():
             ctypes.c_int, ctypes.c_double, ctypes.c_double, _c_int_p, ctypes.c_int,
             _c_float_p, _c_ubyte_p,
             _c_double_p, _c_double_p, _c_double_p,
-            ctypes.c_int, ctypes.c_double, ctypes.c_int,
-            _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p]
+            ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+            _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p, ctypes.c_int, _c_int_p]
         lib.oracle_drot_solve.restype = ctypes.c_int
         lib.oracle_objective_gap.argtypes = [
             _c_float_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p, _c_double_p,
@@ -165,6 +165,7 @@ class OracleResult:
     res_row: np.ndarray  # ||X_k 1 - p||_2 for k = 1..iters
     res_col: np.ndarray
     Y: Optional[np.ndarray] = None
+    gap_trace: Optional[np.ndarray] = None  # rows (k, objective, gap, dual residual) of the gap evaluations
 
 
 def prox_entrywise(Xbar, rho, weights=None, forbidden=None):
@@ -177,7 +178,7 @@ def prox_entrywise(Xbar, rho, weights=None, forbidden=None):
 
 def solve(C, p, q, rho=None, reg_kind=REG_NONE, lam=0.0, mu=0.0, row_class=None, num_classes=0,
           max_iters=1000, tol=0.0, check_every=1, X0=None, phi0=None, varphi0=None,
-          return_Y=False, weights=None, forbidden=None) -> OracleResult:
+          return_Y=False, weights=None, forbidden=None, gap_every=0, gap_tol=0.0) -> OracleResult:
     """Run the plain three-update iteration; see oracle_drot_solve in the C file."""
     C = np.ascontiguousarray(C, dtype=np.float32)
     m, n = C.shape
@@ -196,14 +197,21 @@ def solve(C, p, q, rho=None, reg_kind=REG_NONE, lam=0.0, mu=0.0, row_class=None,
     Y = np.empty((m, n)) if return_Y else None
     phi, varphi = np.empty(m), np.empty(n)
     trace = np.zeros(2 * max(1, max_iters))
+    if gap_tol > 0 and gap_every < 1:
+        gap_every = 1  # (a gap tolerance needs the gap at the checks)
+    gap_cap = max_iters // max(1, check_every * max(1, gap_every)) + 1 if gap_every >= 1 else 1
+    gtrace = np.zeros(4 * gap_cap)
+    glen = ctypes.c_int(0)
     it = _load().oracle_drot_solve(
         C.ctypes.data_as(_c_float_p), _dp(p), _dp(q), m, n, rho, int(reg_kind), float(lam), float(mu),
         _ip(rc), int(num_classes), _fp(W), _bp(S), _dp(X0), _dp(phi0), _dp(varphi0), int(max_iters), float(tol),
-        int(check_every), _dp(X), _dp(Y), _dp(phi), _dp(varphi), _dp(trace))
+        int(check_every), int(gap_every), float(gap_tol), _dp(X), _dp(Y), _dp(phi), _dp(varphi), _dp(trace),
+        _dp(gtrace), int(gap_cap), ctypes.byref(glen))
     if it < 0:
         raise MemoryError("oracle ran out of memory")
     tr = trace[: 2 * it].reshape(-1, 2)
-    return OracleResult(X=X, phi=phi, varphi=varphi, iters=it, res_row=tr[:, 0].copy(), res_col=tr[:, 1].copy(), Y=Y)
+    return OracleResult(X=X, phi=phi, varphi=varphi, iters=it, res_row=tr[:, 0].copy(), res_col=tr[:, 1].copy(), Y=Y,
+                        gap_trace=gtrace[: 4 * glen.value].reshape(-1, 4).copy())
 
 
 @dataclass

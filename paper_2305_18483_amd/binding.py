@@ -22,9 +22,14 @@ DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -
 
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
-    "drot_create", "drot_destroy", "drot_set_check_every", "drot_set_compute_gap", "drot_set_continue",
-    "drot_set_group_two_pass", "drot_set_nontemporal", "drot_set_fused_update", "drot_set_resident", "drot_set_screening", "drot_set_skip_unchanged", "drot_set_skip_cost", "drot_set_profile", "drot_get_profile", "drot_get_profile_sweeps", "drot_get_profile_reads", "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_create", "drot_destroy", "drot_set_option", "drot_set_gap_tolerance", "drot_get_checks", "drot_get_profile",
+    "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
 )
+
+# drot_option
+(DROT_OPT_CHECK_EVERY, DROT_OPT_COMPUTE_GAP, DROT_OPT_GAP_EVERY, DROT_OPT_CONTINUE, DROT_OPT_PROFILE,
+ DROT_OPT_SKIP_UNCHANGED, DROT_OPT_SCREENING, DROT_OPT_SKIP_COST, DROT_OPT_FUSED_UPDATE, DROT_OPT_RESIDENT,
+ DROT_OPT_GROUP_TWO_PASS, DROT_OPT_NONTEMPORAL) = range(12)
 
 
 class drot_reg_params(ctypes.Structure):
@@ -36,6 +41,17 @@ class drot_info(ctypes.Structure):
     _fields_ = [("iters", ctypes.c_int), ("converged", ctypes.c_int), ("r_row", ctypes.c_float),
                 ("r_col", ctypes.c_float), ("objective", ctypes.c_double), ("gap", ctypes.c_double),
                 ("dual_res", ctypes.c_double)]
+
+
+class drot_check(ctypes.Structure):
+    _fields_ = [("iters", ctypes.c_int), ("gap_evaluated", ctypes.c_int), ("r_row", ctypes.c_float),
+                ("r_col", ctypes.c_float), ("objective", ctypes.c_double), ("gap", ctypes.c_double),
+                ("dual_res", ctypes.c_double)]
+
+
+class drot_sweep_timing(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_float), ("kind", ctypes.c_int), ("c_fraction", ctypes.c_double),
+                ("x_fraction", ctypes.c_double)]
 
 
 class DrotError(RuntimeError):
@@ -60,20 +76,10 @@ def load_library() -> ctypes.CDLL:
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lib.drot_create.argtypes = [ctypes.POINTER(vp), ci, ci]
     lib.drot_destroy.argtypes = [vp]
-    lib.drot_set_check_every.argtypes = [vp, ci]
-    lib.drot_set_compute_gap.argtypes = [vp, ci]
-    lib.drot_set_continue.argtypes = [vp, ci]
-    lib.drot_set_group_two_pass.argtypes = [vp, ci]
-    lib.drot_set_nontemporal.argtypes = [vp, ci]
-    lib.drot_set_fused_update.argtypes = [vp, ci]
-    lib.drot_set_resident.argtypes = [vp, ci]
-    lib.drot_set_skip_unchanged.argtypes = [vp, ci]
-    lib.drot_set_screening.argtypes = [vp, ci]
-    lib.drot_set_skip_cost.argtypes = [vp, ci]
-    lib.drot_set_profile.argtypes = [vp, ci]
-    lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
-    lib.drot_get_profile_sweeps.argtypes = [vp, ctypes.POINTER(cf), ctypes.POINTER(ci), ci, ctypes.POINTER(ci)]
-    lib.drot_get_profile_reads.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ci, ctypes.POINTER(ci)]
+    lib.drot_set_option.argtypes = [vp, ci, ci]
+    lib.drot_set_gap_tolerance.argtypes = [vp, cf]
+    lib.drot_get_checks.argtypes = [vp, ctypes.POINTER(drot_check), ci, ctypes.POINTER(ci)]
+    lib.drot_get_profile.argtypes = [vp, ctypes.POINTER(drot_sweep_timing), ci, ctypes.POINTER(ci)]
     lib.drot_solve.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp]
     lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_solve_points.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf,
@@ -129,88 +135,88 @@ class Solver:
         if compute_gap is not None:
             self.set_compute_gap(compute_gap)
 
-    def set_check_every(self, k: int) -> None:
-        rc = self._lib.drot_set_check_every(self._h, int(k))
+    def set_option(self, option: int, value: int) -> None:
+        rc = self._lib.drot_set_option(self._h, int(option), int(value))
         if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_check_every")
+            raise DrotError(rc, f"drot_set_option({option}, {value})")
+
+    # one name per option of include/drot.h
+    def set_check_every(self, k: int) -> None:
+        self.set_option(DROT_OPT_CHECK_EVERY, k)
 
     def set_compute_gap(self, enable: bool) -> None:
-        rc = self._lib.drot_set_compute_gap(self._h, int(bool(enable)))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_compute_gap")
+        self.set_option(DROT_OPT_COMPUTE_GAP, bool(enable))
+
+    def set_gap_every(self, k: int) -> None:
+        self.set_option(DROT_OPT_GAP_EVERY, k)
 
     def set_continue(self, enable: bool) -> None:
-        rc = self._lib.drot_set_continue(self._h, int(bool(enable)))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_continue")
-
-    def set_group_two_pass(self, enable: bool) -> None:
-        rc = self._lib.drot_set_group_two_pass(self._h, int(bool(enable)))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_group_two_pass")
-
-    def set_nontemporal(self, mode: int) -> None:
-        rc = self._lib.drot_set_nontemporal(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_nontemporal")
-
-    def set_fused_update(self, mode: int) -> None:
-        rc = self._lib.drot_set_fused_update(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_fused_update")
-
-    def set_resident(self, mode: int) -> None:
-        rc = self._lib.drot_set_resident(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_resident")
-
-    def set_screening(self, mode: int) -> None:
-        rc = self._lib.drot_set_screening(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_screening")
-
-    def set_skip_unchanged(self, mode: int) -> None:
-        rc = self._lib.drot_set_skip_unchanged(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_skip_unchanged")
-
-    def set_skip_cost(self, mode: int) -> None:
-        rc = self._lib.drot_set_skip_cost(self._h, int(mode))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_skip_cost")
+        self.set_option(DROT_OPT_CONTINUE, bool(enable))
 
     def set_profile(self, enable: bool) -> None:
-        rc = self._lib.drot_set_profile(self._h, int(bool(enable)))
+        self.set_option(DROT_OPT_PROFILE, bool(enable))
+
+    def set_skip_unchanged(self, mode: int) -> None:
+        self.set_option(DROT_OPT_SKIP_UNCHANGED, mode)
+
+    def set_screening(self, mode: int) -> None:
+        self.set_option(DROT_OPT_SCREENING, mode)
+
+    def set_skip_cost(self, mode: int) -> None:
+        self.set_option(DROT_OPT_SKIP_COST, mode)
+
+    def set_fused_update(self, mode: int) -> None:
+        self.set_option(DROT_OPT_FUSED_UPDATE, mode)
+
+    def set_resident(self, mode: int) -> None:
+        self.set_option(DROT_OPT_RESIDENT, mode)
+
+    def set_group_two_pass(self, enable: bool) -> None:
+        self.set_option(DROT_OPT_GROUP_TWO_PASS, bool(enable))
+
+    def set_nontemporal(self, mode: int) -> None:
+        self.set_option(DROT_OPT_NONTEMPORAL, mode)
+
+    def set_gap_tolerance(self, gap_tol: float) -> None:
+        rc = self._lib.drot_set_gap_tolerance(self._h, float(gap_tol))
         if rc != DROT_OK:
-            raise DrotError(rc, "drot_set_profile")
+            raise DrotError(rc, "drot_set_gap_tolerance")
+
+    def checks(self) -> list:
+        """The residual checks of the last solve (drot_get_checks), as drot_check records."""
+        cnt = ctypes.c_int()
+        cap = 4096
+        buf = (drot_check * cap)()
+        rc = self._lib.drot_get_checks(self._h, buf, cap, ctypes.byref(cnt))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_checks")
+        if cnt.value > cap:
+            cap = cnt.value
+            buf = (drot_check * cap)()
+            self._lib.drot_get_checks(self._h, buf, cap, ctypes.byref(cnt))
+        return [buf[e] for e in range(min(cnt.value, cap))]
+
+    def profile_records(self) -> list:
+        """drot_get_profile: one drot_sweep_timing per sweep the last solve timed in profile mode."""
+        buf = (drot_sweep_timing * 256)()
+        cnt = ctypes.c_int()
+        rc = self._lib.drot_get_profile(self._h, buf, 256, ctypes.byref(cnt))
+        if rc != DROT_OK:
+            raise DrotError(rc, "drot_get_profile")
+        return [buf[e] for e in range(min(cnt.value, 256))]
 
     def profile(self) -> tuple:
         """(mean sweep duration in ms, number of sweeps timed) of the last solve in profile mode."""
-        ms, cnt = ctypes.c_double(), ctypes.c_int()
-        rc = self._lib.drot_get_profile(self._h, ctypes.byref(ms), ctypes.byref(cnt))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_get_profile")
-        return ms.value, cnt.value
+        rec = self.profile_records()
+        return (sum(r.ms for r in rec) / len(rec) if rec else 0.0), len(rec)
 
     def profile_sweeps(self) -> list:
-        """[(ms, kind)] of the sweeps the last solve timed in profile mode, in launch order; kind as
-        drot_get_profile_sweeps reports it (0 reads X and C, 1 also stores X - rho*C, 2 reads no C)."""
-        buf = (ctypes.c_float * 256)()
-        kinds = (ctypes.c_int * 256)()
-        cnt = ctypes.c_int()
-        rc = self._lib.drot_get_profile_sweeps(self._h, buf, kinds, 256, ctypes.byref(cnt))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_get_profile_sweeps")
-        return [(float(buf[e]), int(kinds[e])) for e in range(min(cnt.value, 256))]
+        """[(ms, kind)] of the sweeps the last solve timed in profile mode, in launch order."""
+        return [(float(r.ms), int(r.kind)) for r in self.profile_records()]
 
     def profile_reads(self) -> list:
-        """Fraction of the row segments of C that each sweep timed by the last solve read (drot_get_profile_reads)."""
-        buf = (ctypes.c_double * 256)()
-        cnt = ctypes.c_int()
-        rc = self._lib.drot_get_profile_reads(self._h, buf, 256, ctypes.byref(cnt))
-        if rc != DROT_OK:
-            raise DrotError(rc, "drot_get_profile_reads")
-        return [float(buf[e]) for e in range(min(cnt.value, 256))]
+        """Fraction of the row segments of C that each timed sweep of the last solve read."""
+        return [float(r.c_fraction) for r in self.profile_records()]
 
     def solve(self, C: torch.Tensor, p: torch.Tensor, q: torch.Tensor, *, stepsize: float = 0.0,
               reg_kind: int = DROT_REG_NONE, lam: float = 0.0, mu: float = 0.0,

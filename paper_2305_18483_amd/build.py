@@ -8,6 +8,9 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 SOURCES = [os.path.join(_PKG, "csrc", "drot.hip")]
 LIB_PATH = os.path.join(_PKG, "libdrot.so")
+# the launch planner alone, compiled for the host: what the CPU tests of the path selection load
+PLAN_SOURCE = os.path.join(_PKG, "csrc", "drot_plan_host.cpp")
+PLAN_LIB_PATH = os.path.join(_PKG, "libdrot_plan.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instructions are kept out of the generated code
@@ -25,14 +28,21 @@ def _run(cmd, verbose):
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     out = "\n".join(ln for ln in proc.stdout.splitlines() if "packed-fp32-ops" not in ln)
     if proc.returncode != 0:
-        raise RuntimeError(f"hipcc failed:\n{proc.stdout}")
+        raise RuntimeError(f"{cmd[0]} failed:\n{proc.stdout}")
     if verbose and out.strip():
         print(out)
 
 
+def build_plan(verbose: bool = False) -> str:
+    """Compile the launch planner with the host compiler (no GPU code in it)."""
+    _run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", PLAN_LIB_PATH, PLAN_SOURCE], verbose)
+    return PLAN_LIB_PATH
+
+
 def build(verbose: bool = False) -> str:
-    """Compile the HIP sources into libdrot.so; returns the library path."""
+    """Compile the HIP sources into libdrot.so (and the host-only planner library); returns the library path."""
     _run(["hipcc", *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-o", LIB_PATH, *SOURCES], verbose)
+    build_plan(verbose)
     return LIB_PATH
 
 

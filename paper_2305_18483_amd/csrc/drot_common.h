@@ -137,6 +137,8 @@ struct DeviceStatus {
   double nz_segments;            // row partial sums of the last reduction that were not zero (density of the plan)
   int iters;                     // iteration the residuals belong to
   int converged;
+  int gap_iters;                 // iteration the objective / gap / dual residual above belong to (0: none yet)
+  int pad_;
 };
 
 struct SweepArgs {

@@ -19,9 +19,11 @@ struct GapArgs {
   int ldx, ldc;
   float rho;
   PointArgs pts;         // used instead of C when C is null
+  const int* done;       // the stop flag for the passes that belong to a residual check (they skip once it is up), or null
 };
 
 __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
+  if (A.done && *A.done) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
@@ -80,7 +82,8 @@ __global__ __launch_bounds__(1024) void gap_final_kernel(VecState V, const float
                                                          const float* __restrict__ gx, const float* __restrict__ gw,
                                                          size_t ngroups, const float* __restrict__ p,
                                                          const float* __restrict__ q, int m, int n, double rho,
-                                                         int reg_kind, double lambda, double mu) {
+                                                         int reg_kind, double lambda, double mu, const int* done) {
+  if (done && *done) return;
   __shared__ double red[1024];
   const int t = threadIdx.x;
   double cx = 0.0, xx = 0.0, ww = 0.0, dl = 0.0, gl = 0.0, ex2 = 0.0;

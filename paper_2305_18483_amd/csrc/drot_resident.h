@@ -183,15 +183,23 @@ __global__ __launch_bounds__(256) void add_weights_kernel(float* __restrict__ ou
 }
 
 // S6: r_primal of Appendix C; raises the stop flag at the first check that passes so that every
-// later kernel of the solve returns at once.
-__global__ void status_kernel(VecState V, int iters, double tol) {
+// later kernel of the solve returns at once.  With gap_tol > 0 a check passes only if objective,
+// duality gap and dual residual were evaluated for this very iterate (gap_fresh) and
+// |gap| <= gap_tol * |objective|, dual_res <= gap_tol (Section 3, "Stopping criteria").
+__global__ void status_kernel(VecState V, int iters, double tol, double gap_tol, int gap_fresh) {
   if (*V.done) return;
   const double r2 = V.resid[0], s2 = V.resid[1];
   V.status->r2 = r2;
   V.status->s2 = s2;
   V.status->nz_segments = V.resid[2];
   V.status->iters = iters;
-  if (tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol) {
+  if (gap_fresh) V.status->gap_iters = iters;
+  bool pass = tol > 0.0 && r2 <= tol * tol && s2 <= tol * tol;
+  if (pass && gap_tol > 0.0) {
+    const double objective = V.status->cost + V.status->h;
+    pass = gap_fresh && fabs(V.status->gap) <= gap_tol * fabs(objective) && V.status->dual_res <= gap_tol;
+  }
+  if (pass) {
     V.status->converged = 1;
     __threadfence();
     *V.done = 1;

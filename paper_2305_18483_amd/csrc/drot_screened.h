@@ -153,11 +153,12 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
 }
 
-// Profiling: total of the per-wave read counts of one screened sweep.
-__global__ __launch_bounds__(1024) void sum_reads_kernel(const int* __restrict__ wave_reads, int count, double* out) {
+// Profiling: total of `count` per-wave or per-workgroup counters (ints or doubles) into one double.
+template <typename T>
+__global__ __launch_bounds__(1024) void sum_counts_kernel(const T* __restrict__ counts, int count, double* out) {
   __shared__ double red[1024 / 64];
   double acc = 0.0;
-  for (int e = threadIdx.x; e < count; e += 1024) acc += (double)wave_reads[e];
+  for (int e = threadIdx.x; e < count; e += 1024) acc += (double)counts[e];
   const double tot = block_sum_f64(acc, red);
   if (threadIdx.x == 0) *out = tot;
 }

@@ -44,7 +44,8 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.drot_create(ctypes.byref(h), 0, 4) == binding.DROT_ERR_INVALID_ARG
     assert lib.drot_create(ctypes.byref(h), 4, -1) == binding.DROT_ERR_INVALID_ARG
     assert lib.drot_destroy(None) == binding.DROT_ERR_INVALID_ARG
-    assert lib.drot_set_check_every(None, 10) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_set_option(None, binding.DROT_OPT_CHECK_EVERY, 10) == binding.DROT_ERR_INVALID_ARG
+    assert lib.drot_set_gap_tolerance(None, 0.1) == binding.DROT_ERR_INVALID_ARG
     assert lib.drot_get_info(None, None) == binding.DROT_ERR_INVALID_ARG
     assert lib.drot_solve(None, None, None, None, 1, 1, 0.0, 0, None, 1, 0.0, None, None) == binding.DROT_ERR_INVALID_ARG
     for code in (0, 1, -1, -2, -3, -4, 99):
@@ -57,6 +58,8 @@ def test_struct_layouts_match_the_header():
     # drot_info: int, int, float, float, double x3 ; drot_reg_params: float, float, int, pointer, pointer
     assert ctypes.sizeof(binding.drot_info) == 40
     assert binding.drot_info.objective.offset == 16
+    assert ctypes.sizeof(binding.drot_check) == 40 and binding.drot_check.objective.offset == 16
+    assert ctypes.sizeof(binding.drot_sweep_timing) == 24 and binding.drot_sweep_timing.c_fraction.offset == 8
     assert ctypes.sizeof(binding.drot_reg_params) == 32
     assert binding.drot_reg_params.row_class.offset == 16
     assert binding.drot_reg_params.weights.offset == 24

@@ -422,6 +422,34 @@ def test_stopping_rule_takes_first_passing_check(oracle):
     assert max(res.res_row[-1], res.res_col[-1]) <= tol
 
 
+@pytest.mark.parametrize("kind", [0, 1])
+def test_gap_stopping_rule_takes_the_first_check_that_passes_both_tests(oracle, kind):
+    # Section 3 "Stopping criteria" / Appendix C: with a gap tolerance a check passes when the residual
+    # test does and |gap| <= gap_tol |objective|, dual residual <= gap_tol, the gap being evaluated at
+    # every gap_every-th check only.  The expected stop is rebuilt from separate fixed-length runs and
+    # the (separately pinned) evaluation of the gap at their iterates.
+    C, p, q = _rand_problem(18, 22, 11)
+    kw = dict(reg_kind=kind, lam=0.5 if kind else 0.0)
+    tol, gap_tol, every, gap_every = 2e-3, 5e-3, 10, 3
+    rho = oracle.default_stepsize(18, 22)
+    res = oracle.solve(C, p, q, max_iters=20000, tol=tol, check_every=every, gap_every=gap_every, gap_tol=gap_tol, **kw)
+    plain = oracle.solve(C, p, q, max_iters=20000, tol=tol, check_every=every, **kw)
+    expected = None
+    for k in range(every * gap_every, 20001, every * gap_every):
+        it = oracle.solve(C, p, q, max_iters=k, **kw)
+        t = oracle.objective_gap(C, it.X, p, q, it.phi, it.varphi, rho, **kw)
+        if (max(it.res_row[-1], it.res_col[-1]) <= tol and abs(t.gap) <= gap_tol * abs(t.objective)
+                and t.dual_res <= gap_tol):
+            expected = k
+            break
+    assert expected is not None and res.iters == expected
+    assert res.iters > plain.iters  # (the gap test is the binding one here)
+    # the trace holds every evaluation up to the stop, at the multiples of every * gap_every
+    assert list(res.gap_trace[:, 0]) == list(range(every * gap_every, expected + 1, every * gap_every))
+    last = oracle.objective_gap(C, res.X, p, q, res.phi, res.varphi, rho, **kw)
+    assert res.gap_trace[-1, 1] == last.objective and res.gap_trace[-1, 2] == last.gap and res.gap_trace[-1, 3] == last.dual_res
+
+
 def test_point_cloud_cost_matches_numpy_and_scipy(oracle):
     from scipy.spatial.distance import cdist
 
