@@ -48,7 +48,8 @@ enum {
   DROT_ERR_INVALID_ARG = -1,
   DROT_ERR_ALLOC = -2,
   DROT_ERR_HIP = -3,
-  DROT_ERR_NOT_INITIALIZED = -4
+  DROT_ERR_NOT_INITIALIZED = -4,
+  DROT_ERR_TOO_LARGE = -5
 };
 
 /* Regularizer parameters; HOST struct, read during the call. */
@@ -279,6 +280,34 @@ int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* 
                     float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,
                     int max_iters, float tol, float* X_inout, const float* phi0, const float* varphi0,
                     void* stream);
+
+/*
+ * For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: drot_solve without a handle.  The workspace is a fixed array inside the
+ * library's code object (6 MiB, held by every GPU the library runs on until the process ends), so the call
+ * allocates nothing, on the device or the host; it only enqueues kernels on `stream` and returns WITHOUT
+ * waiting for them.  Results arrive in the caller's DEVICE buffers once the stream has run:
+ *   X_out [out]       DEVICE, m*n, as drot_solve
+ *   phi_out, varphi_out [out]  DEVICE, m resp. n floats, or NULL: phi and varphi of the returned iterate
+ *   info_out [out]    DEVICE pointer to one drot_info (all fields, the gap ones included), or NULL
+ * Limits: m <= DROT_STATIC_MAX_M and n <= DROT_STATIC_MAX_N, else DROT_ERR_TOO_LARGE; DROT_REG_NONE or
+ * DROT_REG_QUADRATIC without weights; n % 32 == 0 and C, X_out at addresses that are multiples of 128 (the
+ * padded working copies other shapes need are allocations), else DROT_ERR_INVALID_ARG.  Defaults of every
+ * option of drot_set_option; residual test every 100 iterations.  The host never looks at the status block,
+ * so the whole schedule is fixed when the call returns: the work enqueued is proportional to max_iters even
+ * if the tolerance is reached early (the sweeps behind the stop return at once), and the sweeps are the ones
+ * that need no report on the plan's density (no even/odd pairs, no lean sweep; same iterates as drot_solve
+ * unless that switches to the even/odd pairs).  The return value says whether the work was enqueued (DROT_OK),
+ * not whether the tolerance was reached: read info_out.
+ * All calls on one GPU share the one workspace, which keeps the last call's contents (everything that must
+ * start from zero is cleared by the call): calls that overlap on one GPU -- from two streams or two threads --
+ * race; calls on different GPUs are independent.
+ */
+#define DROT_STATIC_MAX_M 4096
+#define DROT_STATIC_MAX_N 4096
+int drot_solve_static(const float* C, const float* p, const float* q, int m, int n, float stepsize,
+                      drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol,
+                      float* X_out, float* phi_out, float* varphi_out, drot_info* info_out, void* stream);
 
 /* Results of the last solve (host struct).  NOT_INITIALIZED if no solve has run. */
 int drot_get_info(drot_handle h, drot_info* out);

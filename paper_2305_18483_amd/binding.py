@@ -18,12 +18,14 @@ LIB_PATH = os.path.join(_PKG, "libdrot.so")
 
 DROT_REG_NONE, DROT_REG_QUADRATIC, DROT_REG_GROUP_LASSO = 0, 1, 2
 DROT_OK, DROT_MAX_ITERS = 0, 1
-DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED = -1, -2, -3, -4
+DROT_ERR_INVALID_ARG, DROT_ERR_ALLOC, DROT_ERR_HIP, DROT_ERR_NOT_INITIALIZED, DROT_ERR_TOO_LARGE = -1, -2, -3, -4, -5
+DROT_STATIC_MAX_M = DROT_STATIC_MAX_N = 4096
 
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_option", "drot_set_gap_tolerance", "drot_get_checks", "drot_get_profile",
-    "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_get_info", "drot_get_duals", "drot_strerror",
+    "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_solve_static", "drot_get_info", "drot_get_duals",
+    "drot_strerror",
 )
 
 # drot_option
@@ -84,6 +86,7 @@ def load_library() -> ctypes.CDLL:
     lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_solve_points.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf,
                                       vp, vp]
+    lib.drot_solve_static.argtypes = [vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp, vp]
     lib.drot_get_info.argtypes = [vp, ctypes.POINTER(drot_info)]
     lib.drot_get_duals.argtypes = [vp, vp, vp]
     lib.drot_strerror.argtypes = [ci]
@@ -118,6 +121,36 @@ class SolveResult:
     objective: float
     gap: float
     dual_res: float
+
+
+def solve_static(C: torch.Tensor, p: torch.Tensor, q: torch.Tensor, X_out: torch.Tensor, *, stepsize: float = 0.0,
+                 reg_kind: int = DROT_REG_NONE, lam: float = 0.0, max_iters: int = 1000, tol: float = 0.0,
+                 phi_out: Optional[torch.Tensor] = None, varphi_out: Optional[torch.Tensor] = None,
+                 info_out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> int:
+    """drot_solve_static: enqueues the solve on the stream and returns at once, allocating nothing.  info_out: a
+    device tensor of at least ctypes.sizeof(drot_info) bytes (uint8) that receives the drot_info block.  Returns
+    the code of the call (DROT_OK: enqueued); raises DrotError on a negative one."""
+    lib = load_library()
+    m, n = C.shape
+    params = drot_reg_params(float(lam), 0.0, 0, None, None)
+    stream = stream if stream is not None else torch.cuda.current_stream(C.device)
+    if info_out is not None and (not info_out.is_cuda or info_out.numel() * info_out.element_size() < ctypes.sizeof(drot_info)):
+        raise ValueError("info_out must be a device buffer of at least sizeof(drot_info) bytes")
+    rc = lib.drot_solve_static(_ptr(C, torch.float32, "C"), _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), int(m),
+                               int(n), float(stepsize), int(reg_kind), ctypes.byref(params), int(max_iters), float(tol),
+                               _ptr(X_out, torch.float32, "X_out"), _ptr(phi_out, torch.float32, "phi_out"),
+                               _ptr(varphi_out, torch.float32, "varphi_out"),
+                               None if info_out is None else ctypes.c_void_p(info_out.data_ptr()),
+                               ctypes.c_void_p(stream.cuda_stream))
+    if rc < 0:
+        raise DrotError(rc, "drot_solve_static")
+    return rc
+
+
+def read_info(info_out: torch.Tensor) -> drot_info:
+    """The drot_info block a drot_solve_static call left in a device buffer (synchronises with the device)."""
+    raw = info_out.view(torch.uint8).cpu().numpy().tobytes()[:ctypes.sizeof(drot_info)]
+    return drot_info.from_buffer_copy(raw)
 
 
 class Solver:

@@ -31,7 +31,9 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "drot.h"
@@ -482,6 +484,7 @@ struct SolveCall {
   const float *phi0 = nullptr, *varphi0 = nullptr;
   bool warm = false;
   void* stream = nullptr;
+  bool fixed_schedule = false;  // the host never reads the status block during the solve (drot_solve_static)
 };
 
 // Checks the arguments, analyses the labels, grows the on-demand buffers, builds the plan and the
@@ -555,7 +558,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   P.c_on_lines = reinterpret_cast<uintptr_t>(C) % 128 == 0;
   P.x_on_lines = reinterpret_cast<uintptr_t>(A.X_out) % 128 == 0;
   P.tilesum_half = h->tilesum_half;
-  P.feedback = true;
+  P.feedback = !A.fixed_schedule;
   P.checking = A.tol > 0.f;
   P.max_iters = A.max_iters;
   Z.O = h->opt;
@@ -724,6 +727,10 @@ int iterate(Solve& Z, bool* converged_out) {
       // the test runs on the device; the host reads it one stretch late so the queue never drains
       if (R.gap) enqueue_gap(Z, h->done);
       enqueue_status(Z, Z.T.k, Z.P.checking && !R.probe, R.gap);
+      if (!Z.P.feedback) {  // (the stop flag alone ends the solve: the sweeps queued behind it return at once)
+        DROT_HIP(hipGetLastError());
+        continue;
+      }
       DROT_HIP(hipMemcpyAsync(&h->host_status[slot], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream));
       DROT_HIP(hipEventRecord(h->ev[slot], stream));
       was_probe[slot] = R.probe;
@@ -827,6 +834,136 @@ int solve_impl(drot_handle h, const SolveCall& A) {
   return DROT_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// drot_solve_static: the same solve out of a workspace that is part of the loaded code object, for
+// callers that cannot allocate.  Every GPU holds its own copy of the array at its own address.
+// ------------------------------------------------------------------------------------------
+constexpr int kStaticMaxM = DROT_STATIC_MAX_M, kStaticMaxN = DROT_STATIC_MAX_N;
+constexpr size_t kScratchBytes = (size_t)6 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch`, per device (the array's name is no device address on the host)
+std::mutex g_scratch_mutex;
+
+int static_workspace(int device, unsigned char** out) {
+  if (device < 0 || device >= kMaxDevices) return DROT_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fprintf(stderr, "drot: hipGetSymbolAddress(scratch) failed: %s\n", hipGetErrorString(e));
+      return DROT_ERR_HIP;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = static_cast<unsigned char*>(g_scratch_ptr[device]);
+  return DROT_OK;
+}
+
+// Points the workspace fields of a handle into `base` (a stretch of at least kScratchBytes bytes, 256-byte
+// aligned), sized for problems up to kStaticMaxM x kStaticMaxN without group lasso.  Returns the bytes used.
+size_t carve_static(drot_handle_s& H, unsigned char* base) {
+  size_t off = 0;
+  auto take = [&](auto** field, size_t count) {
+    using T = std::remove_pointer_t<std::remove_pointer_t<decltype(field)>>;
+    *field = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off = (off + count * sizeof(T) + 255) & ~(size_t)255;
+  };
+  const size_t M = kStaticMaxM, N = kStaticMaxN;
+  const size_t nseg = ceil_div(kStaticMaxN, kSegCols), ntr = ceil_div(kStaticMaxM, kTileRows);
+  const size_t nb = ceil_div(kStaticMaxM, 64) + ceil_div(kStaticMaxN, 64);
+  H.max_m = kStaticMaxM;
+  H.max_n = kStaticMaxN;
+  H.rowpart_half = nseg * M;  // (256-column segments only: no group-resident path here)
+  H.colpart_half = ntr * N;
+  H.tilesum_half = nseg * ntr > 4096 ? nseg * ntr : 4096;
+  H.max_runs = 0;
+  take(&H.phi, M);
+  take(&H.varphi, N + 4);
+  take(&H.a, 2 * M);
+  take(&H.b, 2 * N);
+  take(&H.theta, 2);
+  take(&H.sum_p, 1);
+  take(&H.r, M);
+  take(&H.s, N);
+  take(&H.part, 3 * nb);
+  take(&H.resid, 3);
+  take(&H.rowpart, 2 * H.rowpart_half);
+  take(&H.colpart, 2 * H.colpart_half);
+  take(&H.tilesum, 2 * H.tilesum_half);
+  take(&H.mprime, nseg * M);
+  take(&H.varphi0, N);
+  take(&H.screen_ctl, (size_t)kCtlWords);
+  take(&H.xlines, nseg * M);
+  take(&H.wg_reads, nseg * (size_t)ceil_div(ceil_div(kStaticMaxM, 64), kLeanWaves));
+  take(&H.gap_part, nseg * ntr * 3);
+  take(&H.done, 1);
+  take(&H.status, 1);
+  return off;
+}
+
+// Result block and dual vectors from the workspace into the caller's device buffers.
+__global__ __launch_bounds__(256) void export_kernel(const DeviceStatus* __restrict__ st, drot_info* __restrict__ info,
+                                                     const float* __restrict__ phi, const float* __restrict__ varphi,
+                                                     float* __restrict__ phi_out, float* __restrict__ varphi_out, int m, int n,
+                                                     int max_iters) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+  if (phi_out)
+    for (int i = t; i < m; i += stride) phi_out[i] = phi[i];
+  if (varphi_out)
+    for (int j = t; j < n; j += stride) varphi_out[j] = varphi[j];
+  if (t == 0 && info) {
+    info->iters = max_iters == 0 ? 0 : st->iters;
+    info->converged = st->converged;
+    info->r_row = max_iters == 0 ? INFINITY : (float)sqrt(st->r2);
+    info->r_col = max_iters == 0 ? INFINITY : (float)sqrt(st->s2);
+    info->objective = st->cost + st->h;
+    info->gap = st->gap;
+    info->dual_res = st->dual_res;
+  }
+}
+
+int solve_static_impl(SolveCall A, float* phi_out, float* varphi_out, drot_info* info_out) {
+  if (!A.cost.C || !A.p || !A.q || !A.X_out) return DROT_ERR_INVALID_ARG;
+  if (A.m < 1 || A.n < 1 || A.max_iters < 0) return DROT_ERR_INVALID_ARG;
+  if (A.m > kStaticMaxM || A.n > kStaticMaxN) {
+    fprintf(stderr, "drot_solve_static: %d x %d exceeds the static workspace (at most %d x %d)\n", A.m, A.n, kStaticMaxM,
+            kStaticMaxN);
+    return DROT_ERR_TOO_LARGE;
+  }
+  // the paths that need memory of a size only known at run time are not available here
+  if (A.reg_kind == DROT_REG_GROUP_LASSO || (A.reg_params && A.reg_params->weights)) return DROT_ERR_INVALID_ARG;
+  if (A.n % kAlignElems != 0 || reinterpret_cast<uintptr_t>(A.cost.C) % 128 != 0 ||
+      reinterpret_cast<uintptr_t>(A.X_out) % 128 != 0) {
+    fprintf(stderr, "drot_solve_static: rows of C and X_out must start on 128-byte lines (n %% 32 == 0, aligned bases)\n");
+    return DROT_ERR_INVALID_ARG;
+  }
+  static_assert(sizeof(drot_handle_s) < (1 << 16), "lives on the stack here");
+  drot_handle_s H;  // a handle whose workspace is the static array; it owns nothing
+  if (carve_static(H, nullptr) > kScratchBytes) return DROT_ERR_ALLOC;
+  DROT_HIP(hipGetDevice(&H.device));
+  unsigned char* base = nullptr;
+  int rc = static_workspace(H.device, &base);
+  if (rc != DROT_OK) return rc;
+  carve_static(H, base);
+  A.fixed_schedule = true;
+  Solve Z;
+  rc = prepare(&H, A, Z);
+  if (rc != DROT_OK) return rc;
+  if (Z.S.pad_c || Z.S.pad_x) return DROT_ERR_INVALID_ARG;  // (checked above; nothing has been queued that matters)
+  bool converged = false;
+  rc = iterate(Z, &converged);
+  if (rc != DROT_OK) return rc;
+  if (Z.T.k > 0) enqueue_status(Z, Z.T.k, Z.P.checking, false);
+  enqueue_gap(Z, nullptr);
+  hipLaunchKernelGGL(export_kernel, dim3(16), dim3(256), 0, Z.stream, (const DeviceStatus*)H.status, info_out,
+                     (const float*)H.phi, (const float*)H.varphi, phi_out, varphi_out, A.m, A.n, A.max_iters);
+  DROT_HIP(hipGetLastError());
+  return DROT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -839,6 +976,7 @@ const char* drot_strerror(int code) {
     case DROT_ERR_ALLOC: return "device or pinned-host allocation failed";
     case DROT_ERR_HIP: return "HIP runtime error";
     case DROT_ERR_NOT_INITIALIZED: return "no solve has been run on this handle";
+    case DROT_ERR_TOO_LARGE: return "the problem exceeds the fixed workspace of drot_solve_static";
     default: return "unknown code";
   }
 }
@@ -1021,6 +1159,16 @@ int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* 
   A.max_iters = max_iters; A.tol = tol; A.X_out = X_inout; A.phi0 = phi0; A.varphi0 = varphi0; A.warm = true;
   A.stream = stream;
   return solve_impl(h, A);
+}
+
+int drot_solve_static(const float* C, const float* p, const float* q, int m, int n, float stepsize,
+                      drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters, float tol, float* X_out,
+                      float* phi_out, float* varphi_out, drot_info* info_out, void* stream) {
+  SolveCall A;
+  A.cost.C = C;
+  A.p = p; A.q = q; A.m = m; A.n = n; A.stepsize = stepsize; A.reg_kind = reg_kind; A.reg_params = reg_params;
+  A.max_iters = max_iters; A.tol = tol; A.X_out = X_out; A.stream = stream;
+  return solve_static_impl(A, phi_out, varphi_out, info_out);
 }
 
 int drot_get_info(drot_handle h, drot_info* out) {
