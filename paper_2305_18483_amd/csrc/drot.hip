@@ -129,6 +129,10 @@ struct drot_handle_s {
   size_t ptbuf_len = 0;
   int* runbuf = nullptr;  // group-resident path: run_start[], run_len[] of the label runs
   size_t runbuf_len = 0;
+  int* chunkbuf = nullptr;  // two-pass path: perm[m], chunk_start[nchunks + 1], class_first[num_classes + 1]
+  size_t chunkbuf_len = 0;
+  float* gpart = nullptr;   // two-pass path: [nchunks][n] squared sums of the chunks
+  size_t gpart_len = 0;
   int max_runs = 0;       // rows of colpart available
   int* done = nullptr;
   DeviceStatus* status = nullptr;
@@ -175,9 +179,9 @@ int grow_buffer(T** buf, size_t* len, size_t need, hipStream_t stream) {
 
 void free_all(drot_handle h) {
   float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf, h->mprime, h->varphi0,
-                    h->cpad, h->xpad, h->ptbuf};
+                    h->cpad, h->xpad, h->ptbuf, h->gpart};
   double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid, h->prof_counts};
-  int* ibufs[] = {h->done, h->runbuf, h->wave_reads, h->screen_ctl, h->wg_reads};
+  int* ibufs[] = {h->done, h->runbuf, h->chunkbuf, h->wave_reads, h->screen_ctl, h->wg_reads};
   for (float* b : fbufs) (void)hipFree(b);
   for (double* b : dbufs) (void)hipFree(b);
   for (int* b : ibufs) (void)hipFree(b);
@@ -271,6 +275,8 @@ struct Solve {
   ReduceArgs RA{};
   UpdateArgs UA{};
   float thr = 0.f;  // rho * mu
+  ChunkArgs CK{};   // two-pass group lasso: the classes' rows in chunks
+  int num_classes = 0;
 
   double* a_buf(long long g) const { return h->a + (size_t)(g & 1) * (size_t)h->max_m; }
   double* b_buf(long long g) const { return h->b + (size_t)(g & 1) * (size_t)h->max_n; }
@@ -326,15 +332,13 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
     }
     case plan::kTwoPass: {
       const GroupArgs G{A, Z.row_class, h->gbuf, Z.thr};
-      hipLaunchKernelGGL(fill_kernel, dim3(ceil_div((int)((Z.ngroups + 255) / 256), 4)), dim3(256), 0, stream, h->gbuf,
-                         Z.ngroups, 0.f, (const int*)h->done);
-      if (Q.first) {
-        hipLaunchKernelGGL(gl_norm_kernel<true>, grid, block, 0, stream, G);
-        hipLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, G);
-      } else {
-        hipLaunchKernelGGL(gl_norm_kernel<false>, grid, block, 0, stream, G);
-        hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
-      }
+      const dim3 cgrid(S.nseg, ceil_div(Z.CK.nchunks, kWavesPerBlock));
+      const dim3 fgrid(ceil_div(n, kBlock), Z.num_classes < 65535 ? Z.num_classes : 65535);
+      if (Q.first) hipLaunchKernelGGL(gl_norm_kernel<true>, cgrid, block, 0, stream, G, Z.CK);
+      else hipLaunchKernelGGL(gl_norm_kernel<false>, cgrid, block, 0, stream, G, Z.CK);
+      hipLaunchKernelGGL(gl_norm_finish_kernel, fgrid, block, 0, stream, Z.CK, h->gbuf, n, Z.num_classes, (const int*)h->done);
+      if (Q.first) hipLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, G);
+      else hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
       break;
     }
     case plan::kPro32: {
@@ -583,7 +587,19 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
       std::vector<int> table(L.start);  // run_start[0..nruns), run_len[0..nruns)
       table.insert(table.end(), L.len.begin(), L.len.end());
       DROT_HIP(hipMemcpy(h->runbuf, table.data(), sizeof(int) * table.size(), hipMemcpyHostToDevice));
+    } else {
+      // two passes: the rows of every class in chunks, so that the group norms add up in a fixed order
+      const plan::ClassChunks K = plan::chunk_classes(labels.data(), m, num_classes);
+      std::vector<int> table(K.perm);
+      table.insert(table.end(), K.chunk_start.begin(), K.chunk_start.end());
+      table.insert(table.end(), K.class_first.begin(), K.class_first.end());
+      int rc2 = grow_buffer(&h->chunkbuf, &h->chunkbuf_len, table.size(), stream);
+      if (rc2 == DROT_OK) rc2 = grow_buffer(&h->gpart, &h->gpart_len, (size_t)K.nchunks() * (size_t)n, stream);
+      if (rc2 != DROT_OK) return rc2;
+      DROT_HIP(hipMemcpy(h->chunkbuf, table.data(), sizeof(int) * table.size(), hipMemcpyHostToDevice));
+      Z.CK = ChunkArgs{h->chunkbuf, h->chunkbuf + m, h->chunkbuf + m + K.nchunks() + 1, h->gpart, K.nchunks()};
     }
+    Z.num_classes = num_classes;
   }
   Z.S = plan::make_static(P, Z.O);
   Z.T = plan::start_state(Z.S, P, h->carry);

@@ -4,7 +4,8 @@
 // ------------------------------------------------------------------------------------------
 // Group lasso, general labels, two passes (Section "Group-lasso Regularized DROT": when a
 // group does not fit one workgroup the reduction goes through global memory and a second
-// kernel applies the scale).  Pass 1 accumulates sum_{i in class} Xbar_ij^2 per (class, column).
+// kernel applies the scale).  Pass 1 accumulates sum_{i in class} Xbar_ij^2 per (class, column), in a
+// fixed order: the rows of a class in chunks, then the chunks (the paper's kernel uses atomics here).
 // ------------------------------------------------------------------------------------------
 struct GroupArgs {
   SweepArgs S;
@@ -20,32 +21,51 @@ __device__ __forceinline__ void flush_group(float* __restrict__ g, f4v acc, int 
   if (nvalid > 3) atomicAdd(g + 3, acc.w);
 }
 
+// Pass 1: one wave adds up Xbar_ij^2 over the (at most 16) rows of one chunk of one class, for its 256
+// columns, and stores the sums as row `chunk` of gpart.  grid = (nseg, ceil(nchunks / 4)).
+struct ChunkArgs {
+  const int* perm;         // [m] rows sorted by (class, row)
+  const int* chunk_start;  // [nchunks + 1] offsets into perm
+  const int* class_first;  // [num_classes + 1] first chunk of every class
+  float* gpart;            // [nchunks][n]
+  int nchunks;
+};
+
 template <bool FIRST>
-__global__ __launch_bounds__(kBlock) void gl_norm_kernel(GroupArgs G) {
+__global__ __launch_bounds__(kBlock) void gl_norm_kernel(GroupArgs G, ChunkArgs K) {
   const SweepArgs& A = G.S;
   if (*A.done) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int chunk = blockIdx.y * kWavesPerBlock + wave;
+  if (chunk >= K.nchunks) return;
   const int j0 = blockIdx.x * kSegCols + lane * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
   const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const int rbeg = blockIdx.y * kTileRows + wave * kLoopRows;
-  const int rend = min(rbeg + kLoopRows, A.m);
-  int cur = -1;
+  const int beg = K.chunk_start[chunk], end = K.chunk_start[chunk + 1];
   f4v acc = {0.f, 0.f, 0.f, 0.f};
-  for (int i = rbeg; i < rend; ++i) {
-    const int cls = G.row_class[i];
-    if (cls != cur) {
-      if (cur >= 0) flush_group(G.gsq + (size_t)cur * A.n + j0, acc, nvalid);
-      cur = cls;
-      acc = f4v{0.f, 0.f, 0.f, 0.f};
-    }
+  for (int e = beg; e < end; ++e) {
+    const int i = K.perm[e];
     const f4v c = load4(A.C + (size_t)i * A.ldc + j0, nvalid);
     const f4v x = FIRST ? f4v{0.f, 0.f, 0.f, 0.f} : load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v v = xbar4(x, c, vp + A.phi[i], A.rho);
     acc += v * v;
   }
-  if (cur >= 0) flush_group(G.gsq + (size_t)cur * A.n + j0, acc, nvalid);
+  store4(K.gpart + (size_t)chunk * A.n + j0, acc, nvalid);
+}
+
+// Between the passes: the chunks of every class added up in order, one thread per (class, column).
+// grid = (ceil(n / 256), min(num_classes, 65535)).
+__global__ __launch_bounds__(kBlock) void gl_norm_finish_kernel(ChunkArgs K, float* __restrict__ gsq, int n, int num_classes,
+                                                                const int* done) {
+  if (*done) return;
+  const int j = blockIdx.x * kBlock + threadIdx.x;
+  if (j >= n) return;
+  for (int cls = blockIdx.y; cls < num_classes; cls += gridDim.y) {
+    float t = 0.f;
+    for (int k = K.class_first[cls]; k < K.class_first[cls + 1]; ++k) t += K.gpart[(size_t)k * n + j];
+    gsq[(size_t)cls * n + j] = t;
+  }
 }
 
 // scale of one group from its squared norm t: [1 - rho mu / sqrt(t)]_+ / (1 + rho lambda), 0 at t = 0

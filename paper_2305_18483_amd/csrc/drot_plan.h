@@ -366,6 +366,37 @@ struct LabelRuns {
   int slab_k = 0;                 // rows per lane of the slab kernel, 0: two-pass path
 };
 
+// Two-pass path (any labels): the rows of every class, in ascending order, cut into chunks of at most
+// kNormChunkRows rows.  The first pass adds up the squared entries of one chunk per wave, the second
+// adds the chunks of a class in order: the group norms come out the same in every run (no atomics).
+constexpr int kNormChunkRows = 16;
+struct ClassChunks {
+  std::vector<int> perm;          // [m] the rows sorted by (class, row)
+  std::vector<int> chunk_start;   // [nchunks + 1] offsets into perm
+  std::vector<int> class_first;   // [num_classes + 1] the chunks of class c are class_first[c] .. class_first[c+1] - 1
+  int nchunks() const { return (int)chunk_start.size() - 1; }
+};
+
+inline ClassChunks chunk_classes(const int* labels, int m, int num_classes) {
+  ClassChunks K;
+  std::vector<int> count((size_t)num_classes + 1, 0);
+  for (int i = 0; i < m; ++i) ++count[(size_t)labels[i] + 1];
+  for (int c = 0; c < num_classes; ++c) count[(size_t)c + 1] += count[(size_t)c];  // first position of every class
+  K.perm.resize((size_t)m);
+  std::vector<int> next(count.begin(), count.end() - 1);
+  for (int i = 0; i < m; ++i) K.perm[(size_t)next[(size_t)labels[i]]++] = i;       // stable: rows stay in order
+  K.class_first.push_back(0);
+  K.chunk_start.push_back(0);
+  for (int c = 0; c < num_classes; ++c) {
+    for (int b = count[(size_t)c]; b < count[(size_t)c + 1]; b += kNormChunkRows) {
+      const int e = b + kNormChunkRows < count[(size_t)c + 1] ? b + kNormChunkRows : count[(size_t)c + 1];
+      K.chunk_start.push_back(e);
+    }
+    K.class_first.push_back(K.nchunks());
+  }
+  return K;
+}
+
 inline LabelRuns analyze_labels(const int* labels, int m, int num_classes, int max_runs, bool force_two_pass) {
   LabelRuns L;
   std::vector<char> seen((size_t)num_classes, 0);

@@ -141,4 +141,16 @@ int drot_plan_labels(const int* labels, int m, int num_classes, int max_runs, in
   return L.slab_k;
 }
 
+// The chunk tables of the two-pass group-lasso path: perm[m], chunk_start[nchunks + 1] (capacity
+// cap_chunks + 1), class_first[num_classes + 1].  Returns the number of chunks, or -1 if they do not fit.
+int drot_plan_chunks(const int* labels, int m, int num_classes, int* perm, int* chunk_start, int cap_chunks,
+                     int* class_first) {
+  const ClassChunks K = chunk_classes(labels, m, num_classes);
+  if (K.nchunks() > cap_chunks) return -1;
+  std::memcpy(perm, K.perm.data(), sizeof(int) * (size_t)m);
+  std::memcpy(chunk_start, K.chunk_start.data(), sizeof(int) * K.chunk_start.size());
+  std::memcpy(class_first, K.class_first.data(), sizeof(int) * K.class_first.size());
+  return K.nchunks();
+}
+
 }  // extern "C"

@@ -260,6 +260,22 @@ def test_group_lasso_unsorted_labels(drot, oracle):
     _run_case(drot, oracle, P, 300, "group lasso, unsorted labels")
 
 
+def test_two_pass_group_lasso_is_bit_reproducible(drot):
+    # the group norms of the general path are added up in a fixed order (rows of a class in chunks, then the
+    # chunks): two runs give the same bits, on unsorted labels and on a class too long for the resident kernel
+    cases = [drot_inputs.random_problem(700, 900, seed=79, reg_kind=2, lam=0.1, mu=0.08, num_classes=6, sorted_classes=False),
+             _two_class_problem(1500, 333, 1100, seed=80)]
+    for P in cases:
+        solver = drot.Solver(P.m, P.n)
+        _say(f"two-pass group lasso, run twice, {P.m}x{P.n}")
+        runs = [pu.gpu_solve(solver, P, 150)[1:] for _ in range(2)]
+        other = drot.Solver(P.m, P.n)
+        runs.append(pu.gpu_solve(other, P, 150)[1:])
+        for r in runs[1:]:
+            for a, b in zip(runs[0], r):
+                assert np.array_equal(a, b)
+
+
 def test_group_lasso_without_quadratic_term(drot, oracle):
     P = drot_inputs.random_problem(200, 320, seed=78, reg_kind=2, lam=0.0, mu=0.05, num_classes=4)
     _run_case(drot, oracle, P, 300, "group lasso, lambda=0")

@@ -218,3 +218,27 @@ def test_label_analysis(planlib):
     assert labels(np.repeat(np.arange(10), 5), 10, max_runs=9) == (0, 10)
     assert labels([0, 1, 2, 3], 3)[0] == -1 and labels([0, -1], 3)[0] == -1
     assert labels([2, 2, 2], 5) == (1, 1)                             # unused classes are fine
+
+
+def test_class_chunks_of_the_two_pass_group_lasso_path(planlib):
+    rng = np.random.default_rng(7)
+    for m, classes in ((1, 1), (50, 3), (1000, 7), (333, 40)):
+        labels = np.ascontiguousarray(rng.integers(0, classes, size=m), dtype=np.int32)
+        if classes > 2:
+            labels[labels == 1] = 0  # an empty class
+        perm = np.zeros(m, dtype=np.int32)
+        cap = m // 16 + classes + 1
+        chunk_start = np.zeros(cap + 1, dtype=np.int32)
+        class_first = np.zeros(classes + 1, dtype=np.int32)
+        ip = ctypes.POINTER(ctypes.c_int)
+        nchunks = planlib.drot_plan_chunks(labels.ctypes.data_as(ip), m, classes, perm.ctypes.data_as(ip),
+                                           chunk_start.ctypes.data_as(ip), cap, class_first.ctypes.data_as(ip))
+        assert nchunks >= 1 and class_first[0] == 0 and class_first[classes] == nchunks and chunk_start[nchunks] == m
+        assert sorted(perm.tolist()) == list(range(m))          # a permutation of the rows
+        for c in range(classes):
+            rows = []
+            for k in range(class_first[c], class_first[c + 1]):
+                chunk = perm[chunk_start[k]:chunk_start[k + 1]].tolist()
+                assert 1 <= len(chunk) <= 16
+                rows += chunk
+            assert rows == np.flatnonzero(labels == c).tolist()  # every row of the class once, in ascending order
