@@ -37,6 +37,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 MFMA_F32_PEAK_TFLOPS = 157.3
 SEG_COLS = 256             # columns of a row segment, the unit of the zero-segment skipping
 STEADY_WARMUP, STEADY_STEPS = 200, 500
+ALIGN_STEPS = 600
 KERNEL_NAMES = {
     0: "sweep_kernel (reads X and C, stores X)",
     1: "sweep_kernel, first of a pair (reads X and C, stores X - rho*C)",
@@ -435,14 +436,17 @@ def alignment(torch, drot, dev):
                 else:
                     solver.set_skip_cost(-1)
                     solver.set_skip_unchanged(-1)
-                solver.set_continue(False)
-                solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=200, X_out=X)
-                solver.set_continue(True)
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=300, X_out=X)
-                torch.cuda.synchronize()
-                pair[(size, scheme)] = 300 / (time.perf_counter() - t0)
+                best = 0.0
+                for _ in range(3):  # (the best of three: these runs are a few milliseconds long)
+                    solver.set_continue(False)
+                    solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=200, X_out=X)
+                    solver.set_continue(True)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=ALIGN_STEPS, X_out=X)
+                    torch.cuda.synchronize()
+                    best = max(best, ALIGN_STEPS / (time.perf_counter() - t0))
+                pair[(size, scheme)] = best
             solver.close()
             del C, X
             torch.cuda.empty_cache()
@@ -451,8 +455,8 @@ def alignment(torch, drot, dev):
             rows.append({"n": n, "scheme": scheme, "its_per_s_n": round(a, 1), "its_per_s_n_minus_1": round(b, 1),
                          "slowdown_percent": round((a / b - 1.0) * 100.0, 2)})
             log(f"alignment {n} vs {n - 1} [{scheme}]: {a:.0f} vs {b:.0f} it/s ({(a / b - 1.0) * 100.0:+.2f} %)")
-    return {"note": "300 iterations continuing a 200-iteration cold start, each call copying X out of the padded working copy "
-                    "when n % 32 != 0", "rows": rows}
+    return {"note": f"{ALIGN_STEPS} iterations continuing a 200-iteration cold start (best of three), each call copying X out of "
+                    "the padded working copy when n % 32 != 0", "rows": rows}
 
 
 if __name__ == "__main__":

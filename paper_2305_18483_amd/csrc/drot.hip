@@ -241,6 +241,13 @@ int enable_profile(drot_handle h) {
   return DROT_OK;
 }
 
+// dst[i][j] = src[i][j] for an m x n matrix held with two different row pitches (in elements).
+void copy_rows(float* dst, size_t dpitch, const float* src, size_t spitch, int m, int n, hipStream_t stream) {
+  const int rows16 = ceil_div(m, 16);
+  hipLaunchKernelGGL(copy_rows_kernel, dim3(ceil_div(n, 1024), rows16 < 65535 ? rows16 : 65535), dim3(256), 0, stream, dst,
+                     dpitch, src, spitch, m, n);
+}
+
 // Where the cost comes from: a stored matrix, or two point clouds (C_ij = scale * ||xs_i - xt_j||^2).
 struct CostSource {
   const float* C = nullptr;
@@ -606,6 +613,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   const plan::Static& S = Z.S;
 
   Z.V = VecState{h->phi, h->varphi, h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid, h->done, h->status};
+  hipLaunchKernelGGL(mask_tail_kernel, dim3(1), dim3(256), 0, stream, h->varphi, h->varphi0, n);
   if (resume) hipLaunchKernelGGL(reset_kernel, dim3(1), dim3(1), 0, stream, Z.V);
   else if (!A.warm) hipLaunchKernelGGL(init_kernel, dim3(1), dim3(1024), 0, stream, Z.V, A.p, A.q, m, n);
 
@@ -634,8 +642,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
       hipLaunchKernelGGL(add_weights_kernel, dim3(ceil_div(n, 256), m < 65535 ? m : 65535), dim3(256), 0, stream, h->cpad, C,
                          weights, m, n, S.ld_pad);
     else if (!reuse)
-      DROT_HIP(hipMemcpy2DAsync(h->cpad, sizeof(float) * (size_t)S.ld_pad, C, sizeof(float) * (size_t)n,
-                                sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
+      copy_rows(h->cpad, (size_t)S.ld_pad, C, (size_t)n, m, n, stream);
     h->cpad_of = weights ? nullptr : C;
   }
   if (S.pad_x) {
@@ -646,13 +653,14 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
     Z.ldx = S.ld_pad;
     const bool reuse = resume && had >= padded && h->xpad_live;
     if ((resume && !reuse) || A.warm)  // the plan to start from is in X_out
-      DROT_HIP(hipMemcpy2DAsync(h->xpad, sizeof(float) * (size_t)S.ld_pad, A.X_out, sizeof(float) * (size_t)n,
-                                sizeof(float) * (size_t)n, (size_t)m, hipMemcpyDeviceToDevice, stream));
+      copy_rows(h->xpad, (size_t)S.ld_pad, A.X_out, (size_t)n, m, n, stream);
   }
   h->xpad_live = false;  // (until this solve has returned)
   Z.SA = SweepArgs{Z.Xw, Z.Cw, h->phi, h->varphi, nullptr, nullptr, nullptr, h->done, m, n, Z.ldx, Z.ldc, Z.rho,
                    A.reg_kind == DROT_REG_NONE ? 1.0f : qscale,
                    (S.pad_x && (S.pad_c || from_points)) ? S.ld_pad : n, nullptr};
+  // (the sweeps' edge handling counts on rows that are whole 128-byte lines: the planner's pad_c, pad_x see to it)
+  if (!S.resident && Z.SA.n_mem % kAlignElems != 0) return DROT_ERR_INVALID_ARG;
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
   if (from_points) {
     const int dq = ceil_div(A.cost.d, 16) * 4;
@@ -800,11 +808,7 @@ int solve_impl(drot_handle h, const SolveCall& A) {
   if (k > 0) enqueue_status(Z, k, Z.P.checking, false);
   if (h->compute_gap) enqueue_gap(Z, nullptr);
   const bool untouched = A.max_iters == 0 && !Z.P.resume && !A.warm;
-  if (S.pad_x && !untouched) {
-    if (hipMemcpy2DAsync(A.X_out, sizeof(float) * (size_t)Z.n, h->xpad, sizeof(float) * (size_t)S.ld_pad,
-                         sizeof(float) * (size_t)Z.n, (size_t)Z.m, hipMemcpyDeviceToDevice, stream) != hipSuccess)
-      return fail(DROT_ERR_HIP);
-  }
+  if (S.pad_x && !untouched) copy_rows(A.X_out, (size_t)Z.n, h->xpad, (size_t)S.ld_pad, Z.m, Z.n, stream);
   if (hipMemcpyAsync(&h->host_status[0], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream) != hipSuccess ||
       hipStreamSynchronize(stream) != hipSuccess || hipGetLastError() != hipSuccess)
     return fail(DROT_ERR_HIP);
@@ -897,7 +901,7 @@ size_t carve_static(drot_handle_s& H, unsigned char* base) {
   H.tilesum_half = nseg * ntr > 4096 ? nseg * ntr : 4096;
   H.max_runs = 0;
   take(&H.phi, M);
-  take(&H.varphi, N + 4);
+  take(&H.varphi, nseg * kSegCols);  // (to the end of the last column segment: see mask_tail_kernel)
   take(&H.a, 2 * M);
   take(&H.b, 2 * N);
   take(&H.theta, 2);
@@ -910,7 +914,7 @@ size_t carve_static(drot_handle_s& H, unsigned char* base) {
   take(&H.colpart, 2 * H.colpart_half);
   take(&H.tilesum, 2 * H.tilesum_half);
   take(&H.mprime, nseg * M);
-  take(&H.varphi0, N);
+  take(&H.varphi0, nseg * kSegCols);
   take(&H.screen_ctl, (size_t)kCtlWords);
   take(&H.xlines, nseg * M);
   take(&H.wg_reads, nseg * (size_t)ceil_div(ceil_div(kStaticMaxM, 64), kLeanWaves));
@@ -1014,7 +1018,7 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   int rc = DROT_OK;
   auto take = [&](int r) { if (rc == DROT_OK) rc = r; };
   take(dev_alloc(&h->phi, (size_t)max_m));
-  take(dev_alloc(&h->varphi, (size_t)max_n + 4));
+  take(dev_alloc(&h->varphi, nseg * kSegCols));  // (to the end of the last column segment: see mask_tail_kernel)
   take(dev_alloc(&h->a, 2 * (size_t)max_m));
   take(dev_alloc(&h->b, 2 * (size_t)max_n));
   take(dev_alloc(&h->theta, 2));
@@ -1030,7 +1034,7 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->colpart, 2 * h->colpart_half));
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
   take(dev_alloc(&h->mprime, nseg * (size_t)max_m));
-  take(dev_alloc(&h->varphi0, (size_t)max_n));
+  take(dev_alloc(&h->varphi0, nseg * kSegCols));
   take(dev_alloc(&h->screen_ctl, (size_t)kCtlWords));
   take(dev_alloc(&h->xlines, nseg * (size_t)max_m));
   take(dev_alloc(&h->wg_reads, nseg * (size_t)ceil_div(ceil_div(max_m, 64), kLeanWaves)));

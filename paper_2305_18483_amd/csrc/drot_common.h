@@ -103,6 +103,16 @@ __device__ __forceinline__ f4v load_varphi(const float* __restrict__ varphi, int
   return v;
 }
 
+// The same from the solver's own varphi buffers (workspace and the screening epoch's copy), which are
+// allocated up to the end of the last 256-column segment and hold the mask value past n (set at the
+// start of every solve): one 128-bit load, no edge case.
+__device__ __forceinline__ f4v load_varphi_padded(const float* __restrict__ varphi, int j0) {
+  return *reinterpret_cast<const f4u*>(varphi + j0);
+}
+
+// |v| of a varphi entry, 0 for the mask value of the columns past n.
+__device__ __forceinline__ float unmasked_abs(float v) { return v == kMaskedOut ? 0.f : fabsf(v); }
+
 // [x + phi_i + varphi_j - rho c]_+   (first half of eq. (8))
 __device__ __forceinline__ f4v xbar4(f4v x, f4v c, f4v pv, float rho) {
   f4v v;

@@ -308,6 +308,25 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
   }
 }
 
+// Copy of an m x n matrix between two row pitches (the caller's arrays and the padded working copies):
+// 128-bit accesses that need no more than 4-byte alignment, one row of workgroups per 16 rows.
+__global__ __launch_bounds__(256) void copy_rows_kernel(float* __restrict__ dst, size_t dpitch, const float* __restrict__ src,
+                                                        size_t spitch, int m, int n) {
+  const int j0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (j0 >= n) return;
+  const int nvalid = min(n - j0, 4);
+  for (int i0 = blockIdx.y * 16; i0 < m; i0 += gridDim.y * 16) {
+    const int i1 = min(i0 + 16, m);
+    f4v v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (i0 + u < i1) v[u] = load4(src + (size_t)(i0 + u) * spitch + j0, nvalid);
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      if (i0 + u < i1) store4(dst + (size_t)(i0 + u) * dpitch + j0, v[u], nvalid);
+  }
+}
+
 __global__ void fill_kernel(float* __restrict__ dst, size_t count, float value, const int* done) {
   if (done && *done) return;
   for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x)

@@ -48,7 +48,6 @@ template <bool EDGE, bool NT, bool REFRESH>
 __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int wave, int seg, int tr) {
   constexpr int U = kScreenRows, NW = kScreenWaves;
   const int j0 = seg * kSegCols + lane * 4;
-  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
   const int r0 = (tr * NW + wave) * U;
   const int nrows = min(max(A.m - r0, 0), U);
@@ -59,7 +58,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   const size_t ridx = (size_t)seg * A.m + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
 
   // lane u: old sum, phi and M of row r0 + u
-  const f4v vp = load_varphi(A.varphi, j0, nvalid);
+  const f4v vp = load_varphi_padded(A.varphi, j0);
   float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
   if (lane < nrows) {
     prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
@@ -68,15 +67,11 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   }
   bool certified = lane >= nrows;  // rows past the end of the matrix: nothing to do
   if (!REFRESH) {
-    const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+    const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
     // drift of varphi since the epoch and its magnitude over this wave's columns (columns past n: both
     // carry the same mask value, their difference is 0; they are left out of the magnitude)
     float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
-    float a = 0.f;
-    if (nvalid > 0) a = fabsf(vp.x);
-    if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
-    if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
-    if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+    const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
     const float delta = wave_max(d), mag = wave_max(a);
     // S bounds every phi_i + varphi_j - rho C_ij of the row segment from above; the margin, 8 units in
     // the last place of the largest term, covers the roundings of M, of delta, of this sum and of the
@@ -92,13 +87,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
     // the first wave of every column segment stores the varphi the new bounds are recorded against
     // (here, behind the stop flag, so that bounds and epoch always belong together; nobody reads
     // varphi0 in a refresh sweep)
-    float* __restrict__ v0 = SC.varphi0_out + j0;
-    if (nvalid == 4) *reinterpret_cast<f4u*>(v0) = vp;
-    else {
-      if (nvalid > 0) v0[0] = vp.x;
-      if (nvalid > 1) v0[1] = vp.y;
-      if (nvalid > 2) v0[2] = vp.z;
-    }
+    *reinterpret_cast<f4u*>(SC.varphi0_out + j0) = vp;  // (past n both buffers hold the mask value)
   }
 
   f4v x[U], c[U];
@@ -170,7 +159,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
   if ((seg + 1) * kSegCols <= A.n) screened_body<false, NT, REFRESH>(A, SC, lane, wave, seg, tr);
-  else screened_body<true, false, REFRESH>(A, SC, lane, wave, seg, tr);
+  else screened_body<true, NT, REFRESH>(A, SC, lane, wave, seg, tr);
 }
 
 // The screened sweep for plans known to be sparse (a few percent of the row segments left to
@@ -186,7 +175,6 @@ template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
                                                   int stop, bool renew, float& tile_total, int& reads) {
   const int j0 = seg * kSegCols + lane * 4;
-  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;
   const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
   const int r0 = tr * 64;
   const int nrows = min(A.m - r0, 64);
@@ -196,8 +184,8 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const float rho = A.rho, scale = A.scale;
   const size_t ridx = (size_t)seg * A.m + r0 + lane;
 
-  const f4v vp = load_varphi(A.varphi, j0, nvalid);
-  const f4v vp0 = load_varphi(SC.varphi0, j0, nvalid);
+  const f4v vp = load_varphi_padded(A.varphi, j0);
+  const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
   float ph = kMaskedOut, mpr = 0.f;
   // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31).  From
   // the flags the previous lean sweep left; after any other sweep from the row sums (nonzero sum:
@@ -212,11 +200,7 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
   // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
   float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
-  float a = 0.f;
-  if (nvalid > 0) a = fabsf(vp.x);
-  if (nvalid > 1) a = fmaxf(a, fabsf(vp.y));
-  if (nvalid > 2) a = fmaxf(a, fabsf(vp.z));
-  if (nvalid > 3) a = fmaxf(a, fabsf(vp.w));
+  const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
   const float delta = wave_max(d), mag = wave_max(a);
   const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
   const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
@@ -303,13 +287,7 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   if (renew) {
     if (lane < nrows) SC.mprime_out[ridx] = mkeep;
     if (tr == 0) {  // the first tile of the column segment also stores the epoch's varphi
-      float* __restrict__ v0 = SC.varphi0_out + j0;
-      if (nvalid == 4) *reinterpret_cast<f4u*>(v0) = vp;
-      else {
-        if (nvalid > 0) v0[0] = vp.x;
-        if (nvalid > 1) v0[1] = vp.y;
-        if (nvalid > 2) v0[2] = vp.z;
-      }
+      *reinterpret_cast<f4u*>(SC.varphi0_out + j0) = vp;  // (past n both buffers hold the mask value)
     }
   }
   tile_total = tile_tot;
@@ -339,7 +317,7 @@ __global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArg
   int reads = 0;
   if (tr < ntiles_rows) {
     if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
-    else acc = screened_lean_body<true, false>(A, SC, lane, seg, tr, stop, renew, total, reads);
+    else acc = screened_lean_body<true, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
   }
   if (stop) return;
   *reinterpret_cast<f4v*>(&fold[wave][lane * 4]) = acc;

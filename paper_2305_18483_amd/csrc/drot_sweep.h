@@ -13,16 +13,20 @@
 // rows that start on a line: the caller's arrays when n % 32 == 0 and the base is aligned, else
 // working copies with the pitch rounded up to 32 elements (ldx, ldc).
 // ------------------------------------------------------------------------------------------
+// The four columns of a lane in X or C.  In the last column segment (EDGE) a lane's columns either all
+// lie inside the row as it is laid out in memory or all outside (nmem is 4 or 0): rows are a multiple
+// of 32 columns long there, the caller's when n % 32 == 0, the padded working copies' otherwise, and
+// the columns between n and the pitch hold zeros.  So the edge costs one predicate, not scalar accesses.
 template <bool EDGE, bool NT>
-__device__ __forceinline__ f4v ld4(const float* __restrict__ ptr, int nvalid) {
-  if (EDGE) return load4(ptr, nvalid);
+__device__ __forceinline__ f4v ld4(const float* __restrict__ ptr, int nmem) {
+  if (EDGE && nmem != 4) return f4v{0.f, 0.f, 0.f, 0.f};
   if (NT) return __builtin_nontemporal_load(reinterpret_cast<const f4u*>(ptr));
   return *reinterpret_cast<const f4u*>(ptr);
 }
 template <bool EDGE, bool NT>
-__device__ __forceinline__ void st4(float* __restrict__ ptr, f4v v, int nvalid) {
-  if (EDGE) store4(ptr, v, nvalid);
-  else if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(ptr));
+__device__ __forceinline__ void st4(float* __restrict__ ptr, f4v v, int nmem) {
+  if (EDGE && nmem != 4) return;
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(ptr));
   else *reinterpret_cast<f4u*>(ptr) = v;
 }
 
@@ -198,7 +202,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       x[u] = f4v{0.f, 0.f, 0.f, 0.f};
-      if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+      if (MODE == 3) x[u] = load4(Xp + u * ldx, nmem);  // (any number of a lane's columns may exist there)
+      else if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
     }
   } else {
 #pragma unroll
@@ -207,7 +212,8 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
       x[u] = f4v{0.f, 0.f, 0.f, 0.f};
       if (u < nrows) {
         if (MODE < 2) c[u] = ld4<EDGE, NT>(Cp + u * ldc, nmem);
-        if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
+        if (MODE == 3) x[u] = load4(Xp + u * ldx, nmem);
+        else if (!FIRST && readx[u]) x[u] = ld4<EDGE, NT>(Xp + u * ldx, nmem);
       }
     }
   }
@@ -217,7 +223,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
   float wave_total = 0.f;
   {
-    const f4v vp = PRO ? *reinterpret_cast<const f4v*>(lds_varphi + lane * 4) : load_varphi(A.varphi, j0, nvalid);
+    const f4v vp = PRO ? *reinterpret_cast<const f4v*>(lds_varphi + lane * 4) : load_varphi_padded(A.varphi, j0);
     // lane u holds phi of row r0 + u; rows read it back with a scalar lane read.  Rows past the end of
     // the matrix get the huge negative value: with x = c = 0 they come out as exact zeros, so the loop
     // below needs no per-row branches (only the stores are guarded).
@@ -273,5 +279,5 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_kernel(SweepArgs A, Fu
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y;
   if ((seg + 1) * kSegCols <= A.n) sweep_body<FIRST, false, NT, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
-  else sweep_body<FIRST, true, false, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
+  else sweep_body<FIRST, true, NT, PRO, MODE, U, NW>(A, F, lane, wave, seg, tr, lds_phi, lds_varphi);
 }

@@ -50,6 +50,16 @@ __global__ __launch_bounds__(1024) void init_kernel(VecState V, const float* __r
   }
 }
 
+// varphi and the screening epoch's copy of it hold the mask value from column n to the end of the last
+// 256-column segment (the sweeps load them without an edge case).  One workgroup.
+__global__ __launch_bounds__(256) void mask_tail_kernel(float* __restrict__ varphi, float* __restrict__ varphi0, int n) {
+  const int j = n + (int)threadIdx.x;
+  if (j < (n + kSegCols - 1) / kSegCols * kSegCols) {
+    varphi[j] = kMaskedOut;
+    varphi0[j] = kMaskedOut;
+  }
+}
+
 // Re-arms the stop flag and the status block when a solve continues from the handle's state.
 __global__ void reset_kernel(VecState V) {
   *V.done = 0;
