@@ -317,18 +317,42 @@ def main() -> int:
         dt = time.perf_counter() - t0
         solver.set_profile(True)
         solver.solve_points(xs, xt, cs, p, q, max_iters=256, **pkw)
-        pms, _ = solver.profile()
+        recs = solver.profile_records()
         solver.set_profile(False)
         solver.set_continue(False)
         d = int(P.xs.shape[1])
-        tflops = 2.0 * d * m * n / (pms * 1e-3) / 1e12
+        kernels = []
+        for kind, name in ((8, "lean_points_kernel (cost formed on the matrix cores only for the row segments no bound covers)"),
+                           (9, "sweep_points_kernel, recording the bounds (all costs formed: 2 d flops per element)"),
+                           (0, "sweep_points_kernel (all costs formed: 2 d flops per element)")):
+            sel = [r for r in recs if r.kind == kind]
+            if not sel:
+                continue
+            ms = sum(r.ms for r in sel) / len(sel)
+            e = {"kernel": name, "kernel_ms": round(ms, 5), "launches_timed": len(sel)}
+            if kind == 8:
+                formed = sum(r.c_fraction for r in sel) / len(sel)
+                # per row segment: old and new row sum, bound (12 B); the strip's column sums; X on its nonzero row
+                # segments (read and written); the costs are not traffic; flops: blocks of 16 rows x 256 columns
+                xnz = sum(max(r.x_fraction, 0.0) for r in sel) / len(sel)
+                nbytes = 12.0 * m * nseg + 4.0 * n * ((m + 255) // 256) + 8.0 * xnz * m * n
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                e.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                          "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
+                          "row_segments_with_cost_formed_fraction": round(formed, 5),
+                          "nonzero_row_segment_fraction": round(xnz, 5),
+                          "useful_tflops": round(2.0 * d * formed * m * n / (ms * 1e-3) / 1e12, 2)})
+            else:
+                tflops = 2.0 * d * m * n / (ms * 1e-3) / 1e12
+                e.update({"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None})
+            kernels.append(e)
         points_leg = {"value": round(STEADY_STEPS / dt, 2), "unit": "iterations/s", "ms_per_step": round(dt / STEADY_STEPS * 1e3, 5),
-                      "d": d, "kernel_ms": round(pms, 5),
-                      "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": round(tflops / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
-                                   "kernel": "sweep_points_kernel (2 d flops per element on the fp32 matrix cores)"}}
-        log(f"cost from point clouds (d={d}): {STEADY_STEPS / dt:.1f} it/s, {dt / STEADY_STEPS * 1e3:.4f} ms/iteration; sweep "
-            f"{pms:.4f} ms = {tflops:.1f} TFLOP/s fp32 MFMA")
+                      "d": d, "kernels": kernels}
+        log(f"cost from point clouds (d={d}): {STEADY_STEPS / dt:.1f} it/s, {dt / STEADY_STEPS * 1e3:.4f} ms/iteration; " +
+            "; ".join(f"[{e['kernel'].split(' ')[0]}] {e['kernel_ms']:.4f} ms x {e['launches_timed']} = {e['achieved']} {e['unit']} "
+                      f"({e['frac']:.1%})" + (f", cost formed on {e['row_segments_with_cost_formed_fraction']:.2%} of the row segments"
+                                              if "row_segments_with_cost_formed_fraction" in e else "") for e in kernels))
 
     # ---- time to tolerance / to a duality gap (cold start), verified in fp64 by independent code -------
     def to_tolerance(label, gap_tol):

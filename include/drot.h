@@ -212,9 +212,11 @@ int drot_get_checks(drot_handle h, drot_check* out, int capacity, int* count);
  *               3 = a launch of the resident kernel (its duration divided by the iterations it ran),
  *               4 = as 0 on 64-row tiles with the zero-segment skipping, 5 = the same with screening,
  *               6 = a screening sweep that reads all of C and records the bounds, 7 = the screened sweep
- *               for plans known to be sparse (one wave per tile)
- *   c_fraction  fraction of the row segments of C (256 columns of one row) the sweep read: counted by
- *               the kernel for kinds 5, 6, 7; 1 for the kinds that read all of C, 0 for kind 2
+ *               for plans known to be sparse (one wave per tile), 8 = the screened sweep of
+ *               drot_solve_points (cost formed only for the row segments no bound covers), 9 = a full
+ *               sweep of drot_solve_points that also records the bounds
+ *   c_fraction  fraction of the row segments of C (256 columns of one row) the sweep read (kind 8: formed):
+ *               counted by the kernel for kinds 5 to 8; 1 for the kinds that take all of C, 0 for kind 2
  *   x_fraction  fraction of the row segments of X that hold a nonzero after the sweep (counted by the
  *               vector update that follows it), or -1 where that update is fused into the next sweep
  */

@@ -61,6 +61,7 @@ static_assert(plan::kTallTileRows == kScreenRows * kScreenWaves && plan::kTallTi
 static_assert(plan::kSlabCols == kSlabCols && plan::kSlabRowLanes == kSlabRowLanes && plan::kSlabMaxRows == kSlabMaxRows, "slabs");
 static_assert(plan::kResidentMaxRows == kResidentMaxRows && plan::kResidentCols == kResidentCols, "resident kernel");
 static_assert(plan::kColGroup == kColGroup, "column-sum groups of the lean sweep");
+static_assert(plan::kStripRows == kStripRows && plan::kPointsColGroup == kPointsColGroup, "strips of the screened point-cloud sweep");
 
 template <bool FIRST, bool PRO>
 void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a, const FusedUpdateArgs& f) {
@@ -327,10 +328,19 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
       break;
     }
     case plan::kPoints:
-      if (Q.first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, A, Z.PT);
-      else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, A, Z.PT);
-      else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, A, Z.PT);
+      if (Q.first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
+      else if (Q.refresh && nt) hipLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
+      else if (Q.refresh) hipLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
+      else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
+      else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
       break;
+    case plan::kPointsLean: {
+      const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads, nullptr, h->xlines};
+      const dim3 pgrid(S.nseg, ceil_div(m, kStripRows));
+      if (nt) hipLaunchKernelGGL((lean_points_kernel<true>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
+      else hipLaunchKernelGGL((lean_points_kernel<false>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
+      break;
+    }
     case plan::kSlab: {
       const SlabArgs SL{A, h->runbuf, h->runbuf + Z.P.nruns, Z.thr};
       const dim3 slab_grid(S.nstrips, Z.P.nruns > 0 ? Z.P.nruns : 1);
@@ -664,16 +674,17 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
   if (from_points) {
     const int dq = ceil_div(A.cost.d, 16) * 4;
-    const size_t need = (size_t)(m + n) * 4 * (size_t)dq + (size_t)m + (size_t)n;
+    const int ncb = ceil_div(n, 16);
+    const size_t need = ((size_t)m + (size_t)ncb * 16) * 4 * (size_t)dq + (size_t)m + (size_t)n;
     const int rc = grow_buffer(&h->ptbuf, &h->ptbuf_len, need, stream);
     if (rc != DROT_OK) return rc;
     float* xs_pack = h->ptbuf;
     float* xt_pack = xs_pack + (size_t)m * 4 * dq;
-    float* xs_sq = xt_pack + (size_t)n * 4 * dq;
+    float* xs_sq = xt_pack + (size_t)ncb * 16 * 4 * dq;
     float* xt_sq = xs_sq + m;
-    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(m, 256)), dim3(256), 0, stream, A.cost.xs, m, A.cost.d, dq, xs_pack, xs_sq);
-    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, stream, A.cost.xt, n, A.cost.d, dq, xt_pack, xt_sq);
-    Z.PT = PointArgs{xs_pack, xt_pack, xs_sq, xt_sq, dq, A.cost.scale};
+    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(m, 256)), dim3(256), 0, stream, A.cost.xs, m, A.cost.d, dq, xs_pack, xs_sq, 0);
+    hipLaunchKernelGGL(pack_points_kernel, dim3(ceil_div(ncb * 16, 256)), dim3(256), 0, stream, A.cost.xt, n, A.cost.d, dq, xt_pack, xt_sq, 1);
+    Z.PT = PointArgs{xs_pack, xt_pack, xs_sq, xt_sq, dq, A.cost.scale, ncb};
   }
   // the partial sums the reduction reads: per 256-column segment and 32-row tile, or, on the
   // group-resident path, per 32-column strip and label run
@@ -734,11 +745,11 @@ int iterate(Solve& Z, bool* converged_out) {
       enqueue_sweep(Z, Q, timed);
       if (timed) {
         DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
-        if (Q.profile_kind >= 5)  // (one count per wave of the 8-wave tiles, one per workgroup of the lean kernel)
+        const bool per_workgroup = Q.sweep == plan::kLean || Q.sweep == plan::kPointsLean;
+        if (Q.sweep == plan::kScreened8 || per_workgroup)  // (one count per wave of the 8-wave tiles, one per workgroup of the lean kernels)
           hipLaunchKernelGGL(sum_counts_kernel<int>, dim3(1), dim3(1024), 0, stream,
-                             (const int*)(Q.sweep == plan::kLean ? h->wg_reads : h->wave_reads),
-                             Q.sweep == plan::kLean ? S.nseg * ceil_div(S.ntr_tall, kLeanWaves)
-                                                    : S.nseg * S.ntr_tall * kScreenWaves,
+                             (const int*)(per_workgroup ? h->wg_reads : h->wave_reads),
+                             per_workgroup ? S.nseg * ceil_div(S.ntr_tall, kLeanWaves) : S.nseg * S.ntr_tall * kScreenWaves,
                              h->prof_counts + 2 * pe);
       }
       enqueue_update(Z, Q);
@@ -1141,7 +1152,7 @@ int drot_get_profile(drot_handle h, drot_sweep_timing* out, int capacity, int* c
     const int kind = h->prof_kind[e];
     out[e].ms = h->prof_ms[e];
     out[e].kind = kind;
-    out[e].c_fraction = kind >= 5 ? h->prof_counts_host[2 * e] / segments : (kind == 2 ? 0.0 : 1.0);
+    out[e].c_fraction = (kind >= 5 && kind <= 8) ? h->prof_counts_host[2 * e] / segments : (kind == 2 ? 0.0 : 1.0);
     out[e].x_fraction = kind >= 4 ? h->prof_counts_host[2 * e + 1] / segments : -1.0;
   }
   return DROT_OK;

@@ -16,7 +16,9 @@
 //   Screened8   the same tiles; row segments certified to stay zero also skip their reads of C;
 //               with `refresh` it reads all of C and records the bounds the certificates use
 //   Lean        one wave per 64 x 256 tile, for plans known to be sparse; renews its bounds itself
-//   Points      cost recomputed from point clouds on the matrix cores (32-row tiles)
+//   Points      cost recomputed from point clouds on the matrix cores (32-row tiles); with `refresh` it
+//               also records the screening bounds
+//   PointsLean  the same cost for the rows a certificate does not cover only (256-row strips)
 //   Slab        group lasso, a whole class x 32 columns resident in one workgroup
 //   TwoPass     group lasso, any labels: norms first, then the scaled update
 //
@@ -41,6 +43,8 @@ constexpr int kSlabRowLanes = 128;    // row lanes of the slab kernel (K = 1, 2,
 constexpr int kSlabMaxRows = 1024;    // longest class the slab kernel holds
 constexpr int kResidentMaxRows = 128, kResidentCols = 256;
 constexpr int kColGroup = 4;          // the lean sweep adds the column sums of four tiles before it stores
+constexpr int kStripRows = 256;       // rows of a strip of the point-cloud variant's screened sweep
+constexpr int kPointsColGroup = 8;    // ... which adds the column sums of its eight 32-row tiles before it stores
 constexpr size_t kScreenFrom = (size_t)11 << 20;  // screening on automatic: from this many entries up
 constexpr int kFirstRefreshPeriod = 8, kMaxRefreshPeriod = 256;
 constexpr int kEarlyLooksUntil = 512;  // cold starts: extra density readings over this many iterations
@@ -101,6 +105,7 @@ struct Static {
   int nstrips = 0;
   bool small_slab = false, small = false, fused = false;
   bool can_pair = false, adaptive_pairs = false, may_screen = false, adaptive = false;
+  bool points_screen = false;    // point-cloud variant: screened sweeps once the plan is known to be sparse
   int refresh_max = kMaxRefreshPeriod;
   int sums_strip = kSegCols;
   bool status_at_checks = false; // the stretches end with a status kernel (stopping test and / or density)
@@ -135,7 +140,9 @@ inline Static make_static(const Problem& P, const Options& O) {
   S.adaptive_pairs = P.feedback && S.can_pair && !S.small && O.skip_cost == -1 && O.skip_unchanged != 0;
   S.may_screen = S.can_pair && !S.small && O.skip_cost != 1 && O.skip_unchanged != 0 &&
                  (O.screening > 0 || (O.screening == -1 && (size_t)m * (size_t)n >= kScreenFrom));
-  S.adaptive = P.feedback && (S.adaptive_pairs || S.may_screen);
+  S.points_screen = P.from_points && O.skip_unchanged != 0 &&
+                    (O.screening > 0 || (O.screening == -1 && (size_t)m * (size_t)n >= kScreenFrom));
+  S.adaptive = P.feedback && (S.adaptive_pairs || S.may_screen || S.points_screen);
   S.refresh_max = O.screening >= 2 ? O.screening : kMaxRefreshPeriod;
   S.sums_strip = P.slab_k ? kSlabCols : kSegCols;
   S.status_at_checks = P.checking || S.adaptive || O.gap_every > 0;
@@ -206,7 +213,7 @@ inline Stretch next_stretch(const Static& S, const Problem& P, const Options& O,
   return R;
 }
 
-enum Sweep { kResident = 0, kPro32, kPlain32, kTall64, kScreened8, kLean, kPoints, kSlab, kTwoPass };
+enum Sweep { kResident = 0, kPro32, kPlain32, kTall64, kScreened8, kLean, kPoints, kSlab, kTwoPass, kPointsLean };
 enum Update { kNoUpdate = 0, kSeparate, kMergedSlab, kMergedTiles };
 
 struct Step {
@@ -251,6 +258,29 @@ inline Step next_sweep(const Static& S, const Problem& P, const Options& O, Stat
     Q.sweep = kPoints;
     Q.prev_sums = T.sums_gen == sw - 1 && skipping;
     T.sums_gen = sw;
+    // (the reduction adds the eight 32-row tiles of a 256-row strip first, as the screened sweep stores them: the
+    // same bits with and without the screening)
+    Q.ra_cgroup = kPointsColGroup;
+    if (S.points_screen) {
+      // every full sweep but the first records the bounds; the screened sweep runs on them while the plan is
+      // known to be sparse, until they are due for renewal (after 8, 16, 32, ... sweeps: varphi moves fast at first)
+      const bool due = T.epoch_gen < 0 || sw - T.epoch_gen >= T.refresh_period;
+      const bool lean_points = !Q.first && !due && Q.prev_sums && T.plan_density >= 0.0 && T.plan_density < 0.25;
+      if (lean_points) {
+        Q.sweep = kPointsLean;
+        Q.profile_kind = 8;
+        Q.ra_ntr = ceil_div(P.m, kStripRows);
+        Q.ra_cgroup = 1;
+      } else {
+        if (!Q.first) {
+          Q.refresh = true;
+          Q.profile_kind = 9;
+          if (T.epoch_gen >= 0 && due)
+            T.refresh_period = T.refresh_period * 2 < S.refresh_max ? T.refresh_period * 2 : S.refresh_max;
+          T.epoch_gen = sw;
+        }
+      }
+    }
   } else if (P.slab_k) {
     Q.sweep = kSlab;
     // (large problems: the slab totals give eta, one launch then does the whole vector update)

@@ -114,10 +114,36 @@ struct ReduceArgs {
   const float* p;
   const float* q;
   int m, n, nseg, ntr, nbm, nbn;
-  int cgroup;  // 1, or kColGroup: consecutive rows of colpart are first added up in fp32, in groups of that many
+  int cgroup;  // 1, kColGroup or kPointsColGroup: consecutive rows of colpart are first added up in fp32, in groups of that many
 };
 
 constexpr int kReduceThreads = 1024;
+
+// One of the 16 shares of a column's partial sums when G consecutive rows are added in fp32 first.
+template <int G>
+__device__ __forceinline__ double gather_grouped(const float* __restrict__ part, int share, int nparts, int ntr, int idx, int len) {
+  constexpr int kStride = 16, kGroups = 32 / G > 1 ? 32 / G / 2 : 1;  // (16 loads in flight per batch)
+  double acc = 0.0;
+  for (int k0 = share; k0 < nparts; k0 += kStride * kGroups) {
+    float v[kGroups][G];
+#pragma unroll
+    for (int b = 0; b < kGroups; ++b)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int k = (k0 + b * kStride) * G + g;
+        v[b][g] = (idx < len && k < ntr) ? part[(size_t)k * len + idx] : 0.f;
+      }
+#pragma unroll
+    for (int b = 0; b < kGroups; ++b)
+      if (k0 + b * kStride < nparts) {
+        float t = v[b][0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) t += v[b][g];
+        acc += (double)t;
+      }
+  }
+  return acc;
+}
 
 // First part: the partial sums of 64 entries split 16 ways (share c takes the partials c, c + 16,
 // ...), each share added up in order.  NW waves: wave w forms the shares w, w + NW, ... of entry
@@ -130,32 +156,19 @@ __device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, 
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
   const int len = rows ? A.m : A.n;
-  const bool grouped = !rows && A.cgroup == kColGroup;
-  const int nparts = rows ? A.nseg : grouped ? (A.ntr + kColGroup - 1) / kColGroup : A.ntr;
+  const bool grouped = !rows && A.cgroup > 1;
+  const int nparts = rows ? A.nseg : grouped ? (A.ntr + A.cgroup - 1) / A.cgroup : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
   int nz = 0;
   constexpr int kStride = 16, kBatch = 8;
 #pragma unroll
   for (int share = sub; share < 16; share += NW) {
     double acc = 0.0;
-    if (grouped) {
-      // column sums stored per 64-row tile: tiles 4k .. 4k+3 are added first, in fp32 and in order, as
-      // the workgroups of the lean sweep do before they store (a tile past the end adds +0)
-      constexpr int kGroups = kBatch / 2;
-      for (int k0 = share; k0 < nparts; k0 += kStride * kGroups) {
-        float v[kGroups][kColGroup];
-#pragma unroll
-        for (int b = 0; b < kGroups; ++b)
-#pragma unroll
-          for (int g = 0; g < kColGroup; ++g) {
-            const int k = (k0 + b * kStride) * kColGroup + g;
-            v[b][g] = (idx < len && k < A.ntr) ? part[(size_t)k * len + idx] : 0.f;
-          }
-#pragma unroll
-        for (int b = 0; b < kGroups; ++b)
-          if (k0 + b * kStride < nparts) acc += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
-      }
-    }
+    // column sums stored per tile row: the rows G k .. G k + G - 1 are added first, in fp32 and in order, as the
+    // workgroups of the lean sweeps do before they store (a row past the end adds +0).  G = 4: four 64-row tiles
+    // (screened_lean_kernel); G = 8: the eight 32-row tiles of a 256-row strip (lean_points_kernel)
+    if (grouped && A.cgroup == kColGroup) acc = gather_grouped<kColGroup>(part, share, nparts, A.ntr, idx, len);
+    else if (grouped) acc = gather_grouped<kPointsColGroup>(part, share, nparts, A.ntr, idx, len);
     for (int k0 = share; !grouped && k0 < nparts; k0 += kStride * kBatch) {  // (nparts and share are wave-uniform)
       // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
       // trip would wait for memory once per partial sum)

@@ -944,6 +944,51 @@ def test_point_cloud_sweep_skipping_zero_segments_changes_no_bit(drot, m, n, d, 
     assert float(np.mean(zero_segments)) > 0.02  # (some segments really are skipped)
 
 
+@pytest.mark.parametrize("m,n,d,kind", [(2100, 8232, 8, 1), (2300, 8192, 3, 0), (1531, 9999, 6, 1)])
+def test_point_cloud_screening_changes_no_bit(drot, oracle, m, n, d, kind):
+    # wide rows: once a status has reported a sparse plan the point-cloud variant forms the cost only for the row
+    # segments no bound covers (gathered onto the matrix cores in blocks of 16 rows); the iterates must be those of its
+    # full sweeps bit for bit, over several renewals of the bounds, across residual checks and a continuation, and they
+    # must match the fp64 iteration on the cost formed in fp64
+    P = drot_inputs.random_problem(m, n, seed=2300 + d, d=d, reg_kind=kind, lam=0.01 if kind else 0.0)
+    scale = np.float32(1.0 / P.cmax)
+    dev = torch.device("cuda:0")
+    xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
+    p, q = torch.from_numpy(P.p).to(dev), torch.from_numpy(P.q).to(dev)
+    solver = drot.Solver(m, n, check_every=25)
+    _say(f"point-cloud cost, screening, bitwise, {m}x{n} d={d}")
+    K = 260
+
+    def run(iters, X_out=None):
+        r = solver.solve_points(xs, xt, float(scale), p, q, reg_kind=kind, lam=P.lam, max_iters=iters, tol=1e-12, X_out=X_out)
+        phi, varphi = solver.duals(m, n, dev)
+        return r, r.X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy()
+
+    solver.set_screening(0)
+    _, X_plain, phi_plain, varphi_plain = run(K)
+    solver.set_screening(1)
+    solver.set_profile(True)
+    res, X, phi, varphi = run(K)
+    rec = solver.profile_records()
+    solver.set_profile(False)
+    kinds = [r.kind for r in rec]
+    assert kinds.count(8) >= 10 and kinds.count(9) >= 3, kinds
+    formed = [r.c_fraction for r in rec if r.kind == 8]
+    assert min(formed) < 0.5  # it does leave most of the cost unformed
+    assert np.array_equal(X, X_plain) and np.array_equal(phi, phi_plain) and np.array_equal(varphi, varphi_plain)
+    Xc = torch.empty((m, n), device=dev)
+    run(97, X_out=Xc)
+    solver.set_continue(True)
+    run(11, X_out=Xc)
+    _, X3, phi3, varphi3 = run(K - 108, X_out=Xc)
+    solver.set_continue(False)
+    assert np.array_equal(X3, X_plain) and np.array_equal(phi3, phi_plain) and np.array_equal(varphi3, varphi_plain)
+    P.C = oracle.sqdist_cost(P.xs, P.xt, float(scale))
+    ores = pu.oracle_solve(oracle, P, K)
+    ratio = pu.assert_parity(oracle, P, res, X, phi, varphi, ores, label="points, screened")
+    _say(f"point-cloud cost, screened: plan error / scale = {ratio:.2e}; kinds {kinds.count(8)} screened, {kinds.count(9)} recording")
+
+
 def test_ot_cost_gradient_is_the_plan(drot, oracle):
     # Section "Backpropagation through regularized OT-costs": grad_C OT_h(C) = X* when the
     # solution is unique (quadratic term).  Checked against the oracle's plan at convergence and

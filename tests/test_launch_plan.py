@@ -11,7 +11,7 @@ import os
 import numpy as np
 import pytest
 
-RESIDENT, PRO32, PLAIN32, TALL64, SCREENED8, LEAN, POINTS, SLAB, TWOPASS = range(9)
+RESIDENT, PRO32, PLAIN32, TALL64, SCREENED8, LEAN, POINTS, SLAB, TWOPASS, POINTS_LEAN = range(10)
 NO_UPDATE, SEPARATE, MERGED_SLAB, MERGED_TILES = range(4)
 COLS = ("sweep", "mode", "first", "prev_sums", "lines_in", "refresh", "pro", "tilesum", "update", "ra", "kind", "flags")
 FRESH_CARRY = (0, -1000000, -1, 8, 0, 0, 0, 0)
@@ -111,7 +111,7 @@ def test_cold_start_of_a_large_sparse_problem_moves_to_the_lean_sweep(planlib):
     assert t.col("lines_in")[96] == 0 and set(t.col("lines_in")[97:]) == {1}  # flags are valid from one lean sweep to the next
     assert set(t.col("update")[1:]) == {MERGED_TILES} and t.col("update")[0] == SEPARATE
     # column partials: 625 rows for the 32-row tiles, 313 in groups of four for the 64-row tiles, 79 for the lean sweep
-    assert t.col("ra")[0] == 625 * 8 + 1 and t.col("ra")[5] == 313 * 8 + 4 and t.col("ra")[100] == 79 * 8 + 1
+    assert t.col("ra")[0] == 625 * 16 + 1 and t.col("ra")[5] == 313 * 16 + 4 and t.col("ra")[100] == 79 * 16 + 1
     # never the even/odd pairs here: the dense readings came from early looks
     assert set(t.col("mode")) == {0}
 
@@ -242,3 +242,25 @@ def test_class_chunks_of_the_two_pass_group_lasso_path(planlib):
                 assert 1 <= len(chunk) <= 16
                 rows += chunk
             assert rows == np.flatnonzero(labels == c).tolist()  # every row of the class once, in ascending order
+
+
+def test_point_cloud_variant_screens_once_the_plan_is_sparse(planlib):
+    t = trace(planlib, 20000, 20000, 200, from_points=1, reg_kind=1, checking=0, densities=(0.9, 0.6, 0.2, 0.05))
+    kinds = t.col("kind")
+    assert kinds[0] == 0 and set(kinds[1:96]) == {9}        # full sweeps, all but the first recording the bounds
+    # lean from sweep 97 (the status after 64 iterations is read while the stretch to 96 is queued), on the bounds
+    # of sweep 96; they are renewed by one full sweep after 8 sweeps, then after 16, 32, ...
+    assert kinds[96:103] == [8] * 7 and kinds[103] == 9 and kinds[104:119] == [8] * 15 and kinds[119] == 9
+    assert t.col("sweep")[96] == POINTS_LEAN and t.col("sweep")[103] == POINTS
+    # column sums: eight 32-row tiles of the full sweep are added first, as the strips of the screened sweep store them
+    assert t.col("ra")[5] == 625 * 16 + 8 and t.col("ra")[100] == 79 * 16 + 1 and t.col("ra")[0] == 625 * 16 + 8
+    assert set(t.col("update")) == {SEPARATE}
+    # small problems, or with the screening off: the full sweep only, column sums ungrouped
+    t = trace(planlib, 3000, 3000, 40, from_points=1, reg_kind=1, checking=0, densities=(0.05,))
+    assert set(t.col("kind")) == {0} and set(t.col("ra")) == {94 * 16 + 8}
+    t = trace(planlib, 20000, 20000, 120, from_points=1, reg_kind=1, checking=0, screening=0, densities=(0.05,))
+    assert set(t.col("kind")) == {0}
+    # a continued call goes on with the bounds it finds
+    first = trace(planlib, 20000, 20000, 100, from_points=1, reg_kind=1, checking=0, densities=(0.9, 0.6, 0.2, 0.05))
+    cont = trace(planlib, 20000, 20000, 20, from_points=1, reg_kind=1, checking=0, resume=1, carry=first.carry, densities=(0.05,))
+    assert cont.col("kind")[0] == 8
