@@ -261,7 +261,16 @@ int drot_solve(drot_handle h, const float* C, const float* p, const float* q, in
  * The cost is evaluated in fp32 as cost_scale*max(|xs_i|^2 + |xt_j|^2 - 2 xs_i.xt_j, 0) (squared
  * norms accumulated in fp64), so it agrees with a stored fp32 cost to a few 1e-7 absolute, and the
  * iterates agree with the stored-cost solve to that perturbation accumulated over the iterations.
- * DROT_REG_NONE and DROT_REG_QUADRATIC only.  Other arguments, results and errors as drot_solve.
+ * With DROT_OPT_SKIP_UNCHANGED on (the default) the sweeps screen as the stored-cost sweeps do: every
+ * full sweep records, per row segment, the bound max_j (varphi_j - rho C_ij) in the arithmetic it
+ * sweeps with, and once the plan is sparse a lean sweep forms the cost (on the matrix cores, 16
+ * gathered rows at a time, operand for operand as the full sweep does) only for the row segments the
+ * bound does not certify to stay zero.  Bit for bit the iterates of the sweep that forms every cost.
+ * DROT_REG_NONE and DROT_REG_QUADRATIC only, and no weighted l1 term (INVALID_ARG): a weight matrix
+ * is m*n floats that every sweep would have to read, which is the traffic of the stored cost this
+ * entry point exists to avoid (add the weights to a stored C and call drot_solve); the group-lasso
+ * sweeps keep a class's rows of one column strip in registers or make two passes over X and C, and
+ * have no variant that forms the cost.  Other arguments, results and errors as drot_solve.
  */
 int drot_solve_points(drot_handle h, const float* xs, const float* xt, int d, float cost_scale,
                       const float* p, const float* q, int m, int n, float stepsize,
@@ -282,6 +291,16 @@ int drot_solve_warm(drot_handle h, const float* C, const float* p, const float* 
                     float stepsize, drot_reg_kind reg_kind, const drot_reg_params* reg_params,
                     int max_iters, float tol, float* X_inout, const float* phi0, const float* varphi0,
                     void* stream);
+
+/*
+ * Warm start with the on-the-fly cost: drot_solve_points from the point (X_0, phi_0, varphi_0), with
+ * X_inout, phi0, varphi0 as in drot_solve_warm and everything else as in drot_solve_points.
+ */
+int drot_solve_points_warm(drot_handle h, const float* xs, const float* xt, int d, float cost_scale,
+                           const float* p, const float* q, int m, int n, float stepsize,
+                           drot_reg_kind reg_kind, const drot_reg_params* reg_params, int max_iters,
+                           float tol, float* X_inout, const float* phi0, const float* varphi0,
+                           void* stream);
 
 /*
  * For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,

@@ -24,7 +24,7 @@ DROT_STATIC_MAX_M = DROT_STATIC_MAX_N = 4096
 # every symbol include/drot.h declares
 EXPORTED_SYMBOLS = (
     "drot_create", "drot_destroy", "drot_set_option", "drot_set_gap_tolerance", "drot_get_checks", "drot_get_profile",
-    "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_solve_static", "drot_get_info", "drot_get_duals",
+    "drot_solve", "drot_solve_points", "drot_solve_warm", "drot_solve_points_warm", "drot_solve_static", "drot_get_info", "drot_get_duals",
     "drot_strerror",
 )
 
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.drot_solve_warm.argtypes = [vp, vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp]
     lib.drot_solve_points.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf,
                                       vp, vp]
+    lib.drot_solve_points_warm.argtypes = [vp, vp, vp, ci, cf, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci,
+                                           cf, vp, vp, vp, vp]
     lib.drot_solve_static.argtypes = [vp, vp, vp, ci, ci, cf, ci, ctypes.POINTER(drot_reg_params), ci, cf, vp, vp, vp, vp, vp]
     lib.drot_get_info.argtypes = [vp, ctypes.POINTER(drot_info)]
     lib.drot_get_duals.argtypes = [vp, vp, vp]
@@ -290,23 +292,31 @@ class Solver:
     def solve_points(self, xs: torch.Tensor, xt: torch.Tensor, cost_scale: float, p: torch.Tensor, q: torch.Tensor, *,
                      stepsize: float = 0.0, reg_kind: int = DROT_REG_NONE, lam: float = 0.0, max_iters: int = 1000,
                      tol: float = 0.0, X_out: Optional[torch.Tensor] = None,
-                     stream: Optional[torch.cuda.Stream] = None) -> SolveResult:
-        """drot_solve_points: cost recomputed from the point clouds xs (m x d), xt (n x d) in every sweep."""
+                     stream: Optional[torch.cuda.Stream] = None, phi0: Optional[torch.Tensor] = None,
+                     varphi0: Optional[torch.Tensor] = None) -> SolveResult:
+        """drot_solve_points: cost recomputed from the point clouds xs (m x d), xt (n x d) in every sweep
+        (drot_solve_points_warm when phi0 and varphi0 are given: X_out then holds X_0 on entry)."""
         m, d = xs.shape
         n = xt.shape[0]
         if xt.shape[1] != d:
             raise ValueError("xs and xt must have the same number of columns")
+        warm = phi0 is not None or varphi0 is not None
         if X_out is None:
+            if warm:
+                raise ValueError("a warm start needs X_out holding the starting plan")
             X_out = torch.empty((m, n), dtype=torch.float32, device=xs.device)
         params = drot_reg_params(float(lam), 0.0, 0, None, None)
         stream = stream if stream is not None else torch.cuda.current_stream(xs.device)
-        rc = self._lib.drot_solve_points(self._h, _ptr(xs, torch.float32, "xs"), _ptr(xt, torch.float32, "xt"), int(d),
-                                         float(cost_scale), _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"),
-                                         int(m), int(n), float(stepsize), int(reg_kind), ctypes.byref(params),
-                                         int(max_iters), float(tol), _ptr(X_out, torch.float32, "X_out"),
-                                         ctypes.c_void_p(stream.cuda_stream))
+        common = (self._h, _ptr(xs, torch.float32, "xs"), _ptr(xt, torch.float32, "xt"), int(d), float(cost_scale),
+                  _ptr(p, torch.float32, "p"), _ptr(q, torch.float32, "q"), int(m), int(n), float(stepsize), int(reg_kind),
+                  ctypes.byref(params), int(max_iters), float(tol), _ptr(X_out, torch.float32, "X_out"))
+        if warm:
+            rc = self._lib.drot_solve_points_warm(*common, _ptr(phi0, torch.float32, "phi0"),
+                                                  _ptr(varphi0, torch.float32, "varphi0"), ctypes.c_void_p(stream.cuda_stream))
+        else:
+            rc = self._lib.drot_solve_points(*common, ctypes.c_void_p(stream.cuda_stream))
         if rc < 0:
-            raise DrotError(rc, "drot_solve_points")
+            raise DrotError(rc, "drot_solve_points_warm" if warm else "drot_solve_points")
         info = self.info()
         return SolveResult(X=X_out, code=rc, iters=info.iters, converged=bool(info.converged), r_row=info.r_row,
                            r_col=info.r_col, objective=info.objective, gap=info.gap, dual_res=info.dual_res)

@@ -516,7 +516,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   const int m = A.m, n = A.n;
   if (!h || !A.p || !A.q || !A.X_out) return DROT_ERR_INVALID_ARG;
   if (from_points) {
-    if (!A.cost.xs || !A.cost.xt || A.cost.d < 1 || !(A.cost.scale > 0.f) || A.warm) return DROT_ERR_INVALID_ARG;
+    if (!A.cost.xs || !A.cost.xt || A.cost.d < 1 || !(A.cost.scale > 0.f)) return DROT_ERR_INVALID_ARG;
     if (A.reg_kind == DROT_REG_GROUP_LASSO) return DROT_ERR_INVALID_ARG;  // stored-cost paths only
   }
   if (A.warm && (!A.phi0 || !A.varphi0)) return DROT_ERR_INVALID_ARG;
@@ -1177,6 +1177,19 @@ int drot_solve_points(drot_handle h, const float* xs, const float* xt, int d, fl
   A.cost.xs = xs; A.cost.xt = xt; A.cost.d = d; A.cost.scale = cost_scale;
   A.p = p; A.q = q; A.m = m; A.n = n; A.stepsize = stepsize; A.reg_kind = reg_kind; A.reg_params = reg_params;
   A.max_iters = max_iters; A.tol = tol; A.X_out = X_out; A.stream = stream;
+  return solve_impl(h, A);
+}
+
+int drot_solve_points_warm(drot_handle h, const float* xs, const float* xt, int d, float cost_scale, const float* p,
+                           const float* q, int m, int n, float stepsize, drot_reg_kind reg_kind,
+                           const drot_reg_params* reg_params, int max_iters, float tol, float* X_inout, const float* phi0,
+                           const float* varphi0, void* stream) {
+  if (!xs || !xt) return DROT_ERR_INVALID_ARG;
+  SolveCall A;
+  A.cost.xs = xs; A.cost.xt = xt; A.cost.d = d; A.cost.scale = cost_scale;
+  A.p = p; A.q = q; A.m = m; A.n = n; A.stepsize = stepsize; A.reg_kind = reg_kind; A.reg_params = reg_params;
+  A.max_iters = max_iters; A.tol = tol; A.X_out = X_inout; A.phi0 = phi0; A.varphi0 = varphi0; A.warm = true;
+  A.stream = stream;
   return solve_impl(h, A);
 }
 

@@ -219,7 +219,7 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   float tile_tot = 0.f, group_tot = 0.f;  // the total of the tile, added up in the same order
   int group = -1;
   float rowkeep = 0.f;
-  constexpr int kWalk = 4;  // rows fetched together: their loads overlap, the arithmetic stays in row order
+  constexpr int kWalk = 3;  // rows fetched together: their loads overlap, the arithmetic stays in row order
   while (todo != 0) {
     int row[kWalk];
     f4v c[kWalk], x[kWalk];
@@ -302,7 +302,7 @@ constexpr int kColGroup = kLeanWaves;
 static_assert(64 * kLeanWaves == kSegCols, "one thread per column of the segment in the final fold");
 
 template <bool NT>
-__global__ __launch_bounds__(64 * kLeanWaves) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
+__global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
   // (the stop flag is fetched along with a wave's first loads and tested before its first store)
   const int stop = *A.done;
   const bool renew = SC.ctl[kCtlRenew] != 0;

@@ -912,6 +912,42 @@ def test_cost_from_point_clouds(drot, oracle, m, n, d, kind):
     _say(f"point-cloud cost: plan error / scale = {ratio:.2e}")
 
 
+@pytest.mark.parametrize("m,n,d,kind", [(150, 210, 3, 0), (1300, 911, 12, 1), (2100, 8232, 8, 1)])
+def test_warm_start_with_the_cost_from_point_clouds(drot, oracle, m, n, d, kind):
+    # drot_solve_points_warm from an arbitrary (X_0, phi_0, varphi_0) against the oracle from the same point on the
+    # same cost formed in fp64; and the same bits whether or not the sweeps skip and screen
+    P = drot_inputs.random_problem(m, n, seed=950 + d, d=d, reg_kind=kind, lam=0.05 if kind else 0.0)
+    scale = np.float32(1.0 / P.cmax)
+    P.C = oracle.sqdist_cost(P.xs, P.xt, float(scale))
+    rng = np.random.default_rng(951)
+    X0 = (np.outer(P.p, P.q) * rng.uniform(0.0, 2.0, size=(m, n)) * (rng.uniform(size=(m, n)) < 0.3)).astype(np.float32)
+    X0[:, n // 2:n // 2 + 300] = 0.0  # (whole row segments of zeros: the first sweep leaves them unread)
+    phi0 = rng.uniform(0.0, 1.0 / (m + n), size=m).astype(np.float32)
+    varphi0 = rng.uniform(0.0, 1.0 / (m + n), size=n).astype(np.float32)
+    K = 120
+    _say(f"warm start, point-cloud cost {m}x{n} d={d} kind={kind}")
+    dev = torch.device("cuda:0")
+    args = [torch.from_numpy(a).to(dev) for a in (P.xs, P.xt)]
+    pq = [torch.from_numpy(a).to(dev) for a in (P.p, P.q)]
+    start = dict(phi0=torch.from_numpy(phi0).to(dev), varphi0=torch.from_numpy(varphi0).to(dev))
+    solver = drot.Solver(m, n, check_every=20)
+    X = torch.from_numpy(X0).to(dev)
+    res = solver.solve_points(*args, float(scale), *pq, reg_kind=kind, lam=P.lam, max_iters=K, X_out=X, **start)
+    phi, varphi = solver.duals(m, n, dev)
+    torch.cuda.synchronize()
+    ores = oracle.solve(P.C, P.p, P.q, rho=float(P.rho), reg_kind=kind, lam=float(np.float32(P.lam)), max_iters=K,
+                        X0=X0, phi0=phi0, varphi0=varphi0)
+    assert res.iters == K
+    pu.assert_parity(oracle, P, res, X.cpu().numpy(), phi.cpu().numpy(), varphi.cpu().numpy(), ores, label="points, warm")
+    solver.set_skip_unchanged(0)
+    X2 = torch.from_numpy(X0).to(dev)
+    solver.solve_points(*args, float(scale), *pq, reg_kind=kind, lam=P.lam, max_iters=K, X_out=X2, **start)
+    phi2, varphi2 = solver.duals(m, n, dev)
+    assert torch.equal(X, X2) and torch.equal(phi, phi2) and torch.equal(varphi, varphi2)
+    with pytest.raises(drot.DrotError):  # (both potentials or neither)
+        solver.solve_points(*args, float(scale), *pq, max_iters=1, X_out=X2, phi0=start["phi0"])
+
+
 @pytest.mark.parametrize("m,n,d,kind", [(333, 517, 3, 0), (1300, 2100, 6, 1), (900, 2300, 2, 0)])
 def test_point_cloud_sweep_skipping_zero_segments_changes_no_bit(drot, m, n, d, kind):
     # the sweep that recomputes the cost also leaves all-zero row segments of X unread and unwritten;

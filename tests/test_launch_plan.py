@@ -199,6 +199,10 @@ def test_point_clouds_and_warm_starts(planlib):
     assert t.col("first") == [0, 0, 0, 0] and t.col("prev_sums")[0] == 1 and t.col("kind")[0] == 6
     t = trace(planlib, 5000, 5000, 3, warm=1, reg_kind=2, slab_k=4, nruns=10, checking=0)
     assert t.col("prev_sums") == [0, 1, 1]  # (those sums are per 256 columns, the slab kernel's flags per 32)
+    # a warm start with the cost from point clouds: X_0 is read where its sums say so, and the sweep records bounds
+    t = trace(planlib, 3000, 3000, 4, from_points=1, warm=1, reg_kind=1, checking=0, screening=1)
+    assert set(t.col("sweep")) == {POINTS} and t.col("first") == [0, 0, 0, 0] and t.col("prev_sums") == [1, 1, 1, 1]
+    assert t.col("refresh") == [1, 1, 1, 1] and set(t.col("kind")) == {9}
 
 
 def test_label_analysis(planlib):
