@@ -450,7 +450,9 @@ void enqueue_update(Solve& Z, const plan::Step& Q) {
 
 // S7: objective, duality gap and dual residual of the state in memory into the status block.  guard:
 // the stop flag, for the passes that belong to a check (after a stop they would only repeat it).
-void enqueue_gap(Solve& Z, const int* guard) {
+// flags_current: the host's record of the flags (line flags, row-segment sums) describes the X in memory, i.e. no
+// sweep enqueued so far can have been skipped by a stop raised on the device.
+void enqueue_gap(Solve& Z, const int* guard, bool flags_current) {
   drot_handle h = Z.h;
   hipStream_t stream = Z.stream;
   const plan::Static& S = Z.S;
@@ -461,7 +463,14 @@ void enqueue_gap(Solve& Z, const int* guard) {
                        2 * Z.ngroups, 0.f, guard);
   const GapArgs GA{Z.Xw, Z.Cw, h->phi, h->varphi, Z.row_class, h->gap_part, gx, gw, Z.m, Z.n, S.nseg, Z.ldx, Z.ldc, Z.rho,
                    Z.PT, guard};
-  hipLaunchKernelGGL(gap_kernel, dim3(S.nseg, S.ntr), dim3(kBlock), 0, stream, GA);
+  const plan::GapPass pass = flags_current ? plan::gap_pass(S, Z.P, Z.T) : plan::kGapDense;
+  if (pass != plan::kGapDense) {
+    const GapLeanArgs GL{GA, h->mprime, h->varphi0, pass == plan::kGapLeanLines ? h->xlines : nullptr,
+                         Z.rowp(Z.T.k_base + Z.T.k), Z.SA.n_mem, S.ntr_tall, S.ntr};
+    hipLaunchKernelGGL(gap_lean_kernel, dim3(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), dim3(64 * kLeanWaves), 0, stream, GL);
+  } else {
+    hipLaunchKernelGGL(gap_kernel, dim3(S.nseg, S.ntr), dim3(kBlock), 0, stream, GA);
+  }
   hipLaunchKernelGGL(gap_final_kernel, dim3(1), dim3(1024), 0, stream, Z.V, (const float*)h->gap_part, S.ntiles,
                      (const float*)gx, (const float*)gw, Z.ngroups, Z.p, Z.q, Z.m, Z.n, (double)Z.rho, (int)Z.reg_kind,
                      (double)Z.lambda, (double)Z.mu, guard);
@@ -760,7 +769,7 @@ int iterate(Solve& Z, bool* converged_out) {
     }
     if (S.status_at_checks) {
       // the test runs on the device; the host reads it one stretch late so the queue never drains
-      if (R.gap) enqueue_gap(Z, h->done);
+      if (R.gap) enqueue_gap(Z, h->done, true);  // (behind the stop flag: it runs only if every sweep before it ran)
       enqueue_status(Z, Z.T.k, Z.P.checking && !R.probe, R.gap);
       if (!Z.P.feedback) {  // (the stop flag alone ends the solve: the sweeps queued behind it return at once)
         DROT_HIP(hipGetLastError());
@@ -817,7 +826,9 @@ int solve_impl(drot_handle h, const SolveCall& A) {
   const int k = Z.T.k;
   // final state: residuals of the returned iterate (no-op if the stop flag is already up)
   if (k > 0) enqueue_status(Z, k, Z.P.checking, false);
-  if (h->compute_gap) enqueue_gap(Z, nullptr);
+  // (a stop seen in the loop means the last stretch was enqueued behind it and did not run; without feedback
+  // the host cannot tell)
+  if (h->compute_gap) enqueue_gap(Z, nullptr, !converged && (Z.P.feedback || !Z.P.checking));
   const bool untouched = A.max_iters == 0 && !Z.P.resume && !A.warm;
   if (S.pad_x && !untouched) copy_rows(A.X_out, (size_t)Z.n, h->xpad, (size_t)S.ld_pad, Z.m, Z.n, stream);
   if (hipMemcpyAsync(&h->host_status[0], h->status, sizeof(DeviceStatus), hipMemcpyDeviceToHost, stream) != hipSuccess ||
@@ -988,7 +999,7 @@ int solve_static_impl(SolveCall A, float* phi_out, float* varphi_out, drot_info*
   rc = iterate(Z, &converged);
   if (rc != DROT_OK) return rc;
   if (Z.T.k > 0) enqueue_status(Z, Z.T.k, Z.P.checking, false);
-  enqueue_gap(Z, nullptr);
+  enqueue_gap(Z, nullptr, false);
   hipLaunchKernelGGL(export_kernel, dim3(16), dim3(256), 0, Z.stream, (const DeviceStatus*)H.status, info_out,
                      (const float*)H.phi, (const float*)H.varphi, phi_out, varphi_out, A.m, A.n, A.max_iters);
   DROT_HIP(hipGetLastError());

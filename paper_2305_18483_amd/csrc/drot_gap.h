@@ -22,6 +22,21 @@ struct GapArgs {
   const int* done;       // the stop flag for the passes that belong to a residual check (they skip once it is up), or null
 };
 
+// One row's terms, added to a lane's three running sums.  Products and sums stay separate operations (no
+// contraction into fused multiply-adds), so that every kernel that calls this adds up the same numbers.
+__device__ __forceinline__ void gap_accumulate(const f4v& c, const f4v& x, const f4v& w, float& cx, float& xx, float& ww,
+                                               f4v& x2, f4v& w2) {
+#pragma clang fp contract(off)
+  x2 = x * x;
+  w2 = w * w;
+  // (a forbidden pair carries c = +inf and x = 0: it adds nothing to <C,X>)
+  const f4v cxv = {x.x > 0.f ? c.x * x.x : 0.f, x.y > 0.f ? c.y * x.y : 0.f, x.z > 0.f ? c.z * x.z : 0.f,
+                   x.w > 0.f ? c.w * x.w : 0.f};
+  cx += (cxv.x + cxv.y) + (cxv.z + cxv.w);
+  xx += (x2.x + x2.y) + (x2.z + x2.w);
+  ww += (w2.x + w2.y) + (w2.z + w2.w);
+}
+
 __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
   if (A.done && *A.done) return;
   const int lane = threadIdx.x & 63;
@@ -39,13 +54,8 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
     const f4v c = A.C ? load4(A.C + (size_t)i * A.ldc + j0, nvalid) : cost4_from_points(A.pts, i, j0, nvalid);
     const f4v x = load4(A.X + (size_t)i * A.ldx + j0, nvalid);
     const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c, vp + A.phi[i], A.rho);
-    const f4v x2 = x * x, w2 = w * w;
-    // (a forbidden pair carries c = +inf and x = 0: it adds nothing to <C,X>)
-    const f4v cxv = {x.x > 0.f ? c.x * x.x : 0.f, x.y > 0.f ? c.y * x.y : 0.f, x.z > 0.f ? c.z * x.z : 0.f,
-                     x.w > 0.f ? c.w * x.w : 0.f};
-    cx += (cxv.x + cxv.y) + (cxv.z + cxv.w);
-    xx += (x2.x + x2.y) + (x2.z + x2.w);
-    ww += (w2.x + w2.y) + (w2.z + w2.w);
+    f4v x2, w2;
+    gap_accumulate(c, x, w, cx, xx, ww, x2, w2);
     if (A.row_class) {
       const int cls = A.row_class[i];
       if (cls != cur) {
@@ -72,6 +82,128 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
   if (threadIdx.x < 3) {
     const int k = threadIdx.x;
     A.gap_part[(size_t)(tr * A.nseg + seg) * 3 + k] = (ws[k][0] + ws[k][1]) + (ws[k][2] + ws[k][3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// The same partial sums for plans known to be sparse, from a fraction of the traffic.  A row segment
+// whose X is zero and whose screening bound (the certificate of the screened sweeps, to the letter) is
+// not positive adds nothing to any of the three sums: x = 0 there, and [phi_i + varphi_j - rho C_ij]_+,
+// which is what the sweep would compute from x = 0, is certified to be zero.  One wave per 64 x 256
+// tile decides its 64 row segments at once and walks through those that are left, reading C and the
+// nonzero lines of X only there.  The sums are formed in the order of gap_kernel -- per lane over the
+// rows of a chunk of 8, across the wave, the four chunks of a 32-row tile as (0 + 1) + (2 + 3) -- and
+// the skipped terms are exact zeros, so gap_part comes out bit for bit as gap_kernel leaves it.
+// flags: the line flags of the lean sweep (lines) or the row-segment sums (rowsums) of the X in memory.
+// grid = (nseg, ceil(tiles of 64 rows / 4)), 256 threads.
+// ------------------------------------------------------------------------------------------
+struct GapLeanArgs {
+  GapArgs G;
+  const float* mprime;           // [nseg][m] bounds of the epoch
+  const float* varphi0;          // the epoch's varphi (padded)
+  const unsigned char* lines;    // [nseg][m] nonzero 128-byte lines of every row segment of X, or null
+  const float* rowsums;          // [nseg][m] row-segment sums of X (used when lines is null)
+  int n_mem;                     // columns that may be accessed in a row of X and C
+  int ntr64, ntr32;              // tiles of 64 and of 32 rows
+};
+
+template <bool EDGE>
+__device__ __forceinline__ void gap_lean_body(const GapLeanArgs& L, int lane, int seg, int tr, float (*sums)[3]) {
+  const GapArgs& A = L.G;
+  const int j0 = seg * kSegCols + lane * 4;
+  const int nmem = EDGE ? min(max(L.n_mem - j0, 0), 4) : 4;
+  const int r0 = tr * 64;
+  const int nrows = min(A.m - r0, 64);
+  const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
+  const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
+  const float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
+  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+  const f4v vp = load_varphi_padded(A.varphi, j0);
+  const f4v vp0 = load_varphi_padded(L.varphi0, j0);
+  float ph = kMaskedOut, mpr = 0.f;
+  unsigned lines = 0;
+  if (lane < nrows) {
+    ph = A.phi[r0 + lane];
+    mpr = L.mprime[ridx];
+    if (L.lines) lines = L.lines[ridx];
+    else lines = fbits(L.rowsums[ridx]) != 0 ? 0xffu : 0u;
+  }
+  const float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
+  const float delta = wave_max(d), mag = wave_max(a);
+  const float bound = (mpr + delta) + ph;  // (the certificate of screened_body)
+  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
+  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool certified = lane >= nrows || (lines == 0 && below);
+  unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
+  const unsigned myline = (unsigned)lane >> 3;
+  float cx = 0.f, xx = 0.f, ww = 0.f;
+  int chunk = -1;
+  auto flush = [&]() {
+    const float a0 = wave_sum(cx), a1 = wave_sum(xx), a2 = wave_sum(ww);
+    if (lane == 0) {
+      sums[chunk][0] = a0;
+      sums[chunk][1] = a1;
+      sums[chunk][2] = a2;
+    }
+  };
+  constexpr int kWalk = 4;
+  while (todo != 0) {
+    int row[kWalk];
+    f4v c[kWalk], x[kWalk];
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      row[b] = -1;
+      c[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      x[b] = f4v{0.f, 0.f, 0.f, 0.f};
+      if (todo != 0) {
+        row[b] = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        c[b] = ld4<EDGE, false>(Cp + row[b] * ldc, nmem);
+        const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)lines, row[b]);
+        if ((ol >> myline) & 1) x[b] = ld4<EDGE, false>(Xp + row[b] * ldx, nmem);
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b) {
+      const int u = row[b];
+      if (u >= 0) {
+        if ((u >> 3) != chunk) {
+          if (chunk >= 0) flush();
+          chunk = u >> 3;
+          cx = xx = ww = 0.f;
+        }
+        const float phu = __builtin_bit_cast(float, __builtin_amdgcn_readlane(fbits(ph), u));
+        const f4v w = xbar4(f4v{0.f, 0.f, 0.f, 0.f}, c[b], vp + phu, A.rho);
+        f4v x2, w2;
+        gap_accumulate(c[b], x[b], w, cx, xx, ww, x2, w2);
+      }
+    }
+  }
+  if (chunk >= 0) flush();
+}
+
+__global__ __launch_bounds__(64 * kLeanWaves) void gap_lean_kernel(GapLeanArgs L) {
+  if (L.G.done && *L.G.done) return;
+  __shared__ float sums[kLeanWaves][8][3];  // per wave: the eight chunks of 8 rows of its tile
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
+  if (lane < 24) (&sums[wave][0][0])[lane] = 0.f;
+  __syncthreads();
+  if (tr < L.ntr64) {
+    if ((seg + 1) * kSegCols <= L.G.n) gap_lean_body<false>(L, lane, seg, tr, sums[wave]);
+    else gap_lean_body<true>(L, lane, seg, tr, sums[wave]);
+  }
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < 6 * kLeanWaves) {  // (wave, half, sum): a 32-row tile is four chunks
+    const int w = t / 6, half = (t / 3) & 1, k = t % 3;
+    const int tr32 = (blockIdx.y * kLeanWaves + w) * 2 + half;
+    if (tr32 < L.ntr32) {
+      const float(*c)[3] = sums[w] + 4 * half;
+      L.G.gap_part[(size_t)(tr32 * L.G.nseg + seg) * 3 + k] = (c[0][k] + c[1][k]) + (c[2][k] + c[3][k]);
+    }
   }
 }
 

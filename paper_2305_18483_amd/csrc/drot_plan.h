@@ -388,6 +388,23 @@ inline Carry finish(const Static& S, const Problem& P, const State& T, bool conv
   return C;
 }
 
+// Which pass evaluates the terms of the duality gap for the state after the sweeps enqueued so far.  The
+// lean pass visits only the row segments a screening bound does not certify to contribute nothing; it
+// needs the bounds of an epoch and flags that describe the X in memory: the line flags of a lean sweep,
+// or the row-segment sums of any sweep that leaves them per 256 columns.  (After a stop raised on the
+// device the sweeps enqueued behind it did not run and the host's record of the flags is ahead of the
+// memory: the caller falls back to the dense pass then.)
+enum GapPass { kGapDense = 0, kGapLeanLines, kGapLeanSums };
+
+inline GapPass gap_pass(const Static& S, const Problem& P, const State& T) {
+  const long long cur = T.k_base + T.k;
+  if (!S.may_screen || P.from_points || P.reg_kind == kGroupLasso || P.slab_k) return kGapDense;
+  if (T.epoch_gen < 0 || T.epoch_gen > cur || cur < 1) return kGapDense;
+  if (T.lines_gen == cur) return kGapLeanLines;
+  if (T.sums_gen == cur) return kGapLeanSums;
+  return kGapDense;
+}
+
 // Group lasso: the labels of the m rows as runs of equal labels.  The slab kernel applies when every
 // class is one run of at most kSlabMaxRows rows (and the runs fit the workspace).
 struct LabelRuns {

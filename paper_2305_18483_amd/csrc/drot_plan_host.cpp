@@ -21,7 +21,8 @@ extern "C" {
 // densities[nstatus]: what the k-th status of the call reports (fraction of nonzero row segments);
 //              statuses past the end repeat the last one.  stop_at_status >= 0: that status reports convergence.
 // rows [capacity][12]: sweep, mode, first, prev_sums, lines_in, refresh, pro, tilesum, update, ra_ntr * 16 + ra_cgroup,
-//              profile_kind, flags (1: last sweep of a stretch, 2: that stretch is a probe, 4: its status carries the gap)
+//              profile_kind, flags (1: last sweep of a stretch, 2: that stretch is a probe, 4: its status carries the gap,
+//              8: a gap evaluated there may take the lean pass, 16: with the lean sweep's line flags)
 // statics[10]: nseg, ntr, resident, pad_c, pad_x, small, fused, may_screen, adaptive, nt
 // Returns the number of sweeps (launches) planned, or -1 if capacity was too small.
 int drot_plan_trace(const int* problem, const int* options, long long* carry, const double* densities, int nstatus,
@@ -98,7 +99,9 @@ int drot_plan_trace(const int* problem, const int* options, long long* carry, co
       r[8] = Q.update;
       r[9] = Q.ra_ntr * 16 + Q.ra_cgroup;
       r[10] = Q.profile_kind;
-      r[11] = (T.k == k_end ? 1 : 0) | (T.k == k_end && R.probe ? 2 : 0) | (T.k == k_end && R.gap ? 4 : 0);
+      const GapPass G = T.k == k_end ? gap_pass(S, P, T) : kGapDense;
+      r[11] = (T.k == k_end ? 1 : 0) | (T.k == k_end && R.probe ? 2 : 0) | (T.k == k_end && R.gap ? 4 : 0) |
+              (G != kGapDense ? 8 : 0) | (G == kGapLeanLines ? 16 : 0);
       ++nrows;
     }
     if (S.status_at_checks) {

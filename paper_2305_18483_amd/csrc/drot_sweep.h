@@ -170,7 +170,6 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
                                            int tr, float* __restrict__ lds_phi, float* __restrict__ lds_varphi) {
   static_assert(!PRO || (U == kSweepRows && NW == kSweepWaves), "the fused update is written for 32-row tiles");
   const int j0 = seg * kSegCols + lane * 4;
-  const int nvalid = EDGE ? min(max(A.n - j0, 0), 4) : 4;      // columns of this lane that exist
   // columns of this lane that may be accessed (the plain sums of MODE 3 have no mask: existing columns only)
   const int nmem = EDGE ? min(max((MODE == 3 ? A.n : A.n_mem) - j0, 0), 4) : 4;
   const int r0 = (tr * NW + wave) * U;  // a tile has NW * U rows

@@ -119,6 +119,35 @@ def test_gap_stop_takes_the_same_check_as_the_oracle(drot, oracle, kind, m, n, l
     pu.assert_parity(oracle, P, g2, X2, phi2, varphi2, o2, label="gap stop")
 
 
+@pytest.mark.parametrize("pkw,kind_expected", [
+    (dict(m=2300, n=2500, seed=3401, reg_kind=1, lam=0.05), 5),            # 8-wave screened sweeps: row-segment sums as flags
+    (dict(m=2100, n=8232, seed=3402, d=8, reg_kind=1, lam=0.01), 7),       # lean sweeps: their line flags
+    (dict(m=2301, n=9999, seed=3403, d=6, reg_kind=0), 7),                 # padded rows, no quadratic term (dual residual)
+])
+def test_lean_gap_pass_reports_the_bits_of_the_dense_one(drot, pkw, kind_expected):
+    # with screening bounds at hand the gap terms are summed over the uncertified row segments only; every term
+    # left out is an exact zero and the order of the sums is kept, so the reported numbers do not change by a bit
+    P = drot_inputs.random_problem(**pkw)
+    K, every = 320, 20
+    solver = drot.Solver(P.m, P.n, check_every=every)
+    solver.set_gap_every(1)
+    solver.set_profile(True)
+    reports = []
+    for screening in (1, 0):
+        solver.set_screening(screening)
+        _say(f"gap passes {P.m}x{P.n}, screening={screening}")
+        res, X, phi, varphi = pu.gpu_solve(solver, P, K, tol=1e-12)
+        checks = [(c.iters, c.gap_evaluated, c.objective, c.gap, c.dual_res) for c in solver.checks()]
+        assert len(checks) == K // every and all(c[1] for c in checks)
+        reports.append((checks, (res.objective, res.gap, res.dual_res), X))
+        if screening:
+            kinds = [k for _, k in solver.profile_sweeps()]
+            assert kinds.count(kind_expected) >= 20 and sum(k in (5, 7) for k in kinds) >= 50, kinds
+    assert reports[0][0] == reports[1][0] and reports[0][1] == reports[1][1]
+    assert np.array_equal(reports[0][2], reports[1][2])
+    assert any(c[3] != 0.0 for c in reports[0][0])
+
+
 def test_gap_tolerance_without_an_interval_checks_the_gap_at_every_check(drot):
     P = drot_inputs.random_problem(200, 300, seed=3300, reg_kind=1, lam=0.5)
     solver = drot.Solver(P.m, P.n, check_every=10)

@@ -116,6 +116,26 @@ def test_cold_start_of_a_large_sparse_problem_moves_to_the_lean_sweep(planlib):
     assert set(t.col("mode")) == {0}
 
 
+def test_gap_pass_goes_lean_once_bounds_and_flags_describe_the_plan(planlib):
+    # stretch ends of the cold start above: no bounds after the first sweeps of a call; row-segment sums serve as
+    # flags after the 8-wave sweeps, the line flags after lean sweeps; never on paths that do not screen
+    t = trace(planlib, 20000, 20000, 300, reg_kind=1, checking=1, check_every=100, densities=(0.9, 0.6, 0.2, 0.02))
+    flags = t.col("flags")
+    ends = {i + 1: f for i, f in enumerate(flags) if f & 1}
+    assert all(f & 8 for f in ends.values())  # (bounds exist from sweep 2 on)
+    assert not ends[16] & 16 and not ends[96] & 16 and ends[100] & 16 and ends[300] & 16
+    t = trace(planlib, 1000, 1000, 200, reg_kind=1, checking=1, check_every=100)
+    assert not any(f & 8 for f in t.col("flags"))
+    t = trace(planlib, 20000, 20000, 200, reg_kind=1, checking=1, check_every=100, from_points=1)
+    assert not any(f & 8 for f in t.col("flags"))
+    t = trace(planlib, 5000, 5000, 200, reg_kind=2, slab_k=4, nruns=10, checking=1, check_every=100)
+    assert not any(f & 8 for f in t.col("flags"))
+    # even/odd pairs: the sums of a plain sweep at the stretch end still describe X, the bounds are those of the
+    # last refresh
+    t = trace(planlib, 20000, 20000, 64, reg_kind=1, checking=0, skip_unchanged=0)
+    assert not any(f & 8 for f in t.col("flags"))  # (nothing recorded bounds)
+
+
 def test_dense_plans_switch_to_the_even_odd_pairs_and_back(planlib):
     t = trace(planlib, 2300, 1500, 90, reg_kind=1, checking=0, check_every=10, screening=1, densities=(0.95,))
     kinds = t.col("kind")
