@@ -137,7 +137,7 @@ def main() -> int:
             total += m
         return nz / total
 
-    def sweep_bytes(rec, x_before, line_frac):
+    def sweep_bytes(rec, x_before, line_frac, skipping=None):
         """Algorithmic bytes of one profiled sweep: what it must move for the plan at hand.
 
         C on the fraction of its row segments the kernel read (counted by the kernel); X read on the row
@@ -148,8 +148,10 @@ def main() -> int:
         """
         kind, c, x_after = rec.kind, rec.c_fraction, rec.x_fraction
         mn = float(m) * n
+        if skipping is None:
+            skipping = args.skip_unchanged != 0
         if kind in (0, 1, 3):
-            if kind == 0 and P.reg_kind == 2 and args.skip_unchanged != 0:
+            if kind == 0 and P.reg_kind == 2 and skipping:
                 # group-resident group lasso: all of C; of X the nonzero 128-byte lines; two sums per line
                 return (4.0 + 8.0 * line_frac) * mn + 8.0 * m * ((n + 31) // 32) + 4.0 * n * max(1, P.num_classes)
             return 12.0 * mn
@@ -276,7 +278,7 @@ def main() -> int:
         for r in recs:
             e = kernels.setdefault(r.kind, {"ms": 0.0, "bytes": 0.0, "n": 0})
             e["ms"] += r.ms
-            e["bytes"] += sweep_bytes(r, x_before, line_frac)
+            e["bytes"] += sweep_bytes(r, x_before, line_frac, options.get("skip_unchanged", args.skip_unchanged) != 0)
             e["n"] += 1
             x_before = r.x_fraction
         ks = []
