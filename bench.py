@@ -285,7 +285,8 @@ def main() -> int:
         for kind in sorted(kernels):
             e = kernels[kind]
             gbs = e["bytes"] / (e["ms"] * 1e-3) / 1e9
-            ks.append({"kernel": KERNEL_NAMES[kind], "kernel_ms": round(e["ms"] / e["n"], 5), "launches_timed": e["n"],
+            name = "gl_slab_kernel / group-lasso sweep" if (kind == 0 and P.reg_kind == 2) else KERNEL_NAMES[kind]
+            ks.append({"kernel": name, "kernel_ms": round(e["ms"] / e["n"], 5), "launches_timed": e["n"],
                        "algorithmic_bytes": e["bytes"] / e["n"], "achieved": round(gbs, 1), "unit": "GB/s",
                        "frac": round(gbs / HBM_PEAK_GBS, 4), "bound": "hbm", "peak": HBM_PEAK_GBS, "traffic": None})
         log(f"{label}: {STEADY_STEPS / dt:.1f} it/s, {dt / STEADY_STEPS * 1e3:.4f} ms/iteration; " +
