@@ -115,6 +115,8 @@ struct drot_handle_s {
   float *rowpart = nullptr, *colpart = nullptr, *tilesum = nullptr, *gap_part = nullptr;
   size_t rowpart_half = 0, colpart_half = 0, tilesum_half = 0;
   float *mprime = nullptr, *varphi0 = nullptr;  // screened sweep: per-row-segment bounds and the epoch's varphi
+  float* mprime2 = nullptr;                     //   second largest and the column of the largest
+  unsigned char* jstar = nullptr;
   int* screen_ctl = nullptr;        // control words of the lean sweep's refresh schedule
   unsigned char* xlines = nullptr;  // [nseg][m] nonzero 128-byte lines of every row segment of X (lean sweep)
   int* wg_reads = nullptr;          // per-workgroup read counts of the lean sweep
@@ -179,8 +181,8 @@ int grow_buffer(T** buf, size_t* len, size_t need, hipStream_t stream) {
 }
 
 void free_all(drot_handle h) {
-  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf, h->mprime, h->varphi0,
-                    h->cpad, h->xpad, h->ptbuf, h->gpart};
+  float* fbufs[] = {h->phi, h->varphi, h->rowpart, h->colpart, h->tilesum, h->gap_part, h->gbuf, h->mprime, h->mprime2,
+                    h->varphi0, h->cpad, h->xpad, h->ptbuf, h->gpart};
   double* dbufs[] = {h->a, h->b, h->theta, h->sum_p, h->r, h->s, h->part, h->resid, h->prof_counts};
   int* ibufs[] = {h->done, h->runbuf, h->chunkbuf, h->wave_reads, h->screen_ctl, h->wg_reads};
   for (float* b : fbufs) (void)hipFree(b);
@@ -188,6 +190,7 @@ void free_all(drot_handle h) {
   for (int* b : ibufs) (void)hipFree(b);
   (void)hipFree(h->status);
   (void)hipFree(h->xlines);
+  (void)hipFree(h->jstar);
   if (h->host_status) (void)hipHostFree(h->host_status);
   for (auto& e : h->ev)
     if (e) (void)hipEventDestroy(e);
@@ -328,14 +331,15 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
       break;
     }
     case plan::kPoints:
-      if (Q.first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
-      else if (Q.refresh && nt) hipLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
-      else if (Q.refresh) hipLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
-      else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
-      else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->varphi0);
+      if (Q.first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh && nt) hipLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh) hipLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
       break;
     case plan::kPointsLean: {
-      const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads, nullptr, h->xlines};
+      const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads, nullptr, h->xlines,
+                          h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 pgrid(S.nseg, ceil_div(m, kStripRows));
       if (nt) hipLaunchKernelGGL((lean_points_kernel<true>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
       else hipLaunchKernelGGL((lean_points_kernel<false>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
@@ -387,7 +391,7 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
     }
     case plan::kScreened8: {
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, timed ? h->wave_reads : nullptr, h->varphi0,
-                          h->screen_ctl, h->wg_reads, nullptr, h->xlines};
+                          h->screen_ctl, h->wg_reads, nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 sgrid(S.nseg, S.ntr_tall), sblock(64 * kScreenWaves);
       if (Q.refresh) {
         if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, A, SC);
@@ -400,7 +404,7 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
     }
     case plan::kLean: {
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads,
-                          Q.lines_in ? h->xlines : nullptr, h->xlines};
+                          Q.lines_in ? h->xlines : nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 lgrid(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), lblock(64 * kLeanWaves);
       if (nt) hipLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, A, SC, S.ntr_tall);
       else hipLaunchKernelGGL((screened_lean_kernel<false>), lgrid, lblock, 0, stream, A, SC, S.ntr_tall);
@@ -465,7 +469,7 @@ void enqueue_gap(Solve& Z, const int* guard, bool flags_current) {
                    Z.PT, guard};
   const plan::GapPass pass = flags_current ? plan::gap_pass(S, Z.P, Z.T) : plan::kGapDense;
   if (pass != plan::kGapDense) {
-    const GapLeanArgs GL{GA, h->mprime, h->varphi0, pass == plan::kGapLeanLines ? h->xlines : nullptr,
+    const GapLeanArgs GL{GA, h->mprime, h->mprime2, h->jstar, h->varphi0, pass == plan::kGapLeanLines ? h->xlines : nullptr,
                          Z.rowp(Z.T.k_base + Z.T.k), Z.SA.n_mem, S.ntr_tall, S.ntr};
     hipLaunchKernelGGL(gap_lean_kernel, dim3(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), dim3(64 * kLeanWaves), 0, stream, GL);
   } else {
@@ -936,6 +940,8 @@ size_t carve_static(drot_handle_s& H, unsigned char* base) {
   take(&H.colpart, 2 * H.colpart_half);
   take(&H.tilesum, 2 * H.tilesum_half);
   take(&H.mprime, nseg * M);
+  take(&H.mprime2, nseg * M);
+  take(&H.jstar, nseg * M);
   take(&H.varphi0, nseg * kSegCols);
   take(&H.screen_ctl, (size_t)kCtlWords);
   take(&H.xlines, nseg * M);
@@ -1056,6 +1062,8 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->colpart, 2 * h->colpart_half));
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
   take(dev_alloc(&h->mprime, nseg * (size_t)max_m));
+  take(dev_alloc(&h->mprime2, nseg * (size_t)max_m));
+  take(dev_alloc(&h->jstar, nseg * (size_t)max_m));
   take(dev_alloc(&h->varphi0, nseg * kSegCols));
   take(dev_alloc(&h->screen_ctl, (size_t)kCtlWords));
   take(dev_alloc(&h->xlines, nseg * (size_t)max_m));

@@ -99,7 +99,9 @@ __global__ __launch_bounds__(kBlock) void gap_kernel(GapArgs A) {
 // ------------------------------------------------------------------------------------------
 struct GapLeanArgs {
   GapArgs G;
-  const float* mprime;           // [nseg][m] bounds of the epoch
+  const float* mprime;           // [nseg][m] bounds of the epoch: M,
+  const float* mprime2;          //   M2
+  const unsigned char* jstar;    //   and j*
   const float* varphi0;          // the epoch's varphi (padded)
   const unsigned char* lines;    // [nseg][m] nonzero 128-byte lines of every row segment of X, or null
   const float* rowsums;          // [nseg][m] row-segment sums of X (used when lines is null)
@@ -120,20 +122,21 @@ __device__ __forceinline__ void gap_lean_body(const GapLeanArgs& L, int lane, in
   const size_t ridx = (size_t)seg * A.m + r0 + lane;
   const f4v vp = load_varphi_padded(A.varphi, j0);
   const f4v vp0 = load_varphi_padded(L.varphi0, j0);
-  float ph = kMaskedOut, mpr = 0.f;
-  unsigned lines = 0;
+  float ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f;
+  unsigned lines = 0, js = 0;
   if (lane < nrows) {
     ph = A.phi[r0 + lane];
     mpr = L.mprime[ridx];
+    mpr2 = L.mprime2[ridx];
+    js = L.jstar[ridx];
     if (L.lines) lines = L.lines[ridx];
     else lines = fbits(L.rowsums[ridx]) != 0 ? 0xffu : 0u;
   }
-  const float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  const f4v dv = vp - vp0;
+  const float d = fmaxf(fmaxf(dv.x, dv.y), fmaxf(dv.z, dv.w));
   const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
   const float delta = wave_max(d), mag = wave_max(a);
-  const float bound = (mpr + delta) + ph;  // (the certificate of screened_body)
-  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
-  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool below = certified_zero(mpr, mpr2, js, dv, delta, mag, ph);  // (the certificate of screened_body)
   const bool certified = lane >= nrows || (lines == 0 && below);
   unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
   const unsigned myline = (unsigned)lane >> 3;

@@ -52,11 +52,14 @@ __global__ void pack_points_kernel(const float* __restrict__ pts, int rows, int 
 
 constexpr int kDotPitch = kSegCols + 4;  // LDS row pitch of the inner-product tile (keeps rows 16-byte aligned)
 
-// REFRESH: the sweep also records, per row segment, M = max_j (varphi_j - rho C_ij) and stores its varphi as
-// the epoch's varphi0: the bounds the screened sweep below certifies zero row segments with (same
-// definition and use as in the stored-cost screening).  mprime: [nseg][m]; varphi0: padded like varphi.
+// REFRESH: the sweep also records, per row segment, the largest of varphi_j - rho C_ij, a column that attains
+// it and the largest of the others, and stores its varphi as the epoch's varphi0: the bounds the screened sweep
+// below certifies zero row segments with (same definition and use as in the stored-cost screening).
+// mprime, mprime2, jstar: [nseg][m]; varphi0: padded like varphi.
 template <bool FIRST, bool NT, bool REFRESH = false>
 __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArgs A, PointArgs Pt, float* __restrict__ mprime,
+                                                                        float* __restrict__ mprime2,
+                                                                        unsigned char* __restrict__ jstar,
                                                                         float* __restrict__ varphi0) {
   if (*A.done) return;
   __shared__ float dots[kTileRows][kDotPitch];
@@ -141,7 +144,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
   if (nrows > 0) {
     const float rho = A.rho, scale = A.scale, cs = Pt.cost_scale;
-    float rowkeep = 0.f, mkeep = 0.f;
+    float rowkeep = 0.f, mkeep = 0.f, m2keep = 0.f;
+    int jkeep = 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (u < nrows) {
@@ -164,16 +168,23 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
         if (REFRESH) {  // (columns past n carry the mask value in vp: they never win the maximum)
-          const float mx = fmaxf(fmaxf(fmaf(-rho, c.x, vp.x), fmaf(-rho, c.y, vp.y)),
-                                 fmaxf(fmaf(-rho, c.z, vp.z), fmaf(-rho, c.w, vp.w)));
-          const float mm = wave_max(mx);
+          const f4v t = {fmaf(-rho, c.x, vp.x), fmaf(-rho, c.y, vp.y), fmaf(-rho, c.z, vp.z), fmaf(-rho, c.w, vp.w)};
+          float mm, mm2;
+          int jj;
+          segment_top2(t, lane, mm, jj, mm2);
           mkeep = (lane == u) ? mm : mkeep;
+          m2keep = (lane == u) ? mm2 : m2keep;
+          jkeep = (lane == u) ? jj : jkeep;
         }
       }
     }
     if (lane < nrows) {
       A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
-      if (REFRESH) mprime[(size_t)seg * A.m + r0 + lane] = mkeep;
+      if (REFRESH) {
+        mprime[(size_t)seg * A.m + r0 + lane] = mkeep;
+        mprime2[(size_t)seg * A.m + r0 + lane] = m2keep;
+        jstar[(size_t)seg * A.m + r0 + lane] = (unsigned char)jkeep;
+      }
     }
   }
   if (REFRESH && tr == 0 && wave == 0) *reinterpret_cast<f4u*>(varphi0 + j0) = vp;  // (past n both hold the mask value)
@@ -242,20 +253,22 @@ __global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs
   const f4v vp = load_varphi_padded(A.varphi, j0);
   const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
   const f4v ysq = load4(Pt.xt_sq + j0, nvalid);
-  float prev = 0.f, ph = kMaskedOut, mpr = 0.f, xsq_lane = 0.f;
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f, xsq_lane = 0.f;
+  unsigned js = 0;
   const size_t ridx = (size_t)seg * A.m + r0 + lane;
   if (lane < nrows) {
     prev = A.rowpart_prev[ridx];
     ph = A.phi[r0 + lane];
     mpr = SC.mprime_in[ridx];
+    mpr2 = SC.m2_in[ridx];
+    js = SC.jstar_in[ridx];
     xsq_lane = Pt.xs_sq[r0 + lane];
   }
-  const float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  const f4v dv = vp - vp0;
+  const float d = fmaxf(fmaxf(dv.x, dv.y), fmaxf(dv.z, dv.w));
   const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
   const float delta = wave_max(d), mag = wave_max(a);
-  const float bound = (mpr + delta) + ph;  // (the certificate of screened_body)
-  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
-  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool below = certified_zero(mpr, mpr2, js, dv, delta, mag, ph);  // (the certificate of screened_body)
   const bool certified = lane >= nrows || (fbits(prev) == 0 && below);
   if (stop) return;  // (the flag arrived with the loads above; nothing has been stored yet)
   const unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);

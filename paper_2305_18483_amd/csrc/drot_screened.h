@@ -4,20 +4,25 @@
 // ------------------------------------------------------------------------------------------
 // Screened sweep (large sparse problems).  On top of skipping the all-zero row segments of X, most
 // of C need not be read either: a row segment with x = 0 comes out as zero again whenever
-// phi_i + varphi_j - rho C_ij <= 0 for its 256 columns, and that can be certified from one number.
-// A "refresh" sweep, which reads all of C, records for every row segment
-//     M_is = max_j ( varphi0_j - rho C_ij )            (varphi0 = the varphi of that sweep).
-// Later sweeps form, per column segment, delta_s = max_j (varphi_j - varphi0_j) and, per row,
-//     S = M_is + delta_s + phi_i  >=  max_j ( phi_i + varphi_j - rho C_ij ).
+// phi_i + varphi_j - rho C_ij <= 0 for its 256 columns, and that can be certified from three numbers.
+// A "refresh" sweep, which reads all of C, records for every row segment, with t_j = varphi0_j - rho C_ij
+// (varphi0 = the varphi of that sweep),
+//     M  = max_j t_j,   j* = a column that attains it,   M2 = max_{j != j*} t_j.
+// Later sweeps form, per column segment, the drifts d_j = varphi_j - varphi0_j and delta = max_j d_j.
+// Column j* has moved by exactly d_j*, every other column by at most delta, so
+//     max_j ( phi_i + varphi_j - rho C_ij )  <=  max( M + d_j*, M2 + delta ) + phi_i  =:  S.
 // If S plus a rounding margin is <= 0 and the segment of X is zero, the segment stays zero: its C is
 // not read, nothing is computed, its row sum is 0.  The result is the one the plain sweep would
-// produce (the margin dominates the handful of fp32 roundings between the two evaluations).  As
-// varphi drifts away from varphi0 fewer segments certify, so the bounds are renewed now and then: on
-// the host's schedule while this kernel is in use, on the device's own in the lean kernel below.
+// produce (the margin dominates the handful of fp32 roundings between the two evaluations).  The
+// row's own maximiser is what comes close to zero first, and it is tracked exactly; the second
+// largest lies far enough below it, as a rule, for the cruder term to stay harmless ten times longer
+// than M + delta alone would.  Still, as varphi drifts away from varphi0 fewer segments certify, so the
+// bounds are renewed now and then: on the host's schedule while this kernel is in use, on the
+// device's own in the lean kernel below.
 // Tiles: 8 waves x 8 rows x 256 columns, as the unscreened sweep for sparse plans.
 // ------------------------------------------------------------------------------------------
 struct ScreenArgs {
-  const float* mprime_in;   // [nseg][m] M_is of the current epoch (screening sweeps)
+  const float* mprime_in;   // [nseg][m] M of the current epoch (screening sweeps)
   float* mprime_out;        // [nseg][m] written by a refresh sweep
   const float* varphi0;     // [n] varphi of the epoch
   int* wave_reads;          // 8-wave tiles, profiling only (else null): [workgroup][wave] row segments of C this wave read
@@ -28,7 +33,49 @@ struct ScreenArgs {
   // lean sweep only: which of the eight 128-byte lines of a row segment of X hold a nonzero
   const unsigned char* lines_in;  // [nseg][m] as left by the previous sweep if that was a lean one, else null
   unsigned char* lines_out;       // [nseg][m]
+  // the rest of the bounds: M2 and j* (column within the segment), read and written like mprime
+  const float* m2_in;
+  float* m2_out;
+  const unsigned char* jstar_in;
+  unsigned char* jstar_out;
 };
+
+// What a refresh records for one row segment from the wave's 256 values t (four per lane): the largest, a
+// column that attains it (0 .. 255), and the largest of the others.  All three wave-uniform.
+__device__ __forceinline__ void segment_top2(f4v t, int lane, float& M, int& jstar, float& M2) {
+  // within the lane: largest, its position, largest of the other three
+  const float hi01 = fmaxf(t.x, t.y), lo01 = fminf(t.x, t.y), hi23 = fmaxf(t.z, t.w), lo23 = fminf(t.z, t.w);
+  const float m1 = fmaxf(hi01, hi23);
+  const int a = m1 == t.x ? 0 : m1 == t.y ? 1 : m1 == t.z ? 2 : 3;
+  const float m2l = a < 2 ? fmaxf(lo01, hi23) : fmaxf(hi01, lo23);
+  M = wave_max(m1);
+  const unsigned long long hit = __builtin_amdgcn_ballot_w64(m1 == M);
+  const int L = hit ? (int)__builtin_ctzll(hit) : 0;
+  jstar = L * 4 + __builtin_amdgcn_readlane(a, L);
+  M2 = wave_max(lane == L ? m2l : m1);  // (a tie between lanes leaves M2 = M)
+}
+
+// The certificate, evaluated by lane l for row l from its record (m1, m2, j) and phi_l; dv: this lane's
+// four drifts; delta, mag: their maximum over the wave and the largest |varphi_j| of the segment.  Each of
+// the two candidates carries its own margin, 8 units in the last place of its terms (2^-21), which covers
+// the roundings of the record, of the drifts, of the sums here and of the sweep's own evaluation (each at
+// most half a unit of a term no larger than these); so does the last sum.
+__device__ __forceinline__ bool certified_zero(float m1, float m2, unsigned j, f4v dv, float delta, float mag, float ph) {
+  constexpr float kEps = 4.76837158e-7f;  // 2^-21
+  // the drift of the row's own maximiser: lane j / 4, component j % 4
+  const int src = (int)(j >> 2) << 2;
+  const float d0 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, fbits(dv.x)));
+  const float d1 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, fbits(dv.y)));
+  const float d2 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, fbits(dv.z)));
+  const float d3 = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, fbits(dv.w)));
+  const unsigned c = j & 3u;
+  const float dstar = c == 0 ? d0 : c == 1 ? d1 : c == 2 ? d2 : d3;
+  if (m1 == -INFINITY) return true;  // every pair of the segment is forbidden
+  const float s1 = (m1 + dstar) + kEps * (fabsf(m1) + fabsf(dstar));
+  const float s2 = m2 == -INFINITY ? -INFINITY : (m2 + delta) + kEps * (fabsf(m2) + fabsf(delta));
+  const float bound = fmaxf(s1, s2) + ph;
+  return bound + kEps * (fabsf(ph) + mag + fabsf(bound)) <= 0.f;
+}
 
 // Control words of the lean sweep's own refresh schedule (device memory, updated by
 // reduce_update_kernel after every lean sweep): the classic rent-or-buy rule.  Reading the C of a
@@ -57,28 +104,29 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   const float rho = A.rho, scale = A.scale;
   const size_t ridx = (size_t)seg * A.m + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
 
-  // lane u: old sum, phi and M of row r0 + u
+  // lane u: old sum, phi and the bounds of row r0 + u
   const f4v vp = load_varphi_padded(A.varphi, j0);
-  float prev = 0.f, ph = kMaskedOut, mpr = 0.f;
+  float prev = 0.f, ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f;
+  unsigned js = 0;
   if (lane < nrows) {
     prev = A.rowpart_prev ? A.rowpart_prev[ridx] : 1.f;
     ph = A.phi[r0 + lane];
-    if (!REFRESH) mpr = SC.mprime_in[ridx];
+    if (!REFRESH) {
+      mpr = SC.mprime_in[ridx];
+      mpr2 = SC.m2_in[ridx];
+      js = SC.jstar_in[ridx];
+    }
   }
   bool certified = lane >= nrows;  // rows past the end of the matrix: nothing to do
   if (!REFRESH) {
     const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
     // drift of varphi since the epoch and its magnitude over this wave's columns (columns past n: both
     // carry the same mask value, their difference is 0; they are left out of the magnitude)
-    float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+    const f4v dv = vp - vp0;
+    const float d = fmaxf(fmaxf(dv.x, dv.y), fmaxf(dv.z, dv.w));
     const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
     const float delta = wave_max(d), mag = wave_max(a);
-    // S bounds every phi_i + varphi_j - rho C_ij of the row segment from above; the margin, 8 units in
-    // the last place of the largest term, covers the roundings of M, of delta, of this sum and of the
-    // sweep's own evaluation (each at most half a unit of a term no larger than these)
-    const float bound = (mpr + delta) + ph;
-    const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);  // 2^-21
-    const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;  // (-inf: every pair of the segment is forbidden)
+    const bool below = certified_zero(mpr, mpr2, js, dv, delta, mag, ph);
     certified = certified || (fbits(prev) == 0 && below);
   }
   const unsigned skipmask = (unsigned)__builtin_amdgcn_ballot_w64(certified) & 0xffu;
@@ -112,7 +160,8 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   }
 
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
-  float rowkeep = 0.f, mkeep = 0.f, wave_total = 0.f;
+  float rowkeep = 0.f, mkeep = 0.f, m2keep = 0.f, wave_total = 0.f;
+  int jkeep = 0;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (!((skipmask >> u) & 1)) {
@@ -124,17 +173,24 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
       const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
       rowkeep = (lane == u) ? tot : rowkeep;
       wave_total += tot;
-      if (REFRESH) {
-        const float mx = fmaxf(fmaxf(fmaf(-rho, c[u].x, vp.x), fmaf(-rho, c[u].y, vp.y)),
-                               fmaxf(fmaf(-rho, c[u].z, vp.z), fmaf(-rho, c[u].w, vp.w)));
-        const float mm = wave_max(mx);
+      if (REFRESH) {  // (columns past n carry the mask value in vp: they never win)
+        const f4v t = {fmaf(-rho, c[u].x, vp.x), fmaf(-rho, c[u].y, vp.y), fmaf(-rho, c[u].z, vp.z), fmaf(-rho, c[u].w, vp.w)};
+        float mm, mm2;
+        int jj;
+        segment_top2(t, lane, mm, jj, mm2);
         mkeep = (lane == u) ? mm : mkeep;
+        m2keep = (lane == u) ? mm2 : m2keep;
+        jkeep = (lane == u) ? jj : jkeep;
       }
     }
   }
   if (lane < nrows) {
     A.rowpart[ridx] = rowkeep;
-    if (REFRESH) SC.mprime_out[ridx] = mkeep;
+    if (REFRESH) {
+      SC.mprime_out[ridx] = mkeep;
+      SC.m2_out[ridx] = m2keep;
+      SC.jstar_out[ridx] = (unsigned char)jkeep;
+    }
   }
   if (SC.wave_reads && lane == 0)
     SC.wave_reads[(tr * gridDim.x + seg) * NW + wave] = __builtin_popcount(~skipmask & 0xffu);
@@ -186,7 +242,8 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
 
   const f4v vp = load_varphi_padded(A.varphi, j0);
   const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
-  float ph = kMaskedOut, mpr = 0.f;
+  float ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f;
+  unsigned js = 0;
   // lane u: the lines of row u's segment of X that hold a nonzero (bit g: columns 32g .. 32g+31).  From
   // the flags the previous lean sweep left; after any other sweep from the row sums (nonzero sum:
   // any line may hold something)
@@ -194,24 +251,26 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   if (lane < nrows) {
     ph = A.phi[r0 + lane];
     mpr = SC.mprime_in[ridx];
+    mpr2 = SC.m2_in[ridx];
+    js = SC.jstar_in[ridx];
     if (SC.lines_in) oldlines = SC.lines_in[ridx];
     else oldlines = (A.rowpart_prev == nullptr || fbits(A.rowpart_prev[ridx]) != 0) ? 0xffu : 0u;
   }
   // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
   // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
-  float d = fmaxf(fmaxf(vp.x - vp0.x, vp.y - vp0.y), fmaxf(vp.z - vp0.z, vp.w - vp0.w));
+  const f4v dv = vp - vp0;
+  const float d = fmaxf(fmaxf(dv.x, dv.y), fmaxf(dv.z, dv.w));
   const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
   const float delta = wave_max(d), mag = wave_max(a);
-  const float bound = (mpr + delta) + ph;  // (the same certificate, to the letter, as in screened_body)
-  const float margin = 4.76837158e-7f * (fabsf(mpr) + fabsf(delta) + fabsf(ph) + mag);
-  const bool below = (bound + margin <= 0.f) || mpr == -INFINITY;
+  const bool below = certified_zero(mpr, mpr2, js, dv, delta, mag, ph);  // (the same certificate as in screened_body)
   const bool certified = lane >= nrows || (!renew && oldlines == 0 && below);
   tile_total = 0.f;
   reads = 0;
   if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
   unsigned long long todo = ~__builtin_amdgcn_ballot_w64(certified);
   reads = __builtin_popcountll(todo);
-  float mkeep = 0.f;  // renew: lane u keeps the new bound of row u
+  float mkeep = 0.f, m2keep = 0.f;  // renew: lane u keeps the new bounds of row u
+  int jkeep = 0;
   unsigned newlines = 0;  // lane u keeps the nonzero lines of the new row u
   const unsigned myline = (unsigned)lane >> 3;  // 8 lanes x 16 bytes: one 128-byte line
 
@@ -268,10 +327,13 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
         rowkeep = (lane == u) ? tot : rowkeep;
         group_tot += tot;
         if (renew) {
-          const float mx = fmaxf(fmaxf(fmaf(-rho, c[b].x, vp.x), fmaf(-rho, c[b].y, vp.y)),
-                                 fmaxf(fmaf(-rho, c[b].z, vp.z), fmaf(-rho, c[b].w, vp.w)));
-          const float mm = wave_max(mx);
+          const f4v t = {fmaf(-rho, c[b].x, vp.x), fmaf(-rho, c[b].y, vp.y), fmaf(-rho, c[b].z, vp.z), fmaf(-rho, c[b].w, vp.w)};
+          float mm, mm2;
+          int jj;
+          segment_top2(t, lane, mm, jj, mm2);
           mkeep = (lane == u) ? mm : mkeep;
+          m2keep = (lane == u) ? mm2 : m2keep;
+          jkeep = (lane == u) ? jj : jkeep;
         }
       }
     }
@@ -285,7 +347,11 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
     SC.lines_out[ridx] = (unsigned char)newlines;
   }
   if (renew) {
-    if (lane < nrows) SC.mprime_out[ridx] = mkeep;
+    if (lane < nrows) {
+      SC.mprime_out[ridx] = mkeep;
+      SC.m2_out[ridx] = m2keep;
+      SC.jstar_out[ridx] = (unsigned char)jkeep;
+    }
     if (tr == 0) {  // the first tile of the column segment also stores the epoch's varphi
       *reinterpret_cast<f4u*>(SC.varphi0_out + j0) = vp;  // (past n both buffers hold the mask value)
     }

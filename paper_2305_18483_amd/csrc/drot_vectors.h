@@ -119,7 +119,8 @@ struct ReduceArgs {
 
 constexpr int kReduceThreads = 1024;
 
-// One of the 16 shares of a column's partial sums when G consecutive rows are added in fp32 first.
+// One of the 16 shares of a column's partial sums when G consecutive rows are added in fp32 first.  share, nparts
+// and ntr are wave-uniform; idx is the lane's entry, already clamped to the last one that exists.
 template <int G>
 __device__ __forceinline__ double gather_grouped(const float* __restrict__ part, int share, int nparts, int ntr, int idx, int len) {
   constexpr int kStride = 16, kGroups = 32 / G > 1 ? 32 / G / 2 : 1;  // (16 loads in flight per batch)
@@ -130,8 +131,9 @@ __device__ __forceinline__ double gather_grouped(const float* __restrict__ part,
     for (int b = 0; b < kGroups; ++b)
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const int k = (k0 + b * kStride) * G + g;
-        v[b][g] = (idx < len && k < ntr) ? part[(size_t)k * len + idx] : 0.f;
+        const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used)
+        const float w = (part + (size_t)min(k, ntr - 1) * len)[idx];
+        v[b][g] = k < ntr ? w : 0.f;
       }
 #pragma unroll
     for (int b = 0; b < kGroups; ++b)
@@ -148,40 +150,48 @@ __device__ __forceinline__ double gather_grouped(const float* __restrict__ part,
 // First part: the partial sums of 64 entries split 16 ways (share c takes the partials c, c + 16,
 // ...), each share added up in order.  NW waves: wave w forms the shares w, w + NW, ... of entry
 // idx and leaves them in red[share][lane]; nz_out counts the nonzero partials this wave saw.
+// Which partial a load fetches depends on the wave and the workgroup only, so the row of the
+// partials is a scalar base address and the lane adds its entry: no per-lane address arithmetic.
+// Lanes past the last entry read the last entry (their results are never stored, their nonzero
+// counts masked out).
 template <int NW>
 __device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, int& nz_out) {
   static_assert(16 % NW == 0, "the 16 shares are dealt out to the waves");
   const int t = threadIdx.x;
-  const int sub = t >> 6, l = t & 63;
+  const int sub = __builtin_amdgcn_readfirstlane(t >> 6), l = t & 63;
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
   const int len = rows ? A.m : A.n;
+  const int idc = min(idx, len - 1);
+  const unsigned long long live = __builtin_amdgcn_ballot_w64(idx < len);
   const bool grouped = !rows && A.cgroup > 1;
   const int nparts = rows ? A.nseg : grouped ? (A.ntr + A.cgroup - 1) / A.cgroup : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
   int nz = 0;
   constexpr int kStride = 16, kBatch = 8;
 #pragma unroll
-  for (int share = sub; share < 16; share += NW) {
+  for (int si = 0; si < 16 / NW; ++si) {
+    const int share = sub + si * NW;
     double acc = 0.0;
     // column sums stored per tile row: the rows G k .. G k + G - 1 are added first, in fp32 and in order, as the
     // workgroups of the lean sweeps do before they store (a row past the end adds +0).  G = 4: four 64-row tiles
     // (screened_lean_kernel); G = 8: the eight 32-row tiles of a 256-row strip (lean_points_kernel)
-    if (grouped && A.cgroup == kColGroup) acc = gather_grouped<kColGroup>(part, share, nparts, A.ntr, idx, len);
-    else if (grouped) acc = gather_grouped<kPointsColGroup>(part, share, nparts, A.ntr, idx, len);
+    if (grouped && A.cgroup == kColGroup) acc = gather_grouped<kColGroup>(part, share, nparts, A.ntr, idc, len);
+    else if (grouped) acc = gather_grouped<kPointsColGroup>(part, share, nparts, A.ntr, idc, len);
     for (int k0 = share; !grouped && k0 < nparts; k0 += kStride * kBatch) {  // (nparts and share are wave-uniform)
       // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
       // trip would wait for memory once per partial sum)
       float v[kBatch];
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
-        const int k = k0 + b * kStride;
-        v[b] = (idx < len && k < nparts) ? part[(size_t)k * len + idx] : 0.f;
+        const int k = k0 + b * kStride;  // (past the end: the last partial is fetched and not used; no branch, so that
+        const float w = (part + (size_t)min(k, nparts - 1) * len)[idc];  // the loads of all shares leave together)
+        v[b] = k < nparts ? w : 0.f;
       }
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
         if (k0 + b * kStride < nparts) acc += (double)v[b];
-        nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f));
+        nz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v[b] != 0.f) & live);
       }
     }
     red[share * 64 + l] = acc;
@@ -385,16 +395,18 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   const double ab_in = owner ? (rows ? U.a_in[idx] : U.b_in[idx]) : 0.0;
   const double theta = A.V.theta[U.par], sum_p = *A.V.sum_p;
   const float pq = reduce_entry_pq(A);
-  // the shares of the tile totals: batches of independent loads, added in index order
+  // the shares of the tile totals: batches of independent loads, added in index order.  Share v = 64 w + lane of
+  // accumulator s stands at entry U + lane with U wave-uniform: a scalar base address plus the lane
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6), ln = t & 63;
   double acc[kPerThread];
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
     acc[s] = 0.0;
-    const int v0 = t + s * 64 * NW;
+    const int u0 = 64 * wv + s * 64 * NW;
     if (T.tgroup == kColGroup) {
       constexpr int kGroups = 4;
       const int ngroups = ((T.tile_rows + kColGroup - 1) / kColGroup) * T.nseg;
-      for (int e0 = v0; e0 < ngroups; e0 += kShares * kGroups) {
+      for (int e0 = u0 + ln; e0 - ln < ngroups; e0 += kShares * kGroups) {
         float v[kGroups][kColGroup];
 #pragma unroll
         for (int b = 0; b < kGroups; ++b) {
@@ -412,12 +424,14 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
     } else {
       constexpr int kBatch = 8;
       const int ngroups = T.tile_rows * T.nseg;
-      for (int e0 = v0; e0 < ngroups; e0 += kShares * kBatch) {
+      for (int u = u0; u < ngroups; u += kShares * kBatch) {
         float v[kBatch];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
-          const int e = e0 + b * kShares;
-          v[b] = e < ngroups ? T.tilesum[e] : 0.f;
+          const int ub = u + b * kShares;
+          const int uc = min(ub, ngroups - 1);
+          const float w = (T.tilesum + uc)[min(ln, ngroups - 1 - uc)];
+          v[b] = ub + ln < ngroups ? w : 0.f;
         }
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) acc[s] += (double)v[b];
@@ -428,9 +442,8 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   reduce_gather<NW>(A, red, nz);
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc[s] += __shfl_xor(acc[s], off, 64);
-    if ((t & 63) == 0) eta_part[(t >> 6) + s * NW] = acc[s];
+    const double w = wave_sum_f64(acc[s]);
+    if (ln == 0) eta_part[wv + s * NW] = w;
   }
   if (keeper) {
 #pragma unroll
