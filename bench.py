@@ -160,8 +160,9 @@ def main() -> int:
         xb = x_after if x_before is None or x_before < 0 else x_before
         xw = max(xb, x_after)
         if kind == 7:
-            return 4.0 * c * mn + 8.0 * line_frac * mn + 10.0 * m * nseg + 4.0 * n * ((m + 255) // 256)
-        per_segment = 8.0 if kind == 4 else 12.0
+            # per row segment: the three parts of the bound (4 + 4 + 1 B), the line flags in and out, the new sum
+            return 4.0 * c * mn + 8.0 * line_frac * mn + 15.0 * m * nseg + 4.0 * n * ((m + 255) // 256)
+        per_segment = 8.0 if kind == 4 else 17.0  # (old and new sum; screened: also the three parts of the bound)
         return 4.0 * c * mn + 4.0 * (xb + xw) * mn + per_segment * m * nseg + 4.0 * n * ((m + 63) // 64)
 
     def measure(W, K, label):
@@ -216,7 +217,7 @@ def main() -> int:
         roof["other_kernels"] = [entries[k] for k in sorted(entries) if k != dominant]
         roof["bytes_model"] = ("per launch: 4 B x the row segments of C read (counted by the kernel) + X read on the row segments "
                                "nonzero before and written on those nonzero before or after (counted by the vector updates; lean "
-                               "kernel: the nonzero 128-byte lines of the final plan) + 8-12 B per row segment (sums, bound, line "
+                               "kernel: the nonzero 128-byte lines of the final plan) + 8-17 B per row segment (sums, bounds, line "
                                "flags) + column sums; dense sweeps 12 (8 without C) B per element; dense_model_gbs prices the "
                                "launch at 12 B per element")
         if line_frac:
@@ -335,10 +336,10 @@ def main() -> int:
             e = {"kernel": name, "kernel_ms": round(ms, 5), "launches_timed": len(sel)}
             if kind == 8:
                 formed = sum(r.c_fraction for r in sel) / len(sel)
-                # per row segment: old and new row sum, bound (12 B); the strip's column sums; X on its nonzero row
+                # per row segment: old and new row sum, the three parts of the bound (17 B); the strip's column sums; X on its nonzero row
                 # segments (read and written); the costs are not traffic; flops: blocks of 16 rows x 256 columns
                 xnz = sum(max(r.x_fraction, 0.0) for r in sel) / len(sel)
-                nbytes = 12.0 * m * nseg + 4.0 * n * ((m + 255) // 256) + 8.0 * xnz * m * n
+                nbytes = 17.0 * m * nseg + 4.0 * n * ((m + 255) // 256) + 8.0 * xnz * m * n
                 gbs = nbytes / (ms * 1e-3) / 1e9
                 e.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
@@ -466,7 +467,7 @@ def alignment(torch, drot, dev):
                     solver.set_skip_cost(-1)
                     solver.set_skip_unchanged(-1)
                 best = 0.0
-                for _ in range(3):  # (the best of three: these runs are a few milliseconds long)
+                for _ in range(5):  # (the best of five: the smallest of these runs are a few tens of milliseconds long)
                     solver.set_continue(False)
                     solver.solve(C, p, q, reg_kind=1, lam=1e-3, max_iters=200, X_out=X)
                     solver.set_continue(True)
@@ -484,7 +485,7 @@ def alignment(torch, drot, dev):
             rows.append({"n": n, "scheme": scheme, "its_per_s_n": round(a, 1), "its_per_s_n_minus_1": round(b, 1),
                          "slowdown_percent": round((a / b - 1.0) * 100.0, 2)})
             log(f"alignment {n} vs {n - 1} [{scheme}]: {a:.0f} vs {b:.0f} it/s ({(a / b - 1.0) * 100.0:+.2f} %)")
-    return {"note": f"{ALIGN_STEPS} iterations continuing a 200-iteration cold start (best of three), each call copying X out of "
+    return {"note": f"{ALIGN_STEPS} iterations continuing a 200-iteration cold start (best of five), each call copying X out of "
                     "the padded working copy when n % 32 != 0", "rows": rows}
 
 

@@ -113,9 +113,10 @@ int drot_destroy(drot_handle h);
  *       even/odd scheme (DROT_OPT_SKIP_COST) comes into play: when it starts depends on where the calls
  *       and their stretches of check_every iterations begin.  INVALID_ARG at the next solve if no solve
  *       has run or the sizes differ.  drot_info.iters counts the iterations of the call.
- *   DROT_OPT_PROFILE [0], 0/1: record HIP events on the solve's stream around every sweep launch (the
- *       first 256 of a solve) and count what the sweep read; see drot_get_profile.  Costs two event
- *       records and a few tiny kernels per iteration, so leave it off when timing a solve.
+ *   DROT_OPT_PROFILE [0], 0/1: take the start and the end of every sweep kernel (the first 256 of a solve),
+ *       as the hardware stamps them, through a pair of HIP events attached to the launch, and count what the
+ *       sweep read; see drot_get_profile.  Costs a few tiny kernels per iteration, so leave it off when
+ *       timing a solve.
  *
  * Which kernels run (tuning; the iterates do not depend on these unless stated)
  *   DROT_OPT_SKIP_UNCHANGED [-1 = on], -1/0/1: X >= 0, so a row segment (256 consecutive columns of a
@@ -126,11 +127,14 @@ int drot_destroy(drot_handle h);
  *       group-lasso sweep does the same with 128-byte lines, the sweep of drot_solve_points with row
  *       segments.  Same memory contents either way.  0 reads and stores everything.
  *   DROT_OPT_SCREENING [-1], -1 .. 100000: with the skipping on, sweeps over large sparse plans also leave
- *       out most reads of C.  Now and then a sweep records, per row segment, M = max_j (varphi_j - rho C_ij);
- *       until the next such sweep a row segment whose X is zero and whose bound M + max_j (drift of varphi_j
- *       since then) + phi_i, plus a margin for the fp32 roundings involved, is not positive is known to stay
- *       zero: nothing of it is read, computed or written.  The iterates are those of the unscreened sweeps,
- *       bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first, at most 256 apart; once the
+ *       out most reads of C.  Now and then a sweep records, per row segment, the largest of
+ *       varphi_j - rho C_ij, a column that attains it and the largest over the other columns; until the next
+ *       such sweep these bound phi_i + varphi_j - rho C_ij over the segment from above (the recorded column
+ *       moves by its own drift of varphi since then, the others by at most the largest drift), and a row
+ *       segment whose X is zero and whose bound, plus a margin for the fp32 roundings involved, is not
+ *       positive is known to stay zero: nothing of it is read, computed or written.  The iterates are those
+ *       of the unscreened sweeps, bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first,
+ *       at most 1024 apart; once the
  *       plan is known to be sparse the sweep itself decides, on the device, when the reads that weakened
  *       bounds cost it have added up to the price of new ones.  -1 screens problems of 11.5 million entries
  *       and more (smaller ones stream all of C from the caches just as fast), 1 every problem the skipping
@@ -205,8 +209,9 @@ int drot_get_checks(drot_handle h, drot_check* out, int capacity, int* count);
 
 /*
  * Sweep timings of the last solve in profile mode, in launch order (at most the first 256 sweeps).
- *   ms          duration of the sweep launch from HIP events on the solve's stream, less the reading of
- *               an empty event pair (the smallest of four recorded at the start of the solve)
+ *   ms          duration of the sweep kernel: from its start to its end as the hardware stamps them, read
+ *               through a pair of HIP events attached to the launch (the group-lasso sweep of three
+ *               launches: from the start of the first to the end of the last)
  *   kind        0 = read X and C, stored X (32-row tiles; also the group-lasso sweeps), 1 = also stored
  *               X - rho*C (first of an even/odd pair), 2 = read the shifted X and no C (second of a pair),
  *               3 = a launch of the resident kernel (its duration divided by the iterations it ran),

@@ -15,8 +15,8 @@
 // Data layout in HBM
 //   X, C        m x n fp32 row-major, pitch n, caller-owned
 //   phi/varphi  fp32, what the sweep reads;  a, b, theta, r, s: fp64 vectors of eq. (6)
-//   rowpart     [nseg][m]  fp32: row sums of every 256-column segment
-//   colpart     [ntr][n]   fp32: column sums of every 32-row tile
+//   rowpart     [nseg][mp] fp32: row sums of every 256-column segment (mp, np: m, n rounded up to 64)
+//   colpart     [ntr][np]  fp32: column sums of every 32-row tile
 //
 //   colpart     ... or of every 64-row tile (sweeps for sparse plans), or of four of them (lean sweep)
 //
@@ -26,6 +26,7 @@
 // without a GPU); this file holds the handle, the functions that enqueue what the plan says, the
 // host loop and the C ABI of include/drot.h.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdint>
@@ -63,20 +64,22 @@ static_assert(plan::kResidentMaxRows == kResidentMaxRows && plan::kResidentCols 
 static_assert(plan::kColGroup == kColGroup, "column-sum groups of the lean sweep");
 static_assert(plan::kStripRows == kStripRows && plan::kPointsColGroup == kPointsColGroup, "strips of the screened point-cloud sweep");
 
+// (e0, e1: events that take the start and the end of the kernel itself, as the hardware stamps them; null: none)
 template <bool FIRST, bool PRO>
-void launch_slab_k(int k, dim3 grid, hipStream_t stream, const SlabArgs& a, const FusedUpdateArgs& f) {
+void launch_slab_k(int k, dim3 grid, hipStream_t stream, hipEvent_t e0, hipEvent_t e1, const SlabArgs& a, const FusedUpdateArgs& f) {
   const dim3 block(kSlabThreads);
   switch (k) {
-    case 1: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 1, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
-    case 2: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 2, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
-    case 4: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 4, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
-    default: hipLaunchKernelGGL((gl_slab_kernel<FIRST, 8, kSlabLanes, PRO>), grid, block, 0, stream, a, f); break;
+    case 1: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 1, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
+    case 2: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 2, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
+    case 4: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 4, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
+    default: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 8, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
   }
 }
-void launch_slab(bool first, bool pro, int k, dim3 grid, hipStream_t stream, const SlabArgs& a, const FusedUpdateArgs& f) {
-  if (pro) launch_slab_k<false, true>(k, grid, stream, a, f);
-  else if (first) launch_slab_k<true, false>(k, grid, stream, a, f);
-  else launch_slab_k<false, false>(k, grid, stream, a, f);
+void launch_slab(bool first, bool pro, int k, dim3 grid, hipStream_t stream, hipEvent_t e0, hipEvent_t e1, const SlabArgs& a,
+                 const FusedUpdateArgs& f) {
+  if (pro) launch_slab_k<false, true>(k, grid, stream, e0, e1, a, f);
+  else if (first) launch_slab_k<true, false>(k, grid, stream, e0, e1, a, f);
+  else launch_slab_k<false, false>(k, grid, stream, e0, e1, a, f);
 }
 
 constexpr int kMaxProfiled = 256;   // sweeps timed per solve in profile mode
@@ -100,7 +103,6 @@ struct drot_handle_s {
   bool xpad_live = false;
   // sweep timing (profile mode): event pairs recorded on the solve's stream
   hipEvent_t prof_ev[2 * kMaxProfiled] = {};
-  hipEvent_t cal_ev[8] = {};  // four empty event pairs per profiled solve: what a pair costs without a kernel between
   int prof_count = 0;
   float prof_ms[kMaxProfiled] = {};   // per sweep, in launch order
   int prof_kind[kMaxProfiled] = {};
@@ -196,13 +198,11 @@ void free_all(drot_handle h) {
     if (e) (void)hipEventDestroy(e);
   for (auto& e : h->prof_ev)
     if (e) (void)hipEventDestroy(e);
-  for (auto& e : h->cal_ev)
-    if (e) (void)hipEventDestroy(e);
 }
 
 // Creates the events and counters of profile mode: everything or nothing.
 int enable_profile(drot_handle h) {
-  hipEvent_t made[2 * kMaxProfiled + 8] = {};
+  hipEvent_t made[2 * kMaxProfiled] = {};
   int nmade = 0;
   bool ok = true;
   auto make = [&](hipEvent_t& e) {
@@ -215,7 +215,6 @@ int enable_profile(drot_handle h) {
     made[nmade++] = e;
   };
   for (auto& e : h->prof_ev) make(e);
-  for (auto& e : h->cal_ev) make(e);
   int* wave_reads = nullptr;
   double* prof_counts = nullptr;
   int rc = ok ? DROT_OK : DROT_ERR_HIP;
@@ -233,7 +232,6 @@ int enable_profile(drot_handle h) {
         if (e == made[k]) e = nullptr;
     };
     for (auto& e : h->prof_ev) forget(e);
-    for (auto& e : h->cal_ev) forget(e);
     for (int k = 0; k < nmade; ++k) (void)hipEventDestroy(made[k]);
     (void)hipGetLastError();
     return rc;
@@ -305,7 +303,7 @@ FusedUpdateArgs fused_args(const Solve& Z, long long sw, int nseg, int ntr) {
 }
 
 // One sweep launch (S1-S4), as the plan describes it.
-void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
+void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed, hipEvent_t e0, hipEvent_t e1) {
   drot_handle h = Z.h;
   hipStream_t stream = Z.stream;
   const plan::Static& S = Z.S;
@@ -325,68 +323,69 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
       const ResidentArgs RS{Z.Xw, Z.Cw, Z.p, Z.q, Z.V, Z.a_buf(sw - 1), Z.b_buf(sw - 1), Z.a_buf(last), Z.b_buf(last),
                             (int)((sw - 1) & 1), (int)(last & 1), m, n, Z.ldx, Z.ldc, Z.rho, A.scale, Q.iters,
                             Q.first ? 1 : 0};
-      if (n <= 64) launch_resident<1>(RS, stream);
-      else if (n <= 128) launch_resident<2>(RS, stream);
-      else launch_resident<4>(RS, stream);
+      if (n <= 64) launch_resident<1>(RS, stream, e0, e1);
+      else if (n <= 128) launch_resident<2>(RS, stream, e0, e1);
+      else launch_resident<4>(RS, stream, e0, e1);
       break;
     }
     case plan::kPoints:
-      if (Q.first) hipLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (Q.refresh && nt) hipLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (Q.refresh) hipLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (nt) hipLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else hipLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      if (Q.first) hipExtLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh && nt) hipExtLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh) hipExtLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (nt) hipExtLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else hipExtLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
       break;
     case plan::kPointsLean: {
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads, nullptr, h->xlines,
                           h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 pgrid(S.nseg, ceil_div(m, kStripRows));
-      if (nt) hipLaunchKernelGGL((lean_points_kernel<true>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
-      else hipLaunchKernelGGL((lean_points_kernel<false>), pgrid, dim3(256), 0, stream, A, Z.PT, SC);
+      if (nt) hipExtLaunchKernelGGL((lean_points_kernel<true>), pgrid, dim3(256), 0, stream, e0, e1, 0, A, Z.PT, SC);
+      else hipExtLaunchKernelGGL((lean_points_kernel<false>), pgrid, dim3(256), 0, stream, e0, e1, 0, A, Z.PT, SC);
       break;
     }
     case plan::kSlab: {
       const SlabArgs SL{A, h->runbuf, h->runbuf + Z.P.nruns, Z.thr};
       const dim3 slab_grid(S.nstrips, Z.P.nruns > 0 ? Z.P.nruns : 1);
-      launch_slab(Q.first, Q.pro, Z.P.slab_k, slab_grid, stream, SL, fused_args(Z, sw, S.nstrips, Z.P.nruns));
+      launch_slab(Q.first, Q.pro, Z.P.slab_k, slab_grid, stream, e0, e1, SL, fused_args(Z, sw, S.nstrips, Z.P.nruns));
       break;
     }
     case plan::kTwoPass: {
       const GroupArgs G{A, Z.row_class, h->gbuf, Z.thr};
       const dim3 cgrid(S.nseg, ceil_div(Z.CK.nchunks, kWavesPerBlock));
       const dim3 fgrid(ceil_div(n, kBlock), Z.num_classes < 65535 ? Z.num_classes : 65535);
-      if (Q.first) hipLaunchKernelGGL(gl_norm_kernel<true>, cgrid, block, 0, stream, G, Z.CK);
-      else hipLaunchKernelGGL(gl_norm_kernel<false>, cgrid, block, 0, stream, G, Z.CK);
+      // (three launches: the start of the first and the end of the last are what is timed)
+      if (Q.first) hipExtLaunchKernelGGL(gl_norm_kernel<true>, cgrid, block, 0, stream, e0, nullptr, 0, G, Z.CK);
+      else hipExtLaunchKernelGGL(gl_norm_kernel<false>, cgrid, block, 0, stream, e0, nullptr, 0, G, Z.CK);
       hipLaunchKernelGGL(gl_norm_finish_kernel, fgrid, block, 0, stream, Z.CK, h->gbuf, n, Z.num_classes, (const int*)h->done);
-      if (Q.first) hipLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, G);
-      else hipLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, G);
+      if (Q.first) hipExtLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, nullptr, e1, 0, G);
+      else hipExtLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, nullptr, e1, 0, G);
       break;
     }
     case plan::kPro32: {
       // update sw-1 (from the sums of X_{sw-1} and the state of generation sw-2) rides along
       const FusedUpdateArgs F = fused_args(Z, sw, S.nseg, S.ntr);
-      if (nt) hipLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, A, F);
-      else hipLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, A, F);
+      if (nt) hipExtLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, F);
+      else hipExtLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, F);
       break;
     }
     case plan::kPlain32:
       if (Q.first) {
-        if (Q.mode == 1) hipLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, A, none);
-        else hipLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, A, none);
+        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        else hipExtLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
       } else if (nt) {
-        if (Q.mode == 1) hipLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, A, none);
-        else if (Q.mode == 2) hipLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, A, none);
-        else hipLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, A, none);
+        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        else if (Q.mode == 2) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        else hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
       } else {
-        if (Q.mode == 1) hipLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, A, none);
-        else if (Q.mode == 2) hipLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, A, none);
-        else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, A, none);
+        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        else if (Q.mode == 2) hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        else hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
       }
       break;
     case plan::kTall64: {
       const dim3 tgrid(S.nseg, S.ntr_tall), tblock(64 * kScreenWaves);
-      if (nt) hipLaunchKernelGGL((sweep_kernel<false, true, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, A, none);
-      else hipLaunchKernelGGL((sweep_kernel<false, false, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, A, none);
+      if (nt) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, e0, e1, 0, A, none);
+      else hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, e0, e1, 0, A, none);
       break;
     }
     case plan::kScreened8: {
@@ -394,11 +393,11 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
                           h->screen_ctl, h->wg_reads, nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 sgrid(S.nseg, S.ntr_tall), sblock(64 * kScreenWaves);
       if (Q.refresh) {
-        if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, A, SC);
-        else hipLaunchKernelGGL((screened_sweep_kernel<false, true>), sgrid, sblock, 0, stream, A, SC);
+        if (nt) hipExtLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
+        else hipExtLaunchKernelGGL((screened_sweep_kernel<false, true>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
       } else {
-        if (nt) hipLaunchKernelGGL((screened_sweep_kernel<true, false>), sgrid, sblock, 0, stream, A, SC);
-        else hipLaunchKernelGGL((screened_sweep_kernel<false, false>), sgrid, sblock, 0, stream, A, SC);
+        if (nt) hipExtLaunchKernelGGL((screened_sweep_kernel<true, false>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
+        else hipExtLaunchKernelGGL((screened_sweep_kernel<false, false>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
       }
       break;
     }
@@ -406,8 +405,8 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed) {
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads,
                           Q.lines_in ? h->xlines : nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 lgrid(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), lblock(64 * kLeanWaves);
-      if (nt) hipLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, A, SC, S.ntr_tall);
-      else hipLaunchKernelGGL((screened_lean_kernel<false>), lgrid, lblock, 0, stream, A, SC, S.ntr_tall);
+      if (nt) hipExtLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, e0, e1, 0, A, SC, S.ntr_tall);
+      else hipExtLaunchKernelGGL((screened_lean_kernel<false>), lgrid, lblock, 0, stream, e0, e1, 0, A, SC, S.ntr_tall);
       break;
     }
   }
@@ -470,7 +469,7 @@ void enqueue_gap(Solve& Z, const int* guard, bool flags_current) {
   const plan::GapPass pass = flags_current ? plan::gap_pass(S, Z.P, Z.T) : plan::kGapDense;
   if (pass != plan::kGapDense) {
     const GapLeanArgs GL{GA, h->mprime, h->mprime2, h->jstar, h->varphi0, pass == plan::kGapLeanLines ? h->xlines : nullptr,
-                         Z.rowp(Z.T.k_base + Z.T.k), Z.SA.n_mem, S.ntr_tall, S.ntr};
+                         Z.rowp(Z.T.k_base + Z.T.k), Z.SA.n_mem, Z.SA.mp, S.ntr_tall, S.ntr};
     hipLaunchKernelGGL(gap_lean_kernel, dim3(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), dim3(64 * kLeanWaves), 0, stream, GL);
   } else {
     hipLaunchKernelGGL(gap_kernel, dim3(S.nseg, S.ntr), dim3(kBlock), 0, stream, GA);
@@ -681,7 +680,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   h->xpad_live = false;  // (until this solve has returned)
   Z.SA = SweepArgs{Z.Xw, Z.Cw, h->phi, h->varphi, nullptr, nullptr, nullptr, h->done, m, n, Z.ldx, Z.ldc, Z.rho,
                    A.reg_kind == DROT_REG_NONE ? 1.0f : qscale,
-                   (S.pad_x && (S.pad_c || from_points)) ? S.ld_pad : n, nullptr};
+                   (S.pad_x && (S.pad_c || from_points)) ? S.ld_pad : n, nullptr, ceil_div(m, 64) * 64, ceil_div(n, 64) * 64};
   // (the sweeps' edge handling counts on rows that are whole 128-byte lines: the planner's pad_c, pad_x see to it)
   if (!S.resident && Z.SA.n_mem % kAlignElems != 0) return DROT_ERR_INVALID_ARG;
   // on-the-fly cost: pack the point clouds for the matrix cores and take their squared norms
@@ -702,7 +701,7 @@ int prepare(drot_handle h, const SolveCall& A, Solve& Z) {
   // the partial sums the reduction reads: per 256-column segment and 32-row tile, or, on the
   // group-resident path, per 32-column strip and label run
   Z.RA = ReduceArgs{Z.V, h->rowpart, h->colpart, A.p, A.q, m, n, P.slab_k ? S.nstrips : S.nseg,
-                    P.slab_k ? P.nruns : S.ntr, S.nbm, S.nbn, 1};
+                    P.slab_k ? P.nruns : S.ntr, S.nbm, S.nbn, Z.SA.mp, Z.SA.np, 1};
   Z.UA = UpdateArgs{Z.V, nullptr, 0, nullptr, nullptr, nullptr, nullptr, m, n, S.nbm, S.nbn, 0};
 
   if (A.warm) {
@@ -740,8 +739,6 @@ int iterate(Solve& Z, bool* converged_out) {
   bool converged = false;
   bool was_probe[2] = {false, false};
   h->prof_used = 0;
-  if (h->profile)  // empty event pairs: the time a pair reports with nothing between its two records
-    for (auto& e : h->cal_ev) DROT_HIP(hipEventRecord(e, stream));
   while (Z.T.k < Z.P.max_iters && !converged) {
     const plan::Stretch R = plan::next_stretch(S, Z.P, Z.O, Z.T);
     const int k_end = Z.T.k + R.chunk;
@@ -750,14 +747,13 @@ int iterate(Solve& Z, bool* converged_out) {
       const bool timed = h->profile && h->prof_used < kMaxProfiled;
       const int pe = h->prof_used;
       if (timed) {
-        DROT_HIP(hipEventRecord(h->prof_ev[2 * pe], stream));
         h->prof_kind[pe] = Q.profile_kind;
         h->prof_iters[pe] = Q.iters;
         ++h->prof_used;
       }
-      enqueue_sweep(Z, Q, timed);
+      // (profile mode: the pair of events takes the start and the end of the sweep kernel itself)
+      enqueue_sweep(Z, Q, timed, timed ? h->prof_ev[2 * pe] : nullptr, timed ? h->prof_ev[2 * pe + 1] : nullptr);
       if (timed) {
-        DROT_HIP(hipEventRecord(h->prof_ev[2 * pe + 1], stream));
         const bool per_workgroup = Q.sweep == plan::kLean || Q.sweep == plan::kPointsLean;
         if (Q.sweep == plan::kScreened8 || per_workgroup)  // (one count per wave of the 8-wave tiles, one per workgroup of the lean kernels)
           hipLaunchKernelGGL(sum_counts_kernel<int>, dim3(1), dim3(1024), 0, stream,
@@ -846,18 +842,9 @@ int solve_impl(drot_handle h, const SolveCall& A) {
     if (timed > 0 && hipMemcpy(h->prof_counts_host, h->prof_counts, sizeof(double) * 2 * (size_t)timed,
                                hipMemcpyDeviceToHost) != hipSuccess)
       return fail(DROT_ERR_HIP);
-    // What an event pair reports for an empty interval (the smallest of four) is taken off every
-    // measurement: for kernels of tens of microseconds it is a third of the reading.
-    float overhead = 1e30f;
-    for (int c = 0; c < 4; ++c) {
-      float ms = 0.f;
-      if (hipEventElapsedTime(&ms, h->cal_ev[2 * c], h->cal_ev[2 * c + 1]) != hipSuccess) return fail(DROT_ERR_HIP);
-      if (ms < overhead) overhead = ms;
-    }
     for (int e = 0; e < timed; ++e) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, h->prof_ev[2 * e], h->prof_ev[2 * e + 1]) != hipSuccess) return fail(DROT_ERR_HIP);
-      ms = ms > overhead ? ms - overhead : 0.f;
       h->prof_ms[e] = ms / (float)h->prof_iters[e];  // per iteration (a resident stretch is one launch)
     }
     h->prof_count = timed;
@@ -918,6 +905,7 @@ size_t carve_static(drot_handle_s& H, unsigned char* base) {
     off = (off + count * sizeof(T) + 255) & ~(size_t)255;
   };
   const size_t M = kStaticMaxM, N = kStaticMaxN;
+  static_assert(kStaticMaxM % 64 == 0 && kStaticMaxN % 64 == 0, "the pitches of the partial sums are the sizes themselves");
   const size_t nseg = ceil_div(kStaticMaxN, kSegCols), ntr = ceil_div(kStaticMaxM, kTileRows);
   const size_t nb = ceil_div(kStaticMaxM, 64) + ceil_div(kStaticMaxN, 64);
   H.max_m = kStaticMaxM;
@@ -1055,18 +1043,20 @@ int drot_create(drot_handle* out, int max_m, int max_n) {
   take(dev_alloc(&h->s, (size_t)max_n));
   take(dev_alloc(&h->part, 3 * nb));
   take(dev_alloc(&h->resid, 3));
-  h->rowpart_half = (size_t)ceil_div(max_n, kSlabCols) * (size_t)max_m;  // 32-column strips (group-resident path) are the finest
-  h->colpart_half = ntr * (size_t)max_n;
+  // (rows of the per-row-segment arrays and of the column sums are pitched at multiples of 64 entries)
+  const size_t mpad = (size_t)ceil_div(max_m, 64) * 64, npad = (size_t)ceil_div(max_n, 64) * 64;
+  h->rowpart_half = (size_t)ceil_div(max_n, kSlabCols) * mpad;  // 32-column strips (group-resident path) are the finest
+  h->colpart_half = ntr * npad;
   h->tilesum_half = nseg * ntr > 4096 ? nseg * ntr : 4096;  // (the group-resident path has up to 4096 slabs)
   take(dev_alloc(&h->rowpart, 2 * h->rowpart_half));
   take(dev_alloc(&h->colpart, 2 * h->colpart_half));
   take(dev_alloc(&h->tilesum, 2 * h->tilesum_half));
-  take(dev_alloc(&h->mprime, nseg * (size_t)max_m));
-  take(dev_alloc(&h->mprime2, nseg * (size_t)max_m));
-  take(dev_alloc(&h->jstar, nseg * (size_t)max_m));
+  take(dev_alloc(&h->mprime, nseg * mpad));
+  take(dev_alloc(&h->mprime2, nseg * mpad));
+  take(dev_alloc(&h->jstar, nseg * mpad));
   take(dev_alloc(&h->varphi0, nseg * kSegCols));
   take(dev_alloc(&h->screen_ctl, (size_t)kCtlWords));
-  take(dev_alloc(&h->xlines, nseg * (size_t)max_m));
+  take(dev_alloc(&h->xlines, nseg * mpad));
   take(dev_alloc(&h->wg_reads, nseg * (size_t)ceil_div(ceil_div(max_m, 64), kLeanWaves)));
   h->max_runs = (int)ntr;
   take(dev_alloc(&h->gap_part, nseg * ntr * 3));

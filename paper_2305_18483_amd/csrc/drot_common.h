@@ -169,6 +169,9 @@ struct SweepArgs {
   const float* rowpart_prev;  // plain sweep: the row-segment sums of the X in memory (layout of rowpart), or null
                               // when they are not known or not to be used; a segment whose sum is zero is all
                               // zero: it is not read, and not written back if it stays zero
+  int mp, np;            // pitches of the arrays kept per row segment ([segment][mp]: sums, bounds, line flags) and of
+                         // the rows of column sums ([tile row][np]): m and n rounded up to 64, so that a wave's 64
+                         // consecutive entries never straddle one 128-byte line more than they must
 };
 
 // Inputs of the vector update when it is fused into the head of the next sweep (small problems):

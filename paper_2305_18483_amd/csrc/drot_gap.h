@@ -106,6 +106,7 @@ struct GapLeanArgs {
   const unsigned char* lines;    // [nseg][m] nonzero 128-byte lines of every row segment of X, or null
   const float* rowsums;          // [nseg][m] row-segment sums of X (used when lines is null)
   int n_mem;                     // columns that may be accessed in a row of X and C
+  int mp;                        // pitch of the arrays kept per row segment
   int ntr64, ntr32;              // tiles of 64 and of 32 rows
 };
 
@@ -119,7 +120,7 @@ __device__ __forceinline__ void gap_lean_body(const GapLeanArgs& L, int lane, in
   const size_t ldx = (size_t)A.ldx, ldc = (size_t)A.ldc;
   const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
   const float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
-  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+  const size_t ridx = (size_t)seg * L.mp + r0 + lane;
   const f4v vp = load_varphi_padded(A.varphi, j0);
   const f4v vp0 = load_varphi_padded(L.varphi0, j0);
   float ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f;

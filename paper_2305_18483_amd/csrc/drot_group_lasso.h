@@ -108,8 +108,8 @@ __global__ __launch_bounds__(kBlock) void gl_apply_kernel(GroupArgs G) {
     const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
     rowkeep = (lane == i - rbeg) ? tot : rowkeep;
   }
-  if (lane < rend - rbeg) A.rowpart[(size_t)seg * A.m + rbeg + lane] = rowkeep;
-  write_col_partials<kWavesPerBlock>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  if (lane < rend - rbeg) A.rowpart[(size_t)seg * A.mp + rbeg + lane] = rowkeep;
+  write_col_partials<kWavesPerBlock>(colacc, lane, wave, seg, tr, A.n, A.np, A.colpart);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
   for (int k = 0; k < K; ++k) {
     const int r = ry + RL * k;
     held[k] = true;
-    if (flags && r < len) held[k] = fbits(A.rowpart_prev[(size_t)strip * A.m + start + r]) != 0;
+    if (flags && r < len) held[k] = fbits(A.rowpart_prev[(size_t)strip * A.mp + start + r]) != 0;
   }
 #pragma unroll
   for (int k = 0; k < K; ++k) {
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     const int i = start + t;
     double ri = 0.0, ai = 0.0;
     if (row_thread) {
-      ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.m, F.nseg) - (double)F.p[i];
+      ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.mp, F.nseg) - (double)F.p[i];
       ai = F.a_in[i];
     }
     const int cidx = t - (kSlabThreads - COLS);
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     const bool col_thread = cidx >= 0 && jc < A.n;
     double sres = 0.0, bold = 0.0;
     if (col_thread) {
-      sres = sum_partials_16(F.colpart_prev + jc, (size_t)A.n, F.ntr) - (double)F.q[jc];
+      sres = sum_partials_16(F.colpart_prev + jc, (size_t)A.np, F.ntr) - (double)F.q[jc];
       bold = F.b_in[jc];
     }
     const double sum_p = *F.sum_p;
@@ -294,13 +294,13 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     colacc += v;
     if (r < len) {
       if (held[k] || fbits(rs) != 0) store4(Xp + (size_t)(RL * k) * ldx, v, nvalid);
-      if (cx == 0) A.rowpart[(size_t)strip * A.m + start + r] = rs;
+      if (cx == 0) A.rowpart[(size_t)strip * A.mp + start + r] = rs;
     }
   }
   const float csum = fold(colacc);  // (the barrier inside orders it after every read of the first fold)
   if (t < COLS) {
     const int j = strip * COLS + t;
-    if (j < A.n) A.colpart[(size_t)run * A.n + j] = csum;
+    if (j < A.n) A.colpart[(size_t)run * A.np + j] = csum;
   }
   if (A.tilesum && t < 64) {  // total of the slab, for the fused update of the next sweep (wave 0)
     const float tot = wave_sum(t < COLS ? csum : 0.f);

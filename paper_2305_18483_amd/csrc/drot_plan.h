@@ -46,7 +46,7 @@ constexpr int kColGroup = 4;          // the lean sweep adds the column sums of 
 constexpr int kStripRows = 256;       // rows of a strip of the point-cloud variant's screened sweep
 constexpr int kPointsColGroup = 8;    // ... which adds the column sums of its eight 32-row tiles before it stores
 constexpr size_t kScreenFrom = (size_t)11 << 20;  // screening on automatic: from this many entries up
-constexpr int kFirstRefreshPeriod = 8, kMaxRefreshPeriod = 256;
+constexpr int kFirstRefreshPeriod = 8, kMaxRefreshPeriod = 1024;
 constexpr int kEarlyLooksUntil = 512;  // cold starts: extra density readings over this many iterations
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
   // segments of X that hold something after the matrix phase, which hides the flags' latency.
   const bool flags = !FIRST && A.rowpart_prev != nullptr;
   float prev = 1.f;
-  if (flags && lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.m + r0 + lane];
+  if (flags && lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.mp + r0 + lane];
   f4v x[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -179,16 +179,16 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
       }
     }
     if (lane < nrows) {
-      A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
+      A.rowpart[(size_t)seg * A.mp + r0 + lane] = rowkeep;
       if (REFRESH) {
-        mprime[(size_t)seg * A.m + r0 + lane] = mkeep;
-        mprime2[(size_t)seg * A.m + r0 + lane] = m2keep;
-        jstar[(size_t)seg * A.m + r0 + lane] = (unsigned char)jkeep;
+        mprime[(size_t)seg * A.mp + r0 + lane] = mkeep;
+        mprime2[(size_t)seg * A.mp + r0 + lane] = m2keep;
+        jstar[(size_t)seg * A.mp + r0 + lane] = (unsigned char)jkeep;
       }
     }
   }
   if (REFRESH && tr == 0 && wave == 0) *reinterpret_cast<f4u*>(varphi0 + j0) = vp;  // (past n both hold the mask value)
-  write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.np, A.colpart);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs
   const f4v ysq = load4(Pt.xt_sq + j0, nvalid);
   float prev = 0.f, ph = kMaskedOut, mpr = 0.f, mpr2 = 0.f, xsq_lane = 0.f;
   unsigned js = 0;
-  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+  const size_t ridx = (size_t)seg * A.mp + r0 + lane;
   if (lane < nrows) {
     prev = A.rowpart_prev[ridx];
     ph = A.phi[r0 + lane];
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs
     float sum = fold[t];
 #pragma unroll
     for (int k = 1; k < kPointsColGroup; ++k) sum += fold[k * kSegCols + t];
-    A.colpart[(size_t)strip * A.n + j] = sum;
+    A.colpart[(size_t)strip * A.np + j] = sum;
   }
 }
 

@@ -102,7 +102,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
   float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
   const float rho = A.rho, scale = A.scale;
-  const size_t ridx = (size_t)seg * A.m + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
+  const size_t ridx = (size_t)seg * A.mp + r0 + lane;  // this lane's row in the per-row-segment arrays (lane < nrows)
 
   // lane u: old sum, phi and the bounds of row r0 + u
   const f4v vp = load_varphi_padded(A.varphi, j0);
@@ -194,7 +194,7 @@ __device__ __forceinline__ void screened_body(const SweepArgs& A, const ScreenAr
   }
   if (SC.wave_reads && lane == 0)
     SC.wave_reads[(tr * gridDim.x + seg) * NW + wave] = __builtin_popcount(~skipmask & 0xffu);
-  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.np, A.colpart);
   write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
 }
 
@@ -238,7 +238,7 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const float* __restrict__ Cp = A.C + (size_t)r0 * ldc + j0;
   float* __restrict__ Xp = A.X + (size_t)r0 * ldx + j0;
   const float rho = A.rho, scale = A.scale;
-  const size_t ridx = (size_t)seg * A.m + r0 + lane;
+  const size_t ridx = (size_t)seg * A.mp + r0 + lane;
 
   const f4v vp = load_varphi_padded(A.varphi, j0);
   const f4v vp0 = load_varphi_padded(SC.varphi0, j0);
@@ -393,7 +393,7 @@ __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(Sweep
   }
   __syncthreads();
   const int t = threadIdx.x, j = seg * kSegCols + t;
-  if (j < A.n) A.colpart[(size_t)blockIdx.y * A.n + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
+  if (j < A.n) A.colpart[(size_t)blockIdx.y * A.np + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
   if (t == 0) {
     A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
     SC.wg_reads[blockIdx.y * gridDim.x + seg] = (nreads[0] + nreads[1]) + (nreads[2] + nreads[3]);

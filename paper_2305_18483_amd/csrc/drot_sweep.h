@@ -33,7 +33,7 @@ __device__ __forceinline__ void st4(float* __restrict__ ptr, f4v v, int nmem) {
 // Folds the column partials of the NW waves of a workgroup through LDS and writes the tile's
 // column sums (fixed order: deterministic).
 template <int NW>
-__device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wave, int seg, int tr, int n,
+__device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wave, int seg, int tr, int n, int np,
                                                    float* __restrict__ colpart) {
   __shared__ float cs[NW][kSegCols];
   *reinterpret_cast<f4v*>(&cs[wave][lane * 4]) = colacc;
@@ -44,7 +44,7 @@ __device__ __forceinline__ void write_col_partials(f4v colacc, int lane, int wav
 #pragma unroll
     for (int k = 0; k < NW; ++k) sum += cs[k][t];
     const int j = seg * kSegCols + t;
-    if (j < n) colpart[(size_t)tr * n + j] = sum;
+    if (j < n) colpart[(size_t)tr * np + j] = sum;
   }
 }
 
@@ -109,7 +109,7 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
     double q4[4] = {0.0, 0.0, 0.0, 0.0};
     float v[16];  // at most 64 row tiles on this path: all 16 loads in flight (clamped; the excess ones add +0)
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = F.colpart_prev[(size_t)min(sub + 4 * u, F.ntr - 1) * A.n + j];
+    for (int u = 0; u < 16; ++u) v[u] = F.colpart_prev[(size_t)min(sub + 4 * u, F.ntr - 1) * A.np + j];
 #pragma unroll
     for (int u = 0; u < 16; ++u) q4[u & 3] += (sub + 4 * u < F.ntr) ? (double)v[u] : 0.0;
     sj = (q4[0] + q4[2]) + (q4[1] + q4[3]);  // residues sub, sub+8 | sub+4, sub+12
@@ -120,7 +120,7 @@ __device__ __forceinline__ void fused_update(const SweepArgs& A, const FusedUpda
   const bool row_thread = l >= 0 && l < kTileRows && i < A.m;
   double ri = 0.0, ai = 0.0;
   if (row_thread) {
-    ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.m, F.nseg) - (double)F.p[i];
+    ri = sum_partials_16(F.rowpart_prev + i, (size_t)A.mp, F.nseg) - (double)F.p[i];
     ai = F.a_in[i];
   }
   const bool col_thread = t < kSegCols && j < A.n;
@@ -186,7 +186,7 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
   for (int u = 0; u < U; ++u) readx[u] = true;
   if (MODE == 0 && !FIRST && !PRO && A.rowpart_prev) {
     float prev = 1.f;
-    if (lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.m + r0 + lane];
+    if (lane < nrows) prev = A.rowpart_prev[(size_t)seg * A.mp + r0 + lane];
 #pragma unroll
     for (int u = 0; u < U; ++u)
       readx[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, prev), u)) != 0.f;
@@ -255,9 +255,9 @@ __device__ __forceinline__ void sweep_body(const SweepArgs& A, const FusedUpdate
       rowkeep = (lane == u) ? tot : rowkeep;
       wave_total += tot;
     }
-    if (lane < nrows) A.rowpart[(size_t)seg * A.m + r0 + lane] = rowkeep;
+    if (lane < nrows) A.rowpart[(size_t)seg * A.mp + r0 + lane] = rowkeep;
   }
-  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.colpart);
+  write_col_partials<NW>(colacc, lane, wave, seg, tr, A.n, A.np, A.colpart);
   // total of the tile, for the vector update that forms eta from these
   if (A.tilesum) write_tile_total<NW>(wave_total, lane, wave, seg, tr, A.tilesum);
 }

@@ -114,6 +114,7 @@ struct ReduceArgs {
   const float* p;
   const float* q;
   int m, n, nseg, ntr, nbm, nbn;
+  int mp, np;  // pitches of the rows of rowpart and of colpart
   int cgroup;  // 1, kColGroup or kPointsColGroup: consecutive rows of colpart are first added up in fp32, in groups of that many
 };
 
@@ -122,7 +123,7 @@ constexpr int kReduceThreads = 1024;
 // One of the 16 shares of a column's partial sums when G consecutive rows are added in fp32 first.  share, nparts
 // and ntr are wave-uniform; idx is the lane's entry, already clamped to the last one that exists.
 template <int G>
-__device__ __forceinline__ double gather_grouped(const float* __restrict__ part, int share, int nparts, int ntr, int idx, int len) {
+__device__ __forceinline__ double gather_grouped(const float* __restrict__ part, int share, int nparts, int ntr, int idx, int pitch) {
   constexpr int kStride = 16, kGroups = 32 / G > 1 ? 32 / G / 2 : 1;  // (16 loads in flight per batch)
   double acc = 0.0;
   for (int k0 = share; k0 < nparts; k0 += kStride * kGroups) {
@@ -132,7 +133,7 @@ __device__ __forceinline__ double gather_grouped(const float* __restrict__ part,
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used)
-        const float w = (part + (size_t)min(k, ntr - 1) * len)[idx];
+        const float w = (part + (size_t)min(k, ntr - 1) * pitch)[idx];
         v[b][g] = k < ntr ? w : 0.f;
       }
 #pragma unroll
@@ -161,7 +162,7 @@ __device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, 
   const int sub = __builtin_amdgcn_readfirstlane(t >> 6), l = t & 63;
   const bool rows = (int)blockIdx.x < A.nbm;
   const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + l;
-  const int len = rows ? A.m : A.n;
+  const int len = rows ? A.m : A.n, pitch = rows ? A.mp : A.np;
   const int idc = min(idx, len - 1);
   const unsigned long long live = __builtin_amdgcn_ballot_w64(idx < len);
   const bool grouped = !rows && A.cgroup > 1;
@@ -176,8 +177,8 @@ __device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, 
     // column sums stored per tile row: the rows G k .. G k + G - 1 are added first, in fp32 and in order, as the
     // workgroups of the lean sweeps do before they store (a row past the end adds +0).  G = 4: four 64-row tiles
     // (screened_lean_kernel); G = 8: the eight 32-row tiles of a 256-row strip (lean_points_kernel)
-    if (grouped && A.cgroup == kColGroup) acc = gather_grouped<kColGroup>(part, share, nparts, A.ntr, idc, len);
-    else if (grouped) acc = gather_grouped<kPointsColGroup>(part, share, nparts, A.ntr, idc, len);
+    if (grouped && A.cgroup == kColGroup) acc = gather_grouped<kColGroup>(part, share, nparts, A.ntr, idc, pitch);
+    else if (grouped) acc = gather_grouped<kPointsColGroup>(part, share, nparts, A.ntr, idc, pitch);
     for (int k0 = share; !grouped && k0 < nparts; k0 += kStride * kBatch) {  // (nparts and share are wave-uniform)
       // a batch of independent loads, then the additions in the order k0, k0 + 16, ... (one load per
       // trip would wait for memory once per partial sum)
@@ -185,7 +186,7 @@ __device__ __forceinline__ void reduce_gather(const ReduceArgs& A, double* red, 
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
         const int k = k0 + b * kStride;  // (past the end: the last partial is fetched and not used; no branch, so that
-        const float w = (part + (size_t)min(k, nparts - 1) * len)[idc];  // the loads of all shares leave together)
+        const float w = (part + (size_t)min(k, nparts - 1) * pitch)[idc];  // the loads of all shares leave together)
         v[b] = k < nparts ? w : 0.f;
       }
 #pragma unroll
