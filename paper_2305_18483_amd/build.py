@@ -17,6 +17,9 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # hardware fp32 atomic add for the group-lasso accumulators (coarse-grained device memory)
     "-munsafe-fp-atomics",
+    # device code only: the kernels never see a NaN (the host rejects NaN arguments; infinities are used and kept),
+    # so maxima need no quieting of their inputs and fold into the cross-lane steps of the wave reductions
+    "-Xarch_device", "-fno-honor-nans",
     "-Wall", "-Wno-unused-function",
 ]
 
