@@ -193,8 +193,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
 
 // ------------------------------------------------------------------------------------------
 // The screened sweep of the point-cloud variant, for plans known to be sparse.  A row segment whose X
-// is zero and whose bound M + (drift of varphi) + phi_i is not positive stays zero (the certificate of
-// the stored-cost screening, to the letter); for the few that are left the cost has to be formed, and
+// is zero and whose bound max(M + drift of its own column, M2 + largest drift) + phi_i is not positive stays
+// zero (the certificate of the stored-cost screening, to the letter); for the few that are left the cost has to be formed, and
 // to come out with the bits of the full sweep it is formed the same way, on the matrix cores: a
 // workgroup of four waves owns a strip of 256 rows x 256 columns, gathers the rows that are left (in
 // ascending order) into blocks of 16, computes each block's 16 x 256 inner products with the same
