@@ -69,10 +69,10 @@ template <bool FIRST, bool PRO>
 void launch_slab_k(int k, dim3 grid, hipStream_t stream, hipEvent_t e0, hipEvent_t e1, const SlabArgs& a, const FusedUpdateArgs& f) {
   const dim3 block(kSlabThreads);
   switch (k) {
-    case 1: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 1, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
-    case 2: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 2, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
-    case 4: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 4, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
-    default: hipExtLaunchKernelGGL((gl_slab_kernel<FIRST, 8, kSlabLanes, PRO>), grid, block, 0, stream, e0, e1, 0, a, f); break;
+    case 1: launch_timed((gl_slab_kernel<FIRST, 1, kSlabLanes, PRO>), grid, block, stream, e0, e1, a, f); break;
+    case 2: launch_timed((gl_slab_kernel<FIRST, 2, kSlabLanes, PRO>), grid, block, stream, e0, e1, a, f); break;
+    case 4: launch_timed((gl_slab_kernel<FIRST, 4, kSlabLanes, PRO>), grid, block, stream, e0, e1, a, f); break;
+    default: launch_timed((gl_slab_kernel<FIRST, 8, kSlabLanes, PRO>), grid, block, stream, e0, e1, a, f); break;
   }
 }
 void launch_slab(bool first, bool pro, int k, dim3 grid, hipStream_t stream, hipEvent_t e0, hipEvent_t e1, const SlabArgs& a,
@@ -329,18 +329,18 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed, hipEvent_t e0, hip
       break;
     }
     case plan::kPoints:
-      if (Q.first) hipExtLaunchKernelGGL((sweep_points_kernel<true, false>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (Q.refresh && nt) hipExtLaunchKernelGGL((sweep_points_kernel<false, true, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (Q.refresh) hipExtLaunchKernelGGL((sweep_points_kernel<false, false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else if (nt) hipExtLaunchKernelGGL((sweep_points_kernel<false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
-      else hipExtLaunchKernelGGL((sweep_points_kernel<false, false>), grid, sweep_block, 0, stream, e0, e1, 0, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      if (Q.first) launch_timed((sweep_points_kernel<true, false>), grid, sweep_block, stream, e0, e1, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh && nt) launch_timed((sweep_points_kernel<false, true, true>), grid, sweep_block, stream, e0, e1, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (Q.refresh) launch_timed((sweep_points_kernel<false, false, true>), grid, sweep_block, stream, e0, e1, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else if (nt) launch_timed((sweep_points_kernel<false, true>), grid, sweep_block, stream, e0, e1, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
+      else launch_timed((sweep_points_kernel<false, false>), grid, sweep_block, stream, e0, e1, A, Z.PT, h->mprime, h->mprime2, h->jstar, h->varphi0);
       break;
     case plan::kPointsLean: {
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads, nullptr, h->xlines,
                           h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 pgrid(S.nseg, ceil_div(m, kStripRows));
-      if (nt) hipExtLaunchKernelGGL((lean_points_kernel<true>), pgrid, dim3(256), 0, stream, e0, e1, 0, A, Z.PT, SC);
-      else hipExtLaunchKernelGGL((lean_points_kernel<false>), pgrid, dim3(256), 0, stream, e0, e1, 0, A, Z.PT, SC);
+      if (nt) launch_timed((lean_points_kernel<true>), pgrid, dim3(256), stream, e0, e1, A, Z.PT, SC);
+      else launch_timed((lean_points_kernel<false>), pgrid, dim3(256), stream, e0, e1, A, Z.PT, SC);
       break;
     }
     case plan::kSlab: {
@@ -354,38 +354,38 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed, hipEvent_t e0, hip
       const dim3 cgrid(S.nseg, ceil_div(Z.CK.nchunks, kWavesPerBlock));
       const dim3 fgrid(ceil_div(n, kBlock), Z.num_classes < 65535 ? Z.num_classes : 65535);
       // (three launches: the start of the first and the end of the last are what is timed)
-      if (Q.first) hipExtLaunchKernelGGL(gl_norm_kernel<true>, cgrid, block, 0, stream, e0, nullptr, 0, G, Z.CK);
-      else hipExtLaunchKernelGGL(gl_norm_kernel<false>, cgrid, block, 0, stream, e0, nullptr, 0, G, Z.CK);
+      if (Q.first) launch_timed(gl_norm_kernel<true>, cgrid, block, stream, e0, nullptr, G, Z.CK);
+      else launch_timed(gl_norm_kernel<false>, cgrid, block, stream, e0, nullptr, G, Z.CK);
       hipLaunchKernelGGL(gl_norm_finish_kernel, fgrid, block, 0, stream, Z.CK, h->gbuf, n, Z.num_classes, (const int*)h->done);
-      if (Q.first) hipExtLaunchKernelGGL(gl_apply_kernel<true>, grid, block, 0, stream, nullptr, e1, 0, G);
-      else hipExtLaunchKernelGGL(gl_apply_kernel<false>, grid, block, 0, stream, nullptr, e1, 0, G);
+      if (Q.first) launch_timed(gl_apply_kernel<true>, grid, block, stream, nullptr, e1, G);
+      else launch_timed(gl_apply_kernel<false>, grid, block, stream, nullptr, e1, G);
       break;
     }
     case plan::kPro32: {
       // update sw-1 (from the sums of X_{sw-1} and the state of generation sw-2) rides along
       const FusedUpdateArgs F = fused_args(Z, sw, S.nseg, S.ntr);
-      if (nt) hipExtLaunchKernelGGL((sweep_kernel<false, true, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, F);
-      else hipExtLaunchKernelGGL((sweep_kernel<false, false, true>), grid, sweep_block, 0, stream, e0, e1, 0, A, F);
+      if (nt) launch_timed((sweep_kernel<false, true, true>), grid, sweep_block, stream, e0, e1, A, F);
+      else launch_timed((sweep_kernel<false, false, true>), grid, sweep_block, stream, e0, e1, A, F);
       break;
     }
     case plan::kPlain32:
       if (Q.first) {
-        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<true, false, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
-        else hipExtLaunchKernelGGL((sweep_kernel<true, false, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        if (Q.mode == 1) launch_timed((sweep_kernel<true, false, false, 1>), grid, sweep_block, stream, e0, e1, A, none);
+        else launch_timed((sweep_kernel<true, false, false, 0>), grid, sweep_block, stream, e0, e1, A, none);
       } else if (nt) {
-        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
-        else if (Q.mode == 2) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 2>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
-        else hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        if (Q.mode == 1) launch_timed((sweep_kernel<false, true, false, 1>), grid, sweep_block, stream, e0, e1, A, none);
+        else if (Q.mode == 2) launch_timed((sweep_kernel<false, true, false, 2>), grid, sweep_block, stream, e0, e1, A, none);
+        else launch_timed((sweep_kernel<false, true, false, 0>), grid, sweep_block, stream, e0, e1, A, none);
       } else {
-        if (Q.mode == 1) hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 1>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
-        else if (Q.mode == 2) hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 2>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
-        else hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 0>), grid, sweep_block, 0, stream, e0, e1, 0, A, none);
+        if (Q.mode == 1) launch_timed((sweep_kernel<false, false, false, 1>), grid, sweep_block, stream, e0, e1, A, none);
+        else if (Q.mode == 2) launch_timed((sweep_kernel<false, false, false, 2>), grid, sweep_block, stream, e0, e1, A, none);
+        else launch_timed((sweep_kernel<false, false, false, 0>), grid, sweep_block, stream, e0, e1, A, none);
       }
       break;
     case plan::kTall64: {
       const dim3 tgrid(S.nseg, S.ntr_tall), tblock(64 * kScreenWaves);
-      if (nt) hipExtLaunchKernelGGL((sweep_kernel<false, true, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, e0, e1, 0, A, none);
-      else hipExtLaunchKernelGGL((sweep_kernel<false, false, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, 0, stream, e0, e1, 0, A, none);
+      if (nt) launch_timed((sweep_kernel<false, true, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, stream, e0, e1, A, none);
+      else launch_timed((sweep_kernel<false, false, false, 0, kScreenRows, kScreenWaves>), tgrid, tblock, stream, e0, e1, A, none);
       break;
     }
     case plan::kScreened8: {
@@ -393,11 +393,11 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed, hipEvent_t e0, hip
                           h->screen_ctl, h->wg_reads, nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 sgrid(S.nseg, S.ntr_tall), sblock(64 * kScreenWaves);
       if (Q.refresh) {
-        if (nt) hipExtLaunchKernelGGL((screened_sweep_kernel<true, true>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
-        else hipExtLaunchKernelGGL((screened_sweep_kernel<false, true>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
+        if (nt) launch_timed((screened_sweep_kernel<true, true>), sgrid, sblock, stream, e0, e1, A, SC);
+        else launch_timed((screened_sweep_kernel<false, true>), sgrid, sblock, stream, e0, e1, A, SC);
       } else {
-        if (nt) hipExtLaunchKernelGGL((screened_sweep_kernel<true, false>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
-        else hipExtLaunchKernelGGL((screened_sweep_kernel<false, false>), sgrid, sblock, 0, stream, e0, e1, 0, A, SC);
+        if (nt) launch_timed((screened_sweep_kernel<true, false>), sgrid, sblock, stream, e0, e1, A, SC);
+        else launch_timed((screened_sweep_kernel<false, false>), sgrid, sblock, stream, e0, e1, A, SC);
       }
       break;
     }
@@ -405,8 +405,8 @@ void enqueue_sweep(Solve& Z, const plan::Step& Q, bool timed, hipEvent_t e0, hip
       const ScreenArgs SC{h->mprime, h->mprime, h->varphi0, nullptr, h->varphi0, h->screen_ctl, h->wg_reads,
                           Q.lines_in ? h->xlines : nullptr, h->xlines, h->mprime2, h->mprime2, h->jstar, h->jstar};
       const dim3 lgrid(S.nseg, ceil_div(S.ntr_tall, kLeanWaves)), lblock(64 * kLeanWaves);
-      if (nt) hipExtLaunchKernelGGL((screened_lean_kernel<true>), lgrid, lblock, 0, stream, e0, e1, 0, A, SC, S.ntr_tall);
-      else hipExtLaunchKernelGGL((screened_lean_kernel<false>), lgrid, lblock, 0, stream, e0, e1, 0, A, SC, S.ntr_tall);
+      if (nt) launch_timed((screened_lean_kernel<true>), lgrid, lblock, stream, e0, e1, A, SC, S.ntr_tall);
+      else launch_timed((screened_lean_kernel<false>), lgrid, lblock, stream, e0, e1, A, SC, S.ntr_tall);
       break;
     }
   }
@@ -432,7 +432,7 @@ void enqueue_update(Solve& Z, const plan::Step& Q) {
   UA.par = (int)((sw - 1) & 1);
   UA.tilesum = S.small ? Z.tsum(sw) : nullptr;
   UA.ntiles = S.small_slab ? S.nstrips * Z.P.nruns : S.ntiles;
-  const dim3 merged_grid(S.nbm + S.nbn), merged_block(64 * kMergedWaves);
+  const dim3 merged_grid(ceil_div(Z.m, kMergedEntries) + ceil_div(Z.n, kMergedEntries)), merged_block(64 * kMergedWaves);
   if (Q.update == plan::kMergedSlab) {
     const TileTotals TT{Z.tsum(sw), Q.tt_rows, S.nstrips, Q.tt_group};
     const ScreenCtlArgs KA{nullptr, nullptr, 0, 0, 0, 0};
@@ -446,7 +446,7 @@ void enqueue_update(Solve& Z, const plan::Step& Q) {
                            price < 1.0e9 ? (int)price : 1000000000, Z.O.screening >= 2 ? Z.O.screening : 1024};
     hipLaunchKernelGGL(reduce_update_kernel, merged_grid, merged_block, 0, stream, RA, UA, TT, KA);
   } else {
-    hipLaunchKernelGGL(reduce_kernel, merged_grid, dim3(kReduceThreads), 0, stream, RA);
+    hipLaunchKernelGGL(reduce_kernel, dim3(S.nbm + S.nbn), dim3(kReduceThreads), 0, stream, RA);
     hipLaunchKernelGGL(update_kernel, dim3(ceil_div(Z.m + Z.n, kReduceThreads)), dim3(kReduceThreads), 0, stream, UA);
   }
 }

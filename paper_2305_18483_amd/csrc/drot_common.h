@@ -193,3 +193,12 @@ struct FusedUpdateArgs {
   float* varphi_out;
   int nseg, ntr;
 };
+
+// Launch with, in profile mode, a pair of events that take the kernel's own start and end as the hardware stamps
+// them (the HIP extension launch); without events the plain launch, which is also what a stream capture accepts.
+template <typename... KArgs, typename... Args>
+inline void launch_timed(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, hipEvent_t e0, hipEvent_t e1,
+                         Args&&... args) {
+  if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, e0, e1, 0, static_cast<KArgs>(args)...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, stream, static_cast<KArgs>(args)...);
+}

@@ -165,11 +165,11 @@ __global__ __launch_bounds__(64 * NW) void resident_kernel(ResidentArgs A) {
 template <int CPL>
 void launch_resident(const ResidentArgs& RS, hipStream_t stream, hipEvent_t e0, hipEvent_t e1) {
   const int m = RS.m;  // (e0, e1: events that take the kernel's own start and end, or null)
-  if (m <= 16) hipExtLaunchKernelGGL((resident_kernel<1, 16, CPL>), dim3(1), dim3(1024), 0, stream, e0, e1, 0, RS);
-  else if (m <= 32) hipExtLaunchKernelGGL((resident_kernel<2, 16, CPL>), dim3(1), dim3(1024), 0, stream, e0, e1, 0, RS);
-  else if (m <= 64) hipExtLaunchKernelGGL((resident_kernel<4, 16, CPL>), dim3(1), dim3(1024), 0, stream, e0, e1, 0, RS);
-  else if constexpr (CPL < 4) hipExtLaunchKernelGGL((resident_kernel<8, 16, CPL>), dim3(1), dim3(1024), 0, stream, e0, e1, 0, RS);
-  else hipExtLaunchKernelGGL((resident_kernel<16, 8, CPL>), dim3(1), dim3(512), 0, stream, e0, e1, 0, RS);
+  if (m <= 16) launch_timed((resident_kernel<1, 16, CPL>), dim3(1), dim3(1024), stream, e0, e1, RS);
+  else if (m <= 32) launch_timed((resident_kernel<2, 16, CPL>), dim3(1), dim3(1024), stream, e0, e1, RS);
+  else if (m <= 64) launch_timed((resident_kernel<4, 16, CPL>), dim3(1), dim3(1024), stream, e0, e1, RS);
+  else if constexpr (CPL < 4) launch_timed((resident_kernel<8, 16, CPL>), dim3(1), dim3(1024), stream, e0, e1, RS);
+  else launch_timed((resident_kernel<16, 8, CPL>), dim3(1), dim3(512), stream, e0, e1, RS);
 }
 
 // Working copy of the cost for the weighted l1 term: out[i][j] = C[i][j] + W[i][j] (pitch ld; the

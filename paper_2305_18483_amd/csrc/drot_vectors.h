@@ -357,21 +357,70 @@ struct ScreenCtlArgs {
   int max_since;         // renew after this many lean sweeps at the latest
 };
 
-// (8 waves: every workgroup of a 40000-entry problem is resident at once.  The tile totals are dealt
-// out to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...)
+// Workgroups of 8 waves own 256 rows or 256 columns each.  Partial sums are fetched four entries to a lane
+// (128-bit loads: the rows of the partial sums are pitched at multiples of 64 entries), so a wave's ten loads
+// cover what forty did with one entry per lane, and the totals of the tiles, which every workgroup adds up
+// for itself, are added up a quarter as often.  Per entry the order of the additions is the one of
+// reduce_kernel: 16 interleaved shares, each in order, then the fixed tree.  The tile totals are dealt out
+// to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...
 constexpr int kMergedWaves = 8;
+constexpr int kMergedEntries = 256;  // rows or columns per workgroup
+
+typedef double d4v __attribute__((ext_vector_type(4)));
+
+// One of the 16 shares of four entries' partial sums when G consecutive rows of the partials are added in
+// fp32 first (G = 1: none are).  share, nparts, nrows, pitch are wave-uniform; i4: the lane's first entry,
+// clamped so that the four stay inside a row of the partials.
+typedef int i4v __attribute__((ext_vector_type(4)));
+
+template <int G>
+__device__ __forceinline__ d4v gather4(const float* __restrict__ part, int share, int nparts, int nrows, int i4, int pitch,
+                                       i4v& nz) {  // nz (G = 1 only): nonzero partials seen per entry
+  constexpr int kStride = 16, kBatch = G == 1 ? 8 : (G == 4 ? 2 : 1);  // (8 loads in flight per batch)
+  d4v acc = {0.0, 0.0, 0.0, 0.0};
+  for (int k0 = share; k0 < nparts; k0 += kStride * kBatch) {
+    f4v v[kBatch][G];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used;
+        const f4v w = *reinterpret_cast<const f4v*>(part + (size_t)min(k, nrows - 1) * pitch + i4);  // no branch)
+        v[b][g] = k < nrows ? w : f4v{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b)
+      if (k0 + b * kStride < nparts) {
+        f4v t = v[b][0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) t += v[b][g];
+        if (G == 1) {
+          nz.x += t.x != 0.f ? 1 : 0;
+          nz.y += t.y != 0.f ? 1 : 0;
+          nz.z += t.z != 0.f ? 1 : 0;
+          nz.w += t.w != 0.f ? 1 : 0;
+        }
+        acc.x += (double)t.x;
+        acc.y += (double)t.y;
+        acc.z += (double)t.z;
+        acc.w += (double)t.w;
+      }
+  }
+  return acc;
+}
 
 __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T,
                                                                           ScreenCtlArgs K) {
   // (the stop flag travels with the other loads and is tested before the first store: a test up
   // front would put one more trip to memory ahead of everything)
   const int stop = *A.V.done;
-  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW);
-  __shared__ double red[16 * 64];
+  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW), kE = kMergedEntries;
+  __shared__ double red[16 * kE];
   __shared__ double eta_part[kShares / 64];
-  __shared__ int nzw[NW];
+  __shared__ int nzw[NW][kE / 64];
   __shared__ int readw[NW];
   const int t = threadIdx.x;
+  const int wv = __builtin_amdgcn_readfirstlane(t >> 6), ln = t & 63;
   // the schedule keeper adds up what the lean sweep read (its loads leave with everybody else's)
   const bool keeper = K.mode == 2 && blockIdx.x == gridDim.x - 1;
   int nread = 0, renewed = 0;
@@ -389,16 +438,18 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       for (int b = 0; b < kBatch; ++b) nread += v[b];
     }
   }
-  // eq. (6) inputs of this thread's entry, fetched early
-  const bool rows = (int)blockIdx.x < A.nbm;
-  const int idx = (rows ? (int)blockIdx.x : (int)blockIdx.x - A.nbm) * 64 + t;
-  const bool owner = t < 64 && idx < (rows ? A.m : A.n);
+  // which 256 rows or columns; eq. (6) inputs of this thread's entry (threads 0 .. 255), fetched early
+  const int nwm = (A.m + kE - 1) / kE;
+  const bool rows = (int)blockIdx.x < nwm;
+  const int base = (rows ? (int)blockIdx.x : (int)blockIdx.x - nwm) * kE;
+  const int len = rows ? A.m : A.n, pitch = rows ? A.mp : A.np;
+  const int idx = base + t;
+  const bool owner = t < kE && idx < len;
   const double ab_in = owner ? (rows ? U.a_in[idx] : U.b_in[idx]) : 0.0;
+  const float pq = owner ? (rows ? A.p[idx] : A.q[idx]) : 0.f;
   const double theta = A.V.theta[U.par], sum_p = *A.V.sum_p;
-  const float pq = reduce_entry_pq(A);
   // the shares of the tile totals: batches of independent loads, added in index order.  Share v = 64 w + lane of
   // accumulator s stands at entry U + lane with U wave-uniform: a scalar base address plus the lane
-  const int wv = __builtin_amdgcn_readfirstlane(t >> 6), ln = t & 63;
   double acc[kPerThread];
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
@@ -439,8 +490,27 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       }
     }
   }
-  int nz;
-  reduce_gather<NW>(A, red, nz);
+  // the partial sums of this workgroup's 256 entries: wave w forms the shares w and w + 8 of the lane's four
+  // entries (lanes past the end of a row of partials fetch its last four; nobody reads what they leave)
+  const int i4 = min(base + 4 * ln, pitch - 4);
+  const bool grouped = !rows && A.cgroup > 1;
+  const int nparts = rows ? A.nseg : grouped ? (A.ntr + A.cgroup - 1) / A.cgroup : A.ntr;
+  const int nrows_part = rows ? A.nseg : A.ntr;
+  const float* __restrict__ part = rows ? A.rowpart : A.colpart;
+  i4v nz4 = {0, 0, 0, 0};
+#pragma unroll
+  for (int si = 0; si < 16 / NW; ++si) {
+    const int share = wv + si * NW;
+    d4v a4;
+    if (!grouped) a4 = gather4<1>(part, share, nparts, nrows_part, i4, pitch, nz4);
+    else if (A.cgroup == kColGroup) a4 = gather4<kColGroup>(part, share, nparts, nrows_part, i4, pitch, nz4);
+    else a4 = gather4<kPointsColGroup>(part, share, nparts, nrows_part, i4, pitch, nz4);
+    double* dst = red + share * kE + 4 * ln;
+    dst[0] = a4.x;
+    dst[1] = a4.y;
+    dst[2] = a4.z;
+    dst[3] = a4.w;
+  }
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
     const double w = wave_sum_f64(acc[s]);
@@ -450,9 +520,15 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nread += __shfl_xor(nread, off, 64);
   }
-  if ((t & 63) == 0) {
-    nzw[t >> 6] = nz;
-    readw[t >> 6] = nread;
+  if (ln == 0) readw[wv] = nread;
+  {  // nonzero partials per block of 64 entries (16 lanes): the entries that exist only
+    const int e0 = base + 4 * ln;
+    int cnt = (e0 < len ? nz4.x : 0) + (e0 + 1 < len ? nz4.y : 0) + (e0 + 2 < len ? nz4.z : 0) + (e0 + 3 < len ? nz4.w : 0);
+    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);   // the first four steps of wave_sum: the sum of
+    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);   // each row of 16 lanes, in every lane of it
+    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
+    cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x140, 0xF, 0xF, false);
+    if ((ln & 15) == 0) nzw[wv][ln >> 4] = cnt;
   }
   __syncthreads();
   if (stop) return;
@@ -475,11 +551,24 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       if (paid >= K.price || since >= K.max_since) K.ctl[kCtlRenew] = 1;
     }
   }
-  const double res = reduce_finish<NW>(A, red, nzw, pq);
-  if (t >= 64) return;
-  double total = 0.0;
-  for (int k = 0; k < kShares / 64; ++k) total += eta_part[k];
-  const double eta = (total - sum_p) / ((double)A.m + (double)A.n);
+  if (t >= kE) return;  // (waves 0 .. 3 finish: one entry per thread, one block of 64 entries per wave)
+  // the 16 shares of the entry (the fixed tree sum_partials_16 ends with), the residual, the block's sums
+  double w[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) w[k] = red[k * kE + t];
+  const double total_e = (((w[0] + w[8]) + (w[4] + w[12])) + ((w[2] + w[10]) + (w[6] + w[14]))) +
+                         (((w[1] + w[9]) + (w[5] + w[13])) + ((w[3] + w[11]) + (w[7] + w[15])));
+  double res = 0.0;
+  if (owner) {
+    res = total_e - (double)pq;
+    (rows ? A.V.r : A.V.s)[idx] = res;
+  }
+  const double sum = wave_sum_f64(res), sumsq = wave_sum_f64(res * res);
+  const int blk = (rows ? 0 : A.nbm) + (base >> 6) + wv;  // this wave's block of 64 entries
+  const bool blk_exists = (base >> 6) + wv < (rows ? A.nbm : A.nbn);
+  double eta_total = 0.0;
+  for (int k = 0; k < kShares / 64; ++k) eta_total += eta_part[k];
+  const double eta = (eta_total - sum_p) / ((double)A.m + (double)A.n);
   const double cst = 2.0 * eta - theta;
   if (owner) {
     if (rows) {
@@ -489,6 +578,16 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       A.V.varphi[idx] = (float)((ab_in - 2.0 * res + cst) / (double)A.m);
       U.b_out[idx] = ab_in - res;
     }
+  }
+  if (ln == 0 && blk_exists) {
+    A.V.part[blk] = sum;
+    A.V.part[A.nbm + A.nbn + blk] = sumsq;
+  }
+  // rows: how many of the block's row-segment sums are not zero (the density of the plan the host steers by)
+  if (ln == 0 && blk_exists) {
+    int cnt = 0;
+    for (int k = 0; k < NW; ++k) cnt += nzw[k][wv];
+    A.V.part[2 * (A.nbm + A.nbn) + blk] = rows ? (double)cnt : 0.0;
   }
   if (blockIdx.x == 0 && t == 0) A.V.theta[U.par ^ 1] = theta - eta;
 }
