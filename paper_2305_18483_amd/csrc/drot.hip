@@ -432,11 +432,18 @@ void enqueue_update(Solve& Z, const plan::Step& Q) {
   UA.par = (int)((sw - 1) & 1);
   UA.tilesum = S.small ? Z.tsum(sw) : nullptr;
   UA.ntiles = S.small_slab ? S.nstrips * Z.P.nruns : S.ntiles;
-  const dim3 merged_grid(ceil_div(Z.m, kMergedEntries) + ceil_div(Z.n, kMergedEntries)), merged_block(64 * kMergedWaves);
+  // (four entries per lane where that still leaves a workgroup for every other compute unit)
+  const bool wide = ceil_div(Z.m, 256) + ceil_div(Z.n, 256) >= 64;
+  const int per_wg = wide ? 256 : 64;
+  const dim3 merged_grid(ceil_div(Z.m, per_wg) + ceil_div(Z.n, per_wg)), merged_block(64 * kMergedWaves);
+  auto merged = [&](const TileTotals& TT, const ScreenCtlArgs& KA) {
+    if (wide) hipLaunchKernelGGL(reduce_update_kernel<4>, merged_grid, merged_block, 0, stream, RA, UA, TT, KA);
+    else hipLaunchKernelGGL(reduce_update_kernel<1>, merged_grid, merged_block, 0, stream, RA, UA, TT, KA);
+  };
   if (Q.update == plan::kMergedSlab) {
     const TileTotals TT{Z.tsum(sw), Q.tt_rows, S.nstrips, Q.tt_group};
     const ScreenCtlArgs KA{nullptr, nullptr, 0, 0, 0, 0};
-    hipLaunchKernelGGL(reduce_update_kernel, merged_grid, merged_block, 0, stream, RA, UA, TT, KA);
+    merged(TT, KA);
   } else if (Q.update == plan::kMergedTiles) {
     const TileTotals TT{Z.tsum(sw), Q.tt_rows, S.nseg, Q.tt_group};
     // (the price of a renewal: all row segments of C, read by a sweep that streams them better than
@@ -444,7 +451,7 @@ void enqueue_update(Solve& Z, const plan::Step& Q) {
     const double price = 0.75 * (double)Z.m * (double)S.nseg;
     const ScreenCtlArgs KA{h->screen_ctl, h->wg_reads, S.nseg * ceil_div(S.ntr_tall, kLeanWaves), Q.ctl_mode,
                            price < 1.0e9 ? (int)price : 1000000000, Z.O.screening >= 2 ? Z.O.screening : 1024};
-    hipLaunchKernelGGL(reduce_update_kernel, merged_grid, merged_block, 0, stream, RA, UA, TT, KA);
+    merged(TT, KA);
   } else {
     hipLaunchKernelGGL(reduce_kernel, dim3(S.nbm + S.nbn), dim3(kReduceThreads), 0, stream, RA);
     hipLaunchKernelGGL(update_kernel, dim3(ceil_div(Z.m + Z.n, kReduceThreads)), dim3(kReduceThreads), 0, stream, UA);

@@ -357,64 +357,76 @@ struct ScreenCtlArgs {
   int max_since;         // renew after this many lean sweeps at the latest
 };
 
-// Workgroups of 8 waves own 256 rows or 256 columns each.  Partial sums are fetched four entries to a lane
-// (128-bit loads: the rows of the partial sums are pitched at multiples of 64 entries), so a wave's ten loads
-// cover what forty did with one entry per lane, and the totals of the tiles, which every workgroup adds up
-// for itself, are added up a quarter as often.  Per entry the order of the additions is the one of
-// reduce_kernel: 16 interleaved shares, each in order, then the fixed tree.  The tile totals are dealt out
-// to 1024 shares whatever the number of threads, share v taking the entries v, v + 1024, ...
+// Workgroups of 8 waves own 64 V rows or columns each, V = 4 for large problems: partial sums are fetched four
+// entries to a lane (128-bit loads: the rows of the partial sums are pitched at multiples of 64 entries), so a
+// wave's ten loads cover what forty did with one entry per lane, and the totals of the tiles, which every
+// workgroup adds up for itself, are added up a quarter as often.  V = 1 where that would leave most compute
+// units without a workgroup.  Per entry the order of the additions is the one of reduce_kernel: 16 interleaved
+// shares, each in order, then the fixed tree.  The tile totals are dealt out to 1024 shares whatever the
+// number of threads, share v taking the entries v, v + 1024, ...
 constexpr int kMergedWaves = 8;
-constexpr int kMergedEntries = 256;  // rows or columns per workgroup
 
-typedef double d4v __attribute__((ext_vector_type(4)));
+// One of the 16 shares of V entries' partial sums (the lane's entries i0 .. i0 + V - 1) when G consecutive rows
+// of the partials are added in fp32 first (G = 1: none are).  share, nparts, nrows, pitch are wave-uniform; i0 is
+// clamped so that the entries stay inside a row of the partials.  nz (G = 1 only): nonzero partials seen per entry.
+template <int V>
+struct PartialLoad;
+template <>
+struct PartialLoad<4> {
+  static __device__ __forceinline__ void load(const float* __restrict__ p, float (&v)[4]) {
+    const f4v w = *reinterpret_cast<const f4v*>(p);
+    v[0] = w.x;
+    v[1] = w.y;
+    v[2] = w.z;
+    v[3] = w.w;
+  }
+};
+template <>
+struct PartialLoad<1> {
+  static __device__ __forceinline__ void load(const float* __restrict__ p, float (&v)[1]) { v[0] = *p; }
+};
 
-// One of the 16 shares of four entries' partial sums when G consecutive rows of the partials are added in
-// fp32 first (G = 1: none are).  share, nparts, nrows, pitch are wave-uniform; i4: the lane's first entry,
-// clamped so that the four stay inside a row of the partials.
-typedef int i4v __attribute__((ext_vector_type(4)));
-
-template <int G>
-__device__ __forceinline__ d4v gather4(const float* __restrict__ part, int share, int nparts, int nrows, int i4, int pitch,
-                                       i4v& nz) {  // nz (G = 1 only): nonzero partials seen per entry
+template <int G, int V>
+__device__ __forceinline__ void gather_shares(const float* __restrict__ part, int share, int nparts, int nrows, int i0,
+                                              int pitch, double (&acc)[V], int (&nz)[V]) {
   constexpr int kStride = 16, kBatch = G == 1 ? 8 : (G == 4 ? 2 : 1);  // (8 loads in flight per batch)
-  d4v acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.0;
   for (int k0 = share; k0 < nparts; k0 += kStride * kBatch) {
-    f4v v[kBatch][G];
+    float v[kBatch][G][V];
 #pragma unroll
     for (int b = 0; b < kBatch; ++b)
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used;
-        const f4v w = *reinterpret_cast<const f4v*>(part + (size_t)min(k, nrows - 1) * pitch + i4);  // no branch)
-        v[b][g] = k < nrows ? w : f4v{0.f, 0.f, 0.f, 0.f};
+        const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used; no
+        PartialLoad<V>::load(part + (size_t)min(k, nrows - 1) * pitch + i0, v[b][g]);  // branch, so that all loads leave together)
+        if (k >= nrows) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) v[b][g][e] = 0.f;
+        }
       }
 #pragma unroll
     for (int b = 0; b < kBatch; ++b)
       if (k0 + b * kStride < nparts) {
-        f4v t = v[b][0];
 #pragma unroll
-        for (int g = 1; g < G; ++g) t += v[b][g];
-        if (G == 1) {
-          nz.x += t.x != 0.f ? 1 : 0;
-          nz.y += t.y != 0.f ? 1 : 0;
-          nz.z += t.z != 0.f ? 1 : 0;
-          nz.w += t.w != 0.f ? 1 : 0;
+        for (int e = 0; e < V; ++e) {
+          float t = v[b][0][e];
+#pragma unroll
+          for (int g = 1; g < G; ++g) t += v[b][g][e];
+          if (G == 1) nz[e] += t != 0.f ? 1 : 0;
+          acc[e] += (double)t;
         }
-        acc.x += (double)t.x;
-        acc.y += (double)t.y;
-        acc.z += (double)t.z;
-        acc.w += (double)t.w;
       }
   }
-  return acc;
 }
 
+template <int V>
 __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T,
                                                                           ScreenCtlArgs K) {
   // (the stop flag travels with the other loads and is tested before the first store: a test up
   // front would put one more trip to memory ahead of everything)
   const int stop = *A.V.done;
-  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW), kE = kMergedEntries;
+  constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW), kE = 64 * V;
   __shared__ double red[16 * kE];
   __shared__ double eta_part[kShares / 64];
   __shared__ int nzw[NW][kE / 64];
@@ -438,7 +450,7 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       for (int b = 0; b < kBatch; ++b) nread += v[b];
     }
   }
-  // which 256 rows or columns; eq. (6) inputs of this thread's entry (threads 0 .. 255), fetched early
+  // which rows or columns; eq. (6) inputs of this thread's entry (threads 0 .. 64 V - 1), fetched early
   const int nwm = (A.m + kE - 1) / kE;
   const bool rows = (int)blockIdx.x < nwm;
   const int base = (rows ? (int)blockIdx.x : (int)blockIdx.x - nwm) * kE;
@@ -490,26 +502,26 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       }
     }
   }
-  // the partial sums of this workgroup's 256 entries: wave w forms the shares w and w + 8 of the lane's four
-  // entries (lanes past the end of a row of partials fetch its last four; nobody reads what they leave)
-  const int i4 = min(base + 4 * ln, pitch - 4);
+  // the partial sums of this workgroup's entries: wave w forms the shares w and w + 8 of the lane's V entries
+  // (lanes past the end of a row of partials fetch its last ones; nobody reads what they leave)
+  const int i0 = min(base + V * ln, pitch - V);
   const bool grouped = !rows && A.cgroup > 1;
   const int nparts = rows ? A.nseg : grouped ? (A.ntr + A.cgroup - 1) / A.cgroup : A.ntr;
   const int nrows_part = rows ? A.nseg : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
-  i4v nz4 = {0, 0, 0, 0};
+  int nzv[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) nzv[e] = 0;
 #pragma unroll
   for (int si = 0; si < 16 / NW; ++si) {
     const int share = wv + si * NW;
-    d4v a4;
-    if (!grouped) a4 = gather4<1>(part, share, nparts, nrows_part, i4, pitch, nz4);
-    else if (A.cgroup == kColGroup) a4 = gather4<kColGroup>(part, share, nparts, nrows_part, i4, pitch, nz4);
-    else a4 = gather4<kPointsColGroup>(part, share, nparts, nrows_part, i4, pitch, nz4);
-    double* dst = red + share * kE + 4 * ln;
-    dst[0] = a4.x;
-    dst[1] = a4.y;
-    dst[2] = a4.z;
-    dst[3] = a4.w;
+    double av[V];
+    if (!grouped) gather_shares<1, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
+    else if (A.cgroup == kColGroup) gather_shares<kColGroup, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
+    else gather_shares<kPointsColGroup, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
+    double* dst = red + share * kE + V * ln;
+#pragma unroll
+    for (int e = 0; e < V; ++e) dst[e] = av[e];
   }
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
@@ -521,14 +533,21 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
     for (int off = 32; off > 0; off >>= 1) nread += __shfl_xor(nread, off, 64);
   }
   if (ln == 0) readw[wv] = nread;
-  {  // nonzero partials per block of 64 entries (16 lanes): the entries that exist only
-    const int e0 = base + 4 * ln;
-    int cnt = (e0 < len ? nz4.x : 0) + (e0 + 1 < len ? nz4.y : 0) + (e0 + 2 < len ? nz4.z : 0) + (e0 + 3 < len ? nz4.w : 0);
+  {  // nonzero partials per block of 64 entries (64 / V lanes): the entries that exist only
+    int cnt = 0;
+#pragma unroll
+    for (int e = 0; e < V; ++e) cnt += base + V * ln + e < len ? nzv[e] : 0;
     cnt += __builtin_amdgcn_update_dpp(0, cnt, 0xB1, 0xF, 0xF, false);   // the first four steps of wave_sum: the sum of
     cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x4E, 0xF, 0xF, false);   // each row of 16 lanes, in every lane of it
     cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x141, 0xF, 0xF, false);
     cnt += __builtin_amdgcn_update_dpp(0, cnt, 0x140, 0xF, 0xF, false);
-    if ((ln & 15) == 0) nzw[wv][ln >> 4] = cnt;
+    if (V == 4) {
+      if ((ln & 15) == 0) nzw[wv][ln >> 4] = cnt;
+    } else {  // the whole wave is one block: the four rows of lanes
+      const int whole = (__builtin_amdgcn_readlane(cnt, 0) + __builtin_amdgcn_readlane(cnt, 16)) +
+                        (__builtin_amdgcn_readlane(cnt, 32) + __builtin_amdgcn_readlane(cnt, 48));
+      if (ln == 0) nzw[wv][0] = whole;
+    }
   }
   __syncthreads();
   if (stop) return;
@@ -551,7 +570,7 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
       if (paid >= K.price || since >= K.max_since) K.ctl[kCtlRenew] = 1;
     }
   }
-  if (t >= kE) return;  // (waves 0 .. 3 finish: one entry per thread, one block of 64 entries per wave)
+  if (t >= kE) return;  // (waves 0 .. V - 1 finish: one entry per thread, one block of 64 entries per wave)
   // the 16 shares of the entry (the fixed tree sum_partials_16 ends with), the residual, the block's sums
   double w[16];
 #pragma unroll
