@@ -349,6 +349,12 @@ inline Step next_sweep(const Static& S, const Problem& P, const Options& O, Stat
       Q.tt_rows = lean ? ceil_div(S.ntr_tall, kColGroup) : S.ntr_tall;
       Q.tt_group = lean ? 1 : kColGroup;
       Q.ctl_mode = lean ? 2 : Q.refresh ? 1 : 0;
+    } else if (P.from_points) {
+      // (the point-cloud sweeps store the totals of their 32-row tiles, the screened one of its strips of eight)
+      Q.update = kMergedTiles;
+      Q.tilesum = true;
+      Q.tt_rows = Q.sweep == kPointsLean ? ceil_div(P.m, kStripRows) : S.ntr;
+      Q.tt_group = Q.sweep == kPointsLean ? 1 : kPointsColGroup;
     } else {
       Q.update = kSeparate;
     }

@@ -142,6 +142,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
 
   // sweep phase, as in sweep_body with the cost taken from the tile of inner products
   f4v colacc = {0.f, 0.f, 0.f, 0.f};
+  float wave_total = 0.f;  // the total of this wave's rows (the tile's total gives eta to the one-launch vector update)
   if (nrows > 0) {
     const float rho = A.rho, scale = A.scale, cs = Pt.cost_scale;
     float rowkeep = 0.f, mkeep = 0.f, m2keep = 0.f;
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
         colacc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
         rowkeep = (lane == u) ? tot : rowkeep;
+        wave_total += tot;
         if (REFRESH) {  // (columns past n carry the mask value in vp: they never win the maximum)
           const f4v t = {fmaf(-rho, c.x, vp.x), fmaf(-rho, c.y, vp.y), fmaf(-rho, c.z, vp.z), fmaf(-rho, c.w, vp.w)};
           float mm, mm2;
@@ -189,6 +191,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void sweep_points_kernel(SweepArg
   }
   if (REFRESH && tr == 0 && wave == 0) *reinterpret_cast<f4u*>(varphi0 + j0) = vp;  // (past n both hold the mask value)
   write_col_partials<kSweepWaves>(colacc, lane, wave, seg, tr, A.n, A.np, A.colpart);
+  if (A.tilesum) write_tile_total<kSweepWaves>(wave_total, lane, wave, seg, tr, A.tilesum);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -233,11 +236,12 @@ __device__ __forceinline__ void xcd_strip(int nseg, int nstrips, int& seg, int& 
 }
 
 template <bool NT>
-__global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs Pt, ScreenArgs SC) {
+__global__ __launch_bounds__(256, 6) void lean_points_kernel(SweepArgs A, PointArgs Pt, ScreenArgs SC) {
   const int stop = *A.done;
   __shared__ float ctile[16][kDotPitch];  // a block's costs-to-be (inner products); the column fold at the very end
   __shared__ unsigned long long masks[4];
   __shared__ unsigned char list[kStripRows];
+  __shared__ float totals[kPointsColGroup];
   static_assert(sizeof(ctile) >= sizeof(float) * kPointsColGroup * kSegCols, "the column fold reuses the tile");
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -302,6 +306,7 @@ __global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs
     else xpre1 = load4(Xq, nvalid);
   }
   f4v tile_acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}, pair_acc = {0.f, 0.f, 0.f, 0.f};
+  float tile_tot[2] = {0.f, 0.f}, pair_tot = 0.f;  // the totals, added up as the full sweep adds them: rows of a pair, pairs of a tile
   int cur_pair = -1;  // pair of rows (0 .. 31 within this wave's 64 rows) pair_acc belongs to
   float rowkeep = 0.f;
   for (int b0 = 0; b0 < total; b0 += 16) {
@@ -377,24 +382,42 @@ __global__ __launch_bounds__(256) void lean_points_kernel(SweepArgs A, PointArgs
         else store4(Xp, v, nvalid);
       }
       if ((u >> 1) != cur_pair) {  // a new pair of rows: the finished one joins its tile's sum
-        if (cur_pair >= 0) tile_acc[cur_pair >> 4] += pair_acc;
+        if (cur_pair >= 0) {
+          tile_acc[cur_pair >> 4] += pair_acc;
+          tile_tot[cur_pair >> 4] += pair_tot;
+        }
         pair_acc = f4v{0.f, 0.f, 0.f, 0.f};
+        pair_tot = 0.f;
         cur_pair = u >> 1;
       }
       pair_acc += v;
       const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
+      pair_tot += tot;
       rowkeep = (lane == u) ? tot : rowkeep;
     }
     __syncthreads();  // (the tile is overwritten by the next block, and by the fold below)
   }
-  if (cur_pair >= 0) tile_acc[cur_pair >> 4] += pair_acc;
+  if (cur_pair >= 0) {
+    tile_acc[cur_pair >> 4] += pair_acc;
+    tile_tot[cur_pair >> 4] += pair_tot;
+  }
   if (lane < nrows) A.rowpart[ridx] = rowkeep;
   if (threadIdx.x == 0) SC.wg_reads[strip * gridDim.x + seg] = total;  // (row segments whose cost was formed)
   // the strip's column sums: its eight 32-row tiles in order
   float* __restrict__ fold = &ctile[0][0];
   *reinterpret_cast<f4v*>(fold + (2 * wave + 0) * kSegCols + lane * 4) = tile_acc[0];
   *reinterpret_cast<f4v*>(fold + (2 * wave + 1) * kSegCols + lane * 4) = tile_acc[1];
+  if (lane == 0) {
+    totals[2 * wave + 0] = tile_tot[0];
+    totals[2 * wave + 1] = tile_tot[1];
+  }
   __syncthreads();
+  if (A.tilesum && threadIdx.x == 0) {  // the strip's total: its eight tiles in order
+    float tot = totals[0];
+#pragma unroll
+    for (int k = 1; k < kPointsColGroup; ++k) tot += totals[k];
+    A.tilesum[strip * gridDim.x + seg] = tot;
+  }
   const int t = threadIdx.x, j = seg * kSegCols + t;
   if (j < A.n) {
     float sum = fold[t];

@@ -344,7 +344,7 @@ struct TileTotals {
   const float* tilesum;  // [tile_rows][nseg], or one entry per kColGroup tile rows (tgroup = 1)
   int tile_rows;         // rows of tilesum
   int nseg;
-  int tgroup;            // kColGroup: add tile rows 4k .. 4k+3 first; 1: stored that way
+  int tgroup;            // kColGroup, kPointsColGroup: add tile rows G k .. G k + G - 1 first; 1: stored that way
 };
 
 // The lean sweep's refresh schedule rides along (last workgroup): the control words kCtlRenew ... of the screened sweeps.
@@ -356,6 +356,36 @@ struct ScreenCtlArgs {
   int price;             // rent that buys a renewal, in row segments of C
   int max_since;         // renew after this many lean sweeps at the latest
 };
+
+// A share of the tile totals when G consecutive tile rows are added in fp32 first, in order (the sweeps that
+// store one total per group of G tiles add them up that way before they store): entries e0, e0 + 1024, ...
+template <int G>
+__device__ __forceinline__ double grouped_tile_totals(const TileTotals& T, int e0_lane, int ln) {
+  constexpr int kShares = 1024, kGroups = 16 / G;  // (16 loads in flight per batch)
+  const int ngroups = ((T.tile_rows + G - 1) / G) * T.nseg;
+  double acc = 0.0;
+  for (int e0 = e0_lane; e0 - ln < ngroups; e0 += kShares * kGroups) {
+    float v[kGroups][G];
+#pragma unroll
+    for (int b = 0; b < kGroups; ++b) {
+      const int e = e0 + b * kShares;
+      const int k = e / T.nseg, sg = e - k * T.nseg;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int tr = k * G + g;
+        v[b][g] = (e < ngroups && tr < T.tile_rows) ? T.tilesum[tr * T.nseg + sg] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < kGroups; ++b) {
+      float t = v[b][0];
+#pragma unroll
+      for (int g = 1; g < G; ++g) t += v[b][g];
+      acc += (double)t;
+    }
+  }
+  return acc;
+}
 
 // Workgroups of 8 waves own 64 V rows or columns each, V = 4 for large problems: partial sums are fetched four
 // entries to a lane (128-bit loads: the rows of the partial sums are pitched at multiples of 64 entries), so a
@@ -467,25 +497,9 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   for (int s = 0; s < kPerThread; ++s) {
     acc[s] = 0.0;
     const int u0 = 64 * wv + s * 64 * NW;
-    if (T.tgroup == kColGroup) {
-      constexpr int kGroups = 4;
-      const int ngroups = ((T.tile_rows + kColGroup - 1) / kColGroup) * T.nseg;
-      for (int e0 = u0 + ln; e0 - ln < ngroups; e0 += kShares * kGroups) {
-        float v[kGroups][kColGroup];
-#pragma unroll
-        for (int b = 0; b < kGroups; ++b) {
-          const int e = e0 + b * kShares;
-          const int k = e / T.nseg, sg = e - k * T.nseg;
-#pragma unroll
-          for (int g = 0; g < kColGroup; ++g) {
-            const int tr = k * kColGroup + g;
-            v[b][g] = (e < ngroups && tr < T.tile_rows) ? T.tilesum[tr * T.nseg + sg] : 0.f;
-          }
-        }
-#pragma unroll
-        for (int b = 0; b < kGroups; ++b) acc[s] += (double)(((v[b][0] + v[b][1]) + v[b][2]) + v[b][3]);
-      }
-    } else {
+    if (T.tgroup == kColGroup) acc[s] = grouped_tile_totals<kColGroup>(T, u0 + ln, ln);
+    else if (T.tgroup == kPointsColGroup) acc[s] = grouped_tile_totals<kPointsColGroup>(T, u0 + ln, ln);
+    else {
       constexpr int kBatch = 8;
       const int ngroups = T.tile_rows * T.nseg;
       for (int u = u0; u < ngroups; u += kShares * kBatch) {

@@ -211,7 +211,7 @@ def test_gap_checks_ride_on_the_residual_checks(planlib):
 
 def test_point_clouds_and_warm_starts(planlib):
     t = trace(planlib, 3000, 3000, 5, from_points=1, reg_kind=1, checking=0)
-    assert set(t.col("sweep")) == {POINTS} and t.col("prev_sums") == [0, 1, 1, 1, 1] and set(t.col("update")) == {SEPARATE}
+    assert set(t.col("sweep")) == {POINTS} and t.col("prev_sums") == [0, 1, 1, 1, 1] and set(t.col("update")) == {MERGED_TILES}
     t = trace(planlib, 3000, 3000, 5, from_points=1, reg_kind=1, checking=0, skip_unchanged=0)
     assert set(t.col("prev_sums")) == {0}
     t = trace(planlib, 2300, 2500, 4, warm=1, reg_kind=1, checking=0, screening=1)
@@ -278,7 +278,8 @@ def test_point_cloud_variant_screens_once_the_plan_is_sparse(planlib):
     assert t.col("sweep")[96] == POINTS_LEAN and t.col("sweep")[103] == POINTS
     # column sums: eight 32-row tiles of the full sweep are added first, as the strips of the screened sweep store them
     assert t.col("ra")[5] == 625 * 16 + 8 and t.col("ra")[100] == 79 * 16 + 1 and t.col("ra")[0] == 625 * 16 + 8
-    assert set(t.col("update")) == {SEPARATE}
+    # one launch for the vector update: the sweeps store the totals of their tiles (the screened one of its strips)
+    assert set(t.col("update")) == {MERGED_TILES} and set(t.col("tilesum")) == {1}
     # small problems, or with the screening off: the full sweep only, column sums ungrouped
     t = trace(planlib, 3000, 3000, 40, from_points=1, reg_kind=1, checking=0, densities=(0.05,))
     assert set(t.col("kind")) == {0} and set(t.col("ra")) == {94 * 16 + 8}
