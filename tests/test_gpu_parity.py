@@ -980,6 +980,41 @@ def test_point_cloud_sweep_skipping_zero_segments_changes_no_bit(drot, m, n, d, 
     assert float(np.mean(zero_segments)) > 0.02  # (some segments really are skipped)
 
 
+@pytest.mark.parametrize("points", [False, True])
+def test_screening_bounds_hold_over_long_stretches_without_renewal(drot, points):
+    # thousands of sweeps, the bounds renewed only when the schedule's cap or the device's rent-or-buy rule says so
+    # (hundreds of sweeps apart): the drift of varphi since the epoch grows large against the gaps the certificate
+    # lives on, and the iterates must still be those of the sweeps that certify nothing, bit for bit
+    m, n, K = 2100, 8232, 3000
+    P = drot_inputs.random_problem(m, n, seed=2500 + int(points), d=8, reg_kind=1, lam=0.01)
+    dev = torch.device("cuda:0")
+    solver = drot.Solver(m, n, check_every=100)
+    _say(f"long screened run, {'point clouds' if points else 'stored cost'}, {m}x{n}, K={K}")
+    scale = np.float32(1.0 / P.cmax)
+    xs, xt = torch.from_numpy(P.xs).to(dev), torch.from_numpy(P.xt).to(dev)
+    C, p, q, _ = pu.to_dev(P)
+
+    def run():
+        if points:
+            r = solver.solve_points(xs, xt, float(scale), p, q, reg_kind=1, lam=P.lam, max_iters=K, tol=1e-12)
+        else:
+            r = solver.solve(C, p, q, reg_kind=1, lam=P.lam, max_iters=K, tol=1e-12)
+        phi, varphi = solver.duals(m, n, dev)
+        return r.X.clone(), phi, varphi
+
+    outs = []
+    for screening in (0, 1):
+        solver.set_screening(screening)
+        solver.set_profile(bool(screening))
+        outs.append(run())
+        if screening:
+            kinds = [r.kind for r in solver.profile_records()]
+            assert sum(k in (7, 8) for k in kinds) >= 20, kinds  # (the lean sweeps took over within the 256 sweeps profiled)
+    solver.set_profile(False)
+    for a, b in zip(outs[0], outs[1]):
+        assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("m,n,d,kind", [(2100, 8232, 8, 1), (2300, 8192, 3, 0), (1531, 9999, 6, 1)])
 def test_point_cloud_screening_changes_no_bit(drot, oracle, m, n, d, kind):
     # wide rows: once a status has reported a sparse plan the point-cloud variant forms the cost only for the row
