@@ -101,7 +101,9 @@ int drot_destroy(drot_handle h);
  *   DROT_OPT_CHECK_EVERY [100], >= 1: the residual test of Appendix C (r_primal) is evaluated on the
  *       device every this many iterations; the solve stops at the first test that passes.
  *   DROT_OPT_COMPUTE_GAP [1], 0/1: evaluate objective, duality gap and dual residual of the returned
- *       iterate (Appendix C; one read-only pass over X and C at the end of the solve).
+ *       iterate (Appendix C; one read-only pass over X and C at the end of the solve, or, where screening
+ *       bounds certify that a row segment adds nothing to any of the sums, over the other row segments
+ *       only: the same numbers, bit for bit).
  *   DROT_OPT_GAP_EVERY [0], >= 0: k >= 1 evaluates objective, duality gap and dual residual also during
  *       the solve, at every k-th residual check (iterations that are multiples of k * check_every), and
  *       records them (drot_get_checks); 0: only at the end.  See drot_set_gap_tolerance.
@@ -134,9 +136,8 @@ int drot_destroy(drot_handle h);
  *       segment whose X is zero and whose bound, plus a margin for the fp32 roundings involved, is not
  *       positive is known to stay zero: nothing of it is read, computed or written.  The iterates are those
  *       of the unscreened sweeps, bit for bit.  The bounds are renewed after 8, 16, 32, ... sweeps at first,
- *       at most 1024 apart; once the
- *       plan is known to be sparse the sweep itself decides, on the device, when the reads that weakened
- *       bounds cost it have added up to the price of new ones.  -1 screens problems of 11.5 million entries
+ *       at most 1024 apart; once the plan is known to be sparse the sweep itself decides, on the device,
+ *       when the reads that weakened bounds cost it have added up to the price of new ones.  -1 screens problems of 11.5 million entries
  *       and more (smaller ones stream all of C from the caches just as fast), 1 every problem the skipping
  *       applies to, k >= 2 the same with the bounds renewed at least every k-th sweep, 0 never.
  *   DROT_OPT_SKIP_COST [-1], -1/0/1: the even/odd scheme of the paper's GPU appendix (Section
