@@ -360,12 +360,16 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   return tile_acc;  // column sums of the tile (columns past n: 0)
 }
 
-// Four waves per workgroup, stacked along the rows: they work independently and meet once, at the
-// end, to add their tiles' column sums in the order tile 0, 1, 2, 3 (kColGroup in the reduction:
-// the sweeps that store one row of column sums per 64-row tile are added up in that order too).
+// Four waves per workgroup, stacked along the rows.  They work independently; each leaves its tile's column sums
+// in LDS, counts itself in and ends, and the one that finds itself the last adds the four tiles' sums in the
+// order tile 0, 1, 2, 3 (kColGroup in the reduction: the sweeps that store one row of column sums per 64-row
+// tile are added up in that order too) and stores them.  No wave waits for another: a wave that has little to
+// do gives its place on the SIMD to the next workgroup's at once.  (LDS serves a wave's operations in the order
+// it issued them, so a wave's sums are in place before its count is; the count starts at zero behind the one
+// barrier at the start, where nobody has anything to wait for yet.)
 constexpr int kLeanWaves = 4;
 constexpr int kColGroup = kLeanWaves;
-static_assert(64 * kLeanWaves == kSegCols, "one thread per column of the segment in the final fold");
+static_assert(64 * kLeanWaves == kSegCols, "four columns per lane of the wave that does the final fold");
 
 template <bool NT>
 __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
@@ -375,6 +379,9 @@ __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(Sweep
   __shared__ float fold[kLeanWaves][kSegCols];
   __shared__ float totals[kLeanWaves];
   __shared__ int nreads[kLeanWaves];
+  __shared__ int arrived;
+  if (threadIdx.x == 0) arrived = 0;
+  __syncthreads();
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
@@ -391,10 +398,25 @@ __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(Sweep
     totals[wave] = total;
     nreads[wave] = reads;
   }
-  __syncthreads();
-  const int t = threadIdx.x, j = seg * kSegCols + t;
-  if (j < A.n) A.colpart[(size_t)blockIdx.y * A.np + j] = ((fold[0][t] + fold[1][t]) + fold[2][t]) + fold[3][t];
-  if (t == 0) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  int before = 0;
+  if (lane == 0) before = __hip_atomic_fetch_add(&arrived, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  before = __builtin_amdgcn_readfirstlane(before);
+  if (before != kLeanWaves - 1) return;  // (somebody is still at work: they will do the rest)
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  const int c0 = lane * 4, j0 = seg * kSegCols + c0;
+  const f4v f0 = *reinterpret_cast<const f4v*>(&fold[0][c0]), f1 = *reinterpret_cast<const f4v*>(&fold[1][c0]);
+  const f4v f2 = *reinterpret_cast<const f4v*>(&fold[2][c0]), f3 = *reinterpret_cast<const f4v*>(&fold[3][c0]);
+  const f4v sum = ((f0 + f1) + f2) + f3;
+  float* __restrict__ dst = A.colpart + (size_t)blockIdx.y * A.np + j0;
+  if (j0 + 3 < A.n) {
+    *reinterpret_cast<f4v*>(dst) = sum;  // (np is a multiple of 64: 16-byte aligned)
+  } else {
+    if (j0 < A.n) dst[0] = sum.x;
+    if (j0 + 1 < A.n) dst[1] = sum.y;
+    if (j0 + 2 < A.n) dst[2] = sum.z;
+  }
+  if (lane == 0) {
     A.tilesum[blockIdx.y * gridDim.x + seg] = ((totals[0] + totals[1]) + totals[2]) + totals[3];
     SC.wg_reads[blockIdx.y * gridDim.x + seg] = (nreads[0] + nreads[1]) + (nreads[2] + nreads[3]);
   }
