@@ -219,8 +219,8 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
 }
 
 // The screened sweep for plans known to be sparse (a few percent of the row segments left to
-// process): one wave owns a whole 64 x 256 tile, lane l holding the line flags, phi and M of row l.
-// It decides all 64 rows at once and then walks through the rows left over, four at a time (their
+// process): one wave owns a whole 64 x 256 tile, lane l holding the line flags, phi and the bounds of row l.
+// It decides all 64 rows at once and then walks through the rows left over, three at a time (their
 // loads overlap; the arithmetic stays in row order).  The waves of a workgroup work on their own
 // and meet once, at the end (screened_lean_kernel).  8 times fewer waves than the tile of 8 waves x
 // 8 rows, and the same bits: the rows of every group of 8 are added up in order and the 8 groups in
