@@ -20,6 +20,9 @@ HIPCC_FLAGS = [
     # device code only: the kernels never see a NaN (the host rejects NaN arguments; infinities are used and kept),
     # so maxima need no quieting of their inputs and fold into the cross-lane steps of the wave reductions
     "-Xarch_device", "-fno-honor-nans",
+    # a product and a sum become one fused operation only where the source says fmaf: the sweeps promise each other
+    # the same bits, and with fusion left to the compiler that would hang on which statements share a basic block
+    "-ffp-contract=off",
     "-Wall", "-Wno-unused-function",
 ]
 

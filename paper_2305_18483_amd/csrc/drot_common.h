@@ -27,6 +27,17 @@ __device__ __forceinline__ float dpp_mov(float v) {
 // vector, as in bit_cast(int, v.y), reads the vector's first element.)
 __device__ __forceinline__ int fbits(float f) { return __builtin_bit_cast(int, f); }
 
+// A word every lane needs, fetched through the vector memory path (an atomic load is never made a scalar one).
+// Scalar loads share their counter with the LDS operations and the kernel arguments, and waiting on that counter
+// waits for all of them: a flag fetched that way sits in front of the first wait for an argument, one trip to
+// memory ahead of every other load.  These count with the vector loads and arrive with them.
+__device__ __forceinline__ int vector_load_uniform(const int* p) {
+  return __builtin_amdgcn_readfirstlane(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+}
+__device__ __forceinline__ double vector_load_uniform(const double* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // Sum over the 64 lanes of a wave; the result is wave-uniform (read back from lane 63).
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_mov<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(64 * kSweepWaves) void screened_sweep_kernel(SweepA
 // reads: how many row segments of C it fetched.
 template <bool EDGE, bool NT>
 __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const ScreenArgs& SC, int lane, int seg, int tr,
-                                                  int stop, bool renew, float& tile_total, int& reads) {
+                                                  int& stop, float& tile_total, int& reads) {
   const int j0 = seg * kSegCols + lane * 4;
   const int nmem = EDGE ? min(max(A.n_mem - j0, 0), 4) : 4;
   const int r0 = tr * 64;
@@ -256,6 +256,12 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
     if (SC.lines_in) oldlines = SC.lines_in[ridx];
     else oldlines = (A.rowpart_prev == nullptr || fbits(A.rowpart_prev[ridx]) != 0) ? 0xffu : 0u;
   }
+  // The stop flag and the renewal word travel with the loads above (asked for before them, a wave would
+  // sit out their latency with nothing of its own in flight); both are tested before the first store.
+  __builtin_amdgcn_sched_barrier(0);
+  stop = *A.done;
+  const bool renew = SC.ctl[kCtlRenew] != 0;
+  __builtin_amdgcn_sched_barrier(0);
   // (renew, wave-uniform: this sweep records new bounds against the varphi of now; it certifies
   // nothing, walks through all its rows and takes the maximum of varphi_j - rho C_ij of each)
   const f4v dv = vp - vp0;
@@ -281,10 +287,12 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   constexpr int kWalk = 3;  // rows fetched together: their loads overlap, the arithmetic stays in row order
   while (todo != 0) {
     int row[kWalk];
+    unsigned wl[kWalk];  // the lines of the new row to write
     f4v c[kWalk], x[kWalk];
 #pragma unroll
     for (int b = 0; b < kWalk; ++b) {
       row[b] = -1;
+      wl[b] = 0;
       c[b] = f4v{0.f, 0.f, 0.f, 0.f};
       x[b] = f4v{0.f, 0.f, 0.f, 0.f};
       if (todo != 0) {
@@ -296,6 +304,9 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
         if ((ol >> myline) & 1) x[b] = ld4<EDGE, NT>(Xp + row[b] * ldx, nmem);
       }
     }
+    // (everything fetched has arrived from here on: said once, for all the rows, so that no row's arithmetic and
+    // no store below waits again, which on this counter would mean waiting for the stores issued before it)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #pragma unroll
     for (int b = 0; b < kWalk; ++b) {
       const int u = row[b];
@@ -320,7 +331,8 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
         nzb |= nzb >> 1;
         const unsigned nl = (unsigned)(((nzb & 0x0101010101010101ull) * 0x0102040810204080ull) >> 56);
         const unsigned ol = (unsigned)__builtin_amdgcn_readlane((int)oldlines, u);
-        if (((ol | nl) >> myline) & 1) st4<EDGE, NT>(Xp + u * ldx, v, nmem);
+        x[b] = v;
+        wl[b] = ol | nl;
         newlines = (lane == u) ? nl : newlines;
         group_acc += v;
         const float tot = wave_sum((v.x + v.y) + (v.z + v.w));
@@ -337,6 +349,12 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
         }
       }
     }
+    // the stores leave together, after the arithmetic of all the rows fetched together: the one counter for loads
+    // and stores cannot tell a store still on its way from a load, so a row worked on after another row's store
+    // would wait for that store to come back
+#pragma unroll
+    for (int b = 0; b < kWalk; ++b)
+      if (row[b] >= 0 && ((wl[b] >> myline) & 1)) st4<EDGE, NT>(Xp + row[b] * ldx, x[b], nmem);
   }
   if (group >= 0) {
     tile_acc += group_acc;
@@ -373,9 +391,6 @@ static_assert(64 * kLeanWaves == kSegCols, "four columns per lane of the wave th
 
 template <bool NT>
 __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(SweepArgs A, ScreenArgs SC, int ntiles_rows) {
-  // (the stop flag is fetched along with a wave's first loads and tested before its first store)
-  const int stop = *A.done;
-  const bool renew = SC.ctl[kCtlRenew] != 0;
   __shared__ float fold[kLeanWaves][kSegCols];
   __shared__ float totals[kLeanWaves];
   __shared__ int nreads[kLeanWaves];
@@ -387,10 +402,12 @@ __global__ __launch_bounds__(64 * kLeanWaves, 8) void screened_lean_kernel(Sweep
   const int seg = blockIdx.x, tr = blockIdx.y * kLeanWaves + wave;
   f4v acc = {0.f, 0.f, 0.f, 0.f};
   float total = 0.f;
-  int reads = 0;
+  int reads = 0, stop;
   if (tr < ntiles_rows) {
-    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
-    else acc = screened_lean_body<true, NT>(A, SC, lane, seg, tr, stop, renew, total, reads);
+    if ((seg + 1) * kSegCols <= A.n) acc = screened_lean_body<false, NT>(A, SC, lane, seg, tr, stop, total, reads);
+    else acc = screened_lean_body<true, NT>(A, SC, lane, seg, tr, stop, total, reads);
+  } else {
+    stop = *A.done;
   }
   if (stop) return;
   *reinterpret_cast<f4v*>(&fold[wave][lane * 4]) = acc;

@@ -416,46 +416,107 @@ struct PartialLoad<1> {
   static __device__ __forceinline__ void load(const float* __restrict__ p, float (&v)[1]) { v[0] = *p; }
 };
 
-template <int G, int V>
-__device__ __forceinline__ void gather_shares(const float* __restrict__ part, int share, int nparts, int nrows, int i0,
-                                              int pitch, double (&acc)[V], int (&nz)[V]) {
-  constexpr int kStride = 16, kBatch = G == 1 ? 8 : (G == 4 ? 2 : 1);  // (8 loads in flight per batch)
+// The partial sums are gathered NS shares at once (share0, share0 + step, ...), a batch of 16 loads at a time: the
+// loads of a batch leave together (a row past the end: the last row is fetched and not used; no branch), then each
+// share's additions follow in their order.
+template <int G, int NS>
+struct GatherBatch {
+  static constexpr int kStride = 16, kBatch = (G == 1 ? 8 : (G == 4 ? 2 : 1)) * 2 / NS;
+};
+
+template <int G, int V, int NS>
+__device__ __forceinline__ void gather_batch_load(const float* __restrict__ part, int k0, int step, int nrows, int i0,
+                                                  int pitch, float (&v)[NS][GatherBatch<G, NS>::kBatch][G][V]) {
+  using B = GatherBatch<G, NS>;
 #pragma unroll
-  for (int e = 0; e < V; ++e) acc[e] = 0.0;
-  for (int k0 = share; k0 < nparts; k0 += kStride * kBatch) {
-    float v[kBatch][G][V];
+  for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b)
+    for (int b = 0; b < B::kBatch; ++b)
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const int k = (k0 + b * kStride) * G + g;  // (a row past the end: the last row is fetched and not used; no
-        PartialLoad<V>::load(part + (size_t)min(k, nrows - 1) * pitch + i0, v[b][g]);  // branch, so that all loads leave together)
-        if (k >= nrows) {
-#pragma unroll
-          for (int e = 0; e < V; ++e) v[b][g][e] = 0.f;
-        }
+        const int k = (k0 + s * step + b * B::kStride) * G + g;
+        PartialLoad<V>::load(part + (size_t)min(k, nrows - 1) * pitch + i0, v[s][b][g]);
       }
+}
+
+template <int G, int V, int NS>
+__device__ __forceinline__ void gather_batch_add(const float (&v)[NS][GatherBatch<G, NS>::kBatch][G][V], int k0, int step,
+                                                 int nparts, int nrows, double (&acc)[NS][V], int (&nz)[V]) {
+  using B = GatherBatch<G, NS>;
 #pragma unroll
-    for (int b = 0; b < kBatch; ++b)
-      if (k0 + b * kStride < nparts) {
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int b = 0; b < B::kBatch; ++b) {
+      const int kb = k0 + s * step + b * B::kStride;
+      if (kb < nparts) {
 #pragma unroll
         for (int e = 0; e < V; ++e) {
-          float t = v[b][0][e];
+          float t = v[s][b][0][e];
 #pragma unroll
-          for (int g = 1; g < G; ++g) t += v[b][g][e];
+          for (int g = 1; g < G; ++g) t += kb * G + g < nrows ? v[s][b][g][e] : 0.f;
           if (G == 1) nz[e] += t != 0.f ? 1 : 0;
-          acc[e] += (double)t;
+          acc[s][e] += (double)t;
         }
       }
+    }
+}
+
+// the batches from k0 on (acc and nz are added to)
+template <int G, int V, int NS>
+__device__ __forceinline__ void gather_shares(const float* __restrict__ part, int k0, int step, int nparts, int nrows,
+                                              int i0, int pitch, double (&acc)[NS][V], int (&nz)[V]) {
+  using B = GatherBatch<G, NS>;
+  for (; k0 < nparts; k0 += B::kStride * B::kBatch) {
+    float v[NS][B::kBatch][G][V];
+    gather_batch_load<G, V, NS>(part, k0, step, nrows, i0, pitch, v);
+    gather_batch_add<G, V, NS>(v, k0, step, nparts, nrows, acc, nz);
+  }
+}
+
+// The totals of the tiles stored one per group (tgroup = 1): the thread's NP shares side by side, a batch of 16 loads
+// at a time; share s stands at entry u + s * step + lane with u wave-uniform (a scalar base address plus the lane).
+template <int NP>
+struct TileBatch {
+  static constexpr int kShares = 1024, kBatch = 16 / NP;
+};
+
+template <int NP>
+__device__ __forceinline__ void tile_batch_load(const float* __restrict__ tilesum, int ngroups, int u, int step, int ln,
+                                                float (&v)[NP][TileBatch<NP>::kBatch]) {
+  using B = TileBatch<NP>;
+#pragma unroll
+  for (int s = 0; s < NP; ++s)
+#pragma unroll
+    for (int b = 0; b < B::kBatch; ++b) {
+      const int ub = u + s * step + b * B::kShares;
+      const int uc = min(ub, ngroups - 1);
+      const float w = (tilesum + uc)[min(ln, ngroups - 1 - uc)];
+      v[s][b] = ub + ln < ngroups ? w : 0.f;
+    }
+}
+
+template <int NP>
+__device__ __forceinline__ void tile_batch_add(const float (&v)[NP][TileBatch<NP>::kBatch], double (&acc)[NP]) {
+#pragma unroll
+  for (int s = 0; s < NP; ++s)
+#pragma unroll
+    for (int b = 0; b < TileBatch<NP>::kBatch; ++b) acc[s] += (double)v[s][b];
+}
+
+template <int NP>
+__device__ __forceinline__ void plain_tile_totals(const float* __restrict__ tilesum, int ngroups, int u, int step, int ln,
+                                                  double (&acc)[NP]) {
+  using B = TileBatch<NP>;
+  for (; u < ngroups; u += B::kShares * B::kBatch) {
+    float v[NP][B::kBatch];
+    tile_batch_load<NP>(tilesum, ngroups, u, step, ln, v);
+    tile_batch_add<NP>(v, acc);
   }
 }
 
 template <int V>
 __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(ReduceArgs A, UpdateArgs U, TileTotals T,
                                                                           ScreenCtlArgs K) {
-  // (the stop flag travels with the other loads and is tested before the first store: a test up
-  // front would put one more trip to memory ahead of everything)
-  const int stop = *A.V.done;
   constexpr int NW = kMergedWaves, kShares = 1024, kPerThread = kShares / (64 * NW), kE = 64 * V;
   __shared__ double red[16 * kE];
   __shared__ double eta_part[kShares / 64];
@@ -487,35 +548,13 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   const int len = rows ? A.m : A.n, pitch = rows ? A.mp : A.np;
   const int idx = base + t;
   const bool owner = t < kE && idx < len;
-  const double ab_in = owner ? (rows ? U.a_in[idx] : U.b_in[idx]) : 0.0;
-  const float pq = owner ? (rows ? A.p[idx] : A.q[idx]) : 0.f;
-  const double theta = A.V.theta[U.par], sum_p = *A.V.sum_p;
-  // the shares of the tile totals: batches of independent loads, added in index order.  Share v = 64 w + lane of
-  // accumulator s stands at entry U + lane with U wave-uniform: a scalar base address plus the lane
-  double acc[kPerThread];
-#pragma unroll
-  for (int s = 0; s < kPerThread; ++s) {
-    acc[s] = 0.0;
-    const int u0 = 64 * wv + s * 64 * NW;
-    if (T.tgroup == kColGroup) acc[s] = grouped_tile_totals<kColGroup>(T, u0 + ln, ln);
-    else if (T.tgroup == kPointsColGroup) acc[s] = grouped_tile_totals<kPointsColGroup>(T, u0 + ln, ln);
-    else {
-      constexpr int kBatch = 8;
-      const int ngroups = T.tile_rows * T.nseg;
-      for (int u = u0; u < ngroups; u += kShares * kBatch) {
-        float v[kBatch];
-#pragma unroll
-        for (int b = 0; b < kBatch; ++b) {
-          const int ub = u + b * kShares;
-          const int uc = min(ub, ngroups - 1);
-          const float w = (T.tilesum + uc)[min(ln, ngroups - 1 - uc)];
-          v[b] = ub + ln < ngroups ? w : 0.f;
-        }
-#pragma unroll
-        for (int b = 0; b < kBatch; ++b) acc[s] += (double)v[b];
-      }
-    }
-  }
+  // (fetched by every thread, from an entry that exists: no branch around the loads, nothing waits here)
+  const int idc = min(idx, len - 1);
+  const double ab_ld = rows ? U.a_in[idc] : U.b_in[idc];
+  const float pq_ld = rows ? A.p[idc] : A.q[idc];
+  // (the stop flag, theta and the sum of p travel with the other loads; the flag is tested before the first store)
+  const int stop_ld = __hip_atomic_load(A.V.done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  const double theta = vector_load_uniform(A.V.theta + U.par), sum_p = vector_load_uniform(A.V.sum_p);
   // the partial sums of this workgroup's entries: wave w forms the shares w and w + 8 of the lane's V entries
   // (lanes past the end of a row of partials fetch its last ones; nobody reads what they leave)
   const int i0 = min(base + V * ln, pitch - V);
@@ -523,20 +562,57 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
   const int nparts = rows ? A.nseg : grouped ? (A.ntr + A.cgroup - 1) / A.cgroup : A.ntr;
   const int nrows_part = rows ? A.nseg : A.ntr;
   const float* __restrict__ part = rows ? A.rowpart : A.colpart;
+  constexpr int NS = 16 / NW;  // shares of the partial sums per wave: w and w + 8
   int nzv[V];
+  double av[NS][V];
 #pragma unroll
   for (int e = 0; e < V; ++e) nzv[e] = 0;
 #pragma unroll
-  for (int si = 0; si < 16 / NW; ++si) {
-    const int share = wv + si * NW;
-    double av[V];
-    if (!grouped) gather_shares<1, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
-    else if (A.cgroup == kColGroup) gather_shares<kColGroup, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
-    else gather_shares<kPointsColGroup, V>(part, share, nparts, nrows_part, i0, pitch, av, nzv);
-    double* dst = red + share * kE + V * ln;
+  for (int si = 0; si < NS; ++si)
 #pragma unroll
-    for (int e = 0; e < V; ++e) dst[e] = av[e];
+    for (int e = 0; e < V; ++e) av[si][e] = 0.0;
+  // the shares of the tile totals: share v = 64 w + lane of accumulator s, added in index order
+  double acc[kPerThread];
+#pragma unroll
+  for (int s = 0; s < kPerThread; ++s) acc[s] = 0.0;
+  const bool tiles_grouped = T.tgroup == kColGroup || T.tgroup == kPointsColGroup;
+  if (!tiles_grouped && !grouped) {
+    // everything stored ready to add (the lean sweeps): the first batch of the tile totals and the first batch of
+    // the partial sums are on their way together before anything is added: one trip to memory instead of two
+    using TB = TileBatch<kPerThread>;
+    using GB = GatherBatch<1, NS>;
+    const int ngroups = T.tile_rows * T.nseg;
+    float tv[kPerThread][TB::kBatch];
+    float gv[NS][GB::kBatch][1][V];
+    tile_batch_load<kPerThread>(T.tilesum, ngroups, 64 * wv, 64 * NW, ln, tv);
+    gather_batch_load<1, V, NS>(part, wv, NW, nrows_part, i0, pitch, gv);
+    __builtin_amdgcn_sched_barrier(0);
+    tile_batch_add<kPerThread>(tv, acc);
+    plain_tile_totals<kPerThread>(T.tilesum, ngroups, 64 * wv + TB::kShares * TB::kBatch, 64 * NW, ln, acc);
+    gather_batch_add<1, V, NS>(gv, wv, NW, nparts, nrows_part, av, nzv);
+    gather_shares<1, V, NS>(part, wv + GB::kStride * GB::kBatch, NW, nparts, nrows_part, i0, pitch, av, nzv);
+  } else {
+    if (T.tgroup == kColGroup) {
+#pragma unroll
+      for (int s = 0; s < kPerThread; ++s) acc[s] = grouped_tile_totals<kColGroup>(T, 64 * wv + s * 64 * NW + ln, ln);
+    } else if (T.tgroup == kPointsColGroup) {
+#pragma unroll
+      for (int s = 0; s < kPerThread; ++s) acc[s] = grouped_tile_totals<kPointsColGroup>(T, 64 * wv + s * 64 * NW + ln, ln);
+    } else {
+      plain_tile_totals<kPerThread>(T.tilesum, T.tile_rows * T.nseg, 64 * wv, 64 * NW, ln, acc);
+    }
+    if (!grouped) gather_shares<1, V, NS>(part, wv, NW, nparts, nrows_part, i0, pitch, av, nzv);
+    else if (A.cgroup == kColGroup) gather_shares<kColGroup, V, NS>(part, wv, NW, nparts, nrows_part, i0, pitch, av, nzv);
+    else gather_shares<kPointsColGroup, V, NS>(part, wv, NW, nparts, nrows_part, i0, pitch, av, nzv);
   }
+#pragma unroll
+  for (int si = 0; si < NS; ++si) {
+    double* dst = red + (wv + si * NW) * kE + V * ln;
+#pragma unroll
+    for (int e = 0; e < V; ++e) dst[e] = av[si][e];
+  }
+  const double ab_in = owner ? ab_ld : 0.0;
+  const float pq = owner ? pq_ld : 0.f;
 #pragma unroll
   for (int s = 0; s < kPerThread; ++s) {
     const double w = wave_sum_f64(acc[s]);
@@ -564,7 +640,7 @@ __global__ __launch_bounds__(64 * kMergedWaves) void reduce_update_kernel(Reduce
     }
   }
   __syncthreads();
-  if (stop) return;
+  if (__builtin_amdgcn_readfirstlane(stop_ld)) return;
   if (t == 0 && blockIdx.x == gridDim.x - 1 && K.mode != 0) {
     if (K.mode == 1 || renewed) {  // new bounds: nothing paid yet, the floor is what the next sweep reads
       K.ctl[kCtlRenew] = 0;
