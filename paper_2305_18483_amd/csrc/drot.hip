@@ -289,7 +289,10 @@ struct Solve {
 
   double* a_buf(long long g) const { return h->a + (size_t)(g & 1) * (size_t)h->max_m; }
   double* b_buf(long long g) const { return h->b + (size_t)(g & 1) * (size_t)h->max_n; }
-  float* rowp(long long g) const { return h->rowpart + (size_t)(g & 1) * h->rowpart_half; }
+  // (row-segment sums: two halves only where the vector update rides at the head of the next sweep and reads the old
+  // sums while the new ones are written; everywhere else a sweep reads nothing but its own old sums, before it writes
+  // them, so one buffer serves, and a sweep may leave alone what it knows to be unchanged)
+  float* rowp(long long g) const { return h->rowpart + (S.fused ? (size_t)(g & 1) * h->rowpart_half : 0); }
   float* colp(long long g) const { return h->colpart + (size_t)(g & 1) * h->colpart_half; }
   float* tsum(long long g) const { return h->tilesum + (size_t)(g & 1) * h->tilesum_half; }
 };

@@ -156,7 +156,6 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
   constexpr int COLS = 4 * CX, RL = kSlabThreads / CX;
   static_assert(kSlabMaxRows <= kSlabThreads, "the fused update gives every row of a run a thread");
   const SweepArgs& A = G.S;
-  if (*A.done) return;
   __shared__ float red[RL][COLS];  // 16 KiB either way
   __shared__ float part[16][COLS];
   __shared__ float bcast[COLS];
@@ -166,6 +165,9 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
   const int t = threadIdx.x;
   const int cx = t % CX, ry = t / CX;
   const int strip = blockIdx.x, run = blockIdx.y;
+  // (the stop flag is asked for together with the run's place and length, one trip to memory instead of two, and
+  // tested once the loads below are on their way; nothing is stored before that)
+  const int stop = *A.done;
   const int start = G.run_start[run], len = G.run_len[run];
   const int j0 = strip * COLS + cx * 4;
   const int nvalid = min(max(A.n - j0, 0), 4);
@@ -193,11 +195,12 @@ __global__ __launch_bounds__(kSlabThreads) void gl_slab_kernel(SlabArgs G, Fused
     x[k] = f4v{0.f, 0.f, 0.f, 0.f};
     ph[k] = kMaskedOut;  // rows past the run: the clamp zeroes them
     if (r < len) {
+      if (!PRO) ph[k] = A.phi[start + r];  // (first: what follows a fetch of X waits for everything asked for before it)
       c[k] = load4(Cp + (size_t)(RL * k) * ldc, nvalid);
       if (!FIRST && held[k]) x[k] = load4(Xp + (size_t)(RL * k) * ldx, nvalid);
-      if (!PRO) ph[k] = A.phi[start + r];
     }
   }
+  if (stop) return;
   f4v vp;
   if (PRO) {
     // ---- eq. (6) from the previous sweep's sums (F.nseg = number of strips, F.ntr = number of runs) ----

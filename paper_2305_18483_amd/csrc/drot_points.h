@@ -237,7 +237,6 @@ __device__ __forceinline__ void xcd_strip(int nseg, int nstrips, int& seg, int& 
 
 template <bool NT>
 __global__ __launch_bounds__(256, 6) void lean_points_kernel(SweepArgs A, PointArgs Pt, ScreenArgs SC) {
-  const int stop = *A.done;
   __shared__ float ctile[16][kDotPitch];  // a block's costs-to-be (inner products); the column fold at the very end
   __shared__ unsigned long long masks[4];
   __shared__ unsigned char list[kStripRows];
@@ -268,6 +267,11 @@ __global__ __launch_bounds__(256, 6) void lean_points_kernel(SweepArgs A, PointA
     js = SC.jstar_in[ridx];
     xsq_lane = Pt.xs_sq[r0 + lane];
   }
+  // (the stop flag travels with the loads above: asked for before them, a wave would sit out its latency with
+  // nothing of its own in flight; it is tested before the first store)
+  __builtin_amdgcn_sched_barrier(0);
+  const int stop = *A.done;
+  __builtin_amdgcn_sched_barrier(0);
   const f4v dv = vp - vp0;
   const float d = fmaxf(fmaxf(dv.x, dv.y), fmaxf(dv.z, dv.w));
   const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
@@ -401,7 +405,8 @@ __global__ __launch_bounds__(256, 6) void lean_points_kernel(SweepArgs A, PointA
     tile_acc[cur_pair >> 4] += pair_acc;
     tile_tot[cur_pair >> 4] += pair_tot;
   }
-  if (lane < nrows) A.rowpart[ridx] = rowkeep;
+  // (the sums are kept in place: a row segment certified to stay all zero has a zero there already)
+  if (lane < nrows && !certified) A.rowpart[ridx] = rowkeep;
   if (threadIdx.x == 0) SC.wg_reads[strip * gridDim.x + seg] = total;  // (row segments whose cost was formed)
   // the strip's column sums: its eight 32-row tiles in order
   float* __restrict__ fold = &ctile[0][0];

@@ -269,7 +269,9 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
   const float a = fmaxf(fmaxf(unmasked_abs(vp.x), unmasked_abs(vp.y)), fmaxf(unmasked_abs(vp.z), unmasked_abs(vp.w)));
   const float delta = wave_max(d), mag = wave_max(a);
   const bool below = certified_zero(mpr, mpr2, js, dv, delta, mag, ph);  // (the same certificate as in screened_body)
-  const bool certified = lane >= nrows || (!renew && oldlines == 0 && below);
+  // (unchanged: the row segment was all zero and stays so; its sum and its line flags in memory are zeros already)
+  const bool unchanged = !renew && oldlines == 0 && below;
+  const bool certified = lane >= nrows || unchanged;
   tile_total = 0.f;
   reads = 0;
   if (stop) return f4v{0.f, 0.f, 0.f, 0.f};
@@ -361,8 +363,10 @@ __device__ __forceinline__ f4v screened_lean_body(const SweepArgs& A, const Scre
     tile_tot += group_tot;
   }
   if (lane < nrows) {
-    A.rowpart[ridx] = rowkeep;
-    SC.lines_out[ridx] = (unsigned char)newlines;
+    // (the sums are kept in place, and the flags too when the previous sweep left them: what has not changed is
+    // not written again, which is nearly everything)
+    if (!unchanged) A.rowpart[ridx] = rowkeep;
+    if (SC.lines_in == nullptr || newlines != oldlines) SC.lines_out[ridx] = (unsigned char)newlines;
   }
   if (renew) {
     if (lane < nrows) {
