@@ -160,8 +160,9 @@ def main() -> int:
         xb = x_after if x_before is None or x_before < 0 else x_before
         xw = max(xb, x_after)
         if kind == 7:
-            # per row segment: the three parts of the bound (4 + 4 + 1 B), the line flags in and out, the new sum
-            return 4.0 * c * mn + 8.0 * line_frac * mn + 15.0 * m * nseg + 4.0 * n * ((m + 255) // 256)
+            # per row segment: the three parts of the bound (4 + 4 + 1 B) and the line flags read; the new sum and
+            # flags written only where the bound did not certify zeros (the rest is unchanged in memory)
+            return 4.0 * c * mn + 8.0 * line_frac * mn + (10.0 + 5.0 * c) * m * nseg + 4.0 * n * ((m + 255) // 256)
         per_segment = 8.0 if kind == 4 else 17.0  # (old and new sum; screened: also the three parts of the bound)
         return 4.0 * c * mn + 4.0 * (xb + xw) * mn + per_segment * m * nseg + 4.0 * n * ((m + 63) // 64)
 
@@ -218,7 +219,7 @@ def main() -> int:
         roof["bytes_model"] = ("per launch: 4 B x the row segments of C read (counted by the kernel) + X read on the row segments "
                                "nonzero before and written on those nonzero before or after (counted by the vector updates; lean "
                                "kernel: the nonzero 128-byte lines of the final plan) + 8-17 B per row segment (sums, bounds, line "
-                               "flags) + column sums; dense sweeps 12 (8 without C) B per element; dense_model_gbs prices the "
+                               "flags; lean kernel: 10 B read, 5 B written where no bound certified zeros) + column sums; dense sweeps 12 (8 without C) B per element; dense_model_gbs prices the "
                                "launch at 12 B per element")
         if line_frac:
             roof["nonzero_line_fraction"] = round(line_frac, 6)
@@ -336,10 +337,11 @@ def main() -> int:
             e = {"kernel": name, "kernel_ms": round(ms, 5), "launches_timed": len(sel)}
             if kind == 8:
                 formed = sum(r.c_fraction for r in sel) / len(sel)
-                # per row segment: old and new row sum, the three parts of the bound (17 B); the strip's column sums; X on its nonzero row
-                # segments (read and written); the costs are not traffic; flops: blocks of 16 rows x 256 columns
+                # per row segment: the old row sum and the three parts of the bound read (13 B), the new sum written where the
+                # cost was formed; the strip's column sums; X on its nonzero row segments (read and written); the costs are
+                # not traffic; flops: blocks of 16 rows x 256 columns
                 xnz = sum(max(r.x_fraction, 0.0) for r in sel) / len(sel)
-                nbytes = 17.0 * m * nseg + 4.0 * n * ((m + 255) // 256) + 8.0 * xnz * m * n
+                nbytes = (13.0 + 4.0 * formed) * m * nseg + 4.0 * n * ((m + 255) // 256) + 8.0 * xnz * m * n
                 gbs = nbytes / (ms * 1e-3) / 1e9
                 e.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                           "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
