@@ -100,6 +100,17 @@ def test_product_package_does_not_import_the_oracle():
                 assert "oracle" not in text.lower(), os.path.join(base, name)
 
 
+def test_kernels_are_built_without_compiler_chosen_fma_contraction():
+    # the sweeps promise each other the same bits (screened against unscreened, lean against 8-wave tiles, stored
+    # cost against point clouds); that holds only if a product and a sum are fused where the source says fmaf and
+    # nowhere else: left to the compiler, fusion depends on which statements happen to share a basic block
+    from paper_2305_18483_amd import build
+    assert "-ffp-contract=off" in build.HIPCC_FLAGS
+    # and packed fp32 instructions stay out of the generated code
+    flags = " ".join(build.HIPCC_FLAGS)
+    assert "-Xclang -target-feature -Xclang -packed-fp32-ops" in flags
+
+
 def test_public_header_is_plain_c(tmp_path):
     # the boundary is a C ABI: include/drot.h must compile as C99 on its own, with warnings as errors
     import shutil
