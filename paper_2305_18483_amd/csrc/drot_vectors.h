@@ -396,9 +396,7 @@ __device__ __forceinline__ double grouped_tile_totals(const TileTotals& T, int e
 // number of threads, share v taking the entries v, v + 1024, ...
 constexpr int kMergedWaves = 8;
 
-// One of the 16 shares of V entries' partial sums (the lane's entries i0 .. i0 + V - 1) when G consecutive rows
-// of the partials are added in fp32 first (G = 1: none are).  share, nparts, nrows, pitch are wave-uniform; i0 is
-// clamped so that the entries stay inside a row of the partials.  nz (G = 1 only): nonzero partials seen per entry.
+// V consecutive entries of one row of the partial sums (one load per lane).
 template <int V>
 struct PartialLoad;
 template <>
@@ -416,9 +414,11 @@ struct PartialLoad<1> {
   static __device__ __forceinline__ void load(const float* __restrict__ p, float (&v)[1]) { v[0] = *p; }
 };
 
-// The partial sums are gathered NS shares at once (share0, share0 + step, ...), a batch of 16 loads at a time: the
-// loads of a batch leave together (a row past the end: the last row is fetched and not used; no branch), then each
-// share's additions follow in their order.
+// The 16 shares of V entries' partial sums (the lane's entries i0 .. i0 + V - 1, i0 clamped so that they stay inside
+// a row of the partials) are gathered NS shares at once (share0, share0 + step, ...), a batch of 16 loads at a time:
+// the loads of a batch leave together (a row past the end: the last row is fetched and not used; no branch), then
+// each share's additions follow in their order.  G consecutive rows of the partials are added in fp32 first (G = 1:
+// none are).  k0, step, nparts, nrows, pitch are wave-uniform.  nz (G = 1 only): nonzero partials seen per entry.
 template <int G, int NS>
 struct GatherBatch {
   static constexpr int kStride = 16, kBatch = (G == 1 ? 8 : (G == 4 ? 2 : 1)) * 2 / NS;
